@@ -1,0 +1,277 @@
+"""CPU oracle for the block-scaled FP8 grouped GEMM.  TEST INFRASTRUCTURE ONLY.
+
+This file is the yardstick the HIP library is measured against.  It is plain
+NumPy in float64, shares no code, table or helper with the HIP path, and must
+only be imported by tests/, by ``__graft_entry__.smoke()`` and by the
+``cpu_baseline`` leg of ``bench.py``.  The product never routes through it.
+
+What it computes (paper Sec. 2.1, Table 1; 1x128 scaling of A and 128x128
+scaling of B as stated right below Table 1):
+
+    for every group g, every row r in [off[g], off[g+1]), every column n
+
+        D[r, n] = sum_{kb ascending} ( SA[r, kb] * SB[g, n // 128, kb] )
+                                     * ( sum_{k in K-block kb} dec(A[r, k]) * dec(B[g, n, k]) )
+        C[r, n] = bf16_round_to_nearest_even( D[r, n] )
+
+``dec`` is the OCP e4m3 ("fn") decoding.  Rows of C outside
+[off[0], off[G]) are not produced.  N and K are shared by all groups, M^g is
+per group (paragraph below Table 1); the output is a 2-byte float (App. A,
+analysis of C^g) and this build fixes it to bfloat16.
+
+Why a float64 matmul may serve as the inner step without being an
+approximation: every e4m3 value is an integer multiple of 2^-9 of magnitude at
+most 448, so every product is an integer multiple of 2^-18 below 2^18 and a sum
+of 128 of them needs at most 43 significant bits.  The inner sum is therefore
+exact in float64 in ANY summation order, and so is SA*SB (24+24 bits).  Only
+the outer accumulation over kb rounds, and its order is fixed (ascending).
+
+Every function here is pinned by tests/test_oracle_pins.py (exact rational
+brute force, closed forms, the paper's worked example, the padded == unpadded
+invariant of Sec. 3.2).  No function is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+SCALE_BLOCK = 128  # width of a scale block along K (A and B) and along N (B)  -- Sec. 2.1
+
+
+# ----------------------------------------------------------------------------
+# number formats
+# ----------------------------------------------------------------------------
+def e4m3_decode_table() -> np.ndarray:
+    """float64[256]: value of every OCP e4m3fn byte, from the bit definition.
+
+    1 sign, 4 exponent (bias 7), 3 mantissa bits; exponent field 0 is
+    subnormal (m * 2^-9); there is no infinity; S.1111.111 is NaN; the largest
+    finite magnitude is 448.  (The paper only says "FP8"; e4m3 with max 448 is
+    the reading fixed for this build.)
+    """
+    table = np.empty(256, dtype=np.float64)
+    for byte in range(256):
+        sign = -1.0 if (byte & 0x80) else 1.0
+        e = (byte >> 3) & 0xF
+        m = byte & 0x7
+        if e == 0xF and m == 0x7:
+            v = float("nan")
+        elif e == 0:
+            v = sign * m * 2.0 ** (-9)
+        else:
+            v = sign * (1.0 + m / 8.0) * 2.0 ** (e - 7)
+        table[byte] = v
+    return table
+
+
+_DEC = e4m3_decode_table()
+
+
+def e4m3_decode(u8: np.ndarray) -> np.ndarray:
+    """Decode an array of e4m3 bytes to float64."""
+    u8 = np.asarray(u8)
+    assert u8.dtype == np.uint8
+    return _DEC[u8]
+
+
+def bf16_bits_from_f64(x: np.ndarray) -> np.ndarray:
+    """uint16 bfloat16 bit patterns of float64 values, ONE rounding step (RNE).
+
+    bfloat16 = 1 sign, 8 exponent (bias 127), 7 mantissa bits.  The value is
+    rounded on the bfloat16 grid directly (no detour through float32, which
+    would round twice).  Overflow goes to +-inf, NaN becomes the canonical
+    quiet NaN 0x7FC0, signed zeros are kept.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    sign = np.signbit(x)
+    a = np.abs(x)
+    nan = np.isnan(a)
+    a = np.where(nan, 0.0, a)
+    # exponent e with 2^e <= a < 2^(e+1); frexp gives a = f * 2^E, f in [0.5, 1)
+    _, E = np.frexp(a)
+    e = np.maximum(E.astype(np.int64) - 1, -126)  # subnormals share the grid of 2^-126
+    quantum = np.ldexp(1.0, (e - 7).astype(np.int32))  # spacing of bf16 values in that binade
+    with np.errstate(over="ignore", invalid="ignore"):
+        ratio = a / quantum                  # exact: division by a power of two
+        ratio = np.where(np.isinf(a), np.inf, ratio)
+        r = np.rint(ratio) * quantum         # np.rint rounds half to even; product exact
+    # r is now exactly a bfloat16 value (or 2^128 / inf => overflow); float32 holds it exactly
+    with np.errstate(over="ignore"):
+        f32 = r.astype(np.float32)
+    bits = (f32.view(np.uint32) >> 16).astype(np.uint16)
+    bits = np.where(sign, bits | np.uint16(0x8000), bits)
+    bits = np.where(nan, np.uint16(0x7FC0), bits)
+    return bits.astype(np.uint16)
+
+
+def f64_from_bf16_bits(bits: np.ndarray) -> np.ndarray:
+    """float64 value of bfloat16 bit patterns (exact)."""
+    bits = np.asarray(bits, dtype=np.uint16)
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def bf16_ulp(x: np.ndarray) -> np.ndarray:
+    """Spacing of bfloat16 values in the binade that holds |x| (float64)."""
+    a = np.abs(np.asarray(x, dtype=np.float64))
+    _, E = np.frexp(np.where(a == 0, 1.0, a))
+    e = np.maximum(E.astype(np.int64) - 1, -126)
+    e = np.where(a == 0, -126, e)
+    return np.ldexp(1.0, (e - 7).astype(np.int32))
+
+
+# ----------------------------------------------------------------------------
+# the operation
+# ----------------------------------------------------------------------------
+def _check_shapes(A, SA, B, SB, off, N, K):
+    G = off.shape[0] - 1
+    KB = -(-K // SCALE_BLOCK)
+    NB = -(-N // SCALE_BLOCK)
+    assert A.dtype == np.uint8 and A.ndim == 2 and A.shape[1] == K
+    assert B.dtype == np.uint8 and B.shape == (G, N, K)
+    assert SA.shape == (A.shape[0], KB)
+    assert SB.shape == (G, NB, KB)
+    return G, KB, NB
+
+
+def grouped_gemm(A, SA, B, SB, group_offsets, rows=None, with_abs_sum=False):
+    """Block-scaled FP8 grouped GEMM by its definition (Sec. 2.1, Table 1).
+
+    A   uint8 [M_total, K]   e4m3 bytes, groups concatenated along rows
+    SA  float [M_total, ceil(K/128)]     one scale per (row, 128-wide K block)
+    B   uint8 [G, N, K]      e4m3 bytes; B[g, n, k] is element (k, n) of the paper's B^g
+    SB  float [G, ceil(N/128), ceil(K/128)]   one scale per 128x128 block of B^g
+    group_offsets int [G+1]  rows of group g are [off[g], off[g+1])
+    rows  optional 1-D array of global row indices; only those rows are
+          evaluated (each one by the same formula), in the order given.
+
+    Returns a dict:
+      "rows"  int64 [R]      global row index of each output row
+      "group" int64 [R]      the group each row belongs to
+      "D"     float64 [R, N] the block-scaled dot products
+      "C"     uint16 [R, N]  bfloat16 bit patterns of D (one RNE rounding)
+      "S"     float64 [R, N] (with_abs_sum) sum_kb |sa*sb| * sum_k |a*b| -- the
+              magnitude against which a float32 accumulation error is bounded
+    Scales are dequantisation multipliers: real value = dec(byte) * scale.
+    """
+    A = np.asarray(A)
+    B = np.asarray(B)
+    off = np.asarray(group_offsets, dtype=np.int64)
+    K = A.shape[1]
+    N = B.shape[1]
+    SA = np.asarray(SA, dtype=np.float64)
+    SB = np.asarray(SB, dtype=np.float64)
+    G, KB, NB = _check_shapes(A, SA, B, SB, off, N, K)
+    assert np.all(np.diff(off) >= 0) and off[0] >= 0 and off[-1] <= A.shape[0]
+
+    if rows is None:
+        rows = np.arange(off[0], off[-1], dtype=np.int64)
+    rows = np.asarray(rows, dtype=np.int64)
+    assert np.all((rows >= off[0]) & (rows < off[-1])), "row outside every group"
+    # group of row r: the g with off[g] <= r < off[g+1] (empty groups are skipped by 'right')
+    grp = np.searchsorted(off, rows, side="right") - 1
+
+    R = rows.shape[0]
+    D = np.zeros((R, N), dtype=np.float64)
+    S = np.zeros((R, N), dtype=np.float64) if with_abs_sum else None
+    col_block = np.arange(N) // SCALE_BLOCK            # n -> index of its 128-wide N block
+
+    for g in np.unique(grp):
+        sel = np.nonzero(grp == g)[0]
+        rg = rows[sel]
+        Dg = np.zeros((sel.shape[0], N), dtype=np.float64)
+        Sg = np.zeros_like(Dg) if with_abs_sum else None
+        for kb in range(KB):
+            k0, k1 = kb * SCALE_BLOCK, min((kb + 1) * SCALE_BLOCK, K)
+            a = e4m3_decode(A[rg, k0:k1])               # [R_g, <=128] float64
+            b = e4m3_decode(B[g, :, k0:k1])             # [N,   <=128] float64
+            inner = a @ b.T                             # exact (see module docstring)
+            scale = SA[rg, kb][:, None] * SB[g, col_block, kb][None, :]   # exact product
+            Dg += scale * inner                         # the only rounding steps: * and +=
+            if with_abs_sum:
+                Sg += np.abs(scale) * (np.abs(a) @ np.abs(b).T)
+        D[sel] = Dg
+        if with_abs_sum:
+            S[sel] = Sg
+
+    out = {"rows": rows, "group": grp, "D": D, "C": bf16_bits_from_f64(D)}
+    if with_abs_sum:
+        out["S"] = S
+    return out
+
+
+# ----------------------------------------------------------------------------
+# the padded formulation the paper compares against (Sec. 3: padding of A and
+# S_A to multiples of 128 rows per group, then the same GEMM, then removal of
+# the pad rows)
+# ----------------------------------------------------------------------------
+def padded_offsets(group_offsets, align=SCALE_BLOCK):
+    """Offsets of the groups after each is rounded up to a multiple of `align` rows."""
+    off = np.asarray(group_offsets, dtype=np.int64)
+    sizes = np.diff(off)
+    padded = -(-sizes // align) * align
+    return np.concatenate([[0], np.cumsum(padded)]).astype(np.int64)
+
+
+def pad(A, SA, group_offsets, align=SCALE_BLOCK, rows_cap=None):
+    """Copy every group to its aligned offset; pad rows of A and SA are zero.
+
+    Returns (A_pad uint8 [M_pad, K], SA_pad [M_pad, KB], padded_offsets [G+1]).
+    `rows_cap` >= M_pad allocates a larger (zero) tail, as a caller that cannot
+    know M_pad in advance would.
+    """
+    A = np.asarray(A)
+    SA = np.asarray(SA)
+    off = np.asarray(group_offsets, dtype=np.int64)
+    poff = padded_offsets(off, align)
+    M_pad = int(poff[-1]) if rows_cap is None else int(rows_cap)
+    assert M_pad >= poff[-1]
+    A_pad = np.zeros((M_pad, A.shape[1]), dtype=A.dtype)    # byte 0x00 decodes to +0
+    SA_pad = np.zeros((M_pad, SA.shape[1]), dtype=SA.dtype)
+    for g in range(off.shape[0] - 1):
+        n = off[g + 1] - off[g]
+        A_pad[poff[g]:poff[g] + n] = A[off[g]:off[g + 1]]
+        SA_pad[poff[g]:poff[g] + n] = SA[off[g]:off[g + 1]]
+    return A_pad, SA_pad, poff
+
+
+def unpad(C_pad, group_offsets, padded_off, M_total, fill=0):
+    """Gather the valid rows of a padded output back to the concatenated layout."""
+    off = np.asarray(group_offsets, dtype=np.int64)
+    poff = np.asarray(padded_off, dtype=np.int64)
+    C = np.full((M_total, C_pad.shape[1]), fill, dtype=C_pad.dtype)
+    for g in range(off.shape[0] - 1):
+        n = off[g + 1] - off[g]
+        C[off[g]:off[g + 1]] = C_pad[poff[g]:poff[g] + n]
+    return C
+
+
+# ----------------------------------------------------------------------------
+# the paper's own residual-row store rule (Sec. 2.2, Eq. 1-2 and App. B).  The
+# HIP path does not use it (bounded stores replace it); it is kept so that the
+# claim "exactly the residual rows are written, none beyond" can be checked
+# for the paper's mechanism as well as for ours.
+# ----------------------------------------------------------------------------
+def descriptor_pool(block_M):
+    """Row counts of the store shapes of Eq. 1: 2^i for 0 <= i <= floor(log2 block_M)."""
+    return [1 << i for i in range(int(block_M).bit_length())]
+
+
+def two_phase_cover(M_g, block_M=128):
+    """Row ranges (inclusive) of the two stores that write the residual block of a group.
+
+    res = M_g mod block_M; p = 2^floor(log2 res) is the selected shape (Eq. 2).
+    Phase 1 copies tile rows [0, p-1] to group rows [M_g-res, M_g-res+p-1];
+    phase 2 copies tile rows [res-p, res-1] to group rows [M_g-p, M_g-1].
+    Returns None when res == 0 (no residual block; log2(0) is undefined in Eq. 2).
+    """
+    res = M_g % block_M
+    if res == 0:
+        return None
+    p = 1 << (res.bit_length() - 1)
+    return {
+        "res": res,
+        "rows_desc": p,
+        "phase1_tile": (0, p - 1),
+        "phase1_group": (M_g - res, M_g - res + p - 1),
+        "phase2_tile": (res - p, res - 1),
+        "phase2_group": (M_g - p, M_g - 1),
+    }
