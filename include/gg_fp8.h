@@ -1,0 +1,125 @@
+/* libgg_fp8 -- padding-free FP8 (e4m3) grouped GEMM with fine-grained block
+ * scaling for AMD MI355X (gfx950).  C ABI; no C++ or framework types cross it.
+ *
+ * The operation (paper Sec. 2.1, Table 1; scaling granularity stated below the
+ * table): G groups share N and K, group g owns M^g rows.  With
+ *   A   [M_total, K]  e4m3 bytes, the groups' rows concatenated,
+ *   SA  [M_total, K/128]            one fp32 scale per (row, 128-wide K block),
+ *   B   [G, N, K]     e4m3 bytes, B[g][n][k] = element (k, n) of the paper's B^g,
+ *   SB  [G, N/128, K/128]           one fp32 scale per 128x128 block of B^g,
+ *   group_offsets [G+1] int32       rows of group g are [off[g], off[g+1]),
+ * the library writes, for every row r of group g and every n,
+ *   C[r][n] = bf16( sum_kb  SA[r][kb] * SB[g][n/128][kb]
+ *                           * sum_{k in block kb} dec(A[r][k]) * dec(B[g][n][k]) ).
+ * Scales are dequantisation multipliers.  M^g is arbitrary (0, 1, not a
+ * multiple of anything): only valid rows are read, computed and written; there
+ * is no padded copy (the capability of Sec. 2.2, obtained here with bounded
+ * buffer descriptors instead of a descriptor pool and two-phase stores).
+ *
+ * Conventions common to all entry points
+ *  - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *    never allocates, frees or synchronises (except gg_fp8_check_offsets) and
+ *    keeps no state between calls; calls are asynchronous on `stream`
+ *    (a hipStream_t passed as void*, NULL = the default stream).
+ *  - All matrices are row-major and dense (leading dimension = row length).
+ *    A, B, C, A_pad, C_pad must be 16-byte aligned; SA, SB, offsets 4-byte.
+ *  - K and N must be positive multiples of 128 (GG_ERR_UNSUPPORTED otherwise).
+ *  - group_offsets lives on the device and is trusted to be non-decreasing with
+ *    0 <= off[0] and off[G] <= M_total.  If it is not, rows may be skipped or
+ *    computed with the wrong group, but nothing outside C[0:M_total] is written.
+ *    Rows of C outside [off[0], off[G]) are never written.
+ *  - Return value: a gg_status.  On any error nothing has been enqueued.
+ *    G == 0 or M_total == 0 returns GG_OK without a launch.
+ */
+#ifndef GG_FP8_H
+#define GG_FP8_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GG_OK = 0,
+  GG_ERR_NULL = 1,        /* a required pointer is NULL                              */
+  GG_ERR_SHAPE = 2,       /* G < 0, M_total < 0, N <= 0, K <= 0, or a size overflows */
+  GG_ERR_UNSUPPORTED = 3, /* N or K not a multiple of 128, unknown variant           */
+  GG_ERR_WORKSPACE = 4,   /* workspace smaller than gg_fp8_workspace_bytes()         */
+  GG_ERR_HIP = 5,         /* the HIP runtime refused a launch or a query             */
+  GG_ERR_OFFSETS = 6      /* gg_fp8_check_offsets found invalid offsets              */
+} gg_status;
+
+/* Library version: major*10000 + minor*100 + patch. */
+int gg_fp8_version(void);
+
+/* Static, never-NULL description of a gg_status value. */
+const char* gg_fp8_status_str(int status);
+
+/* Bytes of device scratch the GEMM entry points need for this problem size
+ * (may be 0).  The same value serves the padded GEMM with M_total = M_pad_cap. */
+size_t gg_fp8_workspace_bytes(int G, int64_t M_total, int N, int K);
+
+/* The padding-free grouped GEMM defined at the top of this file (Sec. 2.1 and
+ * 2.2).  One persistent kernel walks the (group, m-tile, n-tile) list derived
+ * from group_offsets on the device; rows past the end of a group are neither
+ * loaded (they read as zero) nor stored.  `workspace` may be NULL when
+ * gg_fp8_workspace_bytes() is 0. */
+int gg_fp8_grouped_gemm(const void* A, const float* SA, const void* B, const float* SB,
+                        const int32_t* group_offsets, void* C,
+                        int G, int64_t M_total, int N, int K,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same operation with an explicit tile variant (for benchmarking and tests).
+ * variant < 0 selects automatically, exactly like gg_fp8_grouped_gemm.
+ * gg_fp8_num_variants() variants exist; gg_fp8_variant_name(v) describes one
+ * ("BMxBN/waves/stages"), NULL if v is out of range. */
+int gg_fp8_grouped_gemm_variant(const void* A, const float* SA, const void* B, const float* SB,
+                                const int32_t* group_offsets, void* C,
+                                int G, int64_t M_total, int N, int K,
+                                void* workspace, size_t workspace_bytes, void* stream, int variant);
+int gg_fp8_num_variants(void);
+const char* gg_fp8_variant_name(int variant);
+
+/* ---- the pad-then-GEMM comparison path (the baseline of Sec. 3) ------------
+ * Every group is copied to an offset that is a multiple of 128 rows, pad rows
+ * are zero, the same GEMM kernels run on the aligned problem, and the valid
+ * rows are gathered back.  Numerically identical to the padding-free path on
+ * valid rows (the equivalence claimed in Sec. 3.2). */
+
+/* Upper bound on the padded row count for ANY offsets with this G and M_total:
+ * 128 * (ceil(M_total / 128) + G).  Size A_pad, SA_pad and C_pad with it. */
+int64_t gg_fp8_padded_rows_cap(int G, int64_t M_total);
+
+/* Writes padded_offsets[G+1] (padded_offsets[0] = 0, each group rounded up to a
+ * multiple of 128 rows), copies the valid rows of A [M_total,K] and SA
+ * [M_total,K/128] to A_pad [M_pad_cap,K] and SA_pad [M_pad_cap,K/128] and
+ * zero-fills every other row up to M_pad_cap.  M_pad_cap must be at least
+ * gg_fp8_padded_rows_cap(G, M_total) (GG_ERR_SHAPE otherwise). */
+int gg_fp8_pad(const void* A, const float* SA, const int32_t* group_offsets,
+               void* A_pad, float* SA_pad, int32_t* padded_offsets,
+               int G, int64_t M_total, int64_t M_pad_cap, int K, void* stream);
+
+/* The GEMM on the aligned problem: identical to gg_fp8_grouped_gemm with
+ * M_total = M_pad_cap and group_offsets = padded_offsets.  Pad rows inside
+ * [0, padded_offsets[G]) of C_pad are written (as zeros); rows beyond are not. */
+int gg_fp8_grouped_gemm_padded(const void* A_pad, const float* SA_pad, const void* B, const float* SB,
+                               const int32_t* padded_offsets, void* C_pad,
+                               int G, int64_t M_pad_cap, int N, int K,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/* Gathers the valid rows of C_pad [*, N] bf16 into C [M_total, N] bf16:
+ * C[off[g] + i] = C_pad[padded_offsets[g] + i] for i < M^g. */
+int gg_fp8_unpad(const void* C_pad, const int32_t* group_offsets, const int32_t* padded_offsets,
+                 void* C, int G, int64_t M_total, int N, void* stream);
+
+/* Debug helper, NOT for the hot path: synchronises `stream`, copies the G+1
+ * offsets to the host and returns GG_ERR_OFFSETS unless they are non-decreasing
+ * with 0 <= off[0] and off[G] <= M_total. */
+int gg_fp8_check_offsets(const int32_t* group_offsets, int G, int64_t M_total, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GG_FP8_H */

@@ -1,0 +1,24 @@
+"""libgg_fp8 for MI355X: padding-free FP8 grouped GEMM with fine-grained block scaling.
+
+Thin Python binding (ctypes) over the C-ABI shared library built from csrc/.
+Every step of the computation runs in the library's HIP kernels; this package
+only marshals arguments.  There is no CPU fallback: without the built library
+`load_library()` raises.
+"""
+from .binding import (  # noqa: F401
+    GGError,
+    build_library,
+    check_offsets,
+    grouped_gemm,
+    grouped_gemm_padded,
+    library_path,
+    load_library,
+    num_variants,
+    pad,
+    padded_rows_cap,
+    status_str,
+    unpad,
+    variant_name,
+    version,
+    workspace_bytes,
+)

@@ -1,0 +1,252 @@
+"""ctypes binding of include/gg_fp8.h -- same names, argument marshalling only.
+
+torch is used for device memory and streams; tensors are passed to the library
+as raw device pointers.  Functions raise GGError with the library's status text
+when a call returns an error code.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_PKG_DIR)
+_LIB_NAME = "libgg_fp8.so"
+_lib = None
+
+GG_OK = 0
+
+
+class GGError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"libgg_fp8 status {status}: {text}")
+        self.status = status
+
+
+def library_path() -> str:
+    return os.path.join(_PKG_DIR, _LIB_NAME)
+
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    # keep hipcc from forming packed-fp32 instructions on its own
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+]
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile csrc/gg_fp8.hip for gfx950 into the package directory (needs hipcc, no GPU)."""
+    src = os.path.join(_PKG_DIR, "csrc", "gg_fp8.hip")
+    out = library_path()
+    tmp = out + ".tmp"
+    cmd = ["hipcc", *HIPCC_FLAGS, "-I", os.path.join(_ROOT, "include"), "-o", tmp, src]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + res.stdout + res.stderr)
+    if verbose:
+        print(res.stderr)
+    os.replace(tmp, out)
+    global _lib
+    _lib = None
+    return out
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(
+            f"{path} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(there is no CPU fallback for libgg_fp8)")
+    lib = ctypes.CDLL(path)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+    lib.gg_fp8_version.restype = i32
+    lib.gg_fp8_version.argtypes = []
+    lib.gg_fp8_status_str.restype = ctypes.c_char_p
+    lib.gg_fp8_status_str.argtypes = [i32]
+    lib.gg_fp8_workspace_bytes.restype = sz
+    lib.gg_fp8_workspace_bytes.argtypes = [i32, i64, i32, i32]
+    lib.gg_fp8_grouped_gemm.restype = i32
+    lib.gg_fp8_grouped_gemm.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp, sz, vp]
+    lib.gg_fp8_grouped_gemm_variant.restype = i32
+    lib.gg_fp8_grouped_gemm_variant.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp, sz, vp, i32]
+    lib.gg_fp8_num_variants.restype = i32
+    lib.gg_fp8_num_variants.argtypes = []
+    lib.gg_fp8_variant_name.restype = ctypes.c_char_p
+    lib.gg_fp8_variant_name.argtypes = [i32]
+    lib.gg_fp8_padded_rows_cap.restype = i64
+    lib.gg_fp8_padded_rows_cap.argtypes = [i32, i64]
+    lib.gg_fp8_pad.restype = i32
+    lib.gg_fp8_pad.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i64, i32, vp]
+    lib.gg_fp8_grouped_gemm_padded.restype = i32
+    lib.gg_fp8_grouped_gemm_padded.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp, sz, vp]
+    lib.gg_fp8_unpad.restype = i32
+    lib.gg_fp8_unpad.argtypes = [vp, vp, vp, vp, i32, i64, i32, vp]
+    lib.gg_fp8_check_offsets.restype = i32
+    lib.gg_fp8_check_offsets.argtypes = [vp, i32, i64, vp]
+    _lib = lib
+    return lib
+
+
+EXPORTED_SYMBOLS = [
+    "gg_fp8_version", "gg_fp8_status_str", "gg_fp8_workspace_bytes", "gg_fp8_grouped_gemm",
+    "gg_fp8_grouped_gemm_variant", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_padded_rows_cap",
+    "gg_fp8_pad", "gg_fp8_grouped_gemm_padded", "gg_fp8_unpad", "gg_fp8_check_offsets",
+]
+
+
+# ---------------------------------------------------------------------------- helpers
+def _check(status: int):
+    if status != GG_OK:
+        raise GGError(status, status_str(status))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _want(t, name, dtype, ndim):
+    if not isinstance(t, torch.Tensor):
+        raise TypeError(f"{name} must be a torch tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if t.dim() != ndim:
+        raise ValueError(f"{name} must have {ndim} dimensions, got {t.dim()}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+
+
+def _gemm_shapes(A, SA, B, SB, group_offsets):
+    _want(A, "A", torch.uint8, 2)
+    _want(SA, "SA", torch.float32, 2)
+    _want(B, "B", torch.uint8, 3)
+    _want(SB, "SB", torch.float32, 3)
+    _want(group_offsets, "group_offsets", torch.int32, 1)
+    M_total, K = A.shape
+    G, N, K2 = B.shape
+    if K2 != K:
+        raise ValueError(f"A has K={K} but B has K={K2}")
+    if group_offsets.shape[0] != G + 1:
+        raise ValueError(f"group_offsets must have G+1={G + 1} entries")
+    if K % 128 == 0 and N % 128 == 0:
+        if tuple(SA.shape) != (M_total, K // 128):
+            raise ValueError(f"SA must be [{M_total}, {K // 128}]")
+        if tuple(SB.shape) != (G, N // 128, K // 128):
+            raise ValueError(f"SB must be [{G}, {N // 128}, {K // 128}]")
+    return G, M_total, N, K
+
+
+# ---------------------------------------------------------------------------- the API
+def version() -> int:
+    return load_library().gg_fp8_version()
+
+
+def status_str(status: int) -> str:
+    return load_library().gg_fp8_status_str(int(status)).decode()
+
+
+def workspace_bytes(G: int, M_total: int, N: int, K: int) -> int:
+    return int(load_library().gg_fp8_workspace_bytes(G, M_total, N, K))
+
+
+def num_variants() -> int:
+    return load_library().gg_fp8_num_variants()
+
+
+def variant_name(v: int):
+    s = load_library().gg_fp8_variant_name(v)
+    return None if s is None else s.decode()
+
+
+def _workspace(G, M_total, N, K, device):
+    n = workspace_bytes(G, M_total, N, K)
+    return (torch.empty(n, dtype=torch.uint8, device=device) if n else None), n
+
+
+def grouped_gemm(A, SA, B, SB, group_offsets, C=None, variant: int = -1, stream=None):
+    """C[r, :] = bf16(block-scaled A[r, :] @ B[g]^T) for every row r of every group g (gg_fp8_grouped_gemm).
+
+    A uint8 [M_total, K] (e4m3 bytes), SA float32 [M_total, K/128], B uint8 [G, N, K],
+    SB float32 [G, N/128, K/128], group_offsets int32 [G+1]; returns C bfloat16 [M_total, N]
+    (allocated here unless given; rows outside the groups are left as they are).
+    """
+    lib = load_library()
+    G, M_total, N, K = _gemm_shapes(A, SA, B, SB, group_offsets)
+    if C is None:
+        C = torch.empty((M_total, N), dtype=torch.bfloat16, device=A.device)
+    _want(C, "C", torch.bfloat16, 2)
+    if tuple(C.shape) != (M_total, N):
+        raise ValueError(f"C must be [{M_total}, {N}]")
+    ws, n = _workspace(G, M_total, N, K, A.device)
+    _check(lib.gg_fp8_grouped_gemm_variant(_ptr(A), _ptr(SA), _ptr(B), _ptr(SB), _ptr(group_offsets), _ptr(C),
+                                           G, M_total, N, K, _ptr(ws), n, _stream(stream), int(variant)))
+    return C
+
+
+def padded_rows_cap(G: int, M_total: int) -> int:
+    return int(load_library().gg_fp8_padded_rows_cap(G, M_total))
+
+
+def pad(A, SA, group_offsets, M_pad_cap: int | None = None, stream=None):
+    """gg_fp8_pad: returns (A_pad, SA_pad, padded_offsets) with every group at a multiple of 128 rows."""
+    lib = load_library()
+    _want(A, "A", torch.uint8, 2)
+    _want(SA, "SA", torch.float32, 2)
+    _want(group_offsets, "group_offsets", torch.int32, 1)
+    M_total, K = A.shape
+    G = group_offsets.shape[0] - 1
+    if M_pad_cap is None:
+        M_pad_cap = padded_rows_cap(G, M_total)
+    A_pad = torch.empty((M_pad_cap, K), dtype=torch.uint8, device=A.device)
+    SA_pad = torch.empty((M_pad_cap, SA.shape[1]), dtype=torch.float32, device=A.device)
+    poff = torch.empty(G + 1, dtype=torch.int32, device=A.device)
+    _check(lib.gg_fp8_pad(_ptr(A), _ptr(SA), _ptr(group_offsets), _ptr(A_pad), _ptr(SA_pad), _ptr(poff),
+                          G, M_total, M_pad_cap, K, _stream(stream)))
+    return A_pad, SA_pad, poff
+
+
+def grouped_gemm_padded(A_pad, SA_pad, B, SB, padded_offsets, C_pad=None, stream=None):
+    """gg_fp8_grouped_gemm_padded: the same GEMM on the 128-aligned problem; returns C_pad."""
+    lib = load_library()
+    G, M_pad_cap, N, K = _gemm_shapes(A_pad, SA_pad, B, SB, padded_offsets)
+    if C_pad is None:
+        C_pad = torch.empty((M_pad_cap, N), dtype=torch.bfloat16, device=A_pad.device)
+    _want(C_pad, "C_pad", torch.bfloat16, 2)
+    ws, n = _workspace(G, M_pad_cap, N, K, A_pad.device)
+    _check(lib.gg_fp8_grouped_gemm_padded(_ptr(A_pad), _ptr(SA_pad), _ptr(B), _ptr(SB), _ptr(padded_offsets),
+                                          _ptr(C_pad), G, M_pad_cap, N, K, _ptr(ws), n, _stream(stream)))
+    return C_pad
+
+
+def unpad(C_pad, group_offsets, padded_offsets, M_total: int, C=None, stream=None):
+    """gg_fp8_unpad: gathers the valid rows of C_pad into C [M_total, N]."""
+    lib = load_library()
+    _want(C_pad, "C_pad", torch.bfloat16, 2)
+    N = C_pad.shape[1]
+    G = group_offsets.shape[0] - 1
+    if C is None:
+        C = torch.empty((M_total, N), dtype=torch.bfloat16, device=C_pad.device)
+    _check(lib.gg_fp8_unpad(_ptr(C_pad), _ptr(group_offsets), _ptr(padded_offsets), _ptr(C), G, M_total, N,
+                            _stream(stream)))
+    return C
+
+
+def check_offsets(group_offsets, M_total: int, stream=None) -> int:
+    """gg_fp8_check_offsets (debug; synchronises): returns the status instead of raising."""
+    lib = load_library()
+    G = group_offsets.shape[0] - 1
+    return lib.gg_fp8_check_offsets(_ptr(group_offsets), G, M_total, _stream(stream))

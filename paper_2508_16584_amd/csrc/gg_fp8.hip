@@ -1,0 +1,248 @@
+// libgg_fp8: C-ABI entry points, argument validation and kernel dispatch.
+// The operation and every convention are documented in include/gg_fp8.h.
+#include "../../include/gg_fp8.h"
+
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <vector>
+
+#include "gemm_kernel.h"
+#include "pad_kernels.h"
+
+namespace {
+
+constexpr int kVersion = 100;  // 0.1.0
+constexpr int kXcds = 8;       // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
+
+struct DeviceInfo {
+  int cus = 0;
+};
+
+// Number of compute units of the current device (queried once per device, cached).
+int device_cus() {
+  static std::atomic<int> cache[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  int v = cache[dev].load(std::memory_order_relaxed);
+  if (v > 0) return v;
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+  cache[dev].store(cus, std::memory_order_relaxed);
+  return cus;
+}
+
+struct Variant {
+  const char* name;
+  int BM, BN;
+  int lds_bytes;
+  int wg_per_cu;
+  hipError_t (*launch)(const gg::GemmArgs&, int grid, hipStream_t);
+};
+
+template <class Cfg>
+hipError_t launch_gemm(const gg::GemmArgs& args, int grid, hipStream_t stream) {
+  static std::atomic<int> prepared[64];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < 64 && !prepared[dev].load(std::memory_order_acquire)) {
+    // more than 64 KB of LDS per workgroup has to be requested explicitly
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_gemm_kernel<Cfg>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    prepared[dev].store(1, std::memory_order_release);
+  }
+  hipLaunchKernelGGL(gg::gg_gemm_kernel<Cfg>, dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, args);
+  return hipGetLastError();
+}
+
+#define GG_VARIANT(BM, BN, WM, WN, ST, WGPC)                                                   \
+  {#BM "x" #BN "/" #WM "x" #WN "w/" #ST "s", BM, BN, gg::GemmCfg<BM, BN, WM, WN, ST>::LDS_BYTES, \
+   WGPC, &launch_gemm<gg::GemmCfg<BM, BN, WM, WN, ST>>}
+
+const Variant kVariants[] = {
+    GG_VARIANT(256, 256, 2, 4, 2, 1),
+    GG_VARIANT(128, 256, 2, 4, 2, 1),
+    GG_VARIANT(128, 128, 2, 4, 2, 2),
+    GG_VARIANT(64, 256, 1, 8, 2, 2),
+    GG_VARIANT(32, 256, 1, 8, 2, 2),
+    GG_VARIANT(16, 256, 1, 8, 2, 2),
+};
+constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+
+// Tile height by the mean number of rows per group (the only size information the host has:
+// the offsets stay on the device).
+int pick_variant(int G, int64_t M_total, int N) {
+  const double avg = G > 0 ? (double)M_total / G : 0.0;
+  int v;
+  if (avg >= 384) v = 0;
+  else if (avg >= 96) v = 1;
+  else if (avg >= 48) v = 3;
+  else if (avg >= 24) v = 4;
+  else v = 5;
+  if (N % kVariants[v].BN != 0) v = 2;  // N is a multiple of 128 but not of 256
+  return v;
+}
+
+int validate_gemm(const void* A, const float* SA, const void* B, const float* SB, const int32_t* off, void* C,
+                  int G, int64_t M_total, int N, int K) {
+  if (G < 0 || M_total < 0 || N <= 0 || K <= 0) return GG_ERR_SHAPE;
+  if (M_total > 0x7FFFFFFFLL || N > (1 << 21) || K > (1 << 22)) return GG_ERR_SHAPE;
+  if (N % 128 != 0 || K % 128 != 0) return GG_ERR_UNSUPPORTED;
+  if (G == 0 || M_total == 0) return GG_OK;
+  if (!A || !SA || !B || !SB || !off || !C) return GG_ERR_NULL;
+  return GG_OK;
+}
+
+int run_gemm(const void* A, const float* SA, const void* B, const float* SB, const int32_t* off, void* C,
+             int G, int64_t M_total, int N, int K, void* stream, int variant) {
+  int st = validate_gemm(A, SA, B, SB, off, C, G, M_total, N, K);
+  if (st != GG_OK) return st;
+  if (G == 0 || M_total == 0) return GG_OK;
+  if (variant >= kNumVariants) return GG_ERR_UNSUPPORTED;
+  if (variant < 0) variant = pick_variant(G, M_total, N);
+  const Variant& v = kVariants[variant];
+  if (N % v.BN != 0) return GG_ERR_UNSUPPORTED;
+
+  gg::GemmArgs args;
+  args.A = static_cast<const uint8_t*>(A);
+  args.SA = SA;
+  args.B = static_cast<const uint8_t*>(B);
+  args.SB = SB;
+  args.off = off;
+  args.C = static_cast<uint16_t*>(C);
+  args.G = G;
+  args.M_total = (int)M_total;
+  args.N = N;
+  args.K = K;
+  args.KB = K / 128;
+  args.n_tiles = N / v.BN;
+  args.n_chunk = args.n_tiles < 8 ? args.n_tiles : 8;
+
+  // upper bound on the number of tiles for any offsets: every group adds at most one partial m-tile
+  const int64_t max_tiles = (M_total / v.BM + G) * (int64_t)args.n_tiles;
+  int64_t grid = (int64_t)device_cus() * v.wg_per_cu;
+  if (grid > max_tiles) grid = max_tiles;
+  if (grid < 1) grid = 1;
+  if (grid >= kXcds) {
+    grid -= grid % kXcds;
+    args.slots = (int)(grid / kXcds);
+  } else {
+    args.slots = 0;
+  }
+  hipError_t e = v.launch(args, (int)grid, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? GG_OK : GG_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gg_fp8_version(void) { return kVersion; }
+
+const char* gg_fp8_status_str(int status) {
+  switch (status) {
+    case GG_OK: return "ok";
+    case GG_ERR_NULL: return "a required pointer is NULL";
+    case GG_ERR_SHAPE: return "invalid or overflowing size argument";
+    case GG_ERR_UNSUPPORTED: return "unsupported shape (N and K must be multiples of 128) or variant";
+    case GG_ERR_WORKSPACE: return "workspace too small";
+    case GG_ERR_HIP: return "HIP runtime error";
+    case GG_ERR_OFFSETS: return "group offsets are not non-decreasing within [0, M_total]";
+    default: return "unknown status";
+  }
+}
+
+size_t gg_fp8_workspace_bytes(int G, int64_t M_total, int N, int K) {
+  (void)G; (void)M_total; (void)N; (void)K;
+  return 0;  // the tile schedule is static: no counters, no scratch
+}
+
+int gg_fp8_num_variants(void) { return kNumVariants; }
+
+const char* gg_fp8_variant_name(int variant) {
+  return (variant >= 0 && variant < kNumVariants) ? kVariants[variant].name : nullptr;
+}
+
+int gg_fp8_grouped_gemm_variant(const void* A, const float* SA, const void* B, const float* SB,
+                                const int32_t* group_offsets, void* C, int G, int64_t M_total, int N, int K,
+                                void* workspace, size_t workspace_bytes, void* stream, int variant) {
+  (void)workspace;
+  if (workspace_bytes < gg_fp8_workspace_bytes(G, M_total, N, K)) return GG_ERR_WORKSPACE;
+  return run_gemm(A, SA, B, SB, group_offsets, C, G, M_total, N, K, stream, variant);
+}
+
+int gg_fp8_grouped_gemm(const void* A, const float* SA, const void* B, const float* SB,
+                        const int32_t* group_offsets, void* C, int G, int64_t M_total, int N, int K,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  return gg_fp8_grouped_gemm_variant(A, SA, B, SB, group_offsets, C, G, M_total, N, K, workspace, workspace_bytes,
+                                     stream, -1);
+}
+
+int64_t gg_fp8_padded_rows_cap(int G, int64_t M_total) {
+  if (G < 0 || M_total < 0) return 0;
+  return 128 * ((M_total + 127) / 128 + (int64_t)G);
+}
+
+int gg_fp8_pad(const void* A, const float* SA, const int32_t* group_offsets, void* A_pad, float* SA_pad,
+               int32_t* padded_offsets, int G, int64_t M_total, int64_t M_pad_cap, int K, void* stream) {
+  if (G < 0 || M_total < 0 || K <= 0 || M_pad_cap < 0) return GG_ERR_SHAPE;
+  if (M_total > 0x7FFFFFFFLL || M_pad_cap > 0x7FFFFFFFLL || K > (1 << 22)) return GG_ERR_SHAPE;
+  if (M_pad_cap < gg_fp8_padded_rows_cap(G, M_total)) return GG_ERR_SHAPE;
+  if (K % 128 != 0) return GG_ERR_UNSUPPORTED;
+  if (!padded_offsets || !group_offsets) return GG_ERR_NULL;
+  if (M_pad_cap > 0 && (!A_pad || !SA_pad)) return GG_ERR_NULL;
+  if (M_total > 0 && (!A || !SA)) return GG_ERR_NULL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(gg::gg_pad_offsets_kernel, dim3(1), dim3(gg::PAD_THREADS), 0, s, group_offsets, padded_offsets, G,
+                     (int)M_total);
+  if (hipGetLastError() != hipSuccess) return GG_ERR_HIP;
+  if (M_pad_cap == 0) return GG_OK;
+  const int64_t nblocks = (M_pad_cap + gg::PAD_BLOCK_ROWS - 1) / gg::PAD_BLOCK_ROWS;
+  int64_t grid = (int64_t)device_cus() * 8;
+  if (grid > nblocks) grid = nblocks;
+  hipLaunchKernelGGL(gg::gg_pad_rows_kernel, dim3((unsigned)grid), dim3(gg::PAD_THREADS), 0, s,
+                     static_cast<const uint8_t*>(A), SA, group_offsets, padded_offsets, static_cast<uint8_t*>(A_pad),
+                     SA_pad, G, (int)M_total, (int)M_pad_cap, K, K / 128);
+  return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
+}
+
+int gg_fp8_grouped_gemm_padded(const void* A_pad, const float* SA_pad, const void* B, const float* SB,
+                               const int32_t* padded_offsets, void* C_pad, int G, int64_t M_pad_cap, int N, int K,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+  return gg_fp8_grouped_gemm(A_pad, SA_pad, B, SB, padded_offsets, C_pad, G, M_pad_cap, N, K, workspace,
+                             workspace_bytes, stream);
+}
+
+int gg_fp8_unpad(const void* C_pad, const int32_t* group_offsets, const int32_t* padded_offsets, void* C, int G,
+                 int64_t M_total, int N, void* stream) {
+  if (G < 0 || M_total < 0 || N <= 0) return GG_ERR_SHAPE;
+  if (M_total > 0x7FFFFFFFLL || N > (1 << 21)) return GG_ERR_SHAPE;
+  if (N % 128 != 0) return GG_ERR_UNSUPPORTED;
+  if (G == 0 || M_total == 0) return GG_OK;
+  if (!C_pad || !group_offsets || !padded_offsets || !C) return GG_ERR_NULL;
+  const int64_t nblocks = (M_total + gg::PAD_BLOCK_ROWS - 1) / gg::PAD_BLOCK_ROWS;
+  int64_t grid = (int64_t)device_cus() * 8;
+  if (grid > nblocks) grid = nblocks;
+  hipLaunchKernelGGL(gg::gg_unpad_rows_kernel, dim3((unsigned)grid), dim3(gg::PAD_THREADS), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(C_pad), group_offsets, padded_offsets,
+                     static_cast<uint16_t*>(C), G, (int)M_total, N);
+  return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
+}
+
+int gg_fp8_check_offsets(const int32_t* group_offsets, int G, int64_t M_total, void* stream) {
+  if (G < 0 || M_total < 0) return GG_ERR_SHAPE;
+  if (!group_offsets) return GG_ERR_NULL;
+  std::vector<int32_t> host((size_t)G + 1);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (hipMemcpyAsync(host.data(), group_offsets, host.size() * sizeof(int32_t), hipMemcpyDeviceToHost, s) != hipSuccess)
+    return GG_ERR_HIP;
+  if (hipStreamSynchronize(s) != hipSuccess) return GG_ERR_HIP;
+  if (host[0] < 0 || (int64_t)host[G] > M_total) return GG_ERR_OFFSETS;
+  for (int g = 0; g < G; ++g)
+    if (host[g + 1] < host[g]) return GG_ERR_OFFSETS;
+  return GG_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,115 @@
+"""Host-side checks of the C-ABI library: it loads, exports what include/gg_fp8.h declares, and
+rejects bad arguments before anything is enqueued.  No GPU is needed: every call below returns
+from argument validation."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2508_16584_amd as gg
+from paper_2508_16584_amd import binding
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "gg_fp8.h")
+
+GG_OK, GG_ERR_NULL, GG_ERR_SHAPE, GG_ERR_UNSUPPORTED, GG_ERR_WORKSPACE, GG_ERR_HIP, GG_ERR_OFFSETS = range(7)
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(gg.library_path()):
+        gg.build_library()
+    return gg.load_library()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gg_fp8_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in gg_fp8.h but not exported"
+    assert sorted(binding.EXPORTED_SYMBOLS) == names
+
+
+def test_version_status_strings_and_variants(lib):
+    assert gg.version() >= 100
+    texts = {gg.status_str(s) for s in range(7)}
+    assert len(texts) == 7 and gg.status_str(0) == "ok"
+    assert gg.status_str(99) == "unknown status"
+    n = gg.num_variants()
+    assert n >= 1
+    for v in range(n):
+        assert re.fullmatch(r"\d+x\d+/\d+x\d+w/\d+s", gg.variant_name(v))
+    assert gg.variant_name(n) is None and gg.variant_name(-1) is None
+
+
+def test_padded_rows_cap_and_workspace(lib):
+    assert gg.padded_rows_cap(0, 0) == 0
+    assert gg.padded_rows_cap(8, 8192) == 128 * (64 + 8)
+    assert gg.padded_rows_cap(3, 1) == 128 * 4
+    # the cap covers the worst case: every group one row over a multiple of 128
+    for G, M in [(4, 4 * 129), (7, 5), (32, 16384)]:
+        worst = sum(-(-s // 128) * 128 for s in [M // G + (1 if i < M % G else 0) for i in range(G)])
+        assert gg.padded_rows_cap(G, M) >= worst
+    assert gg.workspace_bytes(8, 8192, 4096, 7168) == 0
+
+
+def test_gemm_argument_validation(lib):
+    f = lib.gg_fp8_grouped_gemm
+    p = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
+    nul = ctypes.c_void_p(0)
+    ok_args = dict(G=2, M=100, N=256, K=256)
+
+    def call(A=p, SA=p, B=p, SB=p, off=p, C=p, G=2, M=100, N=256, K=256):
+        return f(A, SA, B, SB, off, C, G, M, N, K, nul, 0, nul)
+
+    assert call(N=200) == GG_ERR_UNSUPPORTED
+    assert call(K=64) == GG_ERR_UNSUPPORTED
+    assert call(N=0) == GG_ERR_SHAPE
+    assert call(K=-128) == GG_ERR_SHAPE
+    assert call(G=-1) == GG_ERR_SHAPE
+    assert call(M=-1) == GG_ERR_SHAPE
+    assert call(M=2 ** 31) == GG_ERR_SHAPE
+    for name in ("A", "SA", "B", "SB", "off", "C"):
+        assert call(**{name: nul}) == GG_ERR_NULL, name
+    # empty problems succeed without touching any pointer
+    assert f(nul, nul, nul, nul, nul, nul, 0, 0, 256, 256, nul, 0, nul) == GG_OK
+    assert f(nul, nul, nul, nul, nul, nul, 4, 0, 256, 256, nul, 0, nul) == GG_OK
+    assert lib.gg_fp8_grouped_gemm_variant(p, p, p, p, p, p, 2, 100, 256, 256, nul, 0, nul, 999) == GG_ERR_UNSUPPORTED
+    assert lib.gg_fp8_grouped_gemm_padded(p, p, p, p, p, p, 2, 256, 100, 256, nul, 0, nul) == GG_ERR_UNSUPPORTED
+    del ok_args
+
+
+def test_pad_unpad_argument_validation(lib):
+    p = ctypes.c_void_p(0x1000)
+    nul = ctypes.c_void_p(0)
+    cap = gg.padded_rows_cap(2, 100)
+    assert lib.gg_fp8_pad(p, p, p, p, p, p, 2, 100, cap - 1, 256, nul) == GG_ERR_SHAPE
+    assert lib.gg_fp8_pad(p, p, p, p, p, p, 2, 100, cap, 100, nul) == GG_ERR_UNSUPPORTED
+    assert lib.gg_fp8_pad(p, p, p, p, p, nul, 2, 100, cap, 256, nul) == GG_ERR_NULL
+    assert lib.gg_fp8_pad(p, p, p, nul, p, p, 2, 100, cap, 256, nul) == GG_ERR_NULL
+    assert lib.gg_fp8_pad(p, p, p, p, p, p, -2, 100, cap, 256, nul) == GG_ERR_SHAPE
+    assert lib.gg_fp8_unpad(p, p, p, p, 2, 100, 100, nul) == GG_ERR_UNSUPPORTED
+    assert lib.gg_fp8_unpad(nul, p, p, p, 2, 100, 256, nul) == GG_ERR_NULL
+    assert lib.gg_fp8_unpad(nul, nul, nul, nul, 0, 0, 256, nul) == GG_OK
+    assert lib.gg_fp8_check_offsets(nul, 2, 100, nul) == GG_ERR_NULL
+
+
+def test_binding_rejects_wrong_tensors_before_calling_the_library(lib):
+    import torch
+    A = torch.zeros((4, 256), dtype=torch.uint8)
+    SA = torch.zeros((4, 2))
+    B = torch.zeros((1, 256, 256), dtype=torch.uint8)
+    SB = torch.zeros((1, 2, 2))
+    off = torch.tensor([0, 4], dtype=torch.int32)
+    with pytest.raises(ValueError, match="GPU"):
+        gg.grouped_gemm(A, SA, B, SB, off)                     # host tensors are refused: no CPU path
+    with pytest.raises(TypeError):
+        gg.grouped_gemm(A.float(), SA, B, SB, off)
+    with pytest.raises(ValueError):
+        gg.grouped_gemm(A, SA, B[:, :, :128], SB, off)

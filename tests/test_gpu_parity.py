@@ -1,0 +1,285 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Every test here needs a real MI355X.  Inputs are seeded and synthetic; the tolerance is defined and
+justified in tests/gg_testlib.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2508_16584_amd as gg
+from oracle import gg_oracle as orc
+from workloads import CONFIGS, WorkloadConfig, group_sizes, make_problem
+
+from gg_testlib import assert_parity, bits_of, np_problem, raw_problem
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+CANARY = 0x7B7B          # bf16 bit pattern that no test result produces in bulk
+
+
+def variants_for(N):
+    out = []
+    for v in range(gg.num_variants()):
+        bn = int(gg.variant_name(v).split("/")[0].split("x")[1])
+        if N % bn == 0:
+            out.append(v)
+    return out
+
+
+def canary_C(M, N):
+    return torch.full((M, N), CANARY, dtype=torch.int16, device=DEV).view(torch.bfloat16)
+
+
+def run_gpu(dev, M, N, variant=-1, C=None):
+    A, SA, B, SB, off = dev
+    if C is None:
+        C = canary_C(M, N)
+    gg.grouped_gemm(A, SA, B, SB, off, C=C, variant=variant)
+    torch.cuda.synchronize()
+    return bits_of(C)
+
+
+# ----------------------------------------------------------------------------------------------
+def test_library_loaded_is_the_in_tree_hip_build():
+    lib = gg.load_library()
+    assert lib.gg_fp8_version() >= 100
+    assert gg.library_path().endswith("paper_2508_16584_amd/libgg_fp8.so")
+    assert gg.num_variants() >= 1
+
+
+def test_tiny_config_every_variant_full_compare():
+    p = make_problem(CONFIGS["tiny"])
+    host = np_problem(p)
+    ref = orc.grouped_gemm(*host, with_abs_sum=True)
+    dev = tuple(p[k].to(DEV) for k in ("A", "SA", "B", "SB", "group_offsets"))
+    first = None
+    for v in [-1] + variants_for(p["N"]):
+        got = run_gpu(dev, p["M_total"], p["N"], v)
+        assert_parity(got, ref, what=f"tiny variant {v}")
+        # the arithmetic per element does not depend on the tiling: all variants agree bit for bit
+        if first is None:
+            first = got
+        assert np.array_equal(got, first), f"variant {v} differs from the default"
+
+
+@pytest.mark.parametrize("sizes,N,K", [
+    ([1], 256, 128),
+    ([0, 0, 0], 256, 256),
+    ([127, 128, 129], 256, 384),
+    ([253], 128, 256),                       # the group of the paper's worked example (App. B)
+    ([381, 0, 125], 128, 256),               # and of its figure caption
+    ([16, 17, 15, 1, 0, 31, 33], 512, 512),
+    ([255, 256, 257, 0, 1], 256, 256),
+    ([700], 384, 640),                       # N a multiple of 128 but not of 256
+])
+def test_edge_group_sizes_every_variant(sizes, N, K):
+    cfg = WorkloadConfig("edge", 50, len(sizes), K, N, 0, "custom", "latency")
+    p = make_problem(cfg, sizes=np.array(sizes))
+    host = np_problem(p)
+    ref = orc.grouped_gemm(*host, with_abs_sum=True)
+    dev = tuple(p[k].to(DEV) for k in ("A", "SA", "B", "SB", "group_offsets"))
+    for v in [-1] + variants_for(N):
+        got = run_gpu(dev, p["M_total"], N, v)
+        assert_parity(got, ref, empirical=p["M_total"] * N >= 50000, what=f"sizes {sizes} variant {v}")
+
+
+def test_rows_outside_the_groups_and_guard_bands_are_untouched():
+    # groups cover rows [5, 5+sum) of a larger buffer; C has guard rows before and after
+    rng = np.random.default_rng(60)
+    sizes, N, K = [130, 0, 67], 256, 256
+    host, dev = raw_problem(rng, sizes, N, K, DEV)
+    A, SA, B, SB, off = host
+    pre, post = 5, 9
+    M = A.shape[0] + pre + post
+    A2 = np.concatenate([rng.integers(0, 120, (pre, K), dtype=np.uint8), A, rng.integers(0, 120, (post, K), dtype=np.uint8)])
+    SA2 = np.concatenate([np.ones((pre, K // 128), np.float32), SA, np.ones((post, K // 128), np.float32)])
+    off2 = (off + pre).astype(np.int32)
+    ref = orc.grouped_gemm(A2, SA2, B, SB, off2, with_abs_sum=True)
+    dev2 = tuple(torch.from_numpy(x).to(DEV) for x in (A2, SA2, B, SB, off2))
+    for v in variants_for(N):
+        guard = 64
+        buf = torch.full(((M + 2 * guard), N), CANARY, dtype=torch.int16, device=DEV)
+        C = buf[guard:guard + M].view(torch.bfloat16)
+        got = run_gpu(dev2, M, N, v, C=C)
+        allb = buf.cpu().numpy().view(np.uint16)
+        assert np.all(allb[:guard + pre] == CANARY), f"variant {v} wrote before the first group"
+        assert np.all(allb[guard + pre + A.shape[0]:] == CANARY), f"variant {v} wrote past the last group"
+        assert_parity(got[pre:pre + A.shape[0]], ref, empirical=False, what=f"guard variant {v}")
+
+
+def test_raw_bytes_full_dynamic_range_hard_bound():
+    # every e4m3 code (subnormals included), arbitrary scales: only the hard bound applies
+    rng = np.random.default_rng(61)
+    sizes, N, K = [77, 200, 3], 256, 512
+    host, dev = raw_problem(rng, sizes, N, K, DEV)
+    ref = orc.grouped_gemm(*host, with_abs_sum=True)
+    for v in variants_for(N):
+        got = run_gpu(dev, int(sum(sizes)), N, v)
+        assert_parity(got, ref, empirical=False, what=f"raw bytes variant {v}")
+
+
+def test_closed_forms_are_exact():
+    # (a) all ones: every output is K * alpha * beta exactly
+    N, K, M = 256, 640, 70
+    A = torch.full((M, K), 0x38, dtype=torch.uint8, device=DEV)
+    B = torch.full((2, N, K), 0x38, dtype=torch.uint8, device=DEV)
+    SA = torch.full((M, K // 128), 0.375, device=DEV)
+    SB = torch.full((2, N // 128, K // 128), 1.25, device=DEV)
+    off = torch.tensor([0, 33, 70], dtype=torch.int32, device=DEV)
+    got = bits_of(gg.grouped_gemm(A, SA, B, SB, off))
+    want = orc.bf16_bits_from_f64(np.array([K * 0.375 * 1.25]))[0]
+    assert np.all(got == want)
+    # (b) small integers and power-of-two scales: every intermediate is exact in fp32, so the GPU must
+    #     reproduce the oracle bit for bit, not merely within tolerance
+    rng = np.random.default_rng(62)
+    small = [0x00, 0x38, 0x40, 0x44, 0xB8, 0xC0, 0xC4]        # 0, 1, 2, 3, -1, -2, -3
+    host, dev = raw_problem(rng, [129, 1, 62], 256, 384, DEV, byte_choices=small, scale_pow2=True)
+    ref = orc.grouped_gemm(*host)
+    for v in variants_for(256):
+        got = run_gpu(dev, 192, 256, v)
+        assert np.array_equal(got, ref["C"]), f"variant {v}"
+    # (c) subnormal codes only on the A side, B = +-1: products are exact multiples of 2^-9
+    sub = [0x01, 0x02, 0x03, 0x04, 0x05, 0x06, 0x07, 0x81, 0x83, 0x87]
+    host, dev = raw_problem(rng, [40, 90], 256, 256, DEV, byte_choices=sub, scale_pow2=True)
+    Bh = np.where(rng.integers(0, 2, host[2].shape) == 1, 0x38, 0xB8).astype(np.uint8)
+    host = (host[0], host[1], Bh, host[3], host[4])
+    dev = (dev[0], dev[1], torch.from_numpy(Bh).to(DEV), dev[3], dev[4])
+    ref = orc.grouped_gemm(*host)
+    got = run_gpu(dev, 130, 256)
+    assert np.array_equal(got, ref["C"])
+
+
+def test_group_permutation_permutes_row_blocks_bitwise():
+    cfg = WorkloadConfig("perm", 51, 4, 512, 256, 0, "custom", "latency")
+    sizes = np.array([150, 0, 31, 260])
+    p = make_problem(cfg, sizes=sizes)
+    dev = tuple(p[k].to(DEV) for k in ("A", "SA", "B", "SB", "group_offsets"))
+    base = run_gpu(dev, p["M_total"], 256)
+    perm = [3, 1, 0, 2]
+    off = p["group_offsets"].numpy()
+    rows = np.concatenate([np.arange(off[g], off[g + 1]) for g in perm])
+    A_p, SA_p = p["A"][rows], p["SA"][rows]
+    off_p = np.concatenate([[0], np.cumsum(sizes[perm])]).astype(np.int32)
+    dev_p = (A_p.to(DEV), SA_p.to(DEV), p["B"][perm].to(DEV), p["SB"][perm].to(DEV), torch.from_numpy(off_p).to(DEV))
+    got = run_gpu(dev_p, p["M_total"], 256)
+    assert np.array_equal(got, base[rows])
+
+
+def test_nan_stays_in_its_row_and_column():
+    rng = np.random.default_rng(63)
+    host, dev = raw_problem(rng, [20, 30], 256, 256, DEV)
+    A, SA, B, SB, off = host
+    A[7, 200] = 0x7F
+    B[1, 100, 3] = 0xFF
+    ref = orc.grouped_gemm(A, SA, B, SB, off, with_abs_sum=True)
+    dev = tuple(torch.from_numpy(x).to(DEV) for x in (A, SA, B, SB, off))
+    got = run_gpu(dev, 50, 256)
+    assert_parity(got, ref, empirical=False, what="nan")     # checks the NaN pattern too
+
+
+def test_untrusted_offsets_never_write_outside_C():
+    # decreasing and out-of-range offsets: results are unspecified, but nothing outside C[0:M] is written
+    rng = np.random.default_rng(64)
+    host, dev = raw_problem(rng, [100, 100, 100], 256, 256, DEV)
+    M = 300
+    bad = torch.tensor([-5, 250, 120, 100000], dtype=torch.int32, device=DEV)
+    assert gg.check_offsets(bad, M) == 6          # GG_ERR_OFFSETS
+    assert gg.check_offsets(dev[4], M) == 0
+    for v in variants_for(256):
+        guard = 300
+        buf = torch.full(((M + 2 * guard), 256), CANARY, dtype=torch.int16, device=DEV)
+        C = buf[guard:guard + M].view(torch.bfloat16)
+        gg.grouped_gemm(dev[0], dev[1], dev[2], dev[3], bad, C=C, variant=v)
+        torch.cuda.synchronize()
+        allb = buf.cpu().numpy().view(np.uint16)
+        assert np.all(allb[:guard] == CANARY) and np.all(allb[guard + M:] == CANARY)
+
+
+# ---------------------------------------------------------------------------------------------- pad path
+@pytest.mark.parametrize("sizes,N,K", [
+    ([130, 0, 1, 128, 253, 127], 256, 256),
+    ([5, 300, 64], 256, 512),
+])
+def test_pad_path_equals_padding_free_path_bitwise(sizes, N, K):
+    cfg = WorkloadConfig("pad", 52, len(sizes), K, N, 0, "custom", "latency")
+    p = make_problem(cfg, sizes=np.array(sizes))
+    A_h, SA_h, B_h, SB_h, off_h = np_problem(p)
+    A, SA, B, SB, off = (p[k].to(DEV) for k in ("A", "SA", "B", "SB", "group_offsets"))
+    M = p["M_total"]
+    cap = gg.padded_rows_cap(len(sizes), M)
+    assert cap == 128 * (-(-M // 128) + len(sizes))
+    A_pad, SA_pad, poff = gg.pad(A, SA, off)
+    torch.cuda.synchronize()
+    # pad kernel against the oracle's pad (bytes, scales and offsets exactly)
+    A_ref, SA_ref, poff_ref = orc.pad(A_h, SA_h, off_h, rows_cap=cap)
+    assert np.array_equal(poff.cpu().numpy(), poff_ref.astype(np.int32))
+    assert np.array_equal(A_pad.cpu().numpy(), A_ref)
+    assert np.array_equal(SA_pad.cpu().numpy(), SA_ref)
+    # padded GEMM + unpad against the padding-free GEMM: bitwise equal on valid rows (Sec. 3.2)
+    C_pad = gg.grouped_gemm_padded(A_pad, SA_pad, B, SB, poff)
+    C2 = gg.unpad(C_pad, off, poff, M)
+    C1 = gg.grouped_gemm(A, SA, B, SB, off)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(C1), bits_of(C2))
+    # pad rows inside the padded groups are zeros (zero A rows, zero scales)
+    cp = bits_of(C_pad)
+    valid = np.zeros(cap, bool)
+    for g in range(len(sizes)):
+        valid[poff_ref[g]:poff_ref[g] + sizes[g]] = True
+    inside = np.arange(cap) < poff_ref[-1]
+    assert not (cp[inside & ~valid] & 0x7FFF).any()
+    # and the oracle agrees with both
+    ref = orc.grouped_gemm(A_h, SA_h, B_h, SB_h, off_h, with_abs_sum=True)
+    assert_parity(bits_of(C1), ref, what="pad-free")
+
+
+# ---------------------------------------------------------------------------------------------- full sizes
+def sampled_rows(off, rng, every=97, max_groups=None):
+    """First row, last two rows of (a subset of) the groups plus every `every`-th row."""
+    G = len(off) - 1
+    groups = np.arange(G)
+    if max_groups is not None and G > max_groups:
+        groups = np.sort(rng.choice(G, size=max_groups, replace=False))
+    rows = []
+    for g in groups:
+        n = off[g + 1] - off[g]
+        if n > 0:
+            rows += [off[g], off[g + 1] - 1, max(off[g], off[g + 1] - 2)]
+            rows += list(range(off[g], off[g + 1], every))
+    return np.unique(np.array(rows, dtype=np.int64))
+
+
+@pytest.mark.parametrize("name,max_groups,every", [
+    ("gate_up", None, 61),
+    ("down", None, 127),
+    ("decode", None, 7),
+    ("many_small", 24, 29),
+])
+def test_full_size_configs_sampled_rows(name, max_groups, every):
+    """BASELINE configs at full size, default launch configuration (what bench.py times)."""
+    cfg = CONFIGS[name]
+    p = make_problem(cfg, device=DEV)
+    off = p["group_offsets"].cpu().numpy()
+    assert np.array_equal(np.diff(off), group_sizes(cfg))
+    C = canary_C(p["M_total"], cfg.N)
+    gg.grouped_gemm(p["A"], p["SA"], p["B"], p["SB"], p["group_offsets"], C=C)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(cfg.seed)
+    rows = sampled_rows(off, rng, every=every, max_groups=max_groups)
+    # the oracle only needs the sampled rows of A/SA and the groups they fall in
+    grp = np.searchsorted(off, rows, side="right") - 1
+    used = np.unique(grp)
+    A_s = p["A"][torch.from_numpy(rows).to(DEV)].cpu().numpy()
+    SA_s = p["SA"][torch.from_numpy(rows).to(DEV)].cpu().numpy()
+    B_s = p["B"][torch.from_numpy(used).to(DEV)].cpu().numpy()
+    SB_s = p["SB"][torch.from_numpy(used).to(DEV)].cpu().numpy()
+    counts = np.array([(grp == g).sum() for g in used])
+    off_s = np.concatenate([[0], np.cumsum(counts)])
+    ref = orc.grouped_gemm(A_s, SA_s, B_s, SB_s, off_s, with_abs_sum=True)
+    got = bits_of(C[torch.from_numpy(rows).to(DEV)])
+    stats = assert_parity(got, ref, what=name)
+    print(f"\n{name}: {len(rows)} sampled rows x {cfg.N}: {stats}")
+    # property that holds at any size: every row of every group was written (no canary left)
+    written = (C.view(torch.int16) != CANARY).any(dim=1).cpu().numpy()
+    assert written.all()
