@@ -25,7 +25,20 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 namespace gg {
+
+// compile-time loop: f(std::integral_constant<int, I>{}) for I in [B, E)
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(std::integral_constant<int, B>{});
+    static_for<B + 1, E>(f);
+  }
+}
+
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -36,6 +49,12 @@ typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 #define GG_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 // dword 3 of a raw buffer descriptor on gfx9-family parts: 32-bit data format, no swizzle
 #define GG_RSRC_FLAGS 0x00020000
+
+#ifdef GG_TRACE
+#define GG_TS(slot) do { if (blockIdx.x == GG_TRACE_WG && it < 2 && kb < 64) { long long t_ = __builtin_readcyclecounter(); if (l == 0) a.trace[(((it * 64) + kb) * 8 + w) * 8 + (slot)] = t_; } } while (0)
+#else
+#define GG_TS(slot) do { } while (0)
+#endif
 
 struct GemmArgs {
   const uint8_t* A;
@@ -50,9 +69,12 @@ struct GemmArgs {
   int n_tiles;   // N / BN
   int n_chunk;   // n-tiles that are walked together before moving to the next m-tile
   int slots;     // workgroups per XCD when the grid is a multiple of 8, else 0 (plain round-robin)
+#ifdef GG_TRACE
+  long long* trace;
+#endif
 };
 
-template <int BM_, int BN_, int WM_, int WN_, int STAGES_>
+template <int BM_, int BN_, int WM_, int WN_, int STAGES_, bool XPF_ = false>
 struct GemmCfg {
   static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, STAGES = STAGES_;
   static constexpr int NW = WM * WN;          // waves per workgroup
@@ -71,6 +93,9 @@ struct GemmCfg {
   static constexpr int MFMAS = (BM / WM / 16) * (BN / WN / 16);   // MFMAs per wave per K block
   static constexpr int PIPE = MFMAS < 3 ? MFMAS : 3;               // MFMAs in flight before their FMAs are issued
   static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+  // cross-block operand prefetch with a mid-stream barrier (see the kernel): needs a ring of 3 and an even TM
+  static constexpr bool XPF = XPF_;
+  static_assert(!XPF_ || (STAGES_ >= 3 && (BM_ / WM_ / 16) % 2 == 0), "XPF needs a ring of 3 buffers and an even TM");
   static constexpr int A_SLABS = BM / 8;      // one slab = 8 rows x 128 B = one wave-wide DMA
   static constexpr int B_SLABS = BN / 8;
   static constexpr int A_ITERS = (A_SLABS + NW - 1) / NW;
@@ -83,6 +108,50 @@ struct GemmCfg {
 };
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+// s_waitcnt vmcnt(N): at most N of this wave's vector-memory operations may still be in flight
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// Waits until all but the newest `younger` groups of PER operations have completed (younger <= MAXY).
+template <int PER, int MAXY>
+__device__ __forceinline__ void wait_all_but_n(int younger) {
+  if constexpr (MAXY <= 0) {
+    wait_vmcnt<0>();
+  } else {
+    if (younger >= MAXY) wait_vmcnt<MAXY * PER>();
+    else wait_all_but_n<PER, MAXY - 1>(younger);
+  }
+}
+// The same with PER = BASE + extra, extra in [0, 3] known only at run time (wave-uniform).
+template <int BASE, int MAXY>
+__device__ __forceinline__ void wait_all_but(int younger, int extra) {
+  if constexpr (MAXY <= 0) {
+    wait_vmcnt<0>();
+  } else {
+    if (extra == 0) wait_all_but_n<BASE, MAXY>(younger);
+    else if (extra == 1) wait_all_but_n<BASE + 1, MAXY>(younger);
+    else if (extra == 2) wait_all_but_n<BASE + 2, MAXY>(younger);
+    else wait_all_but_n<BASE + 3, MAXY>(younger);
+  }
+}
+
+// XOR keys of the LDS swizzle: 16-byte chunk c of tile row `row` is stored at chunk position c ^ key(row).
+// ds_read_b128 serves 16 lanes per cycle, and on gfx950 those are not 16 consecutive lanes: of every 32
+// lanes, the quads {0,3,5,6} go together and the quads {1,2,4,7} go together (measured with two-lane
+// probes and SQ_LDS_BANK_CONFLICT).  With MFMA operand lanes (r = lane % 16, q = lane / 16) reading chunks
+// 2q and 2q+1 of row f(r), a cycle therefore sees every r once, with q advanced by one for r in 4..11.
+// The keys below make the 16 lanes of each such cycle hit 16 different 16-byte bank groups.
+__device__ __forceinline__ int swz_key_a(int row) {   // rows read: base + r
+  const int u = (row >> 1) & 7;
+  return u ^ ((((u >> 1) ^ (u >> 2)) & 1) << 1);
+}
+__device__ __forceinline__ int swz_key_b(int row) {   // rows read: base + 8*(r/4) + r%4
+  const int b1 = (row >> 1) & 1, b4 = (row >> 4) & 1;
+  return b1 | (b4 << 1) | (b4 << 2);
+}
 
 template <class Cfg>
 __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
@@ -102,18 +171,23 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
   // The logical chunk it must fetch is physical ^ key(row).
   const int lrow = l >> 3, pch = l & 7;
   const int a_row = w * 8 + lrow;                                   // + i*NW*8
-  const int keyA_ld = ((a_row >> 1) & 7);
+  const int keyA_ld = swz_key_a(a_row);
   const int b_row = w * 8 + lrow;
-  const int keyB_ld = ((b_row >> 1) & 1) | (((b_row >> 3) & 3) << 1);
+  const int keyB_ld = swz_key_b(b_row);
   const int vA = a_row * K + ((pch ^ keyA_ld) << 4);
   const int vB = b_row * K + ((pch ^ keyB_ld) << 4);
   const int vSA = (w * 64 + l) * KB * 4;
   const int vSB = (l < BN / 128 ? l : BN / 128 - 1) * KB * 4;        // lane -> which 128-wide N block of the tile
 
+  // DMAs this wave issues per K block = A_SLABS/NW + B_SLABS/NW + dma_extra (slab remainders, scale fetches)
+  static_assert(Cfg::SA_WAVES <= Cfg::SB_WAVE, "scale fetchers must be distinct waves");
+  static_assert((Cfg::A_SLABS % NW != 0) + (Cfg::B_SLABS % NW != 0) + 1 <= 3, "extra DMA count out of range");
+  const int dma_extra = (w < Cfg::A_SLABS % NW) + (w < Cfg::B_SLABS % NW) + ((w < Cfg::SA_WAVES) || (w == Cfg::SB_WAVE));
+
   // ---- per-lane constants of the LDS operand reads --------------------------------------------
-  const int keyA_rd = (r >> 1) & 7;
+  const int keyA_rd = swz_key_a(r);
   const int rowB_rd = 8 * (r >> 2) + (r & 3);
-  const int keyB_rd = ((r >> 1) & 1) | ((r >> 2) << 1);
+  const int keyB_rd = swz_key_b(rowB_rd);
   const int aRd0 = (wm * WTM + r) * 128 + (((2 * q) ^ keyA_rd) << 4);
   const int aRd1 = (wm * WTM + r) * 128 + (((2 * q + 1) ^ keyA_rd) << 4);
   const int bRd0 = Cfg::A_BYTES + (wn * WTN + rowB_rd) * 128 + (((2 * q) ^ keyB_rd) << 4);
@@ -164,24 +238,43 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
     __amdgpu_buffer_rsrc_t dC = __builtin_amdgcn_make_buffer_rsrc((void*)(a.C + grow * N + n0), 0, rows_valid * N * 2 - n0 * 2, GG_RSRC_FLAGS);
     __amdgpu_buffer_rsrc_t dSB = __builtin_amdgcn_make_buffer_rsrc((void*)(a.SB + ((int64_t)g * (N >> 7) + (n0 >> 7)) * KB), 0, (BN / 128) * KB * 4, GG_RSRC_FLAGS);
 
-    auto issue_loads = [&](int kb, int stage) {
+    // ---- global -> LDS DMA of one K block, split so that it can be fed into the MFMA stream --------
+    // A wave that issues its 8-9 DMAs back to back sits in the issue stage until the CU's vector-memory
+    // front end has taken them all (about a thousand cycles when all 8 waves do it at once), so the
+    // tile DMAs that every wave issues are spread over the MFMA stream, one per few MFMAs; the ones
+    // only some waves issue (slab remainders, scales) would need a branch and go before the stream.
+    constexpr int A_FULL = Cfg::A_SLABS / NW, B_FULL = Cfg::B_SLABS / NW;
+    constexpr int NDMA_ALL = A_FULL + B_FULL;                                  // issued by every wave
+    constexpr int NDMA_STREAM = NDMA_ALL < Cfg::MFMAS ? NDMA_ALL : Cfg::MFMAS;  // of those, inside the stream
+    constexpr int DMA_GAP = Cfg::MFMAS / (NDMA_STREAM > 0 ? NDMA_STREAM : 1);
+    auto dma_tile = [&](auto idx_c, int kb, int stage) {
+      constexpr int idx = decltype(idx_c)::value;
       uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
-#pragma unroll
-      for (int i = 0; i < Cfg::A_ITERS; ++i) {
-        const int sl = w + i * NW;
-        if (Cfg::A_SLABS % NW == 0 || sl < Cfg::A_SLABS)
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(dA, GG_LDS_PTR(st + sl * 1024), 16, vA + i * (NW * 8) * K, kb * 128, 0, 0);
+      if constexpr (idx < A_FULL) {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(dA, GG_LDS_PTR(st + (w + idx * NW) * 1024), 16, vA + idx * (NW * 8) * K, kb * 128, 0, 0);
+      } else {
+        constexpr int i = idx - A_FULL;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(st + Cfg::A_BYTES + (w + i * NW) * 1024), 16, vB, i * (NW * 8) * K + kb * 128, 0, 0);
       }
-#pragma unroll
-      for (int i = 0; i < Cfg::B_ITERS; ++i) {
-        const int sl = w + i * NW;
-        if (Cfg::B_SLABS % NW == 0 || sl < Cfg::B_SLABS)
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(st + Cfg::A_BYTES + sl * 1024), 16, vB, i * (NW * 8) * K + kb * 128, 0, 0);
-      }
+    };
+    auto dma_head = [&](int kb, int stage) {   // everything that is not issued inside the stream
+      uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
       if (w < Cfg::SA_WAVES)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(dSA, GG_LDS_PTR(st + Cfg::A_BYTES + Cfg::B_BYTES + w * 256), 4, vSA, kb * 4, 0, 0);
       if (w == Cfg::SB_WAVE)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(dSB, GG_LDS_PTR(st + Cfg::A_BYTES + Cfg::B_BYTES + Cfg::SA_BYTES), 4, vSB, kb * 4, 0, 0);
+      if constexpr (Cfg::A_SLABS % NW != 0) {
+        if (w < Cfg::A_SLABS % NW)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(dA, GG_LDS_PTR(st + (w + A_FULL * NW) * 1024), 16, vA + A_FULL * (NW * 8) * K, kb * 128, 0, 0);
+      }
+      if constexpr (Cfg::B_SLABS % NW != 0) {
+        if (w < Cfg::B_SLABS % NW)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(st + Cfg::A_BYTES + (w + B_FULL * NW) * 1024), 16, vB, B_FULL * (NW * 8) * K + kb * 128, 0, 0);
+      }
+    };
+    auto dma_all = [&](int kb, int stage) {
+      dma_head(kb, stage);
+      static_for<0, NDMA_ALL>([&](auto ic) { dma_tile(ic, kb, stage); });
     };
 
     v4f acc[TM][TN];
@@ -190,64 +283,228 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
 #pragma unroll
       for (int j = 0; j < TN; ++j) acc[mt][j] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-#pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
-      if (s < KB) issue_loads(s, s);
-    for (int kb = 0; kb < KB; ++kb) {
-      const int stage = kb % STAGES;
-      // the DMA of this K block (issued STAGES-1 iterations ago by every wave) must have landed ...
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      // ... in every wave, and every wave must be done with the buffer that is refilled next
-      __syncthreads();
-      if (kb + STAGES - 1 < KB) issue_loads(kb + STAGES - 1, (kb + STAGES - 1) % STAGES);
+    auto read_b = [&](int j, const uint8_t* st) -> v8i {
+      const int o = (32 * (j >> 1) + 4 * (j & 1)) * 128;
+      const v4i lo = *(const v4i*)(st + bRd0 + o);
+      const v4i hi = *(const v4i*)(st + bRd1 + o);
+      return (v8i){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    };
+    auto read_a = [&](int mt, const uint8_t* st) -> v8i {
+      const v4i lo = *(const v4i*)(st + aRd0 + mt * 2048);
+      const v4i hi = *(const v4i*)(st + aRd1 + mt * 2048);
+      return (v8i){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    };
 
-      const uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
-      const float sb = *(const float*)(st + sbRd);
-      v8i bfr[TN];
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int o = (32 * (j >> 1) + 4 * (j & 1)) * 128;
-        const v4i lo = *(const v4i*)(st + bRd0 + o);
-        const v4i hi = *(const v4i*)(st + bRd1 + o);
-        bfr[j] = (v8i){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-      }
-      float s[TM];
-#pragma unroll
-      for (int mt = 0; mt < TM; ++mt) s[mt] = *(const float*)(st + saRd + mt * 64) * sb;
+    if constexpr (Cfg::XPF) {
+      // ======== ring of >= 3 buffers: no barrier at the K-block boundary ==================================
+      // The barrier that publishes block kb+1 sits in the MIDDLE of the MFMA stream of block kb, and the
+      // operand registers of block kb+1 are refilled during the last activation block of block kb, each
+      // right after its last use.  A wave that waits at the barrier has its MFMAs in flight and the other
+      // wave of its SIMD keeps issuing, so the matrix pipe does not drain at block boundaries.
+      //   WAR: the DMA of block kb+STAGES-1 is issued after the mid barrier of block kb, when every wave has
+      //        finished its reads of block kb-1, whose buffer it refills.
+      //   RAW: block kb+1 was DMA'd at least one block earlier; every wave waits for its own DMAs before the
+      //        mid barrier of block kb, and block kb+1 is first read after it.
+      constexpr int HALF = TN;                                           // MFMAs before the mid barrier
+      constexpr int NDMA_X = NDMA_ALL < Cfg::MFMAS - HALF ? NDMA_ALL : Cfg::MFMAS - HALF;   // DMAs inside the stream
+      constexpr int GAP_X = (Cfg::MFMAS - HALF) / (NDMA_X > 0 ? NDMA_X : 1);
+      static_assert(TM % 2 == 0 && TM >= 2, "operand double buffer needs an even number of activation blocks");
 
-      // software pipeline: MFMA t is issued PIPE steps before the 4 FMAs that consume it, and the
-      // operand reads of the next activation block are issued one block ahead
-      v8i afr[2];
+#pragma unroll
+      for (int s = 0; s < STAGES - 1; ++s)
+        if (s < KB) dma_all(s, s);
+      wait_vmcnt<0>();                 // first block landed (and the previous tile's stores are done)
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      v8i bfr[TN], afr[2];
+      float sa_c, sb_c;
       {
-        const v4i lo = *(const v4i*)(st + aRd0);
-        const v4i hi = *(const v4i*)(st + aRd1);
-        afr[0] = (v8i){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-      }
-      v4f p[Cfg::MFMAS];
+        const uint8_t* st = lds;
 #pragma unroll
-      for (int t = 0; t < Cfg::MFMAS + Cfg::PIPE; ++t) {
-        if (t < Cfg::MFMAS) {
-          const int mt = t / TN, j = t % TN;
-          if (j == 0 && mt + 1 < TM) {
-            const v4i lo = *(const v4i*)(st + aRd0 + (mt + 1) * 2048);
-            const v4i hi = *(const v4i*)(st + aRd1 + (mt + 1) * 2048);
-            afr[(mt + 1) & 1] = (v8i){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        for (int j = 0; j < TN; ++j) bfr[j] = read_b(j, st);
+        afr[0] = read_a(0, st);
+        sa_c = *(const float*)(st + saRd);
+        sb_c = *(const float*)(st + sbRd);
+      }
+
+      int stage = 0;
+      auto kstep_x = [&](int kb, auto issue_c, auto last_c) {
+        constexpr bool ISSUE = decltype(issue_c)::value, LAST = decltype(last_c)::value;
+        const int stage1 = stage + 1 == STAGES ? 0 : stage + 1;                   // buffer of block kb+1
+        const int stageN = stage == 0 ? STAGES - 1 : stage - 1;                   // buffer of block kb+STAGES-1
+        const uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
+        const uint8_t* st1 = lds + stage1 * Cfg::STAGE_BYTES;
+        float s[TM];
+        s[0] = sa_c * sb_c;
+        float sa_n = 0.f, sb_n = 0.f;
+        v4f p[Cfg::MFMAS];
+
+        auto body = [&](auto tc) {
+          constexpr int t = decltype(tc)::value;
+          if constexpr (t < Cfg::MFMAS) {
+            constexpr int mt = t / TN, j = t % TN;
+            if constexpr (j == 0 && mt + 1 < TM) {
+              afr[(mt + 1) & 1] = read_a(mt + 1, st);
+              s[mt + 1] = *(const float*)(st + saRd + (mt + 1) * 64) * sb_c;
+            }
+            if constexpr (j == 0 && mt + 1 == TM && !LAST) {
+              afr[0] = read_a(0, st1);                      // TM is even: slot 0 is free during the last block
+              sa_n = *(const float*)(st1 + saRd);
+              sb_n = *(const float*)(st1 + sbRd);
+            }
+            p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[j], afr[mt & 1], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+            if constexpr (mt + 1 == TM && !LAST) bfr[j] = read_b(j, st1);   // last use of bfr[j] was the MFMA above
+            if constexpr (ISSUE && t >= HALF && NDMA_X > 0 && (t - HALF + 1) % GAP_X == 0 && (t - HALF + 1) / GAP_X <= NDMA_X)
+              dma_tile(std::integral_constant<int, (t - HALF + 1) / GAP_X - 1>{}, kb + STAGES - 1, stageN);
           }
-          p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[j], afr[mt & 1], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+          if constexpr (t >= Cfg::PIPE) {
+            constexpr int u = t - Cfg::PIPE;
+            acc[u / TN][u % TN] += p[u] * s[u / TN];
+          }
+        };
+        auto order = [&](auto tc) {      // the issue order of the instructions `body` creates for step t
+          constexpr int t = decltype(tc)::value;
+          if constexpr (t < Cfg::MFMAS) {
+            constexpr int mt = t / TN, j = t % TN;
+            if constexpr (j == 0 && mt + 1 < TM) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+            if constexpr (j == 0 && mt + 1 == TM && !LAST) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if constexpr (mt + 1 == TM && !LAST) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            if constexpr (ISSUE && t >= HALF && NDMA_X > 0 && (t - HALF + 1) % GAP_X == 0 && (t - HALF + 1) / GAP_X <= NDMA_X)
+              __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            if constexpr (j == 1 || (TN == 1)) __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);   // the scale product of the next block
+          }
+          if constexpr (t >= Cfg::PIPE) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+        };
+
+        static_for<0, HALF>(body);
+        static_for<0, HALF>(order);
+        // ---- mid barrier: block kb+1 becomes readable, the buffer of block kb-1 becomes writable ----------
+        {
+          int younger = KB - 2 - kb;
+          younger = younger < STAGES - 3 ? younger : STAGES - 3;
+          if (younger < 0) younger = 0;
+          wait_all_but<NDMA_ALL, STAGES - 3>(younger, dma_extra);
         }
-        if (t >= Cfg::PIPE) {
-          const int u = t - Cfg::PIPE;
-          acc[u / TN][u % TN] += p[u] * s[u / TN];
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if constexpr (ISSUE) {
+          dma_head(kb + STAGES - 1, stageN);
+          static_for<NDMA_X, NDMA_ALL>([&](auto ic) { dma_tile(ic, kb + STAGES - 1, stageN); });
         }
-      }
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<HALF, Cfg::MFMAS + Cfg::PIPE>(body);
+        static_for<HALF, Cfg::MFMAS + Cfg::PIPE>(order);
+        __builtin_amdgcn_sched_barrier(0);
+        sa_c = sa_n;
+        sb_c = sb_n;
+        stage = stage1;
+      };
+
+      const int kb_issue_end = KB - (STAGES - 1) > 0 ? KB - (STAGES - 1) : 0;
+      int kb = 0;
+      for (; kb < kb_issue_end; ++kb) kstep_x(kb, std::true_type{}, std::false_type{});
+      for (; kb < KB - 1; ++kb) kstep_x(kb, std::false_type{}, std::false_type{});
+      kstep_x(kb, std::false_type{}, std::true_type{});
+    } else {
+      // ======== ring of 2 buffers (or odd TM): one barrier per K block, at the block boundary ============
 #pragma unroll
-      for (int t = 0; t < Cfg::MFMAS + Cfg::PIPE; ++t) {
-        if (t < Cfg::MFMAS) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // 1 MFMA
-          if (t % TN == 0 && t / TN + 1 < TM) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // 2 DS reads
+      for (int s = 0; s < STAGES - 1; ++s)
+        if (s < KB) dma_all(s, s);
+
+      // One K block.  ISSUE: the DMA of block kb + STAGES - 1 is issued during this block.
+      auto kstep = [&](int kb, auto issue_c) {
+        constexpr bool ISSUE = decltype(issue_c)::value;
+        const int stage = kb % STAGES;
+        const int nstage = (kb + STAGES - 1) % STAGES;
+        GG_TS(0);
+        // The DMA of this K block (issued STAGES-1 blocks ago by every wave) must have landed; the newer
+        // blocks may stay in flight.  Loads complete in order, but stores do not order with loads, so
+        // the first block of a tile drains everything (the previous tile's epilogue stores too).
+        {
+          int younger = KB - 1 - kb;
+          younger = younger < STAGES - 2 ? younger : STAGES - 2;
+          if (kb == 0) younger = 0;
+          wait_all_but<NDMA_ALL, STAGES - 2>(younger, dma_extra);
         }
-        if (t >= Cfg::PIPE) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);    // 4 VALU
-      }
+        // ... in every wave, and every wave must be done with the buffer that is refilled next.  A bare
+        // s_barrier: __syncthreads() would add a fence that drains every DMA in flight (vmcnt(0)) and
+        // with it the whole point of the ring.  Visibility is by construction: each wave has waited for
+        // its own DMAs above, and its LDS reads of the previous block were consumed by MFMAs already.
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");   // no LDS access may be moved above the barrier by the compiler
+        GG_TS(1);
+
+        // operand reads that the first MFMAs need go first, then the DMAs that cannot ride in the stream
+        const uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
+        v8i bfr[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int o = (32 * (j >> 1) + 4 * (j & 1)) * 128;
+          const v4i lo = *(const v4i*)(st + bRd0 + o);
+          const v4i hi = *(const v4i*)(st + bRd1 + o);
+          bfr[j] = (v8i){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        }
+        v8i afr[2];
+        {
+          const v4i lo = *(const v4i*)(st + aRd0);
+          const v4i hi = *(const v4i*)(st + aRd1);
+          afr[0] = (v8i){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        }
+        const float sb = *(const float*)(st + sbRd);
+        float s[TM];
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt) s[mt] = *(const float*)(st + saRd + mt * 64) * sb;
+        if constexpr (ISSUE) {
+          dma_head(kb + STAGES - 1, nstage);
+          static_for<NDMA_STREAM, NDMA_ALL>([&](auto ic) { dma_tile(ic, kb + STAGES - 1, nstage); });
+        }
+        GG_TS(2);
+        __builtin_amdgcn_sched_barrier(0);   // everything above stays above; the stream below is ordered by hand
+#ifdef GG_TRACE
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        GG_TS(3);
+#endif
+
+        // software pipeline: MFMA t is issued PIPE steps before the 4 FMAs that consume it, the operand
+        // reads of the next activation block are issued one block ahead, one DMA every DMA_GAP MFMAs
+        v4f p[Cfg::MFMAS];
+        static_for<0, Cfg::MFMAS + Cfg::PIPE>([&](auto tc) {
+          constexpr int t = decltype(tc)::value;
+          if constexpr (t < Cfg::MFMAS) {
+            constexpr int mt = t / TN, j = t % TN;
+            if constexpr (j == 0 && mt + 1 < TM) {
+              const v4i lo = *(const v4i*)(st + aRd0 + (mt + 1) * 2048);
+              const v4i hi = *(const v4i*)(st + aRd1 + (mt + 1) * 2048);
+              afr[(mt + 1) & 1] = (v8i){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            }
+            p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[j], afr[mt & 1], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+            if constexpr (ISSUE && NDMA_STREAM > 0 && (t + 1) % DMA_GAP == 0 && (t + 1) / DMA_GAP <= NDMA_STREAM)
+              dma_tile(std::integral_constant<int, (t + 1) / DMA_GAP - 1>{}, kb + STAGES - 1, nstage);
+          }
+          if constexpr (t >= Cfg::PIPE) {
+            constexpr int u = t - Cfg::PIPE;
+            acc[u / TN][u % TN] += p[u] * s[u / TN];
+          }
+        });
+        static_for<0, Cfg::MFMAS + Cfg::PIPE>([&](auto tc) {
+          constexpr int t = decltype(tc)::value;
+          if constexpr (t < Cfg::MFMAS) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                         // 1 MFMA
+            if constexpr (t % TN == 0 && t / TN + 1 < TM) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // 2 DS reads
+            if constexpr (ISSUE && NDMA_STREAM > 0 && (t + 1) % DMA_GAP == 0 && (t + 1) / DMA_GAP <= NDMA_STREAM)
+              __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                       // 1 DMA
+          }
+          if constexpr (t >= Cfg::PIPE) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);             // 4 VALU
+        });
+        __builtin_amdgcn_sched_barrier(0);
+        GG_TS(4);
+      };
+
+      const int kb_issue_end = KB - (STAGES - 1) > 0 ? KB - (STAGES - 1) : 0;
+      int kb = 0;
+      for (; kb < kb_issue_end; ++kb) kstep(kb, std::true_type{});
+      for (; kb < KB; ++kb) kstep(kb, std::false_type{});
     }
     __syncthreads();  // every wave is done reading LDS before the next tile's prologue overwrites it
 
