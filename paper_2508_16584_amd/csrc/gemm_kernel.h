@@ -50,8 +50,17 @@ typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 // dword 3 of a raw buffer descriptor on gfx9-family parts: 32-bit data format, no swizzle
 #define GG_RSRC_FLAGS 0x00020000
 
+#ifdef GG_NO_DMA
+#define GG_ISSUE(x) false
+#else
+#define GG_ISSUE(x) (x)
+#endif
 #ifdef GG_TRACE
-#define GG_TS(slot) do { if (blockIdx.x == GG_TRACE_WG && it < 2 && kb < 64) { long long t_ = __builtin_readcyclecounter(); if (l == 0) a.trace[(((it * 64) + kb) * 8 + w) * 8 + (slot)] = t_; } } while (0)
+// experiment builds only: cycle-counter samples of workgroup GG_TRACE_WG, kept in the unused tail of LDS
+// (no extra live registers in the hot loop) and copied out at the end of each tile
+#define GG_TS(slot) do { if (blockIdx.x == GG_TRACE_WG && it < 2 && kb < 64) { \
+    unsigned long long t_ = __builtin_readcyclecounter(); \
+    if (l == 0) *(unsigned long long*)(lds + Cfg::LDS_BYTES + ((kb * 8 + w) * 4 + (slot)) * 8) = t_; } } while (0)
 #else
 #define GG_TS(slot) do { } while (0)
 #endif
@@ -74,8 +83,9 @@ struct GemmArgs {
 #endif
 };
 
-template <int BM_, int BN_, int WM_, int WN_, int STAGES_, bool XPF_ = false>
+template <int BM_, int BN_, int WM_, int WN_, int STAGES_, bool XPF_ = false, int GAP_ = 0, int PIPE_ = 3>
 struct GemmCfg {
+  static constexpr int GAP = GAP_;            // MFMAs between two in-stream DMAs (0 = spread over the whole stream)
   static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, STAGES = STAGES_;
   static constexpr int NW = WM * WN;          // waves per workgroup
   static constexpr int NT = 64 * NW;          // threads per workgroup
@@ -91,7 +101,7 @@ struct GemmCfg {
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES + SA_BYTES + SB_BYTES;
   static constexpr int SB_WAVE = NW - 1;      // the wave that fetches them
   static constexpr int MFMAS = (BM / WM / 16) * (BN / WN / 16);   // MFMAs per wave per K block
-  static constexpr int PIPE = MFMAS < 3 ? MFMAS : 3;               // MFMAs in flight before their FMAs are issued
+  static constexpr int PIPE = MFMAS < PIPE_ ? MFMAS : PIPE_;               // MFMAs in flight before their FMAs are issued
   static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
   // cross-block operand prefetch with a mid-stream barrier (see the kernel): needs a ring of 3 and an even TM
   static constexpr bool XPF = XPF_;
@@ -246,7 +256,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
     constexpr int A_FULL = Cfg::A_SLABS / NW, B_FULL = Cfg::B_SLABS / NW;
     constexpr int NDMA_ALL = A_FULL + B_FULL;                                  // issued by every wave
     constexpr int NDMA_STREAM = NDMA_ALL < Cfg::MFMAS ? NDMA_ALL : Cfg::MFMAS;  // of those, inside the stream
-    constexpr int DMA_GAP = Cfg::MFMAS / (NDMA_STREAM > 0 ? NDMA_STREAM : 1);
+    constexpr int DMA_GAP = Cfg::GAP > 0 ? Cfg::GAP : Cfg::MFMAS / (NDMA_STREAM > 0 ? NDMA_STREAM : 1);
     auto dma_tile = [&](auto idx_c, int kb, int stage) {
       constexpr int idx = decltype(idx_c)::value;
       uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
@@ -329,7 +339,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
 
       int stage = 0;
       auto kstep_x = [&](int kb, auto issue_c, auto last_c) {
-        constexpr bool ISSUE = decltype(issue_c)::value, LAST = decltype(last_c)::value;
+        constexpr bool ISSUE = GG_ISSUE(decltype(issue_c)::value), LAST = decltype(last_c)::value;
         const int stage1 = stage + 1 == STAGES ? 0 : stage + 1;                   // buffer of block kb+1
         const int stageN = stage == 0 ? STAGES - 1 : stage - 1;                   // buffer of block kb+STAGES-1
         const uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
@@ -414,7 +424,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
 
       // One K block.  ISSUE: the DMA of block kb + STAGES - 1 is issued during this block.
       auto kstep = [&](int kb, auto issue_c) {
-        constexpr bool ISSUE = decltype(issue_c)::value;
+        constexpr bool ISSUE = GG_ISSUE(decltype(issue_c)::value);
         const int stage = kb % STAGES;
         const int nstage = (kb + STAGES - 1) % STAGES;
         GG_TS(0);
@@ -498,7 +508,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
           if constexpr (t >= Cfg::PIPE) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);             // 4 VALU
         });
         __builtin_amdgcn_sched_barrier(0);
-        GG_TS(4);
+        GG_TS(3);
       };
 
       const int kb_issue_end = KB - (STAGES - 1) > 0 ? KB - (STAGES - 1) : 0;
@@ -507,6 +517,12 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
       for (; kb < KB; ++kb) kstep(kb, std::false_type{});
     }
     __syncthreads();  // every wave is done reading LDS before the next tile's prologue overwrites it
+#ifdef GG_TRACE
+    if (blockIdx.x == GG_TRACE_WG && it < 2) {
+      for (int i = tid; i < 64 * 8 * 4; i += Cfg::NT) a.trace[it * 64 * 8 * 4 + i] = *(long long*)(lds + Cfg::LDS_BYTES + i * 8);
+      __syncthreads();
+    }
+#endif
 
     // ---- epilogue: bf16 RNE, 16-byte bounded stores ---------------------------------------------
 #pragma unroll

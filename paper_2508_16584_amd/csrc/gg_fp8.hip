@@ -57,39 +57,40 @@ hipError_t launch_gemm(const gg::GemmArgs& args, int grid, hipStream_t stream) {
   return hipGetLastError();
 }
 
-#define GG_VARIANT(BM, BN, WM, WN, ST, WGPC)                                                   \
-  {#BM "x" #BN "/" #WM "x" #WN "w/" #ST "s", BM, BN, gg::GemmCfg<BM, BN, WM, WN, ST>::LDS_BYTES, \
-   WGPC, &launch_gemm<gg::GemmCfg<BM, BN, WM, WN, ST>>}
-// the same with the barrier in the middle of the MFMA stream and operand prefetch across K blocks
-#define GG_VARIANT_X(BM, BN, WM, WN, ST, WGPC)                                                        \
-  {#BM "x" #BN "/" #WM "x" #WN "w/" #ST "sx", BM, BN, gg::GemmCfg<BM, BN, WM, WN, ST, true>::LDS_BYTES, \
-   WGPC, &launch_gemm<gg::GemmCfg<BM, BN, WM, WN, ST, true>>}
+// name = "BMxBN/WMxWNw/STAGESs[x]": tile, wave grid, LDS ring depth; x = barrier in the middle of the MFMA
+// stream with operand prefetch across K blocks.  GAP = MFMAs between two DMAs fed into the MFMA stream.
+#define GG_VARIANT(BM, BN, WM, WN, ST, XPF, GAP, WGPC)                                                        \
+  {#BM "x" #BN "/" #WM "x" #WN "w/" #ST "s" XPF_SUFFIX_##XPF, BM, BN, gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>::LDS_BYTES, \
+   WGPC, &launch_gemm<gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>>}
+#define XPF_SUFFIX_false ""
+#define XPF_SUFFIX_true "x"
 
 const Variant kVariants[] = {
-    GG_VARIANT(256, 256, 2, 4, 2, 1),     // 0
-    GG_VARIANT(128, 256, 2, 4, 3, 1),     // 1
-    GG_VARIANT(128, 128, 2, 4, 4, 1),     // 2
-    GG_VARIANT(64, 256, 1, 8, 3, 1),      // 3
-    GG_VARIANT(32, 256, 1, 8, 4, 1),      // 4
-    GG_VARIANT(16, 256, 1, 8, 2, 2),      // 5
-    GG_VARIANT(256, 128, 4, 2, 3, 1),     // 6
-    GG_VARIANT_X(128, 256, 2, 4, 3, 1),   // 7
-    GG_VARIANT_X(128, 128, 2, 4, 4, 1),   // 8
-    GG_VARIANT_X(64, 256, 1, 8, 3, 1),    // 9
-    GG_VARIANT_X(32, 256, 1, 8, 4, 1),    // 10
-    GG_VARIANT_X(256, 128, 4, 2, 3, 1),   // 11
-    GG_VARIANT(128, 128, 2, 4, 2, 2),     // 12
+    GG_VARIANT(256, 256, 2, 4, 2, false, 2, 1),   // 0
+    GG_VARIANT(128, 256, 2, 4, 3, false, 0, 1),   // 1
+    GG_VARIANT(128, 128, 2, 4, 4, false, 0, 1),   // 2
+    GG_VARIANT(64, 256, 1, 8, 3, false, 0, 1),    // 3
+    GG_VARIANT(32, 256, 1, 8, 4, false, 0, 1),    // 4
+    GG_VARIANT(16, 256, 1, 8, 2, false, 0, 2),    // 5
+    GG_VARIANT(256, 128, 4, 2, 3, false, 0, 1),   // 6
+    GG_VARIANT(128, 256, 2, 4, 3, true, 0, 1),    // 7
+    GG_VARIANT(128, 128, 2, 4, 4, true, 0, 1),    // 8
+    GG_VARIANT(32, 256, 1, 8, 4, true, 0, 1),     // 9
+    GG_VARIANT(128, 128, 2, 4, 2, false, 0, 2),   // 10
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
 // Tile shape by the mean number of rows per group (the only size information the host has: the offsets
-// stay on the device).  Measured on MI355X with the five synthetic workloads: 128x256 with a ring of 3 is
-// the best all-rounder; around one 128-row tile per group the taller 256x256 tile wins because it halves
-// the number of tiles that stream a whole B panel.
+// stay on the device).  Chosen from measurements on MI355X with the five synthetic workloads:
+//  * long groups (>= 768 rows): 128x256 tiles with a ring of 3 -- the finer tiles leave a smaller ragged last
+//    round over the 256 CUs than 256x256 tiles do;
+//  * 96..768 rows: 256x256 tiles -- most work per byte moved from L2 to LDS, and around one 128-row tile
+//    per group the taller tile avoids a second, nearly empty m-tile that streams the whole B panel again;
+//  * short groups (< 96 rows, weight-bandwidth bound): 128x256 with a ring of 3, the deepest DMA queue.
 int pick_variant(int G, int64_t M_total, int N) {
   const double avg = G > 0 ? (double)M_total / G : 0.0;
   int v = 1;
-  if (avg >= 96 && avg < 192) v = 0;
+  if (avg >= 96 && avg < 768) v = 0;
   if (N % kVariants[v].BN != 0) v = 2;  // N is a multiple of 128 but not of 256
   return v;
 }
