@@ -27,8 +27,9 @@ FP8_MFMA_PEAK_TFLOPS = 5033.0     # MI355X dense FP8: 256 CU x 8192 flop/clk/CU 
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E
 
 # HBM bytes per launch of the GEMM kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/*.md give the command and the copy-kernel calibration); None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+# (profiles/gg_gemm_kernel_full_size_workloads.md gives the commands and the copy-kernel calibration:
+# FETCH_SIZE counts half of a plain copy's bytes, WRITE_SIZE all of them); None = not measured.
+MEASURED_TRAFFIC_BYTES = {"gate_up": 834995782, "down": 993106147, "decode": 1555338725, "many_small": 8039749494}
 
 
 def algorithmic_bytes(sizes, N, K):
@@ -50,6 +51,8 @@ def main():
     ap.add_argument("--copies", type=int, default=0, help="input copies to rotate over (0 = enough for 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-pad-path", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (groups shard by expert across GPUs with no exchange inside the "
@@ -105,6 +108,14 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     kern_ms = np.array([a.elapsed_time(b) for a, b in ev])
     kern_avg_ms = float(kern_ms.mean())
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # known size: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # hot-cache number (same buffers every step), secondary
     for _ in range(3):
@@ -200,7 +211,7 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import gg_oracle
         off = p["group_offsets"].cpu().numpy()
-        per_group = 192 if cfg.G <= 32 else 16
+        per_group = 2048 if cfg.G <= 32 else 64
         groups = np.arange(G) if G <= 32 else np.arange(0, G, G // 32)
         rows = np.concatenate([np.arange(off[g], min(off[g + 1], off[g] + per_group)) for g in groups]).astype(np.int64)
         grp = np.searchsorted(off, rows, side="right") - 1

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <cstdlib>
 #include <vector>
 
 #include "gemm_kernel.h"
@@ -129,6 +130,10 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
   args.KB = K / 128;
   args.n_tiles = N / v.BN;
   args.n_chunk = args.n_tiles < 8 ? args.n_tiles : 8;
+  if (const char* e = getenv("GG_FP8_N_CHUNK")) {   // benchmarking override
+    const int c = atoi(e);
+    if (c >= 1) args.n_chunk = c < args.n_tiles ? c : args.n_tiles;
+  }
 
   // upper bound on the number of tiles for any offsets: every group adds at most one partial m-tile
   const int64_t max_tiles = (M_total / v.BM + G) * (int64_t)args.n_tiles;
