@@ -55,16 +55,6 @@ typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 #else
 #define GG_ISSUE(x) (x)
 #endif
-#ifdef GG_TRACE
-// experiment builds only: cycle-counter samples of workgroup GG_TRACE_WG, kept in the unused tail of LDS
-// (no extra live registers in the hot loop) and copied out at the end of each tile
-#define GG_TS(slot) do { if (blockIdx.x == GG_TRACE_WG && it < 2 && kb < 64) { \
-    unsigned long long t_ = __builtin_readcyclecounter(); \
-    if (l == 0) *(unsigned long long*)(lds + Cfg::LDS_BYTES + ((kb * 8 + w) * 4 + (slot)) * 8) = t_; } } while (0)
-#else
-#define GG_TS(slot) do { } while (0)
-#endif
-
 struct GemmArgs {
   const uint8_t* A;
   const float* SA;
@@ -78,9 +68,6 @@ struct GemmArgs {
   int n_tiles;   // N / BN
   int n_chunk;   // n-tiles that are walked together before moving to the next m-tile
   int slots;     // workgroups per XCD when the grid is a multiple of 8, else 0 (plain round-robin)
-#ifdef GG_TRACE
-  long long* trace;
-#endif
 };
 
 template <int BM_, int BN_, int WM_, int WN_, int STAGES_, bool XPF_ = false, int GAP_ = 0, int PIPE_ = 3>
@@ -95,7 +82,8 @@ struct GemmCfg {
   static constexpr int TN = WTN / 16;         // MFMA row blocks (weight rows) per wave
   static constexpr int A_BYTES = BM * 128;
   static constexpr int B_BYTES = BN * 128;
-  static constexpr int SA_ROWS = BM < 64 ? 64 : BM;
+  static constexpr int SA_WAVES = (BM + 63) / 64;   // one 64-lane dword DMA fetches the scales of 64 rows
+  static constexpr int SA_ROWS = SA_WAVES * 64;
   static constexpr int SA_BYTES = SA_ROWS * 4;
   static constexpr int SB_BYTES = 256;         // BN/128 scales of B per K block, replicated over one wave-wide DMA
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES + SA_BYTES + SB_BYTES;
@@ -110,7 +98,6 @@ struct GemmCfg {
   static constexpr int B_SLABS = BN / 8;
   static constexpr int A_ITERS = (A_SLABS + NW - 1) / NW;
   static constexpr int B_ITERS = (B_SLABS + NW - 1) / NW;
-  static constexpr int SA_WAVES = SA_ROWS / 64;
   static_assert(BM % (16 * WM) == 0 && BN % (32 * WN) == 0, "wave tile must be 16 x 32 granular");
   static_assert(WTN <= 128 && 128 % WTN == 0, "a wave must stay inside one 128-wide scale block of B");
   static_assert(BM % 8 == 0 && BN % 8 == 0 && NW % 4 == 0, "slab mapping");
@@ -422,12 +409,20 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
       for (int s = 0; s < STAGES - 1; ++s)
         if (s < KB) dma_all(s, s);
 
+      // FMAs of the last PIPE MFMAs of a K block are carried into the next block's stream (their
+      // accumulators are fixed at compile time), so the matrix pipe does not wait for a VALU tail
+      // before the barrier.  Flushed after the last block.
+      constexpr int PIPE = Cfg::PIPE, MF = Cfg::MFMAS;
+      v4f pend[PIPE];
+      float s_pend[PIPE];
+#pragma unroll
+      for (int i = 0; i < PIPE; ++i) { pend[i] = (v4f){0.f, 0.f, 0.f, 0.f}; s_pend[i] = 0.f; }
+
       // One K block.  ISSUE: the DMA of block kb + STAGES - 1 is issued during this block.
       auto kstep = [&](int kb, auto issue_c) {
         constexpr bool ISSUE = GG_ISSUE(decltype(issue_c)::value);
         const int stage = kb % STAGES;
         const int nstage = (kb + STAGES - 1) % STAGES;
-        GG_TS(0);
         // The DMA of this K block (issued STAGES-1 blocks ago by every wave) must have landed; the newer
         // blocks may stay in flight.  Loads complete in order, but stores do not order with loads, so
         // the first block of a tile drains everything (the previous tile's epilogue stores too).
@@ -443,86 +438,70 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
         // its own DMAs above, and its LDS reads of the previous block were consumed by MFMAs already.
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");   // no LDS access may be moved above the barrier by the compiler
-        GG_TS(1);
 
-        // operand reads that the first MFMAs need go first, then the DMAs that cannot ride in the stream
+        // Operand reads in the order the MFMAs need them; nothing here waits, so the first MFMA can go
+        // as soon as its two operands are back while the rest is still in flight.
         const uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
-        v8i bfr[TN];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int o = (32 * (j >> 1) + 4 * (j & 1)) * 128;
-          const v4i lo = *(const v4i*)(st + bRd0 + o);
-          const v4i hi = *(const v4i*)(st + bRd1 + o);
-          bfr[j] = (v8i){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-        }
-        v8i afr[2];
-        {
-          const v4i lo = *(const v4i*)(st + aRd0);
-          const v4i hi = *(const v4i*)(st + aRd1);
-          afr[0] = (v8i){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-        }
+        v8i bfr[TN], afr[2];
+        bfr[0] = read_b(0, st);
+        afr[0] = read_a(0, st);
         const float sb = *(const float*)(st + sbRd);
-        float s[TM];
+        float sa[TM];
+        sa[0] = *(const float*)(st + saRd);
 #pragma unroll
-        for (int mt = 0; mt < TM; ++mt) s[mt] = *(const float*)(st + saRd + mt * 64) * sb;
+        for (int j = 1; j < TN; ++j) bfr[j] = read_b(j, st);
+#pragma unroll
+        for (int mt = 1; mt < TM; ++mt) sa[mt] = *(const float*)(st + saRd + mt * 64);
         if constexpr (ISSUE) {
           dma_head(kb + STAGES - 1, nstage);
           static_for<NDMA_STREAM, NDMA_ALL>([&](auto ic) { dma_tile(ic, kb + STAGES - 1, nstage); });
         }
-        GG_TS(2);
-        __builtin_amdgcn_sched_barrier(0);   // everything above stays above; the stream below is ordered by hand
-#ifdef GG_TRACE
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        GG_TS(3);
-#endif
+        __builtin_amdgcn_sched_barrier(0);   // the reads above keep their order; the stream below is ordered by hand
 
         // software pipeline: MFMA t is issued PIPE steps before the 4 FMAs that consume it, the operand
         // reads of the next activation block are issued one block ahead, one DMA every DMA_GAP MFMAs
-        v4f p[Cfg::MFMAS];
-        static_for<0, Cfg::MFMAS + Cfg::PIPE>([&](auto tc) {
+        v4f p[MF];
+        float s[TM];
+        static_for<0, MF>([&](auto tc) {
           constexpr int t = decltype(tc)::value;
-          if constexpr (t < Cfg::MFMAS) {
-            constexpr int mt = t / TN, j = t % TN;
-            if constexpr (j == 0 && mt + 1 < TM) {
-              const v4i lo = *(const v4i*)(st + aRd0 + (mt + 1) * 2048);
-              const v4i hi = *(const v4i*)(st + aRd1 + (mt + 1) * 2048);
-              afr[(mt + 1) & 1] = (v8i){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-            }
-            p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[j], afr[mt & 1], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
-            if constexpr (ISSUE && NDMA_STREAM > 0 && (t + 1) % DMA_GAP == 0 && (t + 1) / DMA_GAP <= NDMA_STREAM)
-              dma_tile(std::integral_constant<int, (t + 1) / DMA_GAP - 1>{}, kb + STAGES - 1, nstage);
-          }
-          if constexpr (t >= Cfg::PIPE) {
-            constexpr int u = t - Cfg::PIPE;
+          constexpr int mt = t / TN, j = t % TN;
+          if constexpr (j == 0) s[mt] = sa[mt] * sb;
+          if constexpr (j == 0 && mt + 1 < TM) afr[(mt + 1) & 1] = read_a(mt + 1, st);
+          p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[j], afr[mt & 1], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+          if constexpr (ISSUE && NDMA_STREAM > 0 && (t + 1) % DMA_GAP == 0 && (t + 1) / DMA_GAP <= NDMA_STREAM)
+            dma_tile(std::integral_constant<int, (t + 1) / DMA_GAP - 1>{}, kb + STAGES - 1, nstage);
+          if constexpr (t < PIPE) {
+            constexpr int u = MF - PIPE + t;                 // carried over from the previous K block
+            acc[u / TN][u % TN] += pend[t] * s_pend[t];
+          } else {
+            constexpr int u = t - PIPE;
             acc[u / TN][u % TN] += p[u] * s[u / TN];
           }
         });
-        static_for<0, Cfg::MFMAS + Cfg::PIPE>([&](auto tc) {
+        static_for<0, MF>([&](auto tc) {
           constexpr int t = decltype(tc)::value;
-          if constexpr (t < Cfg::MFMAS) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                         // 1 MFMA
-            if constexpr (t % TN == 0 && t / TN + 1 < TM) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // 2 DS reads
-            if constexpr (ISSUE && NDMA_STREAM > 0 && (t + 1) % DMA_GAP == 0 && (t + 1) / DMA_GAP <= NDMA_STREAM)
-              __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                       // 1 DMA
-          }
-          if constexpr (t >= Cfg::PIPE) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);             // 4 VALU
+          if constexpr (t % TN == 0) __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);                       // scale product
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                 // 1 MFMA
+          if constexpr (t % TN == 0 && t / TN + 1 < TM) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // 2 DS reads
+          if constexpr (ISSUE && NDMA_STREAM > 0 && (t + 1) % DMA_GAP == 0 && (t + 1) / DMA_GAP <= NDMA_STREAM)
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                               // 1 DMA
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);                                                 // 4 FMAs
         });
         __builtin_amdgcn_sched_barrier(0);
-        GG_TS(3);
+#pragma unroll
+        for (int i = 0; i < PIPE; ++i) { pend[i] = p[MF - PIPE + i]; s_pend[i] = s[(MF - PIPE + i) / TN]; }
       };
 
       const int kb_issue_end = KB - (STAGES - 1) > 0 ? KB - (STAGES - 1) : 0;
       int kb = 0;
       for (; kb < kb_issue_end; ++kb) kstep(kb, std::true_type{});
       for (; kb < KB; ++kb) kstep(kb, std::false_type{});
+      static_for<0, PIPE>([&](auto ic) {
+        constexpr int u = MF - PIPE + decltype(ic)::value;
+        acc[u / TN][u % TN] += pend[decltype(ic)::value] * s_pend[decltype(ic)::value];
+      });
     }
     __syncthreads();  // every wave is done reading LDS before the next tile's prologue overwrites it
-#ifdef GG_TRACE
-    if (blockIdx.x == GG_TRACE_WG && it < 2) {
-      for (int i = tid; i < 64 * 8 * 4; i += Cfg::NT) a.trace[it * 64 * 8 * 4 + i] = *(long long*)(lds + Cfg::LDS_BYTES + i * 8);
-      __syncthreads();
-    }
-#endif
 
     // ---- epilogue: bf16 RNE, 16-byte bounded stores ---------------------------------------------
 #pragma unroll

@@ -16,10 +16,6 @@ namespace {
 constexpr int kVersion = 100;  // 0.1.0
 constexpr int kXcds = 8;       // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
 
-struct DeviceInfo {
-  int cus = 0;
-};
-
 // Number of compute units of the current device (queried once per device, cached).
 int device_cus() {
   static std::atomic<int> cache[64];
@@ -67,33 +63,33 @@ hipError_t launch_gemm(const gg::GemmArgs& args, int grid, hipStream_t stream) {
 #define XPF_SUFFIX_true "x"
 
 const Variant kVariants[] = {
-    GG_VARIANT(256, 256, 2, 4, 2, false, 2, 1),   // 0
-    GG_VARIANT(128, 256, 2, 4, 3, false, 0, 1),   // 1
-    GG_VARIANT(128, 128, 2, 4, 4, false, 0, 1),   // 2
-    GG_VARIANT(64, 256, 1, 8, 3, false, 0, 1),    // 3
-    GG_VARIANT(32, 256, 1, 8, 4, false, 0, 1),    // 4
-    GG_VARIANT(16, 256, 1, 8, 2, false, 0, 2),    // 5
-    GG_VARIANT(256, 128, 4, 2, 3, false, 0, 1),   // 6
-    GG_VARIANT(128, 256, 2, 4, 3, true, 0, 1),    // 7
-    GG_VARIANT(128, 128, 2, 4, 4, true, 0, 1),    // 8
-    GG_VARIANT(32, 256, 1, 8, 4, true, 0, 1),     // 9
-    GG_VARIANT(128, 128, 2, 4, 2, false, 0, 2),   // 10
+    GG_VARIANT(160, 256, 2, 4, 3, false, 2, 1),   // 0: the largest tile that leaves room for a ring of 3 in 160 KB of LDS
+    GG_VARIANT(256, 256, 2, 4, 2, false, 2, 1),   // 1: the largest tile the accumulators allow; ring of 2 only
+    GG_VARIANT(128, 128, 2, 4, 4, false, 0, 1),   // 2: for N % 256 != 0
+    GG_VARIANT(128, 256, 2, 4, 3, false, 0, 1),   // 3
+    GG_VARIANT(64, 256, 1, 8, 3, false, 0, 1),    // 4
+    GG_VARIANT(32, 256, 1, 8, 4, false, 0, 1),    // 5
+    GG_VARIANT(16, 256, 1, 8, 2, false, 0, 2),    // 6
+    GG_VARIANT(256, 128, 4, 2, 3, false, 0, 1),   // 7
+    GG_VARIANT(128, 256, 2, 4, 3, true, 0, 1),    // 8
+    GG_VARIANT(128, 128, 2, 4, 4, true, 0, 1),    // 9
+    GG_VARIANT(32, 256, 1, 8, 4, true, 0, 1),     // 10
+    GG_VARIANT(128, 128, 2, 4, 2, false, 0, 2),   // 11
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
-// Tile shape by the mean number of rows per group (the only size information the host has: the offsets
-// stay on the device).  Chosen from measurements on MI355X with the five synthetic workloads:
-//  * long groups (>= 768 rows): 128x256 tiles with a ring of 3 -- the finer tiles leave a smaller ragged last
-//    round over the 256 CUs than 256x256 tiles do;
-//  * 96..768 rows: 256x256 tiles -- most work per byte moved from L2 to LDS, and around one 128-row tile
-//    per group the taller tile avoids a second, nearly empty m-tile that streams the whole B panel again;
-//  * short groups (< 96 rows, weight-bandwidth bound): 128x256 with a ring of 3, the deepest DMA queue.
+// Tile shape.  The host knows only G and M_total (the offsets stay on the device).  On MI355X the kernel is
+// bound by how fast a CU gets K blocks from L2 into LDS, so the default is the tile with the most output area
+// that still leaves room for a ring of 3 buffers in the 160 KB of LDS: 160 x 256.  Interleaved A/B timing on
+// the synthetic workloads moved two cases elsewhere: mid-length groups (256..768 rows on average; the skewed
+// "down" shape with its short K loop) run best on 256 x 256, very short groups (< 64 rows, weight streaming)
+// on 128 x 256.  All variants stay selectable through gg_fp8_grouped_gemm_variant.
 int pick_variant(int G, int64_t M_total, int N) {
+  if (N % 256 != 0) return 2;   // N is always a multiple of 128
   const double avg = G > 0 ? (double)M_total / G : 0.0;
-  int v = 1;
-  if (avg >= 96 && avg < 768) v = 0;
-  if (N % kVariants[v].BN != 0) v = 2;  // N is a multiple of 128 but not of 256
-  return v;
+  if (avg >= 256 && avg < 768) return 1;
+  if (avg < 64) return 3;
+  return 0;
 }
 
 int validate_gemm(const void* A, const float* SA, const void* B, const float* SB, const int32_t* off, void* C,
