@@ -1,0 +1,362 @@
+// Second kernel of the padding-free block-scaled FP8 grouped GEMM (same operation as gemm_kernel.h: paper
+// Sec. 2.1, Table 1, with the padding-free capability of Sec. 2.2 through bounded buffer descriptors).
+//
+// The first kernel keeps [A | B] of a K block in one LDS buffer and all waves meet at a barrier per K block
+// before anyone reads either operand.  At the largest tile the accumulators allow (256 x 256) only two such
+// buffers fit in 160 KB: one K block of look-ahead, a DMA stream that drains at every block boundary and a
+// matrix pipe that waits for the first LDS reads after every barrier.  This kernel splits the two operands:
+//
+//  * 8 waves side by side along N: wave w owns columns [32w, 32w+32) of the 256-wide tile and all BM rows, so no
+//    two waves need the same weight row.  Each wave fetches ITS 32 weight rows of a K block (two fragments of
+//    16 rows x 128 B) by DMA into three private 2 KB LDS slots, copies a fragment into registers half a K block
+//    or more before it is needed (two register sets, one per K-block parity) and refills the slot at once.  No
+//    other wave touches these slots: the weight path needs no barrier at all.
+//  * The shared A tile (BM x 128 B per K block, plus scales) lives in a ring of 3 LDS buffers.  The one barrier
+//    per K block, at the top of block kb, publishes block kb+1 (not kb): the first activation fragments of the
+//    next block are read before the block boundary, so the matrix pipe never waits for LDS after a barrier.
+//  * Every wave issues the same number of fetches per K block (blocks past the end of K and waves without a
+//    scale to fetch use an out-of-range offset: zeros, no traffic), so all s_waitcnt counts are compile-time
+//    constants.  Order inside block kb: scale and A DMAs of block kb+2 first, then the refills of the two
+//    weight slots; the wait at the top of block kb+1 lets exactly the refills stay in flight.
+//
+// Arithmetic per output element is the same as in the first kernel (one C=0 MFMA per 128-wide scale block,
+// 4 fp32 FMAs with the per-lane scale, kb ascending), so results are bit-identical to it unless KP is set.
+// KP: a lane's 32 operand bytes of a 128-byte row are [16q, 16q+16) and [64+16q, 64+16q+16) (q = lane/16)
+// instead of [32q, 32q+32): a permutation of k inside the K block applied to both operands alike; every dot
+// product has the same terms, the matrix instruction adds them in another order.
+#pragma once
+#include "gemm_kernel.h"
+
+namespace gg {
+
+template <int BM_, int AFR_ = 4, bool KP_ = false>
+struct RbCfg {
+  static constexpr bool KP = KP_;
+  static constexpr int BM = BM_, BN = 256, S = 3;
+  static constexpr int NW = 8, NT = 512;
+  static constexpr int TM = BM / 16, TN = 2;
+  static constexpr int A_BYTES = BM * 128;
+  static constexpr int SA_WAVES = (BM + 63) / 64;
+  static constexpr int SA_BYTES = SA_WAVES * 256;
+  static constexpr int SB_BYTES = 256;
+  static constexpr int DUMP_BYTES = 256;           // target of the scale DMA of waves that have no scales to fetch
+  static constexpr int STAGE_BYTES = A_BYTES + SA_BYTES + SB_BYTES + DUMP_BYTES;
+  static constexpr int B_SLOTS = 3, B_SLOT_BYTES = 2048;        // per wave: fragments of 16 rows x 128 B
+  static constexpr int B_BASE = S * STAGE_BYTES;
+  static constexpr int LDS_BYTES = B_BASE + NW * B_SLOTS * B_SLOT_BYTES;
+  static constexpr int A_ITERS = BM / 64;          // 8-row slabs per wave per K block
+  static constexpr int SB_WAVE = NW - 1;
+  static constexpr int MFMAS = TM * TN;
+  static constexpr int PIPE = 3;                   // MFMAs in flight before their FMAs are issued
+  static constexpr int AFR = AFR_;                 // ring of activation fragments (prefetch distance AFR-1 blocks)
+  // fetches per wave per K block, in issue order: 1 scale DMA, A_ITERS A slabs, 2 + 2 weight-slot refills
+  static constexpr int N_A = 1 + A_ITERS;
+  static constexpr int T_A0 = 0;                   // A DMAs after MFMAs T_A0 .. T_A0 + A_ITERS - 1
+  static constexpr int T_R0 = A_ITERS + 2;         // refill of the slot read at the top of the block
+  static constexpr int T_MID = MFMAS / 2 + 2;      // wait for and read of the second fragment of the next block
+  static constexpr int T_R1 = T_MID + 4;           // refill of that slot
+  // in flight across the top of a block: the 4 refill DMAs of the previous block
+  static constexpr int W_TOP = 4;
+  // in flight across the mid-block wait: the later refill of the previous block (2), this block's scale and A
+  // DMAs (N_A) and its first refill (2)
+  static constexpr int W_MID = 2 + N_A + 2;
+  static_assert(BM % 64 == 0 && BM <= 256 && AFR_ >= 2 && TM % AFR_ == 0, "BM a multiple of 64, fragment ring a divisor of BM/16");
+  static_assert(SA_WAVES <= SB_WAVE, "scale fetchers must be distinct waves");
+  static_assert(T_R0 + 2 <= T_MID && T_R1 + 2 <= MFMAS, "issue slots must fit the MFMA stream");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+};
+
+// swizzle key for an A tile whose lanes read chunks q and 4+q of row base+r: see swz_key_a for the lane groups
+// that ds_read_b128 serves together; here the chunk index advances by ONE (not two) for r in 4..11
+__device__ __forceinline__ int swz_key_a1(int row) {
+  const int u = (row >> 1) & 7;
+  return u ^ (((u >> 1) ^ (u >> 2)) & 1);
+}
+
+// Buffer descriptor from wave-uniform values.  readfirstlane states the uniformity for the compiler, which
+// otherwise may keep a descriptor in vector registers and loop over its values at every use.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t uniform_rsrc(const void* ptr, int bytes) {
+  const uint64_t p = (uint64_t)ptr;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)p);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(p >> 32));
+  return __builtin_amdgcn_make_buffer_rsrc((void*)(((uint64_t)hi << 32) | lo), 0, __builtin_amdgcn_readfirstlane(bytes), GG_RSRC_FLAGS);
+}
+
+// A buffer offset no descriptor of this kernel covers: loads return zero (a DMA writes zeros) and touch no memory.
+#define GG_OOB_OFFSET 0x7fffff00
+#ifndef GG_RB_LIMIT_A
+#define GG_RB_LIMIT_A KB
+#define GG_RB_LIMIT_B KB
+#endif
+
+template <class Cfg>
+__global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, NW = Cfg::NW, S = Cfg::S;
+  constexpr int TM = Cfg::TM, TN = Cfg::TN, MF = Cfg::MFMAS, PIPE = Cfg::PIPE, AFR = Cfg::AFR;
+  extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+
+  const int tid = threadIdx.x;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l = tid & 63;
+  const int r = l & 15, q = l >> 4;
+  const int K = a.K, KB = a.KB, N = a.N;
+
+  // ---- per-lane constants ---------------------------------------------------------------------------
+  // DMA: lane l of a wave-wide 16 B DMA lands at LDS byte 16*l of its 1 KB slab (row l/8, chunk l%8); the
+  // swizzle is applied on the global side: LDS chunk c of a row holds global chunk c ^ key(row)
+  const int a_row = w * 8 + (l >> 3);                                  // + i * 64
+  const int vA = a_row * K + (((l & 7) ^ (Cfg::KP ? swz_key_a1(a_row) : swz_key_a(a_row))) << 4);
+  // weight fragment j, fragment row rr (= MFMA row) is tile column 32w + 8*(rr/4) + 4j + rr%4: the 8 outputs
+  // a lane ends up with (MFMA rows 4q..4q+3 of both fragments) are then 8 consecutive columns
+  const int f_row = l >> 3;                                            // slab 0; slab 1 is fragment row f_row + 8
+  const int vBrow = (w * 32 + 8 * (f_row >> 2) + (f_row & 3)) * K;
+  const int vB0 = vBrow + (((l & 7) ^ (Cfg::KP ? swz_key_a1(f_row) : swz_key_a(f_row))) << 4);
+  const int vB1 = vBrow + 16 * K + (((l & 7) ^ (Cfg::KP ? swz_key_a1(f_row + 8) : swz_key_a(f_row + 8))) << 4);
+  // Every wave issues exactly one scale DMA per K block: waves [0, SA_WAVES) fetch 64 activation scales each,
+  // wave SB_WAVE the two weight scales, the others an out-of-range offset into a dump area.
+  const bool sa_wave = w < Cfg::SA_WAVES, sb_wave = w == Cfg::SB_WAVE;
+  const int vS = sa_wave ? (w * 64 + l) * KB * 4 : sb_wave ? (l < BN / 128 ? l : BN / 128 - 1) * KB * 4 : GG_OOB_OFFSET;
+  const int ldsS = Cfg::A_BYTES + (sa_wave ? w * 256 : sb_wave ? Cfg::SA_BYTES : Cfg::SA_BYTES + Cfg::SB_BYTES);
+  // operand reads: row r, chunks (2q, 2q+1), or (q, 4+q) with KP
+  const int keyR = Cfg::KP ? swz_key_a1(r) : swz_key_a(r);
+  const int rd0 = r * 128 + (((Cfg::KP ? q : 2 * q) ^ keyR) << 4);
+  const int rd1 = r * 128 + (((Cfg::KP ? 4 + q : 2 * q + 1) ^ keyR) << 4);
+  const int saRd = Cfg::A_BYTES + r * 4;
+  const int sbRd = Cfg::A_BYTES + Cfg::SA_BYTES + ((w * 32) >> 7) * 4;
+  uint8_t* const bslots = lds + Cfg::B_BASE + w * (Cfg::B_SLOTS * Cfg::B_SLOT_BYTES);   // this wave's weight slots
+
+  int g = 0, base = 0;
+  const int nwg = gridDim.x;
+  for (int it = 0;; ++it) {
+    int T;
+    if (a.slots > 0) T = (it * 8 + (int)(blockIdx.x & 7)) * a.slots + (int)(blockIdx.x >> 3);
+    else T = it * nwg + blockIdx.x;
+    int row0 = 0, Mg = 0, mtiles = 0;
+    for (;;) {
+      if (g >= a.G) return;
+      row0 = clampi(a.off[g], 0, a.M_total);
+      const int row1 = clampi(a.off[g + 1], row0, a.M_total);
+      Mg = row1 - row0;
+      mtiles = (Mg + BM - 1) / BM;
+      const int cnt = mtiles * a.n_tiles;
+      if (T < base + cnt) break;
+      base += cnt;
+      ++g;
+    }
+    const int local = T - base;
+    const int per_chunk = mtiles * a.n_chunk;
+    const int nc = local / per_chunk;
+    const int rem = local - nc * per_chunk;
+    int csz = a.n_tiles - nc * a.n_chunk;
+    csz = csz < a.n_chunk ? csz : a.n_chunk;
+    const int mtile = rem / csz;
+    const int ntile = nc * a.n_chunk + (rem - mtile * csz);
+    const int m0 = mtile * BM, n0 = ntile * BN;
+    int rows_valid = Mg - m0;
+    rows_valid = rows_valid < BM ? rows_valid : BM;
+    const int64_t grow = (int64_t)row0 + m0;
+
+    // Bounded descriptors: rows past the group's end read as zero and are never written (paper Sec. 2.2:
+    // no padding, no out-of-group access).
+    // One descriptor per 64-row band of the A tile: a lane's offset inside its band is then the same for every
+    // slab it fetches (one register instead of one per slab).
+    auto band = [&](int i) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
+      int rows_i = rows_valid - 64 * i;
+      rows_i = rows_i < 0 ? 0 : (rows_i > 64 ? 64 : rows_i);
+      return uniform_rsrc(a.A + (grow + 64 * i) * K, rows_i * K);
+    };
+    __amdgpu_buffer_rsrc_t dA0 = band(0), dA1 = band(1 % Cfg::A_ITERS), dA2 = band(2 % Cfg::A_ITERS), dA3 = band(3 % Cfg::A_ITERS);
+    __amdgpu_buffer_rsrc_t dB = uniform_rsrc(a.B + ((int64_t)g * N + n0) * K, BN * K);
+    // this wave's scale source: the activation scales of the tile's rows, or the weight scales of its two column blocks
+    __amdgpu_buffer_rsrc_t dS = sa_wave ? uniform_rsrc(a.SA + grow * KB, rows_valid * KB * 4)
+                                        : uniform_rsrc(a.SB + ((int64_t)g * (N >> 7) + (n0 >> 7)) * KB, (BN / 128) * KB * 4);
+
+    // K blocks past the end are "fetched" from an out-of-range offset: same instruction count, no traffic
+    auto dma_a = [&](auto ic, int kb, int stage) __attribute__((always_inline)) {   // one 8-row slab of block kb's A tile
+      constexpr int i = decltype(ic)::value;
+      const int vo = kb < GG_RB_LIMIT_A ? vA : GG_OOB_OFFSET;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(i == 0 ? dA0 : i == 1 ? dA1 : i == 2 ? dA2 : dA3, GG_LDS_PTR(lds + stage * Cfg::STAGE_BYTES + (w + i * NW) * 1024), 16, vo,
+                                               __builtin_amdgcn_readfirstlane(kb * 128), 0, 0);
+    };
+    auto dma_scales = [&](int kb, int stage) __attribute__((always_inline)) {     // exactly one DMA in every wave
+      const int vo = kb < KB ? vS : GG_OOB_OFFSET;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dS, GG_LDS_PTR(lds + stage * Cfg::STAGE_BYTES + ldsS), 4, vo,
+                                               __builtin_amdgcn_readfirstlane(kb * 4), 0, 0);
+    };
+    // weight fragment j of block kb into slot `slot` of this wave: two slabs of 8 fragment rows
+    auto dma_b = [&](int kb, int j, int slot) __attribute__((always_inline)) {
+      const bool in = kb < GG_RB_LIMIT_B;
+      uint8_t* dst = bslots + slot * Cfg::B_SLOT_BYTES;
+      // all 256 weight rows of the tile exist: only the lane part of the offset needs the bounds check
+      const int so = __builtin_amdgcn_readfirstlane(kb * 128 + j * 4 * K);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(dst), 16, in ? vB0 : GG_OOB_OFFSET, so, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(dst + 1024), 16, in ? vB1 : GG_OOB_OFFSET, so, 0, 0);
+    };
+    auto read_frag = [&](const uint8_t* p) __attribute__((always_inline)) -> v8i {   // 16 rows x 128 B at p -> MFMA operand
+      const v4i lo = *(const v4i*)(p + rd0);
+      const v4i hi = *(const v4i*)(p + rd1);
+      return (v8i){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    };
+
+    v4f acc[TM][TN];
+#pragma unroll
+    for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[mt][j] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+    // ---- prologue ---------------------------------------------------------------------------------------
+    // Weight fragments are numbered F = 2*kb + j and go through slot F % 3.  Fetch A(0), fragments 0..2 and
+    // A(1); once A(0) and fragments 0, 1 have landed, copy those to registers and refill their slots with
+    // fragments 3 and 4.  That is the state every K block starts from: A(kb+1) and fragment 2kb+2 older than
+    // the last 4 fetches, which are the refills with fragments 2kb+3 and 2kb+4.
+    dma_scales(0, 0);
+    static_for<0, Cfg::A_ITERS>([&](auto ic) __attribute__((always_inline)) { dma_a(ic, 0, 0); });
+    dma_b(0, 0, 0);
+    dma_b(0, 1, 1);
+    dma_b(1, 0, 2);
+    dma_scales(1, 1);
+    static_for<0, Cfg::A_ITERS>([&](auto ic) __attribute__((always_inline)) { dma_a(ic, 1, 1); });
+    wait_vmcnt<2 + Cfg::N_A>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    v8i bfr[2][TN];                                            // weight fragments of K block kb in set kb % 2
+    bfr[0][0] = read_frag(bslots);
+    bfr[0][1] = read_frag(bslots + Cfg::B_SLOT_BYTES);
+    v8i afr[AFR];
+    float sa[AFR];
+#pragma unroll
+    for (int i = 0; i < AFR - 1; ++i) {
+      afr[i] = read_frag(lds + i * 2048);
+      sa[i] = *(const float*)(lds + saRd + i * 64);
+    }
+    // the slot reads must be done before their slots are refilled
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    dma_b(1, 1, 0);
+    dma_b(2, 0, 1);
+
+    int stage = 0;                                             // LDS buffer of block kb
+    int bslot = 2;                                             // slot of fragment 2*kb + 2
+    // One K block; BS = kb % 2 is the register set that holds its weights.
+    auto kstep = [&](int kb, auto bs_c) __attribute__((always_inline)) {
+      constexpr int BS = decltype(bs_c)::value;
+      const int stage1 = stage + 1 == S ? 0 : stage + 1;       // buffer of block kb+1
+      const int stageN = stage == 0 ? S - 1 : stage - 1;       // buffer of block kb+2 (= of block kb-1)
+      const int bslot1 = bslot + 1 == Cfg::B_SLOTS ? 0 : bslot + 1;   // slot of fragment 2*kb + 3
+      const uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
+      const uint8_t* st1 = lds + stage1 * Cfg::STAGE_BYTES;
+      // A(kb+1), its scales and weight fragment 2kb+2 are older than the 4 refill DMAs of block kb-1.  (Stores
+      // of the previous tile are older still: they can only make this wait longer, never shorter.)
+      wait_vmcnt<Cfg::W_TOP>();
+      // every wave has its part of block kb+1 in LDS and is done reading block kb-1
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      const float sb = *(const float*)(st + sbRd);
+      bfr[BS ^ 1][0] = read_frag(bslots + bslot * Cfg::B_SLOT_BYTES);
+      dma_scales(kb + 2, stageN);
+      __builtin_amdgcn_sched_barrier(0);
+
+      v4f p[MF];
+      float s[TM];
+      auto body = [&](auto tc) __attribute__((always_inline)) {
+        constexpr int t = decltype(tc)::value;
+        if constexpr (t < MF) {
+          constexpr int mt = t / TN, j = t % TN;
+          if constexpr (j == 0) {
+            s[mt] = sa[mt % AFR] * sb;
+            // fragment of activation block mt + AFR - 1 into the slot block mt - 1 has left; past the end of
+            // this K block that is the next K block's, published by the barrier above
+            constexpr int nb = mt + AFR - 1;
+            if constexpr (nb < TM) {
+              afr[nb % AFR] = read_frag(st + nb * 2048);
+              sa[nb % AFR] = *(const float*)(st + saRd + nb * 64);
+            } else {
+              afr[nb % AFR] = read_frag(st1 + (nb - TM) * 2048);
+              sa[nb % AFR] = *(const float*)(st1 + saRd + (nb - TM) * 64);
+            }
+          }
+          p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[BS][j], afr[mt % AFR], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+          if constexpr (t >= Cfg::T_A0 && t < Cfg::T_A0 + Cfg::A_ITERS)
+            dma_a(std::integral_constant<int, t - Cfg::T_A0>{}, kb + 2, stageN);
+          // refills: fragment F+3 into the slot fragment F was copied from, some MFMAs (and the LDS reads they
+          // waited for, which return in order) after that copy
+          if constexpr (t == Cfg::T_R0) dma_b(kb + 2, 1, bslot);        // 2kb+2 -> 2kb+5
+          if constexpr (t == Cfg::T_R1) dma_b(kb + 3, 0, bslot1);       // 2kb+3 -> 2kb+6
+        }
+        if constexpr (t >= PIPE) {
+          constexpr int u = t - PIPE;
+          acc[u / TN][u % TN] += p[u] * s[u / TN];
+        }
+      };
+      auto order = [&](auto tc) __attribute__((always_inline)) {               // issue order of what body creates
+        constexpr int t = decltype(tc)::value;
+        if constexpr (t < MF) {
+          constexpr int j = t % TN;
+          if constexpr (j == 0) {
+            __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);                                   // scale product
+            __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);                                   // 3 DS reads
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                     // 1 MFMA
+          if constexpr (t >= Cfg::T_A0 && t < Cfg::T_A0 + Cfg::A_ITERS) {
+            __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);                                   // offset select
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+          }
+          if constexpr (t == Cfg::T_R0 || t == Cfg::T_R1) {
+            __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+          }
+        }
+        if constexpr (t >= PIPE) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);              // 4 FMAs
+      };
+      static_for<0, Cfg::T_MID>(body);
+      static_for<0, Cfg::T_MID>(order);
+      __builtin_amdgcn_sched_barrier(0);
+      // weight fragment 2kb+3, fetched a K block ago, is older than the W_MID newest fetches
+      wait_vmcnt<Cfg::W_MID>();
+      bfr[BS ^ 1][1] = read_frag(bslots + bslot1 * Cfg::B_SLOT_BYTES);
+      __builtin_amdgcn_sched_barrier(0);
+      static_for<Cfg::T_MID, MF + PIPE>(body);
+      static_for<Cfg::T_MID, MF + PIPE>(order);
+      __builtin_amdgcn_sched_barrier(0);
+      stage = stage1;
+      bslot = bslot1 + 1 == Cfg::B_SLOTS ? 0 : bslot1 + 1;
+    };
+
+    // The copies of the block for the two register sets follow each other in a straight line (no if/else over
+    // copies: their identical accumulator updates would be merged behind the branches, and all products of a
+    // block would be live at once).
+    for (int kb = 0;;) {
+      kstep(kb, std::integral_constant<int, 0>{});
+      if (++kb >= KB) break;
+      kstep(kb, std::integral_constant<int, 1>{});
+      if (++kb >= KB) break;
+    }
+    // Every wave is done reading LDS before the next tile's prologue refills it; the out-of-range DMAs of the
+    // last blocks (zeros) complete, in order, before that prologue's.
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    // ---- epilogue: bf16 RNE, one bounded 16-byte store per activation block ---------------------------------
+#pragma unroll
+    for (int mt = 0; mt < TM; ++mt) {
+      const v4f x = acc[mt][0], y = acc[mt][1];
+      const v2bf c0 = __builtin_convertvector((v2f){x[0], x[1]}, v2bf);
+      const v2bf c1 = __builtin_convertvector((v2f){x[2], x[3]}, v2bf);
+      const v2bf c2 = __builtin_convertvector((v2f){y[0], y[1]}, v2bf);
+      const v2bf c3 = __builtin_convertvector((v2f){y[2], y[3]}, v2bf);
+      v4i out;
+      out.x = __builtin_bit_cast(int, c0);
+      out.y = __builtin_bit_cast(int, c1);
+      out.z = __builtin_bit_cast(int, c2);
+      out.w = __builtin_bit_cast(int, c3);
+      // one descriptor per 16-row block (scalar work): the lane offset is then the same for every block, and
+      // rows past the group's end still fail its bounds check
+      int rows_mt = rows_valid - 16 * mt;
+      rows_mt = rows_mt < 0 ? 0 : rows_mt;
+      __amdgpu_buffer_rsrc_t dC = uniform_rsrc(a.C + (grow + 16 * mt) * N + n0, rows_mt > 0 ? rows_mt * N * 2 - n0 * 2 : 0);
+      __builtin_amdgcn_raw_buffer_store_b128(out, dC, r * N * 2 + (w * 32 + 8 * q) * 2, 0, 0);
+    }
+  }
+}
+
+}  // namespace gg

@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "gemm_kernel.h"
+#include "gemm_kernel_rb.h"
 #include "pad_kernels.h"
 
 namespace {
@@ -56,6 +57,22 @@ hipError_t launch_gemm(const gg::GemmArgs& args, int grid, hipStream_t stream) {
 
 // name = "BMxBN/WMxWNw/STAGESs[x]": tile, wave grid, LDS ring depth; x = barrier in the middle of the MFMA
 // stream with operand prefetch across K blocks.  GAP = MFMAs between two DMAs fed into the MFMA stream.
+template <class Cfg>
+hipError_t launch_gemm_rb(const gg::GemmArgs& args, int grid, hipStream_t stream) {
+  static std::atomic<int> prepared[64];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < 64 && !prepared[dev].load(std::memory_order_acquire)) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_gemm_rb_kernel<Cfg>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    prepared[dev].store(1, std::memory_order_release);
+  }
+  hipLaunchKernelGGL(gg::gg_gemm_rb_kernel<Cfg>, dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, args);
+  return hipGetLastError();
+}
+
 #define GG_VARIANT(BM, BN, WM, WN, ST, XPF, GAP, WGPC)                                                        \
   {#BM "x" #BN "/" #WM "x" #WN "w/" #ST "s" XPF_SUFFIX_##XPF, BM, BN, gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>::LDS_BYTES, \
    WGPC, &launch_gemm<gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>>}
@@ -75,6 +92,9 @@ const Variant kVariants[] = {
     GG_VARIANT(128, 128, 2, 4, 4, true, 0, 1),    // 9
     GG_VARIANT(32, 256, 1, 8, 4, true, 0, 1),     // 10
     GG_VARIANT(128, 128, 2, 4, 2, false, 0, 2),   // 11
+    {"256x256/1x8w/3s-rb", 256, 256, gg::RbCfg<256, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, false>>},   // 12
+    {"256x256/1x8w/3s-rbk", 256, 256, gg::RbCfg<256, 2, true>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, true>>},    // 13
+    {"128x256/1x8w/3s-rb", 128, 256, gg::RbCfg<128, 4, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<128, 4, false>>},   // 14
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 

@@ -44,7 +44,7 @@ def test_version_status_strings_and_variants(lib):
     n = gg.num_variants()
     assert n >= 1
     for v in range(n):
-        assert re.fullmatch(r"\d+x\d+/\d+x\d+w/\d+sx?", gg.variant_name(v))
+        assert re.fullmatch(r"\d+x\d+/\d+x\d+w/\d+s(x|-rb\w*)?", gg.variant_name(v))
     assert gg.variant_name(n) is None and gg.variant_name(-1) is None
 
 

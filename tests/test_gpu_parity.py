@@ -53,14 +53,17 @@ def test_tiny_config_every_variant_full_compare():
     host = np_problem(p)
     ref = orc.grouped_gemm(*host, with_abs_sum=True)
     dev = tuple(p[k].to(DEV) for k in ("A", "SA", "B", "SB", "group_offsets"))
-    first = None
+    first = {}
     for v in [-1] + variants_for(p["N"]):
         got = run_gpu(dev, p["M_total"], p["N"], v)
         assert_parity(got, ref, what=f"tiny variant {v}")
-        # the arithmetic per element does not depend on the tiling: all variants agree bit for bit
-        if first is None:
-            first = got
-        assert np.array_equal(got, first), f"variant {v} differs from the default"
+        # The arithmetic per element does not depend on the tiling: all variants of one kernel agree bit for
+        # bit.  Variants named "-rbk" feed the 128 products of a scale block to the matrix instruction in
+        # another order, so they form a family of their own.
+        family = "k-permuted" if v >= 0 and gg.variant_name(v).endswith("-rbk") else "plain"
+        if family not in first:
+            first[family] = got
+        assert np.array_equal(got, first[family]), f"variant {v} differs from the first of its family"
 
 
 @pytest.mark.parametrize("sizes,N,K", [
