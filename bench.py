@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0             # MI355X HBM3E
 # HBM bytes per launch of the GEMM kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/gg_gemm_kernel_full_size_workloads.md gives the commands and the copy-kernel calibration:
 # FETCH_SIZE counts half of a plain copy's bytes, WRITE_SIZE all of them); None = not measured.
-MEASURED_TRAFFIC_BYTES = {"gate_up": 834995782, "down": 993106147, "decode": 1555338725, "many_small": 8039749494}
+MEASURED_TRAFFIC_BYTES = {"gate_up": 767463649, "down": 995585524, "decode": 1554341434, "many_small": 8035922676}
 
 
 def algorithmic_bytes(sizes, N, K):
@@ -139,7 +139,8 @@ def main():
         roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": FP8_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / FP8_MFMA_PEAK_TFLOPS, 4)}
     roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(args.workload)
-    roof["kernel"] = "gg_gemm_kernel<" + (gg.variant_name(args.variant) or "auto") + ">"
+    used = args.variant if args.variant >= 0 else gg.auto_variant(p["G"], p["M_total"], p["N"], p["K"])
+    roof["kernel"] = "gg_gemm_kernel<" + gg.variant_name(used) + ">"
     roof["kernel_avg_ms"] = round(kern_avg_ms, 4)
     roof["kernel_min_ms"] = round(float(kern_ms.min()), 4)
     roof["algorithmic_bytes"] = int(alg_bytes)

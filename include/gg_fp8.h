@@ -81,6 +81,10 @@ int gg_fp8_grouped_gemm_variant(const void* A, const float* SA, const void* B, c
                                 void* workspace, size_t workspace_bytes, void* stream, int variant);
 int gg_fp8_num_variants(void);
 const char* gg_fp8_variant_name(int variant);
+/* The variant gg_fp8_grouped_gemm would use for these sizes (the choice looks at
+ * sizes only, never at device memory); a negative gg_status value if the sizes
+ * are not supported. */
+int gg_fp8_auto_variant(int G, int64_t M_total, int N, int K);
 
 /* ---- the pad-then-GEMM comparison path (the baseline of Sec. 3) ------------
  * Every group is copied to an offset that is a multiple of 128 rows, pad rows

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     grouped_gemm_padded,
     library_path,
     load_library,
+    auto_variant,
     num_variants,
     pad,
     padded_rows_cap,

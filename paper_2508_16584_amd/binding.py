@@ -80,6 +80,8 @@ def load_library() -> ctypes.CDLL:
     lib.gg_fp8_num_variants.argtypes = []
     lib.gg_fp8_variant_name.restype = ctypes.c_char_p
     lib.gg_fp8_variant_name.argtypes = [i32]
+    lib.gg_fp8_auto_variant.restype = i32
+    lib.gg_fp8_auto_variant.argtypes = [i32, i64, i32, i32]
     lib.gg_fp8_padded_rows_cap.restype = i64
     lib.gg_fp8_padded_rows_cap.argtypes = [i32, i64]
     lib.gg_fp8_pad.restype = i32
@@ -96,7 +98,7 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED_SYMBOLS = [
     "gg_fp8_version", "gg_fp8_status_str", "gg_fp8_workspace_bytes", "gg_fp8_grouped_gemm",
-    "gg_fp8_grouped_gemm_variant", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_padded_rows_cap",
+    "gg_fp8_grouped_gemm_variant", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_auto_variant", "gg_fp8_padded_rows_cap",
     "gg_fp8_pad", "gg_fp8_grouped_gemm_padded", "gg_fp8_unpad", "gg_fp8_check_offsets",
 ]
 
@@ -165,6 +167,14 @@ def workspace_bytes(G: int, M_total: int, N: int, K: int) -> int:
 
 def num_variants() -> int:
     return load_library().gg_fp8_num_variants()
+
+
+def auto_variant(G: int, M_total: int, N: int, K: int) -> int:
+    """Index of the variant grouped_gemm(variant=-1) uses for these sizes."""
+    v = load_library().gg_fp8_auto_variant(G, M_total, N, K)
+    if v < 0:
+        raise ValueError(f"gg_fp8_auto_variant: {status_str(-v)}")
+    return v
 
 
 def variant_name(v: int):

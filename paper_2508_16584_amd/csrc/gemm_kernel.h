@@ -50,11 +50,6 @@ typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 // dword 3 of a raw buffer descriptor on gfx9-family parts: 32-bit data format, no swizzle
 #define GG_RSRC_FLAGS 0x00020000
 
-#ifdef GG_NO_DMA
-#define GG_ISSUE(x) false
-#else
-#define GG_ISSUE(x) (x)
-#endif
 struct GemmArgs {
   const uint8_t* A;
   const float* SA;
@@ -326,7 +321,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
 
       int stage = 0;
       auto kstep_x = [&](int kb, auto issue_c, auto last_c) {
-        constexpr bool ISSUE = GG_ISSUE(decltype(issue_c)::value), LAST = decltype(last_c)::value;
+        constexpr bool ISSUE = decltype(issue_c)::value, LAST = decltype(last_c)::value;
         const int stage1 = stage + 1 == STAGES ? 0 : stage + 1;                   // buffer of block kb+1
         const int stageN = stage == 0 ? STAGES - 1 : stage - 1;                   // buffer of block kb+STAGES-1
         const uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
@@ -420,7 +415,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
 
       // One K block.  ISSUE: the DMA of block kb + STAGES - 1 is issued during this block.
       auto kstep = [&](int kb, auto issue_c) {
-        constexpr bool ISSUE = GG_ISSUE(decltype(issue_c)::value);
+        constexpr bool ISSUE = decltype(issue_c)::value;
         const int stage = kb % STAGES;
         const int nstage = (kb + STAGES - 1) % STAGES;
         // The DMA of this K block (issued STAGES-1 blocks ago by every wave) must have landed; the newer

@@ -62,7 +62,7 @@ struct RbCfg {
   static constexpr int W_MID = 2 + N_A + 2;
   static_assert(BM % 64 == 0 && BM <= 256 && AFR_ >= 2 && TM % AFR_ == 0, "BM a multiple of 64, fragment ring a divisor of BM/16");
   static_assert(SA_WAVES <= SB_WAVE, "scale fetchers must be distinct waves");
-  static_assert(T_R0 + 2 <= T_MID && T_R1 + 2 <= MFMAS, "issue slots must fit the MFMA stream");
+  static_assert(T_R0 + 2 <= T_MID && T_R1 + 2 <= MFMAS && T_MID % TN == 0, "issue slots must fit the MFMA stream");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
@@ -84,10 +84,6 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t uniform_rsrc(const void* ptr, 
 
 // A buffer offset no descriptor of this kernel covers: loads return zero (a DMA writes zeros) and touch no memory.
 #define GG_OOB_OFFSET 0x7fffff00
-#ifndef GG_RB_LIMIT_A
-#define GG_RB_LIMIT_A KB
-#define GG_RB_LIMIT_B KB
-#endif
 
 template <class Cfg>
 __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
@@ -174,7 +170,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     // K blocks past the end are "fetched" from an out-of-range offset: same instruction count, no traffic
     auto dma_a = [&](auto ic, int kb, int stage) __attribute__((always_inline)) {   // one 8-row slab of block kb's A tile
       constexpr int i = decltype(ic)::value;
-      const int vo = kb < GG_RB_LIMIT_A ? vA : GG_OOB_OFFSET;
+      const int vo = kb < KB ? vA : GG_OOB_OFFSET;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(i == 0 ? dA0 : i == 1 ? dA1 : i == 2 ? dA2 : dA3, GG_LDS_PTR(lds + stage * Cfg::STAGE_BYTES + (w + i * NW) * 1024), 16, vo,
                                                __builtin_amdgcn_readfirstlane(kb * 128), 0, 0);
     };
@@ -185,7 +181,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     };
     // weight fragment j of block kb into slot `slot` of this wave: two slabs of 8 fragment rows
     auto dma_b = [&](int kb, int j, int slot) __attribute__((always_inline)) {
-      const bool in = kb < GG_RB_LIMIT_B;
+      const bool in = kb < KB;
       uint8_t* dst = bslots + slot * Cfg::B_SLOT_BYTES;
       // all 256 weight rows of the tile exist: only the lane part of the offset needs the bounds check
       const int so = __builtin_amdgcn_readfirstlane(kb * 128 + j * 4 * K);
@@ -308,15 +304,23 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
         }
         if constexpr (t >= PIPE) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);              // 4 FMAs
       };
-      static_for<0, Cfg::T_MID>(body);
-      static_for<0, Cfg::T_MID>(order);
-      __builtin_amdgcn_sched_barrier(0);
-      // weight fragment 2kb+3, fetched a K block ago, is older than the W_MID newest fetches
-      wait_vmcnt<Cfg::W_MID>();
-      bfr[BS ^ 1][1] = read_frag(bslots + bslot1 * Cfg::B_SLOT_BYTES);
-      __builtin_amdgcn_sched_barrier(0);
-      static_for<Cfg::T_MID, MF + PIPE>(body);
-      static_for<Cfg::T_MID, MF + PIPE>(order);
+      // One scheduling region per activation block (2 MFMAs, the 8 FMAs of earlier MFMAs, 3 LDS reads, at most
+      // two fetches): the software pipeline is written out in the source, the regions keep the compiler from
+      // rearranging it across blocks.
+      static_for<0, TM>([&](auto mc) __attribute__((always_inline)) {
+        constexpr int mt = decltype(mc)::value;
+        if constexpr (mt * TN == Cfg::T_MID) {
+          // weight fragment 2kb+3, fetched a K block ago, is older than the W_MID newest fetches
+          wait_vmcnt<Cfg::W_MID>();
+          bfr[BS ^ 1][1] = read_frag(bslots + bslot1 * Cfg::B_SLOT_BYTES);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        static_for<mt * TN, mt * TN + TN>(body);
+        static_for<mt * TN, mt * TN + TN>(order);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      static_for<MF, MF + PIPE>(body);
+      static_for<MF, MF + PIPE>(order);
       __builtin_amdgcn_sched_barrier(0);
       stage = stage1;
       bslot = bslot1 + 1 == Cfg::B_SLOTS ? 0 : bslot1 + 1;

@@ -146,10 +146,6 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
   args.KB = K / 128;
   args.n_tiles = N / v.BN;
   args.n_chunk = args.n_tiles < 8 ? args.n_tiles : 8;
-  if (const char* e = getenv("GG_FP8_N_CHUNK")) {   // benchmarking override
-    const int c = atoi(e);
-    if (c >= 1) args.n_chunk = c < args.n_tiles ? c : args.n_tiles;
-  }
 
   // upper bound on the number of tiles for any offsets: every group adds at most one partial m-tile
   const int64_t max_tiles = (M_total / v.BM + G) * (int64_t)args.n_tiles;
@@ -194,6 +190,13 @@ int gg_fp8_num_variants(void) { return kNumVariants; }
 
 const char* gg_fp8_variant_name(int variant) {
   return (variant >= 0 && variant < kNumVariants) ? kVariants[variant].name : nullptr;
+}
+
+int gg_fp8_auto_variant(int G, int64_t M_total, int N, int K) {
+  if (G < 0 || M_total < 0 || N <= 0 || K <= 0) return -GG_ERR_SHAPE;
+  if (M_total > 0x7FFFFFFFLL || N > (1 << 21) || K > (1 << 22)) return -GG_ERR_SHAPE;
+  if (N % 128 != 0 || K % 128 != 0) return -GG_ERR_UNSUPPORTED;
+  return pick_variant(G, M_total, N);
 }
 
 int gg_fp8_grouped_gemm_variant(const void* A, const float* SA, const void* B, const float* SB,
