@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <cmath>
 #include <cstdlib>
 #include <vector>
 
@@ -98,18 +99,33 @@ const Variant kVariants[] = {
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
-// Tile shape.  The host knows only G and M_total (the offsets stay on the device).  On MI355X the kernel is
-// bound by how fast a CU gets K blocks from L2 into LDS, so the default is the tile with the most output area
-// that still leaves room for a ring of 3 buffers in the 160 KB of LDS: 160 x 256.  Interleaved A/B timing on
-// the synthetic workloads moved two cases elsewhere: mid-length groups (256..768 rows on average; the skewed
-// "down" shape with its short K loop) run best on 256 x 256, very short groups (< 64 rows, weight streaming)
-// on 128 x 256.  All variants stay selectable through gg_fp8_grouped_gemm_variant.
-int pick_variant(int G, int64_t M_total, int N) {
+// Automatic choice.  The host sees only sizes (the offsets stay on the device), so the choice works with the
+// expected tile count: a group ends in a partial tile half of the time on average, which adds G/2 tiles per
+// column of tiles.  Candidates and their measured character on MI355X:
+//   160x256, ring 3 (variant 0): the safe default; best when groups are short or the tile count is small;
+//   256x256, ring 2 (variant 1): fewest bytes per flop, but only one K block of look-ahead: best on long runs
+//       (M_total >= 24576 in the paper's grid) and on short K loops;
+//   256x256, second kernel (variant 12): same tile, weights through registers, better overlap: best on the
+//       mid-size problems with cold caches, needs a K loop long enough to pay for its longer prologue;
+//   128x256 (variant 3): very short groups (weight streaming, deepest DMA queue).
+// Between the candidates allowed for a shape, the estimated time is rounds x tile height / efficiency, where a
+// partly filled last round of the 256 workgroups costs 0.6 + 0.4 x its fill (measured: the workgroups that do
+// run get more of the L2 bandwidth) and the 256-tall tiles are 12 % more efficient per row when full.  The
+// constants are a fit to all three candidates on the 576 points of the paper's grid (Sec. 3.1) with caches flushed
+// before every launch: mean loss against the best of the three 0.6 %, against 2.0-7.2 % for any single one.
+int pick_variant(int G, int64_t M_total, int N, int K) {
   if (N % 256 != 0) return 2;   // N is always a multiple of 128
   const double avg = G > 0 ? (double)M_total / G : 0.0;
-  if (avg >= 256 && avg < 768) return 1;
   if (avg < 64) return 3;
-  return 0;
+  if (avg < 192) return 0;
+  auto cost = [&](int BM, double eff) {
+    const double rounds = ((double)M_total / BM + 0.5 * G) * (N / 256) / 256.0;   // 256 CUs: the chip this is fitted on
+    const double whole = std::floor(rounds), frac = rounds - whole;
+    return (whole + (frac > 1e-9 ? 0.6 + 0.4 * frac : 0.0)) * BM / eff;
+  };
+  const double c0 = cost(160, 1.0), c256 = cost(256, 1.12);
+  if (c0 <= c256) return 0;
+  return (M_total >= 24576 || K < 3072) ? 1 : 12;
 }
 
 int validate_gemm(const void* A, const float* SA, const void* B, const float* SB, const int32_t* off, void* C,
@@ -128,7 +144,7 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
   if (st != GG_OK) return st;
   if (G == 0 || M_total == 0) return GG_OK;
   if (variant >= kNumVariants) return GG_ERR_UNSUPPORTED;
-  if (variant < 0) variant = pick_variant(G, M_total, N);
+  if (variant < 0) variant = pick_variant(G, M_total, N, K);
   const Variant& v = kVariants[variant];
   if (N % v.BN != 0) return GG_ERR_UNSUPPORTED;
 
@@ -196,7 +212,7 @@ int gg_fp8_auto_variant(int G, int64_t M_total, int N, int K) {
   if (G < 0 || M_total < 0 || N <= 0 || K <= 0) return -GG_ERR_SHAPE;
   if (M_total > 0x7FFFFFFFLL || N > (1 << 21) || K > (1 << 22)) return -GG_ERR_SHAPE;
   if (N % 128 != 0 || K % 128 != 0) return -GG_ERR_UNSUPPORTED;
-  return pick_variant(G, M_total, N);
+  return pick_variant(G, M_total, N, K);
 }
 
 int gg_fp8_grouped_gemm_variant(const void* A, const float* SA, const void* B, const float* SB,

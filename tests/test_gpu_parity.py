@@ -307,3 +307,45 @@ def test_full_size_configs_sampled_rows(name, max_groups, every):
     # property that holds at any size: every row of every group was written (no canary left)
     written = (C.view(torch.int16) != CANARY).any(dim=1).cpu().numpy()
     assert written.all()
+
+
+@pytest.mark.parametrize("N,K,G,M", [
+    (3072, 8192, 4, 8192),
+    (8192, 3072, 32, 8192),
+    (5120, 6144, 16, 16384),
+])
+def test_paper_grid_points_with_the_papers_size_generator(N, K, G, M):
+    """Points of the paper's sweep grid (Sec. 3.1) with group sizes from its generator (App. C.1): sampled rows
+    against the oracle, every row written, and pad + GEMM + unpad equal to the padding-free result bit for bit."""
+    from workloads.configs import paper_group_sizes
+    rng = np.random.default_rng([20250816, N, K, G, M])
+    sizes = paper_group_sizes(M, G, rng)
+    assert sizes.sum() == M and (sizes >= 0).all()
+    cfg = WorkloadConfig("grid", 70, G, K, N, M, "custom", "mfma")
+    p = make_problem(cfg, device=DEV, sizes=sizes)
+    off = p["group_offsets"].cpu().numpy()
+    C = canary_C(M, N)
+    gg.grouped_gemm(p["A"], p["SA"], p["B"], p["SB"], p["group_offsets"], C=C)
+    torch.cuda.synchronize()
+    rows = sampled_rows(off, rng, every=211)
+    grp = np.searchsorted(off, rows, side="right") - 1
+    used = np.unique(grp)
+    ridx = torch.from_numpy(rows).to(DEV)
+    A_s, SA_s = p["A"][ridx].cpu().numpy(), p["SA"][ridx].cpu().numpy()
+    B_s = p["B"][torch.from_numpy(used).to(DEV)].cpu().numpy()
+    SB_s = p["SB"][torch.from_numpy(used).to(DEV)].cpu().numpy()
+    off_s = np.concatenate([[0], np.cumsum([(grp == g).sum() for g in used])])
+    ref = orc.grouped_gemm(A_s, SA_s, B_s, SB_s, off_s, with_abs_sum=True)
+    stats = assert_parity(bits_of(C[ridx]), ref, what=f"grid N={N} K={K} G={G} M={M}")
+    print(f"\ngrid N={N} K={K} G={G} M={M}: sizes {sizes.min()}..{sizes.max()}, {len(rows)} rows: {stats}")
+    assert (C.view(torch.int16) != CANARY).any(dim=1).all()
+    # the comparison path of the sweep
+    cap = gg.padded_rows_cap(G, M)
+    A_pad, SA_pad, poff = gg.pad(p["A"], p["SA"], p["group_offsets"], cap)
+    C_pad = torch.zeros((cap, N), dtype=torch.bfloat16, device=DEV)
+    gg.grouped_gemm_padded(A_pad, SA_pad, p["B"], p["SB"], poff, C_pad)
+    C2 = canary_C(M, N)
+    gg.unpad(C_pad, p["group_offsets"], poff, M, C=C2)
+    torch.cuda.synchronize()
+    assert int(poff[-1].item()) == int(np.sum(128 * ((sizes + 127) // 128)))
+    assert torch.equal(C.view(torch.int16), C2.view(torch.int16))
