@@ -27,9 +27,9 @@ FP8_MFMA_PEAK_TFLOPS = 5033.0     # MI355X dense FP8: 256 CU x 8192 flop/clk/CU 
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E
 
 # HBM bytes per launch of the GEMM kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/gg_gemm_kernel_full_size_workloads.md gives the commands and the copy-kernel calibration:
+# (profiles/gemm_kernels_full_size_workloads.md gives the commands and the copy-kernel calibration:
 # FETCH_SIZE counts half of a plain copy's bytes, WRITE_SIZE all of them); None = not measured.
-MEASURED_TRAFFIC_BYTES = {"gate_up": 767463649, "down": 995585524, "decode": 1554341434, "many_small": 8035922676}
+MEASURED_TRAFFIC_BYTES = {"gate_up": 712364697, "down": 995585524, "decode": 1554341434, "many_small": 8035922676}
 
 
 def algorithmic_bytes(sizes, N, K):
@@ -140,7 +140,8 @@ def main():
                 "frac": round(achieved / FP8_MFMA_PEAK_TFLOPS, 4)}
     roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(args.workload)
     used = args.variant if args.variant >= 0 else gg.auto_variant(p["G"], p["M_total"], p["N"], p["K"])
-    roof["kernel"] = "gg_gemm_kernel<" + gg.variant_name(used) + ">"
+    vname = gg.variant_name(used)
+    roof["kernel"] = ("gg_gemm_rb_kernel<" if "-rb" in vname else "gg_gemm_kernel<") + vname + ">"
     roof["kernel_avg_ms"] = round(kern_avg_ms, 4)
     roof["kernel_min_ms"] = round(float(kern_ms.min()), 4)
     roof["algorithmic_bytes"] = int(alg_bytes)

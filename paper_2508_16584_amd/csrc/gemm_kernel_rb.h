@@ -35,7 +35,10 @@ struct RbCfg {
   static constexpr int BM = BM_, BN = 256, S = 3;
   static constexpr int NW = 8, NT = 512;
   static constexpr int TM = BM / 16, TN = 2;
-  static constexpr int A_BYTES = BM * 128;
+  static constexpr int A_ITERS = (BM + 63) / 64;   // 8-row slabs per wave per K block
+  // BM need not be a multiple of 64: the last band of 64 rows is then partly outside the tile, its rows fail the
+  // bounds check like any row past the group's end (zeros into LDS rows nobody reads, no traffic)
+  static constexpr int A_BYTES = A_ITERS * 64 * 128;
   static constexpr int SA_WAVES = (BM + 63) / 64;
   static constexpr int SA_BYTES = SA_WAVES * 256;
   static constexpr int SB_BYTES = 256;
@@ -44,7 +47,6 @@ struct RbCfg {
   static constexpr int B_SLOTS = 3, B_SLOT_BYTES = 2048;        // per wave: fragments of 16 rows x 128 B
   static constexpr int B_BASE = S * STAGE_BYTES;
   static constexpr int LDS_BYTES = B_BASE + NW * B_SLOTS * B_SLOT_BYTES;
-  static constexpr int A_ITERS = BM / 64;          // 8-row slabs per wave per K block
   static constexpr int SB_WAVE = NW - 1;
   static constexpr int MFMAS = TM * TN;
   static constexpr int PIPE = 3;                   // MFMAs in flight before their FMAs are issued
@@ -60,7 +62,7 @@ struct RbCfg {
   // in flight across the mid-block wait: the later refill of the previous block (2), this block's scale and A
   // DMAs (N_A) and its first refill (2)
   static constexpr int W_MID = 2 + N_A + 2;
-  static_assert(BM % 64 == 0 && BM <= 256 && AFR_ >= 2 && TM % AFR_ == 0, "BM a multiple of 64, fragment ring a divisor of BM/16");
+  static_assert(BM % 16 == 0 && BM <= 256 && AFR_ >= 2 && TM % AFR_ == 0, "BM a multiple of 16, fragment ring a divisor of BM/16");
   static_assert(SA_WAVES <= SB_WAVE, "scale fetchers must be distinct waves");
   static_assert(T_R0 + 2 <= T_MID && T_R1 + 2 <= MFMAS && T_MID % TN == 0, "issue slots must fit the MFMA stream");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");

@@ -95,24 +95,28 @@ const Variant kVariants[] = {
     GG_VARIANT(128, 128, 2, 4, 2, false, 0, 2),   // 11
     {"256x256/1x8w/3s-rb", 256, 256, gg::RbCfg<256, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, false>>},   // 12
     {"256x256/1x8w/3s-rbk", 256, 256, gg::RbCfg<256, 2, true>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, true>>},    // 13
-    {"128x256/1x8w/3s-rb", 128, 256, gg::RbCfg<128, 4, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<128, 4, false>>},   // 14
+    {"192x256/1x8w/3s-rb", 192, 256, gg::RbCfg<192, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<192, 2, false>>},   // 14
+    {"224x256/1x8w/3s-rb", 224, 256, gg::RbCfg<224, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<224, 2, false>>},   // 15
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
 // Automatic choice.  The host sees only sizes (the offsets stay on the device), so the choice works with the
 // expected tile count: a group ends in a partial tile half of the time on average, which adds G/2 tiles per
 // column of tiles.  Candidates and their measured character on MI355X:
-//   160x256, ring 3 (variant 0): the safe default; best when groups are short or the tile count is small;
+//   160x256, ring 3 (variant 0): the safe default; best when groups are short;
 //   256x256, ring 2 (variant 1): fewest bytes per flop, but only one K block of look-ahead: best on long runs
 //       (M_total >= 24576 in the paper's grid) and on short K loops;
-//   256x256, second kernel (variant 12): same tile, weights through registers, better overlap: best on the
-//       mid-size problems with cold caches, needs a K loop long enough to pay for its longer prologue;
+//   second kernel at 192, 224 and 256 rows (variants 14, 15, 12): weights through registers, better overlap: best
+//       on the small and mid-size problems with cold caches; needs a K loop long enough to pay for its longer
+//       prologue (K >= 3072).  Three heights, because on a few hundred tiles the number of rounds over the 256
+//       workgroups matters more than anything else (8192 rows in 8 groups, N = 4096: 2.9 rounds at 192 rows,
+//       2.25 at 256, 3.45 at 160);
 //   128x256 (variant 3): very short groups (weight streaming, deepest DMA queue).
 // Between the candidates allowed for a shape, the estimated time is rounds x tile height / efficiency, where a
-// partly filled last round of the 256 workgroups costs 0.6 + 0.4 x its fill (measured: the workgroups that do
-// run get more of the L2 bandwidth) and the 256-tall tiles are 12 % more efficient per row when full.  The
-// constants are a fit to all three candidates on the 576 points of the paper's grid (Sec. 3.1) with caches flushed
-// before every launch: mean loss against the best of the three 0.6 %, against 2.0-7.2 % for any single one.
+// partly filled last round costs 0.6 + 0.4 x its fill (measured: the workgroups that do run get more of the L2
+// bandwidth) and the efficiency per row is 1 : 1.08 : 1.08 : 1.16 for 160 : 192 : 224 : 256 rows.  The constants
+// are a fit to the five candidates on the 576 points of the paper's grid (Sec. 3.1) with caches flushed before
+// every launch: mean loss against the per-point best of the five 0.9 %, against 3.3-8.4 % for any single one.
 int pick_variant(int G, int64_t M_total, int N, int K) {
   if (N % 256 != 0) return 2;   // N is always a multiple of 128
   const double avg = G > 0 ? (double)M_total / G : 0.0;
@@ -123,9 +127,16 @@ int pick_variant(int G, int64_t M_total, int N, int K) {
     const double whole = std::floor(rounds), frac = rounds - whole;
     return (whole + (frac > 1e-9 ? 0.6 + 0.4 * frac : 0.0)) * BM / eff;
   };
-  const double c0 = cost(160, 1.0), c256 = cost(256, 1.12);
-  if (c0 <= c256) return 0;
-  return (M_total >= 24576 || K < 3072) ? 1 : 12;
+  const bool long_k = K >= 3072;
+  int best = 0;
+  double c_best = cost(160, 1.0);
+  auto consider = [&](int variant, double c) {
+    if (c < c_best) { c_best = c; best = variant; }
+  };
+  if (long_k) consider(14, cost(192, 1.08));
+  if (long_k) consider(15, cost(224, 1.08));
+  consider((M_total >= 24576 || !long_k) ? 1 : 12, cost(256, 1.16));
+  return best;
 }
 
 int validate_gemm(const void* A, const float* SA, const void* B, const float* SB, const int32_t* off, void* C,
