@@ -19,7 +19,7 @@
 //  * one v_mfma_f32_16x16x128_f8f6f4 with a zero C operand produces the partial sums of one scale
 //    block; the weights sit on the MFMA row side and the activations on the column side, so a lane
 //    holds ONE activation row per MFMA and the dequantisation is 4 fp32 FMAs with a per-lane
-//    scalar  s = SA[row][kb] * SB[g][n/128][kb]  into the fp32 accumulators (a5 of the hot path);
+//    scalar  s = SA[row][kb] * SB[g][n/128][kb]  into the fp32 accumulators (the scale fusion);
 //  * the epilogue rounds to bf16 (RNE) and issues bounded 16-byte stores.
 #pragma once
 #include <hip/hip_runtime.h>

@@ -281,7 +281,7 @@ def sampled_rows(off, rng, every=97, max_groups=None):
     ("many_small", 24, 29),
 ])
 def test_full_size_configs_sampled_rows(name, max_groups, every):
-    """BASELINE configs at full size, default launch configuration (what bench.py times)."""
+    """The four full-size workloads, default launch configuration (what bench.py times)."""
     cfg = CONFIGS[name]
     p = make_problem(cfg, device=DEV)
     off = p["group_offsets"].cpu().numpy()
