@@ -233,6 +233,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     dma_b(1, 1, 0);
     dma_b(2, 0, 1);
 
+    float sb_next = *(const float*)(lds + sbRd);               // weight scale of block 0
     int stage = 0;                                             // LDS buffer of block kb
     int bslot = 2;                                             // slot of fragment 2*kb + 2
     // One K block; BS = kb % 2 is the register set that holds its weights.
@@ -249,7 +250,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       // every wave has its part of block kb+1 in LDS and is done reading block kb-1
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      const float sb = *(const float*)(st + sbRd);
+      const float sb = sb_next;                                // read a block ago: no LDS wait ahead of the first MFMA
       bfr[BS ^ 1][0] = read_frag(bslots + bslot * Cfg::B_SLOT_BYTES);
       dma_scales(kb + 2, stageN);
       __builtin_amdgcn_sched_barrier(0);
@@ -271,6 +272,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
             } else {
               afr[nb % AFR] = read_frag(st1 + (nb - TM) * 2048);
               sa[nb % AFR] = *(const float*)(st1 + saRd + (nb - TM) * 64);
+              if constexpr (nb == TM) sb_next = *(const float*)(st1 + sbRd);   // next block's weight scale
             }
           }
           p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[BS][j], afr[mt % AFR], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
@@ -292,7 +294,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
           constexpr int j = t % TN;
           if constexpr (j == 0) {
             __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);                                   // scale product
-            __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);                                   // 3 DS reads
+            __builtin_amdgcn_sched_group_barrier(0x100, t / TN + AFR - 1 == TM ? 4 : 3, 0);      // 3 (4) DS reads
           }
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                     // 1 MFMA
           if constexpr (t >= Cfg::T_A0 && t < Cfg::T_A0 + Cfg::A_ITERS) {
