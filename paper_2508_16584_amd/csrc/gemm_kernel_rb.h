@@ -131,7 +131,11 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     else T = it * nwg + blockIdx.x;
     int row0 = 0, Mg = 0, mtiles = 0;
     for (;;) {
-      if (g >= a.G) return;
+      if (g >= a.G) {
+        // the out-of-range fetches of the last K blocks write zeros into this workgroup's LDS: let them land
+        wait_vmcnt<0>();
+        return;
+      }
       row0 = clampi(a.off[g], 0, a.M_total);
       const int row1 = clampi(a.off[g + 1], row0, a.M_total);
       Mg = row1 - row0;

@@ -90,7 +90,7 @@ def test_edge_group_sizes_every_variant(sizes, N, K):
 def test_rows_outside_the_groups_and_guard_bands_are_untouched():
     # groups cover rows [5, 5+sum) of a larger buffer; C has guard rows before and after
     rng = np.random.default_rng(60)
-    sizes, N, K = [130, 0, 67], 256, 256
+    sizes, N, K = [130, 0, 67], 256, 384
     host, dev = raw_problem(rng, sizes, N, K, DEV)
     A, SA, B, SB, off = host
     pre, post = 5, 9
@@ -205,7 +205,7 @@ def test_nan_stays_in_its_row_and_column():
 def test_untrusted_offsets_never_write_outside_C():
     # decreasing and out-of-range offsets: results are unspecified, but nothing outside C[0:M] is written
     rng = np.random.default_rng(64)
-    host, dev = raw_problem(rng, [100, 100, 100], 256, 256, DEV)
+    host, dev = raw_problem(rng, [100, 100, 100], 256, 384, DEV)
     M = 300
     bad = torch.tensor([-5, 250, 120, 100000], dtype=torch.int32, device=DEV)
     assert gg.check_offsets(bad, M) == 6          # GG_ERR_OFFSETS
