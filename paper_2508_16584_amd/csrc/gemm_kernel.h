@@ -63,6 +63,7 @@ struct GemmArgs {
   int n_tiles;   // N / BN
   int n_chunk;   // n-tiles that are walked together before moving to the next m-tile
   int slots;     // workgroups per XCD when the grid is a multiple of 8, else 0 (plain round-robin)
+  int rot_mul;   // K blocks by which neighbouring 256-column blocks shift the start of their K loop (0: none)
 };
 
 template <int BM_, int BN_, int WM_, int WN_, int STAGES_, bool XPF_ = false, int GAP_ = 0, int PIPE_ = 3>
@@ -129,6 +130,18 @@ __device__ __forceinline__ void wait_all_but(int younger, int extra) {
     else wait_all_but_n<BASE + 3, MAXY>(younger);
   }
 }
+
+// Start of a tile's K loop.  When the row pitch K is 4096 bytes, the 128-byte pieces that a K block takes from the
+// rows of a tile all sit at the same offset inside a 4 KB frame, and the workgroups of an XCD walk K nearly in
+// step: a pure fetch stream of this shape reaches 4.8 TB/s instead of the 5.9 TB/s of other pitches, and the
+// weight-streaming shapes (few rows per group) lose 3-11 % (measured).  Letting the tiles of neighbouring
+// 256-column blocks start 4 K blocks (512 B) apart and wrap around gives that back; compute-bound shapes do not
+// notice.  The start depends on the column block alone, never on the row tile, the workgroup or the tile shape,
+// so that an output element is accumulated in the same order by every variant and in the padded and the
+// padding-free path (their bitwise equality, paper Sec. 3.1, is kept).  The host sets rot_mul = 4 for pitches
+// that are odd multiples of 4096 and 0 otherwise (at K = 8192 the shift costs 1-8 %, measured).
+__device__ __forceinline__ int k_rotation(const GemmArgs& a, int n0) { return ((n0 >> 8) & 7) * a.rot_mul; }
+__device__ __forceinline__ int k_wrapped(int k, int KB) { return k >= KB ? k - KB : k; }
 
 // XOR keys of the LDS swizzle: 16-byte chunk c of tile row `row` is stored at chunk position c ^ key(row).
 // ds_read_b128 serves 16 lanes per cycle, and on gfx950 those are not 16 consecutive lanes: of every 32
@@ -239,8 +252,12 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
     constexpr int NDMA_ALL = A_FULL + B_FULL;                                  // issued by every wave
     constexpr int NDMA_STREAM = NDMA_ALL < Cfg::MFMAS ? NDMA_ALL : Cfg::MFMAS;  // of those, inside the stream
     constexpr int DMA_GAP = Cfg::GAP > 0 ? Cfg::GAP : Cfg::MFMAS / (NDMA_STREAM > 0 ? NDMA_STREAM : 1);
-    auto dma_tile = [&](auto idx_c, int kb, int stage) {
+    // K blocks are taken in the order rot, rot+1, ..., KB-1, 0, ..., rot-1 (see k_rotation)
+    const int rot = k_rotation(a, n0);
+    auto kphys = [&](int kb) -> int { return k_wrapped(kb + rot, KB); };
+    auto dma_tile = [&](auto idx_c, int kb_l, int stage) {
       constexpr int idx = decltype(idx_c)::value;
+      const int kb = kphys(kb_l);
       uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
       if constexpr (idx < A_FULL) {
         __builtin_amdgcn_raw_ptr_buffer_load_lds(dA, GG_LDS_PTR(st + (w + idx * NW) * 1024), 16, vA + idx * (NW * 8) * K, kb * 128, 0, 0);
@@ -249,7 +266,8 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
         __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(st + Cfg::A_BYTES + (w + i * NW) * 1024), 16, vB, i * (NW * 8) * K + kb * 128, 0, 0);
       }
     };
-    auto dma_head = [&](int kb, int stage) {   // everything that is not issued inside the stream
+    auto dma_head = [&](int kb_l, int stage) {   // everything that is not issued inside the stream
+      const int kb = kphys(kb_l);
       uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
       if (w < Cfg::SA_WAVES)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(dSA, GG_LDS_PTR(st + Cfg::A_BYTES + Cfg::B_BYTES + w * 256), 4, vSA, kb * 4, 0, 0);

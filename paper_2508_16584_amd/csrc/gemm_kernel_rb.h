@@ -20,7 +20,7 @@
 //    weight slots; the wait at the top of block kb+1 lets exactly the refills stay in flight.
 //
 // Arithmetic per output element is the same as in the first kernel (one C=0 MFMA per 128-wide scale block,
-// 4 fp32 FMAs with the per-lane scale, kb ascending), so results are bit-identical to it unless KP is set.
+// 4 fp32 FMAs with the per-lane scale, the K blocks in the same order), so results are bit-identical to it unless KP is set.
 // KP: a lane's 32 operand bytes of a 128-byte row are [16q, 16q+16) and [64+16q, 64+16q+16) (q = lane/16)
 // instead of [32q, 32q+32): a permutation of k inside the K block applied to both operands alike; every dot
 // product has the same terms, the matrix instruction adds them in another order.
@@ -173,24 +173,26 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     __amdgpu_buffer_rsrc_t dS = sa_wave ? uniform_rsrc(a.SA + grow * KB, rows_valid * KB * 4)
                                         : uniform_rsrc(a.SB + ((int64_t)g * (N >> 7) + (n0 >> 7)) * KB, (BN / 128) * KB * 4);
 
+    // K blocks are taken in the order rot, rot+1, ..., KB-1, 0, ..., rot-1 (see k_rotation)
+    const int rot = k_rotation(a, n0);
     // K blocks past the end are "fetched" from an out-of-range offset: same instruction count, no traffic
     auto dma_a = [&](auto ic, int kb, int stage) __attribute__((always_inline)) {   // one 8-row slab of block kb's A tile
       constexpr int i = decltype(ic)::value;
       const int vo = kb < KB ? vA : GG_OOB_OFFSET;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(i == 0 ? dA0 : i == 1 ? dA1 : i == 2 ? dA2 : dA3, GG_LDS_PTR(lds + stage * Cfg::STAGE_BYTES + (w + i * NW) * 1024), 16, vo,
-                                               __builtin_amdgcn_readfirstlane(kb * 128), 0, 0);
+                                               __builtin_amdgcn_readfirstlane(k_wrapped(kb + rot, KB) * 128), 0, 0);
     };
     auto dma_scales = [&](int kb, int stage) __attribute__((always_inline)) {     // exactly one DMA in every wave
       const int vo = kb < KB ? vS : GG_OOB_OFFSET;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(dS, GG_LDS_PTR(lds + stage * Cfg::STAGE_BYTES + ldsS), 4, vo,
-                                               __builtin_amdgcn_readfirstlane(kb * 4), 0, 0);
+                                               __builtin_amdgcn_readfirstlane(k_wrapped(kb + rot, KB) * 4), 0, 0);
     };
     // weight fragment j of block kb into slot `slot` of this wave: two slabs of 8 fragment rows
     auto dma_b = [&](int kb, int j, int slot) __attribute__((always_inline)) {
       const bool in = kb < KB;
       uint8_t* dst = bslots + slot * Cfg::B_SLOT_BYTES;
       // all 256 weight rows of the tile exist: only the lane part of the offset needs the bounds check
-      const int so = __builtin_amdgcn_readfirstlane(kb * 128 + j * 4 * K);
+      const int so = __builtin_amdgcn_readfirstlane(k_wrapped(kb + rot, KB) * 128 + j * 4 * K);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(dst), 16, in ? vB0 : GG_OOB_OFFSET, so, 0, 0);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(dst + 1024), 16, in ? vB1 : GG_OOB_OFFSET, so, 0, 0);
     };

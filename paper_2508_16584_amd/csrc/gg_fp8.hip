@@ -173,6 +173,7 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
   args.KB = K / 128;
   args.n_tiles = N / v.BN;
   args.n_chunk = args.n_tiles < 8 ? args.n_tiles : 8;
+  args.rot_mul = (K % 8192 == 4096) ? 4 : 0;   // 7 * 4 < K / 128; a function of K alone (see k_rotation)
 
   // upper bound on the number of tiles for any offsets: every group adds at most one partial m-tile
   const int64_t max_tiles = (M_total / v.BM + G) * (int64_t)args.n_tiles;

@@ -97,8 +97,9 @@ def main():
         A = torch.empty((Mmax, K), dtype=torch.uint8, device=dev)
         SA = torch.empty((Mmax, K // 128), dtype=torch.float32, device=dev)
         for r0 in range(0, Mmax, 8192):
-            x = torch.randn((8192, K), generator=gen, device=dev, dtype=torch.float32)
-            A[r0:r0 + 8192], SA[r0:r0 + 8192] = quantize_a(x)
+            rows = min(8192, Mmax - r0)
+            x = torch.randn((rows, K), generator=gen, device=dev, dtype=torch.float32)
+            A[r0:r0 + rows], SA[r0:r0 + rows] = quantize_a(x)
         for N in Ns:
             B = torch.empty((Gmax, N, K), dtype=torch.uint8, device=dev)
             SB = torch.empty((Gmax, N // 128, K // 128), dtype=torch.float32, device=dev)

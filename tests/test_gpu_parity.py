@@ -75,6 +75,7 @@ def test_tiny_config_every_variant_full_compare():
     ([16, 17, 15, 1, 0, 31, 33], 512, 512),
     ([255, 256, 257, 0, 1], 256, 256),
     ([700], 384, 640),                       # N a multiple of 128 but not of 256
+    ([40, 0, 3, 130], 2304, 4096),           # row pitch 4096: the K loop of a tile starts at a block that depends on its column
 ])
 def test_edge_group_sizes_every_variant(sizes, N, K):
     cfg = WorkloadConfig("edge", 50, len(sizes), K, N, 0, "custom", "latency")
@@ -224,6 +225,7 @@ def test_untrusted_offsets_never_write_outside_C():
 @pytest.mark.parametrize("sizes,N,K", [
     ([130, 0, 1, 128, 253, 127], 256, 256),
     ([5, 300, 64], 256, 512),
+    ([3, 140, 64], 2304, 4096),              # rotated K loops: same order in both paths
 ])
 def test_pad_path_equals_padding_free_path_bitwise(sizes, N, K):
     cfg = WorkloadConfig("pad", 52, len(sizes), K, N, 0, "custom", "latency")
