@@ -28,7 +28,9 @@ the outer accumulation over kb rounds, and its order is fixed (ascending).
 
 Every function here is pinned by tests/test_oracle_pins.py (exact rational
 brute force, closed forms, the paper's worked example, the padded == unpadded
-invariant of Sec. 3.2).  No function is "parity unpinned".
+invariant of Sec. 3.2; the encoder and the row quantiser at the end of the file
+against the library's float8 cast, round trips through the decode table and
+hand-made ties).  No function is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -275,3 +277,69 @@ def two_phase_cover(M_g, block_M=128):
         "phase2_tile": (res - p, res - 1),
         "phase2_group": (M_g - p, M_g - 1),
     }
+
+
+# ----------------------------------------------------------------------------
+# the step before the GEMM: rows -> e4m3 bytes + 1x128 scales, group-contiguous
+# ----------------------------------------------------------------------------
+E4M3_MAX = 448.0
+
+
+def e4m3_encode_rne(y: np.ndarray) -> np.ndarray:
+    """uint8 codes of float32 values with |y| <= 448 (or NaN): round to nearest e4m3 value, ties to the even code.
+
+    Written from the format's definition (the one e4m3_decode_table spells out), not from a bit trick:
+    below 2^-6 the representable values are m * 2^-9 (m = 0..8, 8 being the smallest normal), from there on
+    (1 + m/8) * 2^e.  Every intermediate below is exact in float64.  NaN -> 0x7F (sign dropped).
+    """
+    y = np.asarray(y, dtype=np.float32)
+    a = np.abs(y.astype(np.float64))
+    nan = np.isnan(a)
+    a = np.where(nan, 0.0, a)
+    assert np.all(a <= E4M3_MAX), "values must be clamped to the e4m3 range first"
+    code = np.zeros(a.shape, dtype=np.int64)
+    sub = a < 2.0 ** -6
+    code[sub] = np.rint(a[sub] * 2.0 ** 9).astype(np.int64)          # 0..8; 8 is the code of 2^-6
+    nrm = ~sub
+    m, e = np.frexp(a[nrm])                                         # a = m * 2^e, m in [0.5, 1)
+    e = e - 1                                                       # a = (2m) * 2^e, 2m in [1, 2)
+    steps = np.rint((2.0 * m - 1.0) * 8.0).astype(np.int64)         # 0..8; 8 carries into the exponent
+    code[nrm] = ((e + 7) << 3) + steps                              # the carry is the integer addition
+    code = np.where(nan, 0x7F, code)
+    sign = np.where(np.signbit(y) & ~nan, 0x80, 0)
+    return (code | sign).astype(np.uint8)
+
+
+def quantize_rows(X_bf16_bits: np.ndarray, row_src=None, M_total=None):
+    """Producer of the GEMM's A operand (the kernel the padding-free layout lets run on valid rows only,
+    Sec. 4): output row r is input row row_src[r] (identity if None), cut into 1x128 blocks along K
+    (Sec. 2.1: 1x128 scaling of A); per block, in float32 as the hardware does it:
+
+        amax  = max |x| over the block, NaNs skipped
+        scale = amax / 448 if amax > 0 else 1               (a dequantisation multiplier)
+        byte  = e4m3_encode_rne( clamp(x / scale, -448, 448) ), NaN stays NaN
+
+    A source index outside [0, T) gives a row of zero bytes with scales 1.
+    Returns (uint8 [M_total, K], float32 [M_total, K/128]).
+    """
+    Xb = np.asarray(X_bf16_bits)
+    assert Xb.dtype == np.uint16 and Xb.ndim == 2
+    T, K = Xb.shape
+    assert K % SCALE_BLOCK == 0
+    KB = K // SCALE_BLOCK
+    if row_src is None:
+        row_src = np.arange(T if M_total is None else M_total, dtype=np.int64)
+    row_src = np.asarray(row_src, dtype=np.int64)
+    M = row_src.shape[0]
+    A = np.zeros((M, K), dtype=np.uint8)
+    SA = np.ones((M, KB), dtype=np.float32)
+    ok = (row_src >= 0) & (row_src < T)
+    x = (Xb[row_src[ok]].astype(np.uint32) << 16).view(np.float32).reshape(-1, KB, SCALE_BLOCK)
+    with np.errstate(invalid="ignore", divide="ignore", over="ignore"):
+        amax = np.nan_to_num(np.abs(x), nan=0.0, posinf=np.inf).max(axis=2).astype(np.float32)
+        scale = np.where(amax > 0, amax / np.float32(E4M3_MAX), np.float32(1.0)).astype(np.float32)
+        y = (x / scale[:, :, None]).astype(np.float32)               # float32 division, correctly rounded
+        y = np.where(np.isnan(y), y, np.clip(y, -E4M3_MAX, E4M3_MAX)).astype(np.float32)
+    A[ok] = e4m3_encode_rne(y).reshape(-1, K)
+    SA[ok] = scale
+    return A, SA

@@ -432,3 +432,115 @@ def test_nan_propagates_only_along_its_row_and_column():
     want[4:8, 5] = True
     assert np.array_equal(nan, want)
     assert np.all(res["C"][nan] == 0x7FC0)
+
+
+# ------------------------------------------------------------------------------------------------------------
+# the row quantiser (producer of A and SA) and its encoder
+# ------------------------------------------------------------------------------------------------------------
+def _torch_e4m3(y32: np.ndarray) -> np.ndarray:
+    return torch.from_numpy(np.ascontiguousarray(y32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+
+
+def test_encoder_round_trips_every_code_and_breaks_ties_to_even():
+    table = orc.e4m3_decode_table()
+    codes = np.arange(256, dtype=np.uint8)
+    finite = ~np.isnan(table)
+    # every finite code is a fixed point (minus zero keeps its sign bit)
+    assert np.array_equal(orc.e4m3_encode_rne(table[finite].astype(np.float32)), codes[finite])
+    # midpoints of neighbouring positive codes go to the even code; one float32 step to either side decides
+    pos = np.arange(0, 0x7E, dtype=np.uint8)                       # 0x7E = 448 is the last finite code
+    lo, hi = table[pos], table[pos + 1]
+    mid = ((lo + hi) / 2).astype(np.float32)
+    assert np.all(mid.astype(np.float64) == (lo + hi) / 2)         # exactly representable
+    even = np.where(pos % 2 == 0, pos, pos + 1).astype(np.uint8)
+    assert np.array_equal(orc.e4m3_encode_rne(mid), even)
+    assert np.array_equal(orc.e4m3_encode_rne(-mid), even | 0x80)
+    assert np.array_equal(orc.e4m3_encode_rne(np.nextafter(mid, np.float32(0))), pos)
+    assert np.array_equal(orc.e4m3_encode_rne(np.nextafter(mid, np.float32(1e9))), pos + 1)
+    # NaN of either sign -> 0x7F
+    assert orc.e4m3_encode_rne(np.array([np.nan, -np.nan], np.float32)).tolist() == [0x7F, 0x7F]
+
+
+def test_encoder_matches_the_library_cast_on_every_bf16_value_in_range_and_on_random_float32():
+    bits = np.arange(65536, dtype=np.uint32)
+    v = (bits << 16).view(np.float32)
+    v = v[np.abs(v) <= 448.0]                                       # drops NaN, inf and out-of-range
+    assert v.size > 30000
+    assert np.array_equal(orc.e4m3_encode_rne(v), _torch_e4m3(v))
+    rng = np.random.default_rng(7)
+    y = np.concatenate([rng.uniform(-448, 448, 300000), rng.normal(0, 1, 300000),
+                        rng.uniform(-2.0 ** -5, 2.0 ** -5, 200000), rng.uniform(-2.0 ** -9, 2.0 ** -9, 50000)]).astype(np.float32)
+    assert np.array_equal(orc.e4m3_encode_rne(y), _torch_e4m3(y))
+
+
+def _bf16_bits(x32: np.ndarray) -> np.ndarray:
+    return torch.from_numpy(np.ascontiguousarray(x32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def test_row_quantiser_matches_the_same_recipe_in_library_ops():
+    rng = np.random.default_rng(11)
+    T, K = 37, 512
+    x = (rng.normal(0, 1, (T, K)) * np.exp(rng.normal(0, 3, (T, 1)))).astype(np.float32)
+    x[3, 128:256] = 0.0
+    xb = _bf16_bits(x)
+    A, SA = orc.quantize_rows(xb)
+    xt = torch.from_numpy(xb.view(np.int16)).view(torch.bfloat16).float().view(T, K // 128, 128)
+    amax = xt.abs().amax(dim=2)
+    scale = torch.where(amax > 0, amax / 448.0, torch.ones_like(amax))
+    q = (xt / scale[:, :, None]).clamp(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8).view(T, K)
+    assert np.array_equal(SA, scale.numpy())
+    assert np.array_equal(A, q.numpy())
+    assert np.all(SA[3, 1] == 1.0) and not A[3, 128:256].any()
+
+
+def test_row_quantiser_closed_forms_and_error_bound():
+    table = orc.e4m3_decode_table()
+    rng = np.random.default_rng(12)
+    # a block made of exact e4m3 values times 2^j, its largest magnitude 448 * 2^j: scale = 2^j, codes come back
+    K = 384
+    codes = rng.integers(0, 0x7F, size=(5, K)).astype(np.uint8) | (rng.integers(0, 2, size=(5, K)).astype(np.uint8) << 7)
+    codes[:, ::128] = 0x7E                                           # 448 somewhere in every block
+    j = np.array([-3, 0, 5], dtype=np.float64)                        # one exponent per K block
+    x = table[codes].reshape(5, 3, 128) * (2.0 ** j)[None, :, None]
+    xb = orc.bf16_bits_from_f64(x.reshape(5, K))
+    assert np.array_equal(orc.f64_from_bf16_bits(xb), x.reshape(5, K))   # 4 significant bits: exact in bf16
+    A, SA = orc.quantize_rows(xb)
+    assert np.array_equal(SA, np.broadcast_to((2.0 ** j).astype(np.float32), (5, 3)))
+    assert np.array_equal(A, codes)
+    # generic data: the largest element of a block encodes to +-448, and dequantising is within half a step
+    x = rng.normal(0, 1, (64, 256)).astype(np.float32)
+    xb = _bf16_bits(x)
+    xv = orc.f64_from_bf16_bits(xb)
+    A, SA = orc.quantize_rows(xb)
+    deq = table[A] * np.repeat(SA.astype(np.float64), 128, axis=1)
+    top = np.abs(xv.reshape(64, 2, 128)).argmax(axis=2)
+    for r in range(64):
+        for kb in range(2):
+            assert (A[r, kb * 128 + top[r, kb]] & 0x7F) == 0x7E
+    step = np.maximum(np.abs(xv) * 2.0 ** -4, np.repeat(SA.astype(np.float64), 128, axis=1) * 2.0 ** -10)
+    assert np.all(np.abs(deq - xv) <= step * (1 + 1e-6))
+    assert np.all(np.sign(deq) * np.sign(xv) >= 0)
+
+
+def test_row_quantiser_gather_invalid_sources_and_nan():
+    rng = np.random.default_rng(13)
+    T, K = 20, 256
+    xb = _bf16_bits(rng.normal(0, 2, (T, K)).astype(np.float32))
+    A0, SA0 = orc.quantize_rows(xb)
+    src = np.array([5, 5, 0, 19, -1, 20, 7], dtype=np.int64)
+    A, SA = orc.quantize_rows(xb, src)
+    for r, s in enumerate(src):
+        if 0 <= s < T:
+            assert np.array_equal(A[r], A0[s]) and np.array_equal(SA[r], SA0[s])
+        else:
+            assert not A[r].any() and np.all(SA[r] == 1.0)
+    # a NaN stays a NaN code in its place; the rest of its block is quantised as if it were not there
+    xn = xb.copy()
+    xn[2, 130] = 0x7FC0
+    An, SAn = orc.quantize_rows(xn)
+    xz = xb.copy()
+    xz[2, 130] = 0
+    Az, SAz = orc.quantize_rows(xz)
+    assert An[2, 130] == 0x7F
+    Az[2, 130] = 0x7F
+    assert np.array_equal(An, Az) and np.array_equal(SAn, SAz)
