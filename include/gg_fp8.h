@@ -118,6 +118,17 @@ int gg_fp8_grouped_gemm_padded(const void* A_pad, const float* SA_pad, const voi
 int gg_fp8_unpad(const void* C_pad, const int32_t* group_offsets, const int32_t* padded_offsets,
                  void* C, int G, int64_t M_total, int N, void* stream);
 
+/* The step in front of the GEMM (the kind of kernel Sec. 4 of the paper says keeps working unchanged on the
+ * padding-free layout): quantises rows of X [T, K] bf16 (device) to e4m3 bytes A [M_total, K] and 1x128 block
+ * scales SA [M_total, K/128] (Table 1 and the paragraph below it), written in group-contiguous order:
+ * output row r takes input row row_src[r] (device int32 [M_total]; NULL = identity).  Per (row, 128-wide K
+ * block), in fp32: amax = max |x| (NaNs skipped), scale = amax > 0 ? amax / 448 : 1, byte = e4m3 round to
+ * nearest even of clamp(x / scale, -448, 448); a NaN gives the byte 0x7F.  A source index outside [0, T)
+ * gives a row of zero bytes with scales 1.  X, A 16-byte aligned; K a multiple of 128 (GG_ERR_UNSUPPORTED
+ * otherwise).  The caller owns every buffer; the call is asynchronous on `stream`. */
+int gg_fp8_quantize_rows(const void* X, const int32_t* row_src, void* A, float* SA,
+                         int64_t T, int64_t M_total, int K, void* stream);
+
 /* Debug helper, NOT for the hot path: synchronises `stream`, copies the G+1
  * offsets to the host and returns GG_ERR_OFFSETS unless they are non-decreasing
  * with 0 <= off[0] and off[G] <= M_total. */

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     padded_rows_cap,
     status_str,
     unpad,
+    quantize_rows,
     variant_name,
     version,
     workspace_bytes,

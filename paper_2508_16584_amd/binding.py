@@ -91,6 +91,8 @@ def load_library() -> ctypes.CDLL:
     lib.gg_fp8_unpad.restype = i32
     lib.gg_fp8_unpad.argtypes = [vp, vp, vp, vp, i32, i64, i32, vp]
     lib.gg_fp8_check_offsets.restype = i32
+    lib.gg_fp8_quantize_rows.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp]
+    lib.gg_fp8_quantize_rows.restype = i32
     lib.gg_fp8_check_offsets.argtypes = [vp, i32, i64, vp]
     _lib = lib
     return lib
@@ -99,7 +101,7 @@ def load_library() -> ctypes.CDLL:
 EXPORTED_SYMBOLS = [
     "gg_fp8_version", "gg_fp8_status_str", "gg_fp8_workspace_bytes", "gg_fp8_grouped_gemm",
     "gg_fp8_grouped_gemm_variant", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_auto_variant", "gg_fp8_padded_rows_cap",
-    "gg_fp8_pad", "gg_fp8_grouped_gemm_padded", "gg_fp8_unpad", "gg_fp8_check_offsets",
+    "gg_fp8_pad", "gg_fp8_grouped_gemm_padded", "gg_fp8_unpad", "gg_fp8_quantize_rows", "gg_fp8_check_offsets",
 ]
 
 
@@ -253,6 +255,27 @@ def unpad(C_pad, group_offsets, padded_offsets, M_total: int, C=None, stream=Non
     _check(lib.gg_fp8_unpad(_ptr(C_pad), _ptr(group_offsets), _ptr(padded_offsets), _ptr(C), G, M_total, N,
                             _stream(stream)))
     return C
+
+
+def quantize_rows(X, row_src=None, M_total=None, A=None, SA=None, stream=None):
+    """gg_fp8_quantize_rows: X [T, K] bf16 -> (A uint8 [M_total, K], SA float32 [M_total, K/128]); output row r
+    is input row row_src[r] (int32 [M_total] on the device; None = identity)."""
+    lib = load_library()
+    _want(X, "X", torch.bfloat16, 2)
+    T, K = X.shape
+    if row_src is not None:
+        _want(row_src, "row_src", torch.int32, 1)
+        M_total = row_src.shape[0]
+    elif M_total is None:
+        M_total = T
+    if A is None:
+        A = torch.empty((M_total, K), dtype=torch.uint8, device=X.device)
+    if SA is None:
+        SA = torch.empty((M_total, K // 128), dtype=torch.float32, device=X.device)
+    _want(A, "A", torch.uint8, 2)
+    _want(SA, "SA", torch.float32, 2)
+    _check(lib.gg_fp8_quantize_rows(_ptr(X), _ptr(row_src), _ptr(A), _ptr(SA), T, M_total, K, _stream(stream)))
+    return A, SA
 
 
 def check_offsets(group_offsets, M_total: int, stream=None) -> int:

@@ -12,6 +12,7 @@
 #include "gemm_kernel.h"
 #include "gemm_kernel_rb.h"
 #include "pad_kernels.h"
+#include "quant_kernel.h"
 
 namespace {
 
@@ -290,6 +291,21 @@ int gg_fp8_unpad(const void* C_pad, const int32_t* group_offsets, const int32_t*
   hipLaunchKernelGGL(gg::gg_unpad_rows_kernel, dim3((unsigned)grid), dim3(gg::PAD_THREADS), 0,
                      static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(C_pad), group_offsets, padded_offsets,
                      static_cast<uint16_t*>(C), G, (int)M_total, N);
+  return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
+}
+
+int gg_fp8_quantize_rows(const void* X, const int32_t* row_src, void* A, float* SA, int64_t T, int64_t M_total, int K,
+                         void* stream) {
+  if (T < 0 || M_total < 0 || K <= 0) return GG_ERR_SHAPE;
+  if (M_total > 0x7FFFFFFFLL || T > 0x7FFFFFFFLL || K > (1 << 22)) return GG_ERR_SHAPE;
+  if (K % 128 != 0) return GG_ERR_UNSUPPORTED;
+  if (M_total == 0) return GG_OK;
+  if (!A || !SA || (!X && T > 0)) return GG_ERR_NULL;
+  int64_t grid = (int64_t)device_cus() * 8;
+  if (grid > M_total) grid = M_total;
+  hipLaunchKernelGGL(gg::gg_quantize_rows_kernel, dim3((unsigned)grid), dim3(gg::Q_THREADS), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(X), row_src,
+                     static_cast<uint8_t*>(A), SA, T, (int)M_total, K, K / 128);
   return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
 }
 
