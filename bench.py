@@ -41,12 +41,84 @@ def algorithmic_bytes(sizes, N, K):
     return M * K + M * KB * 4 + nonempty * N * K + nonempty * NB * KB * 4 + M * N * 2
 
 
+def bench_quantize_rows(args, cfg, dev):
+    """bf16 activations [M_total, K] of the workload -> e4m3 + 1x128 scales, gathered by a routing permutation.
+    HBM-bound: 2K bytes read, K + 4K/128 written per row, plus 4 bytes of index."""
+    import numpy as np
+    import torch
+
+    import paper_2508_16584_amd as gg
+    from workloads import group_sizes
+
+    sizes = group_sizes(cfg, cfg.seed)
+    M, K = int(np.sum(sizes)), cfg.K
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg.seed)
+    alg_bytes = M * (2 * K + K + 4 * (K // 128) + 4)
+    copies = args.copies or max(2, min(8, int(np.ceil(1.0e9 / alg_bytes))))
+    rng = np.random.default_rng(cfg.seed)
+    sets = []
+    for _ in range(copies):
+        X = torch.randn((M, K), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        src = torch.from_numpy(rng.permutation(M).astype(np.int32)).to(dev)
+        sets.append((X, src, torch.empty((M, K), dtype=torch.uint8, device=dev),
+                     torch.empty((M, K // 128), dtype=torch.float32, device=dev)))
+
+    def step(i):
+        X, src, A, SA = sets[i % copies]
+        gg.quantize_rows(X, src, A=A, SA=SA)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        step(i)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    kern_ms = np.array([a.elapsed_time(b) for a, b in ev])
+    achieved = alg_bytes / (float(kern_ms.mean()) * 1e-3) / 1e9
+    out = {
+        "metric": "algorithmic GB/s, bf16 rows -> e4m3 + 1x128 scales gathered into group order",
+        "value": round(alg_bytes / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 in, fp32 arithmetic, e4m3 + fp32 scales out", "data": "synthetic",
+        "config": {"workload": args.workload + " activations", "op": "quantize_rows", "M_total": M, "K": K,
+                   "input_copies_rotated": copies},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "gg_quantize_rows_kernel",
+                     "kernel_avg_ms": round(float(kern_ms.mean()), 4), "kernel_min_ms": round(float(kern_ms.min()), 4),
+                     "algorithmic_bytes": int(alg_bytes)},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import gg_oracle
+        X, src, A, SA = sets[0]
+        rows = np.arange(0, M, max(1, M // 4096))[:4096]
+        xb = X.view(torch.int16).cpu().numpy().view(np.uint16)
+        src_h = src.cpu().numpy()[rows]
+        t0 = time.perf_counter()
+        A_ref, SA_ref = gg_oracle.quantize_rows(xb, src_h)
+        cpu_s = time.perf_counter() - t0
+        same = bool(np.array_equal(A.cpu().numpy()[rows], A_ref) and np.array_equal(SA.cpu().numpy()[rows], SA_ref))
+        out["cpu_baseline"] = {"value": round(len(rows) * (3 * K + 4 * (K // 128) + 4) / cpu_s / 1e9, 4), "unit": "GB/s",
+                               "cores": 1, "kind": "oracle",
+                               "sample": f"{len(rows)} of the {M} output rows, NumPy oracle, {cpu_s:.1f} s",
+                               "gpu_bits_equal_oracle_on_sample": same}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="gate_up")
+    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows"],
+                    help="grouped_gemm: the hot path (default, the headline metric); quantize_rows: the producer of its "
+                         "A operand on the same workload's activation shape")
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--copies", type=int, default=0, help="input copies to rotate over (0 = enough for 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -72,6 +144,9 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     cfg = CONFIGS[args.workload]
+    if args.op == "quantize_rows":
+        bench_quantize_rows(args, cfg, dev)
+        return
     p = make_problem(cfg, device=dev)
     G, M, N, K = p["G"], p["M_total"], p["N"], p["K"]
     sizes = p["sizes"]

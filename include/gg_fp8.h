@@ -122,9 +122,10 @@ int gg_fp8_unpad(const void* C_pad, const int32_t* group_offsets, const int32_t*
  * padding-free layout): quantises rows of X [T, K] bf16 (device) to e4m3 bytes A [M_total, K] and 1x128 block
  * scales SA [M_total, K/128] (Table 1 and the paragraph below it), written in group-contiguous order:
  * output row r takes input row row_src[r] (device int32 [M_total]; NULL = identity).  Per (row, 128-wide K
- * block), in fp32: amax = max |x| (NaNs skipped), scale = amax > 0 ? amax / 448 : 1, byte = e4m3 round to
- * nearest even of clamp(x / scale, -448, 448); a NaN gives the byte 0x7F.  A source index outside [0, T)
- * gives a row of zero bytes with scales 1.  X, A 16-byte aligned; K a multiple of 128 (GG_ERR_UNSUPPORTED
+ * block), in fp32: amax = max(max |x| with NaNs skipped, 2^-100), scale = amax / 448, byte = e4m3 round to
+ * nearest even of clamp(x * (448 / amax), -448, 448); a NaN gives the byte 0x7F (so does an infinity: its
+ * block has scale inf, its finite elements become 0).  A source index outside [0, T) stands for a row of
+ * zeros (zero bytes, scales 2^-100 / 448).  X, A 16-byte aligned; K a multiple of 128 (GG_ERR_UNSUPPORTED
  * otherwise).  The caller owns every buffer; the call is asynchronous on `stream`. */
 int gg_fp8_quantize_rows(const void* X, const int32_t* row_src, void* A, float* SA,
                          int64_t T, int64_t M_total, int K, void* stream);

@@ -310,16 +310,22 @@ def e4m3_encode_rne(y: np.ndarray) -> np.ndarray:
     return (code | sign).astype(np.uint8)
 
 
+AMAX_FLOOR = 2.0 ** -100     # blocks whose largest magnitude is below this are quantised as if it were this
+
+
 def quantize_rows(X_bf16_bits: np.ndarray, row_src=None, M_total=None):
     """Producer of the GEMM's A operand (the kernel the padding-free layout lets run on valid rows only,
     Sec. 4): output row r is input row row_src[r] (identity if None), cut into 1x128 blocks along K
-    (Sec. 2.1: 1x128 scaling of A); per block, in float32 as the hardware does it:
+    (Sec. 2.1: 1x128 scaling of A).  The paper does not define the quantiser; the recipe fixed here is the
+    usual one, per block and in float32 as the hardware does it:
 
-        amax  = max |x| over the block, NaNs skipped
-        scale = amax / 448 if amax > 0 else 1               (a dequantisation multiplier)
-        byte  = e4m3_encode_rne( clamp(x / scale, -448, 448) ), NaN stays NaN
+        amax  = max( max |x| over the block with NaNs skipped, 2^-100 )
+        scale = amax / 448                                    (a dequantisation multiplier)
+        inv   = 448 / amax
+        byte  = e4m3_encode_rne( clamp(x * inv, -448, 448) ), NaN stays NaN (0x7F)
 
-    A source index outside [0, T) gives a row of zero bytes with scales 1.
+    (an infinite amax gives scale = inf, inv = 0: finite elements become 0, infinite ones NaN.)
+    A source index outside [0, T) stands for a row of zeros (zero bytes, scales 2^-100 / 448).
     Returns (uint8 [M_total, K], float32 [M_total, K/128]).
     """
     Xb = np.asarray(X_bf16_bits)
@@ -332,13 +338,15 @@ def quantize_rows(X_bf16_bits: np.ndarray, row_src=None, M_total=None):
     row_src = np.asarray(row_src, dtype=np.int64)
     M = row_src.shape[0]
     A = np.zeros((M, K), dtype=np.uint8)
-    SA = np.ones((M, KB), dtype=np.float32)
+    SA = np.full((M, KB), np.float32(AMAX_FLOOR) / np.float32(E4M3_MAX), dtype=np.float32)
     ok = (row_src >= 0) & (row_src < T)
     x = (Xb[row_src[ok]].astype(np.uint32) << 16).view(np.float32).reshape(-1, KB, SCALE_BLOCK)
     with np.errstate(invalid="ignore", divide="ignore", over="ignore"):
         amax = np.nan_to_num(np.abs(x), nan=0.0, posinf=np.inf).max(axis=2).astype(np.float32)
-        scale = np.where(amax > 0, amax / np.float32(E4M3_MAX), np.float32(1.0)).astype(np.float32)
-        y = (x / scale[:, :, None]).astype(np.float32)               # float32 division, correctly rounded
+        amax = np.maximum(amax, np.float32(AMAX_FLOOR))
+        scale = (amax / np.float32(E4M3_MAX)).astype(np.float32)     # float32 divisions, correctly rounded
+        inv = (np.float32(E4M3_MAX) / amax).astype(np.float32)
+        y = (x * inv[:, :, None]).astype(np.float32)                 # one float32 rounding per element
         y = np.where(np.isnan(y), y, np.clip(y, -E4M3_MAX, E4M3_MAX)).astype(np.float32)
     A[ok] = e4m3_encode_rne(y).reshape(-1, K)
     SA[ok] = scale

@@ -103,7 +103,7 @@ def test_zero_rows_and_empty_calls():
     xb = np.zeros((4, 256), np.uint16)
     xb[1] = 0x8000                                                # minus zeros
     A, SA = run_gpu(xb)
-    assert (SA == 1.0).all() and not A[0].any() and (A[1] == 0x80).all()
+    assert (SA == np.float32(2.0 ** -100) / np.float32(448.0)).all() and not A[0].any() and (A[1] == 0x80).all()
     X = torch.zeros((0, 256), dtype=torch.bfloat16, device=DEV)
     A, SA = gg.quantize_rows(X)
     assert A.shape == (0, 256) and SA.shape == (0, 2)

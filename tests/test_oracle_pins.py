@@ -485,12 +485,13 @@ def test_row_quantiser_matches_the_same_recipe_in_library_ops():
     xb = _bf16_bits(x)
     A, SA = orc.quantize_rows(xb)
     xt = torch.from_numpy(xb.view(np.int16)).view(torch.bfloat16).float().view(T, K // 128, 128)
-    amax = xt.abs().amax(dim=2)
-    scale = torch.where(amax > 0, amax / 448.0, torch.ones_like(amax))
-    q = (xt / scale[:, :, None]).clamp(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8).view(T, K)
+    amax = xt.abs().amax(dim=2).clamp_min(2.0 ** -100)
+    scale = amax / 448.0
+    inv = torch.full_like(amax, 448.0) / amax        # tensor / tensor: a true division (scalar / tensor multiplies by a reciprocal)
+    q = (xt * inv[:, :, None]).clamp(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8).view(T, K)
     assert np.array_equal(SA, scale.numpy())
     assert np.array_equal(A, q.numpy())
-    assert np.all(SA[3, 1] == 1.0) and not A[3, 128:256].any()
+    assert SA[3, 1] == np.float32(2.0 ** -100) / np.float32(448.0) and not A[3, 128:256].any()
 
 
 def test_row_quantiser_closed_forms_and_error_bound():
@@ -533,7 +534,7 @@ def test_row_quantiser_gather_invalid_sources_and_nan():
         if 0 <= s < T:
             assert np.array_equal(A[r], A0[s]) and np.array_equal(SA[r], SA0[s])
         else:
-            assert not A[r].any() and np.all(SA[r] == 1.0)
+            assert not A[r].any() and np.all(SA[r] == np.float32(2.0 ** -100) / np.float32(448.0))
     # a NaN stays a NaN code in its place; the rest of its block is quantised as if it were not there
     xn = xb.copy()
     xn[2, 130] = 0x7FC0
