@@ -41,6 +41,22 @@ def algorithmic_bytes(sizes, N, K):
     return M * K + M * KB * 4 + nonempty * N * K + nonempty * NB * KB * 4 + M * N * 2
 
 
+# the same for gg_quantize_rows_kernel (profiles/quantize_rows_kernel_activation_shapes.md)
+MEASURED_TRAFFIC_BYTES_QUANT = {"gate_up": int((57629.6484375 / 0.5 + 59417.76171875) * 1024),
+                                "many_small": int((230440.953125 / 0.5 + 238107.72265625) * 1024)}
+
+
+def copy_calibration(dev):
+    """A plain device copy of known size (reads 1 GiB, writes 1 GiB), for scaling FETCH_SIZE / WRITE_SIZE."""
+    import torch
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def bench_quantize_rows(args, cfg, dev):
     """bf16 activations [M_total, K] of the workload -> e4m3 + 1x128 scales, gathered by a routing permutation.
     HBM-bound: 2K bytes read, K + 4K/128 written per row, plus 4 bytes of index."""
@@ -80,6 +96,8 @@ def bench_quantize_rows(args, cfg, dev):
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     kern_ms = np.array([a.elapsed_time(b) for a, b in ev])
+    if args.copy_calibration:
+        copy_calibration(dev)
     achieved = alg_bytes / (float(kern_ms.mean()) * 1e-3) / 1e9
     out = {
         "metric": "algorithmic GB/s, bf16 rows -> e4m3 + 1x128 scales gathered into group order",
@@ -89,7 +107,8 @@ def bench_quantize_rows(args, cfg, dev):
         "config": {"workload": args.workload + " activations", "op": "quantize_rows", "M_total": M, "K": K,
                    "input_copies_rotated": copies},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "gg_quantize_rows_kernel",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES_QUANT.get(args.workload), "kernel": "gg_quantize_rows_kernel",
                      "kernel_avg_ms": round(float(kern_ms.mean()), 4), "kernel_min_ms": round(float(kern_ms.min()), 4),
                      "algorithmic_bytes": int(alg_bytes)},
     }
@@ -185,12 +204,7 @@ def main():
     kern_avg_ms = float(kern_ms.mean())
 
     if args.copy_calibration:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)          # known size: reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del src, dst
+        copy_calibration(dev)
 
     # hot-cache number (same buffers every step), secondary
     for _ in range(3):
