@@ -46,6 +46,9 @@ MEASURED_TRAFFIC_BYTES_QUANT = {"gate_up": int((57629.6484375 / 0.5 + 59417.7617
                                 "many_small": int((230440.953125 / 0.5 + 238107.72265625) * 1024)}
 
 
+MEASURED_TRAFFIC_BYTES_SWIGLU = {}
+
+
 def copy_calibration(dev):
     """A plain device copy of known size (reads 1 GiB, writes 1 GiB), for scaling FETCH_SIZE / WRITE_SIZE."""
     import torch
@@ -58,31 +61,39 @@ def copy_calibration(dev):
 
 
 def bench_quantize_rows(args, cfg, dev):
-    """bf16 activations [M_total, K] of the workload -> e4m3 + 1x128 scales, gathered by a routing permutation.
-    HBM-bound: 2K bytes read, K + 4K/128 written per row, plus 4 bytes of index."""
+    """quantize_rows: bf16 activations [M_total, K] of the workload -> e4m3 + 1x128 scales, gathered by a routing
+    permutation (2K bytes read, K + 4K/128 written per row, plus 4 bytes of index).
+    swiglu_quantize_rows: the workload's GEMM output [M_total, N] bf16 (gate | up) -> e4m3 [M_total, N/2] + scales
+    (2N bytes read, N/2 + 4(N/2)/128 written per row).  Both are HBM-bound."""
     import numpy as np
     import torch
 
     import paper_2508_16584_amd as gg
     from workloads import group_sizes
 
+    fused = args.op == "swiglu_quantize_rows"
     sizes = group_sizes(cfg, cfg.seed)
-    M, K = int(np.sum(sizes)), cfg.K
+    M = int(np.sum(sizes))
+    width_in = cfg.N if fused else cfg.K                      # columns of the bf16 input
+    width_out = cfg.N // 2 if fused else cfg.K                # columns of the e4m3 output
     gen = torch.Generator(device=dev)
     gen.manual_seed(cfg.seed)
-    alg_bytes = M * (2 * K + K + 4 * (K // 128) + 4)
+    alg_bytes = M * (2 * width_in + width_out + 4 * (width_out // 128) + (0 if fused else 4))
     copies = args.copies or max(2, min(8, int(np.ceil(1.0e9 / alg_bytes))))
     rng = np.random.default_rng(cfg.seed)
     sets = []
     for _ in range(copies):
-        X = torch.randn((M, K), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
-        src = torch.from_numpy(rng.permutation(M).astype(np.int32)).to(dev)
-        sets.append((X, src, torch.empty((M, K), dtype=torch.uint8, device=dev),
-                     torch.empty((M, K // 128), dtype=torch.float32, device=dev)))
+        X = (torch.randn((M, width_in), generator=gen, device=dev, dtype=torch.float32) * (1.7 if fused else 1.0)).to(torch.bfloat16)
+        src = None if fused else torch.from_numpy(rng.permutation(M).astype(np.int32)).to(dev)
+        sets.append((X, src, torch.empty((M, width_out), dtype=torch.uint8, device=dev),
+                     torch.empty((M, width_out // 128), dtype=torch.float32, device=dev)))
 
     def step(i):
         X, src, A, SA = sets[i % copies]
-        gg.quantize_rows(X, src, A=A, SA=SA)
+        if fused:
+            gg.swiglu_quantize_rows(X, A=A, SA=SA)
+        else:
+            gg.quantize_rows(X, src, A=A, SA=SA)
 
     for i in range(args.warmup):
         step(i)
@@ -99,16 +110,18 @@ def bench_quantize_rows(args, cfg, dev):
     if args.copy_calibration:
         copy_calibration(dev)
     achieved = alg_bytes / (float(kern_ms.mean()) * 1e-3) / 1e9
+    traffic = (MEASURED_TRAFFIC_BYTES_SWIGLU if fused else MEASURED_TRAFFIC_BYTES_QUANT).get(args.workload)
     out = {
-        "metric": "algorithmic GB/s, bf16 rows -> e4m3 + 1x128 scales gathered into group order",
+        "metric": "algorithmic GB/s, " + ("bf16 gate|up rows -> silu(gate)*up -> e4m3 + 1x128 scales" if fused else
+                                          "bf16 rows -> e4m3 + 1x128 scales gathered into group order"),
         "value": round(alg_bytes / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 in, fp32 arithmetic, e4m3 + fp32 scales out", "data": "synthetic",
-        "config": {"workload": args.workload + " activations", "op": "quantize_rows", "M_total": M, "K": K,
-                   "input_copies_rotated": copies},
+        "config": {"workload": args.workload + (" output" if fused else " activations"), "op": args.op, "M_total": M,
+                   "columns_in": width_in, "columns_out": width_out, "input_copies_rotated": copies},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES_QUANT.get(args.workload), "kernel": "gg_quantize_rows_kernel",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "kernel": "gg_swiglu_quantize_rows_kernel" if fused else "gg_quantize_rows_kernel",
                      "kernel_avg_ms": round(float(kern_ms.mean()), 4), "kernel_min_ms": round(float(kern_ms.min()), 4),
                      "algorithmic_bytes": int(alg_bytes)},
     }
@@ -117,15 +130,17 @@ def bench_quantize_rows(args, cfg, dev):
         X, src, A, SA = sets[0]
         rows = np.arange(0, M, max(1, M // 4096))[:4096]
         xb = X.view(torch.int16).cpu().numpy().view(np.uint16)
-        src_h = src.cpu().numpy()[rows]
         t0 = time.perf_counter()
-        A_ref, SA_ref = gg_oracle.quantize_rows(xb, src_h)
+        if fused:
+            _, A_ref, SA_ref = gg_oracle.swiglu_quantize_rows(xb[rows])
+        else:
+            A_ref, SA_ref = gg_oracle.quantize_rows(xb, src.cpu().numpy()[rows])
         cpu_s = time.perf_counter() - t0
-        same = bool(np.array_equal(A.cpu().numpy()[rows], A_ref) and np.array_equal(SA.cpu().numpy()[rows], SA_ref))
-        out["cpu_baseline"] = {"value": round(len(rows) * (3 * K + 4 * (K // 128) + 4) / cpu_s / 1e9, 4), "unit": "GB/s",
+        same = float(np.mean(A.cpu().numpy()[rows] == A_ref))
+        out["cpu_baseline"] = {"value": round(len(rows) * alg_bytes / M / cpu_s / 1e9, 4), "unit": "GB/s",
                                "cores": 1, "kind": "oracle",
                                "sample": f"{len(rows)} of the {M} output rows, NumPy oracle, {cpu_s:.1f} s",
-                               "gpu_bits_equal_oracle_on_sample": same}
+                               "gpu_bytes_equal_oracle_on_sample": round(same, 6)}
     print(json.dumps(out))
 
 
@@ -135,9 +150,10 @@ def main():
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="gate_up")
-    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows"],
+    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows", "swiglu_quantize_rows"],
                     help="grouped_gemm: the hot path (default, the headline metric); quantize_rows: the producer of its "
-                         "A operand on the same workload's activation shape")
+                         "A operand on the same workload's activation shape; swiglu_quantize_rows: activation + quantiser "
+                         "on the workload's output shape [M_total, N] (N = 2 x intermediate width)")
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--copies", type=int, default=0, help="input copies to rotate over (0 = enough for 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -163,7 +179,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     cfg = CONFIGS[args.workload]
-    if args.op == "quantize_rows":
+    if args.op in ("quantize_rows", "swiglu_quantize_rows"):
         bench_quantize_rows(args, cfg, dev)
         return
     p = make_problem(cfg, device=dev)

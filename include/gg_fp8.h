@@ -130,6 +130,16 @@ int gg_fp8_unpad(const void* C_pad, const int32_t* group_offsets, const int32_t*
 int gg_fp8_quantize_rows(const void* X, const int32_t* row_src, void* A, float* SA,
                          int64_t T, int64_t M_total, int K, void* stream);
 
+/* The step between the two grouped GEMMs of an expert MLP, on the group-contiguous rows the first GEMM wrote
+ * (again a kernel that Sec. 4 of the paper says runs unchanged on the padding-free layout): H [M_total, 2*I]
+ * bf16 (device), columns [0, I) the gate projection and [I, 2*I) the up projection;
+ * act = bf16 round-to-nearest-even of silu(gate) * up, silu(g) = g / (1 + exp(-g)), evaluated in fp32; then
+ * A [M_total, I] e4m3 and SA [M_total, I/128] from act by exactly the recipe of gg_fp8_quantize_rows.
+ * act_out (bf16 [M_total, I], device) receives act when it is not NULL.  I a multiple of 128
+ * (GG_ERR_UNSUPPORTED otherwise); H, A, act_out 16-byte aligned.  Asynchronous on `stream`. */
+int gg_fp8_swiglu_quantize_rows(const void* H, void* A, float* SA, void* act_out,
+                                int64_t M_total, int I, void* stream);
+
 /* Debug helper, NOT for the hot path: synchronises `stream`, copies the G+1
  * offsets to the host and returns GG_ERR_OFFSETS unless they are non-decreasing
  * with 0 <= off[0] and off[G] <= M_total. */

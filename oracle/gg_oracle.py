@@ -30,7 +30,7 @@ Every function here is pinned by tests/test_oracle_pins.py (exact rational
 brute force, closed forms, the paper's worked example, the padded == unpadded
 invariant of Sec. 3.2; the encoder and the row quantiser at the end of the file
 against the library's float8 cast, round trips through the decode table and
-hand-made ties).  No function is "parity unpinned".
+hand-made ties; the activation against the library's silu and closed forms).  No function is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -351,3 +351,29 @@ def quantize_rows(X_bf16_bits: np.ndarray, row_src=None, M_total=None):
     A[ok] = e4m3_encode_rne(y).reshape(-1, K)
     SA[ok] = scale
     return A, SA
+
+
+def swiglu_rows(H_bf16_bits: np.ndarray) -> np.ndarray:
+    """The activation between the two grouped GEMMs of an expert MLP, on group-contiguous rows: H [M, 2I] is the
+    output of the first GEMM (columns [0, I): gate projection, [I, 2I): up projection),
+
+        act[r, j] = bf16_round_to_nearest_even( silu(H[r, j]) * H[r, I + j] ),   silu(g) = g / (1 + exp(-g))
+
+    evaluated in float64 and rounded once.  Returns bf16 bits [M, I].  (Not in the paper; it is one of the
+    neighbouring kernels that Sec. 4 says run unchanged on the padding-free layout.)
+    """
+    Hb = np.asarray(H_bf16_bits)
+    assert Hb.dtype == np.uint16 and Hb.ndim == 2 and Hb.shape[1] % 2 == 0
+    half = Hb.shape[1] // 2
+    g = f64_from_bf16_bits(Hb[:, :half])
+    u = f64_from_bf16_bits(Hb[:, half:])
+    with np.errstate(over="ignore", invalid="ignore"):
+        act = g / (1.0 + np.exp(-g)) * u
+    return bf16_bits_from_f64(act)
+
+
+def swiglu_quantize_rows(H_bf16_bits: np.ndarray):
+    """swiglu_rows followed by quantize_rows on its bf16 result: (act bits, A, SA)."""
+    act = swiglu_rows(H_bf16_bits)
+    A, SA = quantize_rows(act)
+    return act, A, SA

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     status_str,
     unpad,
     quantize_rows,
+    swiglu_quantize_rows,
     variant_name,
     version,
     workspace_bytes,

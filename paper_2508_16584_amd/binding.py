@@ -93,6 +93,8 @@ def load_library() -> ctypes.CDLL:
     lib.gg_fp8_check_offsets.restype = i32
     lib.gg_fp8_quantize_rows.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp]
     lib.gg_fp8_quantize_rows.restype = i32
+    lib.gg_fp8_swiglu_quantize_rows.argtypes = [vp, vp, vp, vp, i64, i32, vp]
+    lib.gg_fp8_swiglu_quantize_rows.restype = i32
     lib.gg_fp8_check_offsets.argtypes = [vp, i32, i64, vp]
     _lib = lib
     return lib
@@ -101,7 +103,7 @@ def load_library() -> ctypes.CDLL:
 EXPORTED_SYMBOLS = [
     "gg_fp8_version", "gg_fp8_status_str", "gg_fp8_workspace_bytes", "gg_fp8_grouped_gemm",
     "gg_fp8_grouped_gemm_variant", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_auto_variant", "gg_fp8_padded_rows_cap",
-    "gg_fp8_pad", "gg_fp8_grouped_gemm_padded", "gg_fp8_unpad", "gg_fp8_quantize_rows", "gg_fp8_check_offsets",
+    "gg_fp8_pad", "gg_fp8_grouped_gemm_padded", "gg_fp8_unpad", "gg_fp8_quantize_rows", "gg_fp8_swiglu_quantize_rows", "gg_fp8_check_offsets",
 ]
 
 
@@ -276,6 +278,28 @@ def quantize_rows(X, row_src=None, M_total=None, A=None, SA=None, stream=None):
     _want(SA, "SA", torch.float32, 2)
     _check(lib.gg_fp8_quantize_rows(_ptr(X), _ptr(row_src), _ptr(A), _ptr(SA), T, M_total, K, _stream(stream)))
     return A, SA
+
+
+def swiglu_quantize_rows(H, A=None, SA=None, act_out=None, want_act=False, stream=None):
+    """gg_fp8_swiglu_quantize_rows: H [M, 2I] bf16 -> (A uint8 [M, I], SA float32 [M, I/128], act bf16 [M, I] or None)."""
+    lib = load_library()
+    _want(H, "H", torch.bfloat16, 2)
+    M, two_i = H.shape
+    if two_i % 2:
+        raise ValueError("H must have an even number of columns")
+    inter = two_i // 2
+    if A is None:
+        A = torch.empty((M, inter), dtype=torch.uint8, device=H.device)
+    if SA is None:
+        SA = torch.empty((M, inter // 128), dtype=torch.float32, device=H.device)
+    if act_out is None and want_act:
+        act_out = torch.empty((M, inter), dtype=torch.bfloat16, device=H.device)
+    _want(A, "A", torch.uint8, 2)
+    _want(SA, "SA", torch.float32, 2)
+    if act_out is not None:
+        _want(act_out, "act_out", torch.bfloat16, 2)
+    _check(lib.gg_fp8_swiglu_quantize_rows(_ptr(H), _ptr(A), _ptr(SA), _ptr(act_out), M, inter, _stream(stream)))
+    return A, SA, act_out
 
 
 def check_offsets(group_offsets, M_total: int, stream=None) -> int:

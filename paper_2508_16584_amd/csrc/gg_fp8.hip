@@ -302,10 +302,24 @@ int gg_fp8_quantize_rows(const void* X, const int32_t* row_src, void* A, float* 
   if (M_total == 0) return GG_OK;
   if (!A || !SA || (!X && T > 0)) return GG_ERR_NULL;
   int64_t grid = (int64_t)device_cus() * 8;
-  if (grid > M_total) grid = M_total;
+  if (grid > (M_total + 1) / 2) grid = (M_total + 1) / 2;     // a workgroup takes rows in pairs
   hipLaunchKernelGGL(gg::gg_quantize_rows_kernel, dim3((unsigned)grid), dim3(gg::Q_THREADS), 0,
                      static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(X), row_src,
                      static_cast<uint8_t*>(A), SA, T, (int)M_total, K, K / 128);
+  return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
+}
+
+int gg_fp8_swiglu_quantize_rows(const void* H, void* A, float* SA, void* act_out, int64_t M_total, int I, void* stream) {
+  if (M_total < 0 || I <= 0) return GG_ERR_SHAPE;
+  if (M_total > 0x7FFFFFFFLL || I > (1 << 21)) return GG_ERR_SHAPE;
+  if (I % 128 != 0) return GG_ERR_UNSUPPORTED;
+  if (M_total == 0) return GG_OK;
+  if (!H || !A || !SA) return GG_ERR_NULL;
+  int64_t grid = (int64_t)device_cus() * 8;
+  if (grid > (M_total + 1) / 2) grid = (M_total + 1) / 2;     // a workgroup takes rows in pairs
+  hipLaunchKernelGGL(gg::gg_swiglu_quantize_rows_kernel, dim3((unsigned)grid), dim3(gg::Q_THREADS), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(H), static_cast<uint8_t*>(A), SA,
+                     static_cast<uint16_t*>(act_out), (int)M_total, I, I / 128);
   return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
 }
 

@@ -97,24 +97,107 @@ __device__ __forceinline__ void quantize_block(const q_v4i raw, uint8_t* dst, fl
   if (sub == 0) *dst_scale = scale;
 }
 
+// A workgroup works on two rows at a time (r and r + gridDim.x): their 2 * KB blocks are numbered through and
+// taken 32 per pass, so that short rows (KB <= 16) still fill both load slots of every lane.
+struct RowPairSlot {
+  bool valid;     // this 16-lane group has a block in this pass
+  int row, blk;
+};
+__device__ __forceinline__ RowPairSlot row_pair_slot(int v, int KB, int r, int r2, int M_total) {
+  const bool second = v >= KB;
+  RowPairSlot s;
+  s.row = second ? r2 : r;
+  s.blk = v - (second ? KB : 0);
+  s.valid = v < 2 * KB && s.row < M_total;
+  return s;
+}
+
 __global__ void __launch_bounds__(Q_THREADS) gg_quantize_rows_kernel(const uint16_t* __restrict__ X,
                                                                      const int32_t* __restrict__ row_src,
                                                                      uint8_t* __restrict__ A, float* __restrict__ SA,
                                                                      int64_t T, int M_total, int K, int KB) {
   const int grp = threadIdx.x >> 4, sub = threadIdx.x & 15;
-  for (int r = blockIdx.x; r < M_total; r += gridDim.x) {
-    const int64_t s = row_src ? (int64_t)row_src[r] : (int64_t)r;
-    const bool ok = s >= 0 && s < T;                       // a source outside [0, T) stands for a row of zeros
-    const uint16_t* src = X + (ok ? s : 0) * K;
-    uint8_t* dstA = A + (int64_t)r * K;
-    float* dstS = SA + (int64_t)r * KB;
-    for (int kb0 = 0; kb0 < KB; kb0 += 32) {
-      const int kbA = kb0 + grp, kbB = kb0 + 16 + grp;   // uniform over the 16 lanes of a row
+  for (int64_t r64 = blockIdx.x; r64 < M_total; r64 += 2 * (int64_t)gridDim.x) {
+    const int r = (int)r64;
+    const int r2 = r64 + gridDim.x < M_total ? (int)(r64 + gridDim.x) : M_total;     // M_total = no second row
+    const int64_t s1 = row_src ? (int64_t)row_src[r] : (int64_t)r;
+    const int64_t s2 = r2 < M_total ? (row_src ? (int64_t)row_src[r2] : (int64_t)r2) : -1;
+    for (int v0 = 0; v0 < 2 * KB; v0 += 32) {
+      const RowPairSlot a = row_pair_slot(v0 + grp, KB, r, r2, M_total);            // uniform over the 16 lanes of a row
+      const RowPairSlot b = row_pair_slot(v0 + 16 + grp, KB, r, r2, M_total);
+      const int64_t sa = a.row == r ? s1 : s2, sb = b.row == r ? s1 : s2;
+      // a source outside [0, T) stands for a row of zeros
       q_v4i rawA = {0, 0, 0, 0}, rawB = {0, 0, 0, 0};
-      if (ok && kbA < KB) rawA = *(const q_v4i*)(src + kbA * 128 + sub * 8);
-      if (ok && kbB < KB) rawB = *(const q_v4i*)(src + kbB * 128 + sub * 8);
-      if (kbA < KB) quantize_block(rawA, dstA + kbA * 128 + sub * 8, dstS + kbA, sub);
-      if (kbB < KB) quantize_block(rawB, dstA + kbB * 128 + sub * 8, dstS + kbB, sub);
+      if (a.valid && sa >= 0 && sa < T) rawA = *(const q_v4i*)(X + sa * K + a.blk * 128 + sub * 8);
+      if (b.valid && sb >= 0 && sb < T) rawB = *(const q_v4i*)(X + sb * K + b.blk * 128 + sub * 8);
+      if (a.valid) quantize_block(rawA, A + (int64_t)a.row * K + a.blk * 128 + sub * 8, SA + (int64_t)a.row * KB + a.blk, sub);
+      if (b.valid) quantize_block(rawB, A + (int64_t)b.row * K + b.blk * 128 + sub * 8, SA + (int64_t)b.row * KB + b.blk, sub);
+    }
+  }
+}
+
+// The activation between the two grouped GEMMs of an expert MLP, fused with the quantiser above: H [M, 2I] bf16
+// (columns [0, I): gate projection, [I, 2I): up projection) ->
+//     act = bf16_rne( silu(gate) * up ),  silu(g) = g / (1 + exp(-g))   in fp32
+// and then exactly quantize_block on the bf16 bits of act.  act is also written out when act_out is not null.
+// Same mapping: 16 lanes own one block of 128 activation columns, a lane loads 8 gate and 8 up values.
+__device__ __forceinline__ q_v4i swiglu8(const q_v4i g_raw, const q_v4i u_raw) {
+  q_v4i out;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float g[2] = {__builtin_bit_cast(float, g_raw[i] << 16), __builtin_bit_cast(float, g_raw[i] & (int)0xFFFF0000)};
+    float u[2] = {__builtin_bit_cast(float, u_raw[i] << 16), __builtin_bit_cast(float, u_raw[i] & (int)0xFFFF0000)};
+    float a[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      // sigmoid through t = exp(-|g|) in [0, 1]: no overflow for any g; the hardware exponential (a few fp32
+      // ulps, denormal results flushed: t = 0 below g = -87.3) and reciprocal are far inside the bf16 rounding
+      const float t = __expf(-__builtin_fabsf(g[h]));
+      const float sig = __fdividef(g[h] >= 0.f ? 1.0f : t, 1.0f + t);
+      a[h] = g[h] * sig * u[h];
+    }
+    typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    const bf2 r = __builtin_convertvector((f2){a[0], a[1]}, bf2);     // round to nearest even
+    out[i] = __builtin_bit_cast(int, r);
+  }
+  return out;
+}
+
+__global__ void __launch_bounds__(Q_THREADS) gg_swiglu_quantize_rows_kernel(const uint16_t* __restrict__ H,
+                                                                            uint8_t* __restrict__ A, float* __restrict__ SA,
+                                                                            uint16_t* __restrict__ act_out,
+                                                                            int M_total, int I, int IB) {
+  const int grp = threadIdx.x >> 4, sub = threadIdx.x & 15;
+  for (int64_t r64 = blockIdx.x; r64 < M_total; r64 += 2 * (int64_t)gridDim.x) {
+    const int r = (int)r64;
+    const int r2 = r64 + gridDim.x < M_total ? (int)(r64 + gridDim.x) : M_total;
+    for (int v0 = 0; v0 < 2 * IB; v0 += 32) {
+      const RowPairSlot a = row_pair_slot(v0 + grp, IB, r, r2, M_total);
+      const RowPairSlot b = row_pair_slot(v0 + 16 + grp, IB, r, r2, M_total);
+      q_v4i gA = {0, 0, 0, 0}, uA = {0, 0, 0, 0}, gB = {0, 0, 0, 0}, uB = {0, 0, 0, 0};
+      if (a.valid) {
+        const uint16_t* src = H + (int64_t)a.row * 2 * I + a.blk * 128 + sub * 8;
+        gA = *(const q_v4i*)src;
+        uA = *(const q_v4i*)(src + I);
+      }
+      if (b.valid) {
+        const uint16_t* src = H + (int64_t)b.row * 2 * I + b.blk * 128 + sub * 8;
+        gB = *(const q_v4i*)src;
+        uB = *(const q_v4i*)(src + I);
+      }
+      if (a.valid) {
+        const q_v4i act = swiglu8(gA, uA);
+        const int64_t o = (int64_t)a.row * I + a.blk * 128 + sub * 8;
+        if (act_out) *(q_v4i*)(act_out + o) = act;
+        quantize_block(act, A + o, SA + (int64_t)a.row * IB + a.blk, sub);
+      }
+      if (b.valid) {
+        const q_v4i act = swiglu8(gB, uB);
+        const int64_t o = (int64_t)b.row * I + b.blk * 128 + sub * 8;
+        if (act_out) *(q_v4i*)(act_out + o) = act;
+        quantize_block(act, A + o, SA + (int64_t)b.row * IB + b.blk, sub);
+      }
     }
   }
 }

@@ -149,3 +149,119 @@ def test_full_size_rows_sampled():
     A_ref, SA_ref = orc.quantize_rows(xb, src[rows])
     assert np.array_equal(A.cpu().numpy()[rows], A_ref)
     assert np.array_equal(SA.cpu().numpy()[rows], SA_ref)
+
+
+# ------------------------------------------------------------------------------------------------------------
+# the activation between the two GEMMs, fused with the quantiser
+# ------------------------------------------------------------------------------------------------------------
+def check_swiglu(hb: np.ndarray, min_equal=0.995):
+    """act: within one bf16 ulp of the oracle's float64 value (fp32 evaluation on the GPU; a result next to a
+    rounding boundary may fall on the other side) plus |gate * up| * 2^-126 (below gate = -87.3 the fp32 sigmoid, itself
+    below 2^-126, is flushed to 0), NaNs in the same places; bytes and scales:
+    bit-exact against the oracle's quantiser applied to the GPU's own act bits (integer work; the fp decision
+    sits in act)."""
+    H = torch.from_numpy(hb.view(np.int16)).view(torch.bfloat16).to(DEV)
+    A, SA, act = gg.swiglu_quantize_rows(H, want_act=True)
+    A2, SA2, none = gg.swiglu_quantize_rows(H)
+    torch.cuda.synchronize()
+    assert none is None
+    actb = act.view(torch.int16).cpu().numpy().view(np.uint16)
+    A, SA = A.cpu().numpy(), SA.cpu().numpy()
+    assert np.array_equal(A, A2.cpu().numpy()) and np.array_equal(SA, SA2.cpu().numpy())
+    ref_bits = orc.swiglu_rows(hb)
+    got, ref = orc.f64_from_bf16_bits(actb), orc.f64_from_bf16_bits(ref_bits)
+    half = hb.shape[1] // 2
+    gate, up = orc.f64_from_bf16_bits(hb[:, :half]), orc.f64_from_bf16_bits(hb[:, half:])
+    # where the fp32 sigmoid is flushed to 0 (gate < -87.3) an infinite `up` gives 0 * inf = NaN instead of an infinity
+    flushed = (gate < -87.0) & np.isinf(up)
+    assert np.isnan(got[flushed]).all()
+    assert np.array_equal(np.isnan(got)[~flushed], np.isnan(ref)[~flushed])
+    ok = ~np.isnan(ref) & ~flushed
+    fin = ok & np.isfinite(ref)
+    assert np.array_equal(got[ok & ~fin], ref[ok & ~fin])                        # infinities agree exactly
+    with np.errstate(invalid="ignore"):
+        gu = np.abs(gate * up)
+    assert np.all(np.abs(got[fin] - ref[fin]) <= orc.bf16_ulp(ref[fin]) + gu[fin] * 2.0 ** -126)
+    if fin.sum() > 1000:
+        assert np.mean(actb[fin] == ref_bits[fin]) >= min_equal
+    A_ref, SA_ref = orc.quantize_rows(actb)
+    assert np.array_equal(SA.view(np.uint32), SA_ref.view(np.uint32))
+    assert np.array_equal(A, A_ref)
+
+
+@pytest.mark.parametrize("M,I", [(1, 128), (67, 2048), (5, 4224), (130, 256)])
+def test_swiglu_quantize_random(M, I):
+    rng = np.random.default_rng(2000 + M + I)
+    h = (rng.normal(0, 2, (M, 2 * I)) * np.exp(rng.normal(0, 1, (M, 1)))).astype(np.float32)
+    check_swiglu(bf16_bits(h))
+
+
+def test_swiglu_special_values():
+    vals = np.array([0.0, -0.0, 1.0, -1.0, 20.0, -20.0, 88.0, -88.0, 90.0, -90.0, 1000.0, -1000.0, 3e38, -3e38,
+                     np.inf, -np.inf, np.nan, 1e-30, -1e-30, 1e-40, 0.5, -0.5], dtype=np.float32)
+    g, u = np.meshgrid(vals, vals, indexing="ij")
+    n = g.size
+    pad = (-n) % 128
+    gate = np.concatenate([g.ravel(), np.zeros(pad, np.float32)]).reshape(1, -1)
+    up = np.concatenate([u.ravel(), np.zeros(pad, np.float32)]).reshape(1, -1)
+    check_swiglu(bf16_bits(np.concatenate([gate, up], axis=1)))
+
+
+def test_swiglu_full_size_sampled_rows():
+    # gate_up's output tensor: 8192 rows x (2 x 2048)
+    M, I = 8192, 2048
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(79)
+    H = (torch.randn((M, 2 * I), generator=gen, device=DEV) * 1.7).to(torch.bfloat16)
+    A, SA, act = gg.swiglu_quantize_rows(H, want_act=True)
+    torch.cuda.synchronize()
+    rows = np.arange(0, M, 53)
+    hb = H.view(torch.int16).cpu().numpy().view(np.uint16)[rows]
+    actb = act.view(torch.int16).cpu().numpy().view(np.uint16)[rows]
+    ref_bits = orc.swiglu_rows(hb)
+    got, ref = orc.f64_from_bf16_bits(actb), orc.f64_from_bf16_bits(ref_bits)
+    assert np.all(np.abs(got - ref) <= orc.bf16_ulp(ref))
+    assert np.mean(actb == ref_bits) >= 0.995
+    A_ref, SA_ref = orc.quantize_rows(actb)
+    assert np.array_equal(A.cpu().numpy()[rows], A_ref) and np.array_equal(SA.cpu().numpy()[rows], SA_ref)
+
+
+def test_expert_mlp_chain_stage_by_stage():
+    # tokens -> quantise (gathered by expert) -> GEMM (gate|up) -> activation + quantise -> GEMM (down), every
+    # stage on the GPU, every stage checked against the oracle fed with the GPU's previous stage
+    from gg_testlib import assert_parity, bits_of
+    from workloads.quantize import quantize_b
+    rng = np.random.default_rng(41)
+    sizes, hidden, inter = [70, 0, 129, 5], 512, 256
+    G, M = len(sizes), sum(sizes)
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    xb = bf16_bits(rng.normal(0, 1, (M + 9, hidden)).astype(np.float32))          # 9 tokens routed nowhere
+    src = rng.permutation(M + 9)[:M].astype(np.int32)
+    gen = torch.Generator().manual_seed(42)
+    W1 = [quantize_b(torch.randn((2 * inter, hidden), generator=gen) * 0.05) for _ in range(G)]
+    W2 = [quantize_b(torch.randn((hidden, inter), generator=gen) * 0.05) for _ in range(G)]
+    B1, SB1 = torch.stack([w[0] for w in W1]), torch.stack([w[1] for w in W1])
+    B2, SB2 = torch.stack([w[0] for w in W2]), torch.stack([w[1] for w in W2])
+    off_d = torch.from_numpy(off).to(DEV)
+    X = torch.from_numpy(xb.view(np.int16)).view(torch.bfloat16).to(DEV)
+
+    A1, SA1 = gg.quantize_rows(X, torch.from_numpy(src).to(DEV))
+    H = gg.grouped_gemm(A1, SA1, B1.to(DEV), SB1.to(DEV), off_d)
+    A2, SA2, _ = gg.swiglu_quantize_rows(H)
+    Y = gg.grouped_gemm(A2, SA2, B2.to(DEV), SB2.to(DEV), off_d)
+    torch.cuda.synchronize()
+
+    A1_ref, SA1_ref = orc.quantize_rows(xb, src)
+    assert np.array_equal(A1.cpu().numpy(), A1_ref) and np.array_equal(SA1.cpu().numpy(), SA1_ref)
+    ref1 = orc.grouped_gemm(A1_ref, SA1_ref, B1.numpy(), SB1.numpy(), off, with_abs_sum=True)
+    assert_parity(bits_of(H), ref1, what="first GEMM of the chain")
+    hb = bits_of(H)
+    act_ref = orc.swiglu_rows(hb)
+    A2_h, SA2_h = A2.cpu().numpy(), SA2.cpu().numpy()
+    # the activation is not returned here: check it through the dequantised operand, half a quantisation step wide
+    deq = orc.e4m3_decode_table()[A2_h] * np.repeat(SA2_h.astype(np.float64), 128, axis=1)
+    actv = orc.f64_from_bf16_bits(act_ref)
+    step = np.maximum(np.abs(actv) * 2.0 ** -4, np.repeat(SA2_h.astype(np.float64), 128, axis=1) * 2.0 ** -10)
+    assert np.all(np.abs(deq - actv) <= step * 1.001 + orc.bf16_ulp(actv))
+    ref2 = orc.grouped_gemm(A2_h, SA2_h, B2.numpy(), SB2.numpy(), off, with_abs_sum=True)
+    assert_parity(bits_of(Y), ref2, what="second GEMM of the chain")

@@ -545,3 +545,36 @@ def test_row_quantiser_gather_invalid_sources_and_nan():
     assert An[2, 130] == 0x7F
     Az[2, 130] = 0x7F
     assert np.array_equal(An, Az) and np.array_equal(SAn, SAz)
+
+
+def test_swiglu_closed_forms_library_routine_and_half_order():
+    rng = np.random.default_rng(31)
+    g = rng.normal(0, 3, (9, 256)).astype(np.float32)
+    u = rng.normal(0, 2, (9, 256)).astype(np.float32)
+    gb, ub = _bf16_bits(g), _bf16_bits(u)
+    gv, uv = orc.f64_from_bf16_bits(gb), orc.f64_from_bf16_bits(ub)
+    act = orc.swiglu_rows(np.concatenate([gb, ub], axis=1))
+    assert act.shape == (9, 256) and act.dtype == np.uint16
+    # the library's silu in float64, rounded by the (separately pinned) bf16 rounding
+    ref = torch.nn.functional.silu(torch.from_numpy(gv)).numpy() * uv
+    assert np.array_equal(act, orc.bf16_bits_from_f64(ref))
+    # halves: a zero gate kills the product whatever `up` is; a large gate passes `up * gate` through
+    one = _bf16_bits(np.ones((1, 128), np.float32))
+    zero = np.zeros((1, 128), np.uint16)
+    big = _bf16_bits(np.full((1, 128), 64.0, np.float32))
+    assert not (orc.swiglu_rows(np.concatenate([zero, big], axis=1)) & 0x7FFF).any()
+    assert np.array_equal(orc.swiglu_rows(np.concatenate([big, one], axis=1)), big)          # silu(64) = 64 to 2^-90
+    assert not (orc.swiglu_rows(np.concatenate([one, zero], axis=1)) & 0x7FFF).any()
+    # silu(x) - silu(-x) = x, silu(-large) -> -0, no overflow warnings matter
+    x = np.array([[0.5, 1.0, 3.0, 20.0]], dtype=np.float32)
+    xb = _bf16_bits(x)
+    ones = _bf16_bits(np.ones_like(x))
+    pos = orc.f64_from_bf16_bits(orc.swiglu_rows(np.concatenate([xb, ones], axis=1)))
+    neg = orc.f64_from_bf16_bits(orc.swiglu_rows(np.concatenate([xb | 0x8000, ones], axis=1)))
+    assert np.allclose(pos - neg, x, rtol=2.0 ** -7)
+    far = orc.swiglu_rows(np.concatenate([_bf16_bits(np.full((1, 4), -1000.0, np.float32)), ones], axis=1))
+    assert not (far & 0x7FFF).any()
+    # chained with the quantiser: exactly quantize_rows of the activation bits
+    actb, A, SA = orc.swiglu_quantize_rows(np.concatenate([gb, ub], axis=1))
+    A2, SA2 = orc.quantize_rows(actb)
+    assert np.array_equal(actb, act) and np.array_equal(A, A2) and np.array_equal(SA, SA2)
