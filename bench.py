@@ -41,12 +41,9 @@ def algorithmic_bytes(sizes, N, K):
     return M * K + M * KB * 4 + nonempty * N * K + nonempty * NB * KB * 4 + M * N * 2
 
 
-# the same for gg_quantize_rows_kernel (profiles/quantize_rows_kernel_activation_shapes.md)
-MEASURED_TRAFFIC_BYTES_QUANT = {"gate_up": int((57629.6484375 / 0.5 + 59417.76171875) * 1024),
-                                "many_small": int((230440.953125 / 0.5 + 238107.72265625) * 1024)}
-
-
-MEASURED_TRAFFIC_BYTES_SWIGLU = {}
+# the same for the two row kernels (profiles/row_kernels_quantize_and_swiglu.md)
+MEASURED_TRAFFIC_BYTES_QUANT = {"gate_up": 178728308, "many_small": 714945956}
+MEASURED_TRAFFIC_BYTES_SWIGLU = {"gate_up": 84510332, "many_small": 337914328}
 
 
 def copy_calibration(dev):
