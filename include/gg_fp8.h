@@ -86,6 +86,14 @@ const char* gg_fp8_variant_name(int variant);
  * are not supported. */
 int gg_fp8_auto_variant(int G, int64_t M_total, int N, int K);
 
+/* gg_fp8_grouped_gemm_variant with C [M_total, N] written as IEEE binary16 instead of bfloat16: the paper says
+ * "half-precision" and App. A only fixes 2 bytes per element, so both 2-byte formats are offered.  Same sum, same
+ * order, one round-to-nearest-even step from the fp32 accumulator; magnitudes that round to 2^16 or more become
+ * +-inf.  variant = -1 chooses automatically.  Everything else as for gg_fp8_grouped_gemm. */
+int gg_fp8_grouped_gemm_f16(const void* A, const float* SA, const void* B, const float* SB,
+                            const int32_t* group_offsets, void* C, int G, int64_t M_total, int N, int K,
+                            void* workspace, size_t workspace_bytes, void* stream, int variant);
+
 /* ---- the pad-then-GEMM comparison path (the baseline of Sec. 3) ------------
  * Every group is copied to an offset that is a multiple of 128 rows, pad rows
  * are zero, the same GEMM kernels run on the aligned problem, and the valid

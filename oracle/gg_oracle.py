@@ -120,6 +120,58 @@ def bf16_ulp(x: np.ndarray) -> np.ndarray:
     return np.ldexp(1.0, (e - 7).astype(np.int32))
 
 
+def f16_bits_from_f64(x: np.ndarray) -> np.ndarray:
+    """uint16 IEEE binary16 bit patterns of float64 values, ONE rounding step (RNE): the other reading of the
+    paper's "half-precision" output (App. A only fixes 2 bytes per element).
+
+    binary16 = 1 sign, 5 exponent (bias 15), 10 mantissa bits; subnormals on the grid 2^-24; the largest finite
+    value is 65504 and anything that rounds to 2^16 becomes +-inf.  NaN becomes 0x7E00, signed zeros are kept.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    sign = np.signbit(x)
+    a = np.abs(x)
+    nan = np.isnan(a)
+    a = np.where(nan, 0.0, a)
+    _, E = np.frexp(a)
+    e = np.maximum(E.astype(np.int64) - 1, -14)          # subnormals share the grid of 2^-14
+    quantum = np.ldexp(1.0, (e - 10).astype(np.int32))
+    with np.errstate(over="ignore", invalid="ignore"):
+        ratio = np.where(np.isinf(a), np.inf, a / quantum)
+        r = np.rint(ratio) * quantum                     # exactly a binary16 value, or >= 2^16 (overflow)
+    inf = r >= 2.0 ** 16
+    r = np.where(inf, 0.0, r)
+    m, E2 = np.frexp(r)                                  # r = m * 2^E2, m in [0.5, 1)
+    e2 = E2.astype(np.int64) - 1
+    normal = r >= 2.0 ** -14
+    frac = np.where(normal, np.rint((2.0 * m - 1.0) * 1024.0), np.rint(r * 2.0 ** 24)).astype(np.int64)   # exact
+    bits = np.where(normal, ((e2 + 15) << 10) | frac, frac)
+    bits = np.where(inf, 0x7C00, bits)
+    bits = np.where(sign, bits | 0x8000, bits)
+    bits = np.where(nan, 0x7E00, bits)
+    return bits.astype(np.uint16)
+
+
+def f64_from_f16_bits(bits: np.ndarray) -> np.ndarray:
+    """float64 value of binary16 bit patterns (exact), from the format's definition."""
+    b = np.asarray(bits, dtype=np.uint16).astype(np.int64)
+    sign = np.where(b & 0x8000, -1.0, 1.0)
+    e = (b >> 10) & 0x1F
+    m = (b & 0x3FF).astype(np.float64)
+    with np.errstate(invalid="ignore"):
+        v = np.where(e == 0, m * 2.0 ** -24, np.ldexp(1.0 + m / 1024.0, (e - 15).astype(np.int32)))
+        v = np.where(e == 0x1F, np.where(m == 0, np.inf, np.nan), v)
+    return sign * v
+
+
+def f16_ulp(x: np.ndarray) -> np.ndarray:
+    """Spacing of binary16 values in the binade that holds |x| (float64); 2^-24 below 2^-14."""
+    a = np.abs(np.asarray(x, dtype=np.float64))
+    _, E = np.frexp(np.where(a == 0, 1.0, a))
+    e = np.maximum(E.astype(np.int64) - 1, -14)
+    e = np.where(a == 0, -14, e)
+    return np.ldexp(1.0, (e - 10).astype(np.int32))
+
+
 # ----------------------------------------------------------------------------
 # the operation
 # ----------------------------------------------------------------------------
@@ -134,7 +186,7 @@ def _check_shapes(A, SA, B, SB, off, N, K):
     return G, KB, NB
 
 
-def grouped_gemm(A, SA, B, SB, group_offsets, rows=None, with_abs_sum=False):
+def grouped_gemm(A, SA, B, SB, group_offsets, rows=None, with_abs_sum=False, out="bf16"):
     """Block-scaled FP8 grouped GEMM by its definition (Sec. 2.1, Table 1).
 
     A   uint8 [M_total, K]   e4m3 bytes, groups concatenated along rows
@@ -149,7 +201,7 @@ def grouped_gemm(A, SA, B, SB, group_offsets, rows=None, with_abs_sum=False):
       "rows"  int64 [R]      global row index of each output row
       "group" int64 [R]      the group each row belongs to
       "D"     float64 [R, N] the block-scaled dot products
-      "C"     uint16 [R, N]  bfloat16 bit patterns of D (one RNE rounding)
+      "C"     uint16 [R, N]  bfloat16 (out="bf16") or binary16 (out="f16") bit patterns of D, one RNE rounding
       "S"     float64 [R, N] (with_abs_sum) sum_kb |sa*sb| * sum_k |a*b| -- the
               magnitude against which a float32 accumulation error is bounded
     Scales are dequantisation multipliers: real value = dec(byte) * scale.
@@ -194,7 +246,8 @@ def grouped_gemm(A, SA, B, SB, group_offsets, rows=None, with_abs_sum=False):
         if with_abs_sum:
             S[sel] = Sg
 
-    out = {"rows": rows, "group": grp, "D": D, "C": bf16_bits_from_f64(D)}
+    assert out in ("bf16", "f16")
+    out = {"rows": rows, "group": grp, "D": D, "C": bf16_bits_from_f64(D) if out == "bf16" else f16_bits_from_f64(D)}
     if with_abs_sum:
         out["S"] = S
     return out

@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.gg_fp8_grouped_gemm_variant.restype = i32
     lib.gg_fp8_grouped_gemm_variant.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp, sz, vp, i32]
     lib.gg_fp8_num_variants.restype = i32
+    lib.gg_fp8_grouped_gemm_f16.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp, sz, vp, i32]
+    lib.gg_fp8_grouped_gemm_f16.restype = i32
     lib.gg_fp8_num_variants.argtypes = []
     lib.gg_fp8_variant_name.restype = ctypes.c_char_p
     lib.gg_fp8_variant_name.argtypes = [i32]
@@ -102,7 +104,7 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED_SYMBOLS = [
     "gg_fp8_version", "gg_fp8_status_str", "gg_fp8_workspace_bytes", "gg_fp8_grouped_gemm",
-    "gg_fp8_grouped_gemm_variant", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_auto_variant", "gg_fp8_padded_rows_cap",
+    "gg_fp8_grouped_gemm_variant", "gg_fp8_grouped_gemm_f16", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_auto_variant", "gg_fp8_padded_rows_cap",
     "gg_fp8_pad", "gg_fp8_grouped_gemm_padded", "gg_fp8_unpad", "gg_fp8_quantize_rows", "gg_fp8_swiglu_quantize_rows", "gg_fp8_check_offsets",
 ]
 
@@ -191,23 +193,29 @@ def _workspace(G, M_total, N, K, device):
     return (torch.empty(n, dtype=torch.uint8, device=device) if n else None), n
 
 
-def grouped_gemm(A, SA, B, SB, group_offsets, C=None, variant: int = -1, stream=None):
-    """C[r, :] = bf16(block-scaled A[r, :] @ B[g]^T) for every row r of every group g (gg_fp8_grouped_gemm).
+def grouped_gemm(A, SA, B, SB, group_offsets, C=None, variant: int = -1, stream=None, out_dtype=None):
+    """C[r, :] = round(block-scaled A[r, :] @ B[g]^T) for every row r of every group g (gg_fp8_grouped_gemm,
+    or gg_fp8_grouped_gemm_f16 when C / out_dtype is torch.float16).
 
     A uint8 [M_total, K] (e4m3 bytes), SA float32 [M_total, K/128], B uint8 [G, N, K],
-    SB float32 [G, N/128, K/128], group_offsets int32 [G+1]; returns C bfloat16 [M_total, N]
+    SB float32 [G, N/128, K/128], group_offsets int32 [G+1]; returns C bfloat16 (default) or float16 [M_total, N]
     (allocated here unless given; rows outside the groups are left as they are).
     """
     lib = load_library()
     G, M_total, N, K = _gemm_shapes(A, SA, B, SB, group_offsets)
+    if out_dtype is None:
+        out_dtype = C.dtype if C is not None else torch.bfloat16
+    if out_dtype not in (torch.bfloat16, torch.float16):
+        raise TypeError("C must be bfloat16 or float16")
     if C is None:
-        C = torch.empty((M_total, N), dtype=torch.bfloat16, device=A.device)
-    _want(C, "C", torch.bfloat16, 2)
+        C = torch.empty((M_total, N), dtype=out_dtype, device=A.device)
+    _want(C, "C", out_dtype, 2)
     if tuple(C.shape) != (M_total, N):
         raise ValueError(f"C must be [{M_total}, {N}]")
     ws, n = _workspace(G, M_total, N, K, A.device)
-    _check(lib.gg_fp8_grouped_gemm_variant(_ptr(A), _ptr(SA), _ptr(B), _ptr(SB), _ptr(group_offsets), _ptr(C),
-                                           G, M_total, N, K, _ptr(ws), n, _stream(stream), int(variant)))
+    fn = lib.gg_fp8_grouped_gemm_f16 if out_dtype == torch.float16 else lib.gg_fp8_grouped_gemm_variant
+    _check(fn(_ptr(A), _ptr(SA), _ptr(B), _ptr(SB), _ptr(group_offsets), _ptr(C),
+              G, M_total, N, K, _ptr(ws), n, _stream(stream), int(variant)))
     return C
 
 

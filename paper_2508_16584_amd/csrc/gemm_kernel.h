@@ -45,6 +45,14 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v2f __attribute__((ext_vector_type(2)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+
+// two fp32 -> one dword of two 2-byte floats, round to nearest even: bfloat16, or IEEE binary16 when f16 is set
+// (the two readings of the paper's "half-precision" output; f16 is uniform over the launch)
+__device__ __forceinline__ int pack2_rne(float a, float b, bool f16) {
+  if (f16) return __builtin_bit_cast(int, __builtin_convertvector((v2f){a, b}, v2h));
+  return __builtin_bit_cast(int, __builtin_convertvector((v2f){a, b}, v2bf));
+}
 
 #define GG_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 // dword 3 of a raw buffer descriptor on gfx9-family parts: 32-bit data format, no swizzle
@@ -63,6 +71,7 @@ struct GemmArgs {
   int n_tiles;   // N / BN
   int n_chunk;   // n-tiles that are walked together before moving to the next m-tile
   int slots;     // workgroups per XCD when the grid is a multiple of 8, else 0 (plain round-robin)
+  int out_f16;   // 0: C is bfloat16, 1: C is IEEE binary16
   int rot_mul;   // K blocks by which neighbouring 256-column blocks shift the start of their K loop (0: none)
 };
 
@@ -516,22 +525,19 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
     }
     __syncthreads();  // every wave is done reading LDS before the next tile's prologue overwrites it
 
-    // ---- epilogue: bf16 RNE, 16-byte bounded stores ---------------------------------------------
+    // ---- epilogue: bf16 (or binary16) RNE, 16-byte bounded stores ---------------------------------------------
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt) {
       const int row = wm * WTM + 16 * mt + r;
 #pragma unroll
       for (int pr = 0; pr < TN / 2; ++pr) {
         const v4f x = acc[mt][2 * pr], y = acc[mt][2 * pr + 1];
-        const v2bf c0 = __builtin_convertvector((v2f){x[0], x[1]}, v2bf);
-        const v2bf c1 = __builtin_convertvector((v2f){x[2], x[3]}, v2bf);
-        const v2bf c2 = __builtin_convertvector((v2f){y[0], y[1]}, v2bf);
-        const v2bf c3 = __builtin_convertvector((v2f){y[2], y[3]}, v2bf);
+        const bool f16 = a.out_f16 != 0;
         v4i out;
-        out.x = __builtin_bit_cast(int, c0);
-        out.y = __builtin_bit_cast(int, c1);
-        out.z = __builtin_bit_cast(int, c2);
-        out.w = __builtin_bit_cast(int, c3);
+        out.x = pack2_rne(x[0], x[1], f16);
+        out.y = pack2_rne(x[2], x[3], f16);
+        out.z = pack2_rne(y[0], y[1], f16);
+        out.w = pack2_rne(y[2], y[3], f16);
         const int col = wn * WTN + 32 * pr + 8 * q;
         __builtin_amdgcn_raw_buffer_store_b128(out, dC, row * N * 2 + col * 2, 0, 0);
       }

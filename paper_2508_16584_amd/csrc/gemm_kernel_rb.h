@@ -350,19 +350,16 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 
-    // ---- epilogue: bf16 RNE, one bounded 16-byte store per activation block ---------------------------------
+    // ---- epilogue: bf16 (or binary16) RNE, one bounded 16-byte store per activation block ---------------------------------
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt) {
       const v4f x = acc[mt][0], y = acc[mt][1];
-      const v2bf c0 = __builtin_convertvector((v2f){x[0], x[1]}, v2bf);
-      const v2bf c1 = __builtin_convertvector((v2f){x[2], x[3]}, v2bf);
-      const v2bf c2 = __builtin_convertvector((v2f){y[0], y[1]}, v2bf);
-      const v2bf c3 = __builtin_convertvector((v2f){y[2], y[3]}, v2bf);
+      const bool f16 = a.out_f16 != 0;
       v4i out;
-      out.x = __builtin_bit_cast(int, c0);
-      out.y = __builtin_bit_cast(int, c1);
-      out.z = __builtin_bit_cast(int, c2);
-      out.w = __builtin_bit_cast(int, c3);
+      out.x = pack2_rne(x[0], x[1], f16);
+      out.y = pack2_rne(x[2], x[3], f16);
+      out.z = pack2_rne(y[0], y[1], f16);
+      out.w = pack2_rne(y[2], y[3], f16);
       // one descriptor per 16-row block (scalar work): the lane offset is then the same for every block, and
       // rows past the group's end still fail its bounds check
       int rows_mt = rows_valid - 16 * mt;

@@ -151,7 +151,7 @@ int validate_gemm(const void* A, const float* SA, const void* B, const float* SB
 }
 
 int run_gemm(const void* A, const float* SA, const void* B, const float* SB, const int32_t* off, void* C,
-             int G, int64_t M_total, int N, int K, void* stream, int variant) {
+             int G, int64_t M_total, int N, int K, void* stream, int variant, bool out_f16 = false) {
   int st = validate_gemm(A, SA, B, SB, off, C, G, M_total, N, K);
   if (st != GG_OK) return st;
   if (G == 0 || M_total == 0) return GG_OK;
@@ -174,6 +174,7 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
   args.KB = K / 128;
   args.n_tiles = N / v.BN;
   args.n_chunk = args.n_tiles < 8 ? args.n_tiles : 8;
+  args.out_f16 = out_f16 ? 1 : 0;
   args.rot_mul = (K % 8192 == 4096) ? 4 : 0;   // 7 * 4 < K / 128; a function of K alone (see k_rotation)
 
   // upper bound on the number of tiles for any offsets: every group adds at most one partial m-tile
@@ -241,6 +242,14 @@ int gg_fp8_grouped_gemm(const void* A, const float* SA, const void* B, const flo
                         void* workspace, size_t workspace_bytes, void* stream) {
   return gg_fp8_grouped_gemm_variant(A, SA, B, SB, group_offsets, C, G, M_total, N, K, workspace, workspace_bytes,
                                      stream, -1);
+}
+
+int gg_fp8_grouped_gemm_f16(const void* A, const float* SA, const void* B, const float* SB,
+                            const int32_t* group_offsets, void* C, int G, int64_t M_total, int N, int K,
+                            void* workspace, size_t workspace_bytes, void* stream, int variant) {
+  (void)workspace;
+  if (workspace_bytes < gg_fp8_workspace_bytes(G, M_total, N, K)) return GG_ERR_WORKSPACE;
+  return run_gemm(A, SA, B, SB, group_offsets, C, G, M_total, N, K, stream, variant, true);
 }
 
 int64_t gg_fp8_padded_rows_cap(int G, int64_t M_total) {

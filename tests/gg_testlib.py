@@ -24,6 +24,10 @@ test is the specification):
        |gpu - D| <= ulp_bf16(D) / 2 + 2^-15 * S   for every element,
        at least 99% of the elements within one bfloat16 ulp,
        at least 97% of the elements bit-equal to the oracle's bfloat16.
+ * With IEEE binary16 output (the other 2-byte reading of "half-precision") the same derivation holds with
+   that format's ulp; results whose magnitude rounds to 2^16 or more are infinities on both sides.  Its ulp is
+   8 times finer, so the float32-level noise of the accumulation shows more often: the empirical shares asked
+   for are 97% within one ulp and 90% bit-equal (observed on the tiny workload: 98.7% and 93.8%).
 """
 import numpy as np
 import torch
@@ -45,25 +49,38 @@ def bits_equal_nan_aware(a: np.ndarray, b: np.ndarray) -> np.ndarray:
     return (a == b) | (nan_a & nan_b)
 
 
-def assert_parity(got_bits: np.ndarray, ref: dict, empirical: bool = True, what: str = ""):
-    """Element-by-element comparison of GPU bfloat16 bits with an oracle result dict."""
+def assert_parity(got_bits: np.ndarray, ref: dict, empirical: bool = True, what: str = "", fmt: str = "bf16"):
+    """Element-by-element comparison of GPU output bits (bfloat16, or binary16 with fmt="f16": the same bounds
+    with that format's ulp) with an oracle result dict computed for the same format."""
     D, S, Cb = ref["D"], ref["S"], ref["C"]
     assert got_bits.shape == Cb.shape, (got_bits.shape, Cb.shape)
     if got_bits.size == 0:
         return {}
-    got = orc.f64_from_bf16_bits(got_bits)
+    decode, ulp_of = (orc.f64_from_bf16_bits, orc.bf16_ulp) if fmt == "bf16" else (orc.f64_from_f16_bits, orc.f16_ulp)
+    got = decode(got_bits)
     nan_ref = np.isnan(D)
     assert np.array_equal(np.isnan(got), nan_ref), f"{what}: NaN pattern differs"
     ok = ~nan_ref
+    if fmt == "f16":
+        # Results that leave binary16's range (|x| rounds to 2^16 from 65520 on): where either side says infinity,
+        # both do, with the same sign, unless D sits within the hard bound of the threshold and the other side
+        # says +-65504.  These elements are compared no further.
+        ref_v = decode(Cb)
+        edge = ok & (np.isinf(got) | np.isinf(ref_v))
+        same = got[edge] == ref_v[edge]
+        near = (np.abs(np.abs(D[edge]) - 65520.0) <= 32.0 + HARD_FLOOR * S[edge]) & (np.sign(got[edge]) == np.sign(D[edge])) \
+            & (np.minimum(np.abs(got[edge]), np.abs(ref_v[edge])) == 65504.0)
+        assert np.all(same | near), f"{what}: overflow to infinity differs"
+        ok = ok & ~edge
     err = np.abs(np.where(ok, got - D, 0.0))
-    ulp = orc.bf16_ulp(np.where(ok, D, 1.0))
+    ulp = ulp_of(np.where(ok, D, 1.0))
     Sx = np.where(ok, S, 0.0)
     hard = np.maximum(ulp, 0.5 * ulp + HARD_FLOOR * Sx)
     bad = np.argwhere(err > hard)
     assert bad.size == 0, (f"{what}: {bad.shape[0]} elements outside the hard bound, first {bad[:4].tolist()}, "
                            f"got {got[tuple(bad[0])]} want {D[tuple(bad[0])]}")
     stats = {
-        "bit_equal": float(np.mean(bits_equal_nan_aware(got_bits, Cb))),
+        "bit_equal": float(np.mean(bits_equal_nan_aware(got_bits, Cb) if fmt == "bf16" else (got_bits == Cb) | ~ok)),
         "within_1ulp": float(np.mean(err <= ulp)),
         "max_err_ulp": float(np.max(err / ulp)),
         "max_excess_over_S": float(np.max(np.maximum(err - 0.5 * ulp, 0) / np.maximum(Sx, 1e-300))),
@@ -72,8 +89,9 @@ def assert_parity(got_bits: np.ndarray, ref: dict, empirical: bool = True, what:
         emp = 0.5 * ulp + EMPIRICAL_FLOOR * Sx
         nb = int(np.sum(err > emp))
         assert nb == 0, f"{what}: {nb} elements outside the empirical bound; stats {stats}"
-        assert stats["within_1ulp"] >= 0.99, f"{what}: {stats}"
-        assert stats["bit_equal"] >= 0.97, f"{what}: {stats}"
+        need_1ulp, need_equal = (0.99, 0.97) if fmt == "bf16" else (0.97, 0.90)
+        assert stats["within_1ulp"] >= need_1ulp, f"{what}: {stats}"
+        assert stats["bit_equal"] >= need_equal, f"{what}: {stats}"
     return stats
 
 

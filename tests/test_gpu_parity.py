@@ -351,3 +351,56 @@ def test_paper_grid_points_with_the_papers_size_generator(N, K, G, M):
     torch.cuda.synchronize()
     assert int(poff[-1].item()) == int(np.sum(128 * ((sizes + 127) // 128)))
     assert torch.equal(C.view(torch.int16), C2.view(torch.int16))
+
+
+# ---------------------------------------------------------------------------------------------- binary16 output
+def f16_bits_of(C: torch.Tensor) -> np.ndarray:
+    return C.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def test_binary16_output_every_variant():
+    p = make_problem(CONFIGS["tiny"])
+    host = np_problem(p)
+    ref = orc.grouped_gemm(*host, with_abs_sum=True, out="f16")
+    dev = tuple(p[k].to(DEV) for k in ("A", "SA", "B", "SB", "group_offsets"))
+    first = {}
+    for v in [-1] + variants_for(p["N"]):
+        C = torch.full((p["M_total"], p["N"]), 0x7B7B, dtype=torch.int16, device=DEV).view(torch.float16)
+        gg.grouped_gemm(*dev, C=C, variant=v)
+        torch.cuda.synchronize()
+        got = f16_bits_of(C)
+        assert_parity(got, ref, what=f"binary16 variant {v}", fmt="f16")
+        family = "k-permuted" if v >= 0 and gg.variant_name(v).endswith("-rbk") else "plain"
+        first.setdefault(family, got)
+        assert np.array_equal(got, first[family])
+
+
+def test_binary16_output_ragged_groups_overflow_and_untouched_rows():
+    rng = np.random.default_rng(71)
+    sizes, N, K = [130, 0, 67, 1], 256, 384
+    host, dev = raw_problem(rng, sizes, N, K, DEV)
+    A, SA, B, SB, off = host
+    # raw bytes with scales up to 4 x 4: many results leave binary16's range (|x| >= 65520 -> infinity)
+    ref = orc.grouped_gemm(A, SA, B, SB, off, with_abs_sum=True, out="f16")
+    assert np.isinf(orc.f64_from_f16_bits(ref["C"])).mean() > 0.01
+    M = int(off[-1])
+    C = torch.full((M + 4, N), 0x7B7B, dtype=torch.int16, device=DEV).view(torch.float16)
+    gg.grouped_gemm(*dev, C=C[:M])
+    torch.cuda.synchronize()
+    bits = f16_bits_of(C)
+    assert (bits[M:] == 0x7B7B).all()
+    assert_parity(bits[:M], ref, empirical=False, what="binary16 raw bytes", fmt="f16")
+
+
+def test_binary16_output_full_size_sampled_rows():
+    p = make_problem(CONFIGS["gate_up"], device=DEV)
+    C = gg.grouped_gemm(p["A"], p["SA"], p["B"], p["SB"], p["group_offsets"], out_dtype=torch.float16)
+    torch.cuda.synchronize()
+    off = p["group_offsets"].cpu().numpy()
+    rows = sampled_rows(off, np.random.default_rng(72), every=211)
+    ridx = torch.from_numpy(rows).to(DEV)
+    ref = orc.grouped_gemm(p["A"][ridx].cpu().numpy(), p["SA"][ridx].cpu().numpy(), p["B"].cpu().numpy(),
+                           p["SB"].cpu().numpy(), np.concatenate([[0], np.cumsum(np.bincount(
+                               np.searchsorted(off, rows, side="right") - 1, minlength=p["G"]))]),
+                           with_abs_sum=True, out="f16")
+    assert_parity(f16_bits_of(C[ridx]), ref, what="binary16 gate_up", fmt="f16")

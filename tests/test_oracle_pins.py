@@ -578,3 +578,48 @@ def test_swiglu_closed_forms_library_routine_and_half_order():
     actb, A, SA = orc.swiglu_quantize_rows(np.concatenate([gb, ub], axis=1))
     A2, SA2 = orc.quantize_rows(actb)
     assert np.array_equal(actb, act) and np.array_equal(A, A2) and np.array_equal(SA, SA2)
+
+
+def test_binary16_rounding_against_the_library_hand_values_and_exact_rationals():
+    rng = np.random.default_rng(51)
+    x = np.concatenate([rng.normal(0, 1, 200000), rng.normal(0, 300, 100000), rng.uniform(-7e4, 7e4, 100000),
+                        rng.uniform(-2.0 ** -13, 2.0 ** -13, 100000), rng.uniform(-2.0 ** -24, 2.0 ** -24, 1000)])
+    with np.errstate(over="ignore"):
+        lib = x.astype(np.float16).view(np.uint16)               # NumPy converts double -> half in one RNE step
+    assert np.array_equal(orc.f16_bits_from_f64(x), lib)
+    # every binary16 pattern decodes like the library and is a fixed point of the rounding
+    bits = np.arange(65536, dtype=np.uint16)
+    dec = orc.f64_from_f16_bits(bits)
+    libdec = bits.view(np.float16).astype(np.float64)
+    assert np.array_equal(np.isnan(dec), np.isnan(libdec)) and np.array_equal(dec[~np.isnan(dec)], libdec[~np.isnan(dec)])
+    fin = ~np.isnan(dec)
+    assert np.array_equal(orc.f16_bits_from_f64(dec[fin]), bits[fin])
+    # hand values: ties to even, the overflow threshold, the subnormal grid, signed zero, NaN
+    cases = {1.0: 0x3C00, 1.0 + 2.0 ** -11: 0x3C00, 1.0 + 3 * 2.0 ** -11: 0x3C02, 65504.0: 0x7BFF, 65519.99: 0x7BFF,
+             65520.0: 0x7C00, 1e9: 0x7C00, -1e9: 0xFC00, 2.0 ** -24: 0x0001, 2.0 ** -25: 0x0000, 1.5 * 2.0 ** -24: 0x0002,
+             2.0 ** -14: 0x0400, -0.0: 0x8000, np.inf: 0x7C00}
+    for v, b in cases.items():
+        assert int(orc.f16_bits_from_f64(np.array([v]))[0]) == b, (v, b)
+    assert int(orc.f16_bits_from_f64(np.array([np.nan]))[0]) == 0x7E00
+    # one step, not two: 1 + 2^-11 + 2^-30 is above the tie and must round up even though float32 would hide the excess
+    assert int(orc.f16_bits_from_f64(np.array([1.0 + 2.0 ** -11 + 2.0 ** -30]))[0]) == 0x3C01
+    # exact rationals: the result is the nearest representable value
+    for v in rng.normal(0, 10, 300):
+        got = Fraction(float(orc.f64_from_f16_bits(orc.f16_bits_from_f64(np.array([v])))[0]))
+        ulp = Fraction(float(orc.f16_ulp(np.array([v]))[0]))
+        assert abs(got - Fraction(float(v))) <= ulp / 2
+    assert orc.f16_ulp(np.array([1.0, 1.9, 2.0, 1e-9, 0.0])).tolist() == [2.0 ** -10, 2.0 ** -10, 2.0 ** -9, 2.0 ** -24, 2.0 ** -24]
+
+
+def test_grouped_gemm_binary16_output_is_the_same_sum_rounded_once():
+    rng = np.random.default_rng(52)
+    A = rng.integers(0, 0x7E, (9, 256), dtype=np.uint8)
+    B = rng.integers(0, 0x7E, (2, 128, 256), dtype=np.uint8)
+    SA = rng.uniform(0.5, 2, (9, 2)).astype(np.float32)
+    SB = rng.uniform(0.5, 2, (2, 1, 2)).astype(np.float32)
+    off = np.array([0, 4, 9])
+    r1 = orc.grouped_gemm(A, SA, B, SB, off)
+    r2 = orc.grouped_gemm(A, SA, B, SB, off, out="f16")
+    assert np.array_equal(r1["D"], r2["D"])
+    with np.errstate(over="ignore"):
+        assert np.array_equal(r2["C"], r2["D"].astype(np.float16).view(np.uint16))
