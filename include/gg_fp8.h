@@ -4,9 +4,10 @@
  * The operation (paper Sec. 2.1, Table 1; scaling granularity stated below the
  * table): G groups share N and K, group g owns M^g rows.  With
  *   A   [M_total, K]  e4m3 bytes, the groups' rows concatenated,
- *   SA  [M_total, K/128]            one fp32 scale per (row, 128-wide K block),
+ *   SA  [M_total, ceil(K/128)]      one fp32 scale per (row, 128-wide K block),
  *   B   [G, N, K]     e4m3 bytes, B[g][n][k] = element (k, n) of the paper's B^g,
- *   SB  [G, N/128, K/128]           one fp32 scale per 128x128 block of B^g,
+ *   SB  [G, ceil(N/128), ceil(K/128)]   one fp32 scale per 128x128 block of B^g (the last block along K and
+ *                                   along N may be short: the ceilings of Table 1),
  *   group_offsets [G+1] int32       rows of group g are [off[g], off[g+1]),
  * the library writes, for every row r of group g and every n,
  *   C[r][n] = bf16( sum_kb  SA[r][kb] * SB[g][n/128][kb]
@@ -23,7 +24,10 @@
  *    (a hipStream_t passed as void*, NULL = the default stream).
  *  - All matrices are row-major and dense (leading dimension = row length).
  *    A, B, C, A_pad, C_pad must be 16-byte aligned; SA, SB, offsets 4-byte.
- *  - K and N must be positive multiples of 128 (GG_ERR_UNSUPPORTED otherwise).
+ *  - N must be a positive multiple of 8 and K of 16 (16-byte stores and fetches; GG_ERR_UNSUPPORTED otherwise).
+ *    Shapes with N % 128 != 0 or K % 128 != 0 run on a subset of the tile variants (the automatic choice knows
+ *    them; asking explicitly for another variant returns GG_ERR_UNSUPPORTED).  The row kernels
+ *    (gg_fp8_quantize_rows, gg_fp8_swiglu_quantize_rows) need whole 128-wide blocks.
  *  - group_offsets lives on the device and is trusted to be non-decreasing with
  *    0 <= off[0] and off[G] <= M_total.  If it is not, rows may be skipped or
  *    computed with the wrong group, but nothing outside C[0:M_total] is written.
@@ -45,7 +49,7 @@ typedef enum {
   GG_OK = 0,
   GG_ERR_NULL = 1,        /* a required pointer is NULL                              */
   GG_ERR_SHAPE = 2,       /* G < 0, M_total < 0, N <= 0, K <= 0, or a size overflows */
-  GG_ERR_UNSUPPORTED = 3, /* N or K not a multiple of 128, unknown variant           */
+  GG_ERR_UNSUPPORTED = 3, /* N % 8 or K % 16 nonzero, unknown variant, or a variant / row kernel that needs multiples of 128 */
   GG_ERR_WORKSPACE = 4,   /* workspace smaller than gg_fp8_workspace_bytes()         */
   GG_ERR_HIP = 5,         /* the HIP runtime refused a launch or a query             */
   GG_ERR_OFFSETS = 6      /* gg_fp8_check_offsets found invalid offsets              */

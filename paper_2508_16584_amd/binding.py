@@ -150,11 +150,11 @@ def _gemm_shapes(A, SA, B, SB, group_offsets):
         raise ValueError(f"A has K={K} but B has K={K2}")
     if group_offsets.shape[0] != G + 1:
         raise ValueError(f"group_offsets must have G+1={G + 1} entries")
-    if K % 128 == 0 and N % 128 == 0:
-        if tuple(SA.shape) != (M_total, K // 128):
-            raise ValueError(f"SA must be [{M_total}, {K // 128}]")
-        if tuple(SB.shape) != (G, N // 128, K // 128):
-            raise ValueError(f"SB must be [{G}, {N // 128}, {K // 128}]")
+    KB, NB = -(-K // 128), -(-N // 128)          # ceilings (Table 1 of the paper)
+    if tuple(SA.shape) != (M_total, KB):
+        raise ValueError(f"SA must be [{M_total}, {KB}]")
+    if tuple(SB.shape) != (G, NB, KB):
+        raise ValueError(f"SB must be [{G}, {NB}, {KB}]")
     return G, M_total, N, K
 
 

@@ -57,6 +57,8 @@ __device__ __forceinline__ int pack2_rne(float a, float b, bool f16) {
 #define GG_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 // dword 3 of a raw buffer descriptor on gfx9-family parts: 32-bit data format, no swizzle
 #define GG_RSRC_FLAGS 0x00020000
+// a lane offset that fails the bounds check of every descriptor used here: the access returns zeros / is dropped
+#define GG_OOB_OFFSET 0x7fffff00
 
 struct GemmArgs {
   const uint8_t* A;
@@ -67,10 +69,11 @@ struct GemmArgs {
   uint16_t* C;
   int G;
   int M_total;   // rows of A / C (clamp for untrusted offsets)
-  int N, K, KB;  // KB = K / 128
+  int N, K, KB;  // KB = ceil(K / 128)
   int n_tiles;   // N / BN
   int n_chunk;   // n-tiles that are walked together before moving to the next m-tile
   int slots;     // workgroups per XCD when the grid is a multiple of 8, else 0 (plain round-robin)
+  int k_rem;     // bytes of a row that fall into the last K block: K - 128 * (KB - 1), in (0, 128]
   int out_f16;   // 0: C is bfloat16, 1: C is IEEE binary16
   int rot_mul;   // K blocks by which neighbouring 256-column blocks shift the start of their K loop (0: none)
 };
@@ -167,7 +170,9 @@ __device__ __forceinline__ int swz_key_b(int row) {   // rows read: base + 8*(r/
   return b1 | (b4 << 1) | (b4 << 2);
 }
 
-template <class Cfg>
+// RAGGED: N need not be a multiple of the tile width nor K of 128 (the ceilings in Table 1 of the paper); costs a
+// few lane selects per fetch, so shapes made of whole blocks use the instantiation without it.
+template <class Cfg, bool RAGGED = false>
 __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, WN = Cfg::WN, NW = Cfg::NW;
   constexpr int TM = Cfg::TM, TN = Cfg::TN, WTM = Cfg::WTM, WTN = Cfg::WTN, STAGES = Cfg::STAGES;
@@ -190,6 +195,10 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
   const int keyB_ld = swz_key_b(b_row);
   const int vA = a_row * K + ((pch ^ keyA_ld) << 4);
   const int vB = b_row * K + ((pch ^ keyB_ld) << 4);
+  // K not a multiple of 128 (ceilings in Table 1 of the paper): in the last K block the 16-byte chunks at or past
+  // byte k_rem of the block belong to the next row; those lanes fetch from an out-of-range offset, i.e. zeros
+  const bool a_tail = RAGGED && ((pch ^ keyA_ld) << 4) >= a.k_rem;
+  const bool b_tail = RAGGED && ((pch ^ keyB_ld) << 4) >= a.k_rem;
   const int vSA = (w * 64 + l) * KB * 4;
   const int vSB = (l < BN / 128 ? l : BN / 128 - 1) * KB * 4;        // lane -> which 128-wide N block of the tile
 
@@ -248,9 +257,16 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
     // bounded views: nothing past the last valid row of this tile is loaded or stored
     __amdgpu_buffer_rsrc_t dA = __builtin_amdgcn_make_buffer_rsrc((void*)(a.A + grow * K), 0, rows_valid * K, GG_RSRC_FLAGS);
     __amdgpu_buffer_rsrc_t dSA = __builtin_amdgcn_make_buffer_rsrc((void*)(a.SA + grow * KB), 0, rows_valid * KB * 4, GG_RSRC_FLAGS);
-    __amdgpu_buffer_rsrc_t dB = __builtin_amdgcn_make_buffer_rsrc((void*)(a.B + ((int64_t)g * N + n0) * K), 0, BN * K, GG_RSRC_FLAGS);
+    // N not a multiple of the tile width: the weight rows, scale blocks and output columns past N do not exist
+    // (the row part of a weight fetch is in the lane offset, the only part the descriptor's bounds check sees)
+    const int n_rem = N - n0;
+    const int bn_valid = RAGGED && n_rem < BN ? n_rem : BN;
+    const int nb_all = RAGGED ? (N + 127) >> 7 : N >> 7;
+    int nb_valid = nb_all - (n0 >> 7);
+    nb_valid = RAGGED && nb_valid < BN / 128 ? nb_valid : BN / 128;
+    __amdgpu_buffer_rsrc_t dB = __builtin_amdgcn_make_buffer_rsrc((void*)(a.B + ((int64_t)g * N + n0) * K), 0, bn_valid * K, GG_RSRC_FLAGS);
     __amdgpu_buffer_rsrc_t dC = __builtin_amdgcn_make_buffer_rsrc((void*)(a.C + grow * N + n0), 0, rows_valid * N * 2 - n0 * 2, GG_RSRC_FLAGS);
-    __amdgpu_buffer_rsrc_t dSB = __builtin_amdgcn_make_buffer_rsrc((void*)(a.SB + ((int64_t)g * (N >> 7) + (n0 >> 7)) * KB), 0, (BN / 128) * KB * 4, GG_RSRC_FLAGS);
+    __amdgpu_buffer_rsrc_t dSB = __builtin_amdgcn_make_buffer_rsrc((void*)(a.SB + ((int64_t)g * nb_all + (n0 >> 7)) * KB), 0, nb_valid * KB * 4, GG_RSRC_FLAGS);
 
     // ---- global -> LDS DMA of one K block, split so that it can be fed into the MFMA stream --------
     // A wave that issues its 8-9 DMAs back to back sits in the issue stage until the CU's vector-memory
@@ -267,16 +283,21 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
     auto dma_tile = [&](auto idx_c, int kb_l, int stage) {
       constexpr int idx = decltype(idx_c)::value;
       const int kb = kphys(kb_l);
+      const bool last = kb == KB - 1;
       uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
       if constexpr (idx < A_FULL) {
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(dA, GG_LDS_PTR(st + (w + idx * NW) * 1024), 16, vA + idx * (NW * 8) * K, kb * 128, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(dA, GG_LDS_PTR(st + (w + idx * NW) * 1024), 16, (RAGGED && last && a_tail) ? GG_OOB_OFFSET : vA + idx * (NW * 8) * K, kb * 128, 0, 0);
       } else {
         constexpr int i = idx - A_FULL;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(st + Cfg::A_BYTES + (w + i * NW) * 1024), 16, vB, i * (NW * 8) * K + kb * 128, 0, 0);
+        if constexpr (RAGGED)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(st + Cfg::A_BYTES + (w + i * NW) * 1024), 16, (last && b_tail) ? GG_OOB_OFFSET : vB + i * (NW * 8) * K, kb * 128, 0, 0);
+        else
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(st + Cfg::A_BYTES + (w + i * NW) * 1024), 16, vB, i * (NW * 8) * K + kb * 128, 0, 0);
       }
     };
     auto dma_head = [&](int kb_l, int stage) {   // everything that is not issued inside the stream
       const int kb = kphys(kb_l);
+      const bool last = kb == KB - 1;
       uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
       if (w < Cfg::SA_WAVES)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(dSA, GG_LDS_PTR(st + Cfg::A_BYTES + Cfg::B_BYTES + w * 256), 4, vSA, kb * 4, 0, 0);
@@ -284,11 +305,13 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
         __builtin_amdgcn_raw_ptr_buffer_load_lds(dSB, GG_LDS_PTR(st + Cfg::A_BYTES + Cfg::B_BYTES + Cfg::SA_BYTES), 4, vSB, kb * 4, 0, 0);
       if constexpr (Cfg::A_SLABS % NW != 0) {
         if (w < Cfg::A_SLABS % NW)
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(dA, GG_LDS_PTR(st + (w + A_FULL * NW) * 1024), 16, vA + A_FULL * (NW * 8) * K, kb * 128, 0, 0);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(dA, GG_LDS_PTR(st + (w + A_FULL * NW) * 1024), 16, (RAGGED && last && a_tail) ? GG_OOB_OFFSET : vA + A_FULL * (NW * 8) * K, kb * 128, 0, 0);
       }
       if constexpr (Cfg::B_SLABS % NW != 0) {
         if (w < Cfg::B_SLABS % NW)
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(st + Cfg::A_BYTES + (w + B_FULL * NW) * 1024), 16, vB, B_FULL * (NW * 8) * K + kb * 128, 0, 0);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(st + Cfg::A_BYTES + (w + B_FULL * NW) * 1024), 16,
+                                                   RAGGED ? ((last && b_tail) ? GG_OOB_OFFSET : vB + B_FULL * (NW * 8) * K) : vB,
+                                                   (RAGGED ? 0 : B_FULL * (NW * 8) * K) + kb * 128, 0, 0);
       }
     };
     auto dma_all = [&](int kb, int stage) {
@@ -538,8 +561,8 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
         out.y = pack2_rne(x[2], x[3], f16);
         out.z = pack2_rne(y[0], y[1], f16);
         out.w = pack2_rne(y[2], y[3], f16);
-        const int col = wn * WTN + 32 * pr + 8 * q;
-        __builtin_amdgcn_raw_buffer_store_b128(out, dC, row * N * 2 + col * 2, 0, 0);
+        const int col = wn * WTN + 32 * pr + 8 * q;     // 8 columns; N is a multiple of 8, so they exist together or not at all
+        __builtin_amdgcn_raw_buffer_store_b128(out, dC, (!RAGGED || col < n_rem) ? row * N * 2 + col * 2 : GG_OOB_OFFSET, 0, 0);
       }
     }
   }

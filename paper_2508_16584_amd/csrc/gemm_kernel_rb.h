@@ -85,7 +85,6 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t uniform_rsrc(const void* ptr, 
 }
 
 // A buffer offset no descriptor of this kernel covers: loads return zero (a DMA writes zeros) and touch no memory.
-#define GG_OOB_OFFSET 0x7fffff00
 
 template <class Cfg>
 __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {

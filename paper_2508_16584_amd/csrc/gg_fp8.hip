@@ -38,9 +38,11 @@ struct Variant {
   int lds_bytes;
   int wg_per_cu;
   hipError_t (*launch)(const gg::GemmArgs&, int grid, hipStream_t);
+  // the same tile for N % BN != 0 or K % 128 != 0 (partial tiles, short last K block); null: whole blocks only
+  hipError_t (*launch_ragged)(const gg::GemmArgs&, int grid, hipStream_t) = nullptr;
 };
 
-template <class Cfg>
+template <class Cfg, bool RAGGED = false>
 hipError_t launch_gemm(const gg::GemmArgs& args, int grid, hipStream_t stream) {
   static std::atomic<int> prepared[64];
   int dev = 0;
@@ -48,12 +50,12 @@ hipError_t launch_gemm(const gg::GemmArgs& args, int grid, hipStream_t stream) {
   if (e != hipSuccess) return e;
   if (dev >= 0 && dev < 64 && !prepared[dev].load(std::memory_order_acquire)) {
     // more than 64 KB of LDS per workgroup has to be requested explicitly
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_gemm_kernel<Cfg>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_gemm_kernel<Cfg, RAGGED>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
     if (e != hipSuccess) return e;
     prepared[dev].store(1, std::memory_order_release);
   }
-  hipLaunchKernelGGL(gg::gg_gemm_kernel<Cfg>, dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, args);
+  hipLaunchKernelGGL((gg::gg_gemm_kernel<Cfg, RAGGED>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, args);
   return hipGetLastError();
 }
 
@@ -77,27 +79,30 @@ hipError_t launch_gemm_rb(const gg::GemmArgs& args, int grid, hipStream_t stream
 
 #define GG_VARIANT(BM, BN, WM, WN, ST, XPF, GAP, WGPC)                                                        \
   {#BM "x" #BN "/" #WM "x" #WN "w/" #ST "s" XPF_SUFFIX_##XPF, BM, BN, gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>::LDS_BYTES, \
-   WGPC, &launch_gemm<gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>>}
+   WGPC, &launch_gemm<gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>>, nullptr}
+#define GG_VARIANT_R(BM, BN, WM, WN, ST, XPF, GAP, WGPC)   /* with the instantiation for ragged N and K */         \
+  {#BM "x" #BN "/" #WM "x" #WN "w/" #ST "s" XPF_SUFFIX_##XPF, BM, BN, gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>::LDS_BYTES, \
+   WGPC, &launch_gemm<gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>>, &launch_gemm<gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>, true>}
 #define XPF_SUFFIX_false ""
 #define XPF_SUFFIX_true "x"
 
 const Variant kVariants[] = {
-    GG_VARIANT(160, 256, 2, 4, 3, false, 2, 1),   // 0: the largest tile that leaves room for a ring of 3 in 160 KB of LDS
+    GG_VARIANT_R(160, 256, 2, 4, 3, false, 2, 1),   // 0: the largest tile that leaves room for a ring of 3 in 160 KB of LDS
     GG_VARIANT(256, 256, 2, 4, 2, false, 2, 1),   // 1: the largest tile the accumulators allow; ring of 2 only
-    GG_VARIANT(128, 128, 2, 4, 4, false, 0, 1),   // 2: for N % 256 != 0
-    GG_VARIANT(128, 256, 2, 4, 3, false, 0, 1),   // 3
+    GG_VARIANT_R(128, 128, 2, 4, 4, false, 0, 1),   // 2: for N % 256 != 0
+    GG_VARIANT_R(128, 256, 2, 4, 3, false, 0, 1),   // 3
     GG_VARIANT(64, 256, 1, 8, 3, false, 0, 1),    // 4
-    GG_VARIANT(32, 256, 1, 8, 4, false, 0, 1),    // 5
+    GG_VARIANT_R(32, 256, 1, 8, 4, false, 0, 1),    // 5
     GG_VARIANT(16, 256, 1, 8, 2, false, 0, 2),    // 6
     GG_VARIANT(256, 128, 4, 2, 3, false, 0, 1),   // 7
     GG_VARIANT(128, 256, 2, 4, 3, true, 0, 1),    // 8
     GG_VARIANT(128, 128, 2, 4, 4, true, 0, 1),    // 9
     GG_VARIANT(32, 256, 1, 8, 4, true, 0, 1),     // 10
     GG_VARIANT(128, 128, 2, 4, 2, false, 0, 2),   // 11
-    {"256x256/1x8w/3s-rb", 256, 256, gg::RbCfg<256, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, false>>},   // 12
-    {"256x256/1x8w/3s-rbk", 256, 256, gg::RbCfg<256, 2, true>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, true>>},    // 13
-    {"192x256/1x8w/3s-rb", 192, 256, gg::RbCfg<192, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<192, 2, false>>},   // 14
-    {"224x256/1x8w/3s-rb", 224, 256, gg::RbCfg<224, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<224, 2, false>>},   // 15
+    {"256x256/1x8w/3s-rb", 256, 256, gg::RbCfg<256, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, false>>, nullptr},   // 12
+    {"256x256/1x8w/3s-rbk", 256, 256, gg::RbCfg<256, 2, true>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, true>>, nullptr},    // 13
+    {"192x256/1x8w/3s-rb", 192, 256, gg::RbCfg<192, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<192, 2, false>>, nullptr},   // 14
+    {"224x256/1x8w/3s-rb", 224, 256, gg::RbCfg<224, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<224, 2, false>>, nullptr},   // 15
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -119,7 +124,11 @@ constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 // are a fit to the five candidates on the 576 points of the paper's grid (Sec. 3.1) with caches flushed before
 // every launch: mean loss against the per-point best of the five 0.9 %, against 3.3-8.4 % for any single one.
 int pick_variant(int G, int64_t M_total, int N, int K) {
-  if (N % 256 != 0) return 2;   // N is always a multiple of 128
+  if (N % 256 != 0 || K % 128 != 0) {
+    // partial tiles and a short last K block: first kernel only; the 128-wide tile wastes least on a ragged N
+    const double avg_rows = G > 0 ? (double)M_total / G : 0.0;
+    return N % 128 != 0 || N < 256 ? 2 : (avg_rows < 64 ? 3 : 0);
+  }
   const double avg = G > 0 ? (double)M_total / G : 0.0;
   if (avg < 64) return 3;
   if (avg < 192) return 0;
@@ -144,7 +153,7 @@ int validate_gemm(const void* A, const float* SA, const void* B, const float* SB
                   int G, int64_t M_total, int N, int K) {
   if (G < 0 || M_total < 0 || N <= 0 || K <= 0) return GG_ERR_SHAPE;
   if (M_total > 0x7FFFFFFFLL || N > (1 << 21) || K > (1 << 22)) return GG_ERR_SHAPE;
-  if (N % 128 != 0 || K % 128 != 0) return GG_ERR_UNSUPPORTED;
+  if (N % 8 != 0 || K % 16 != 0) return GG_ERR_UNSUPPORTED;    // 16-byte stores of C, 16-byte fetches of A and B
   if (G == 0 || M_total == 0) return GG_OK;
   if (!A || !SA || !B || !SB || !off || !C) return GG_ERR_NULL;
   return GG_OK;
@@ -158,7 +167,8 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
   if (variant >= kNumVariants) return GG_ERR_UNSUPPORTED;
   if (variant < 0) variant = pick_variant(G, M_total, N, K);
   const Variant& v = kVariants[variant];
-  if (N % v.BN != 0) return GG_ERR_UNSUPPORTED;
+  const bool ragged = N % v.BN != 0 || K % 128 != 0;
+  if (ragged && !v.launch_ragged) return GG_ERR_UNSUPPORTED;   // this variant takes whole tiles and whole K blocks only
 
   gg::GemmArgs args;
   args.A = static_cast<const uint8_t*>(A);
@@ -171,8 +181,9 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
   args.M_total = (int)M_total;
   args.N = N;
   args.K = K;
-  args.KB = K / 128;
-  args.n_tiles = N / v.BN;
+  args.KB = (K + 127) / 128;
+  args.k_rem = K - 128 * (args.KB - 1);
+  args.n_tiles = (N + v.BN - 1) / v.BN;
   args.n_chunk = args.n_tiles < 8 ? args.n_tiles : 8;
   args.out_f16 = out_f16 ? 1 : 0;
   args.rot_mul = (K % 8192 == 4096) ? 4 : 0;   // 7 * 4 < K / 128; a function of K alone (see k_rotation)
@@ -188,7 +199,7 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
   } else {
     args.slots = 0;
   }
-  hipError_t e = v.launch(args, (int)grid, static_cast<hipStream_t>(stream));
+  hipError_t e = (ragged ? v.launch_ragged : v.launch)(args, (int)grid, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? GG_OK : GG_ERR_HIP;
 }
 
@@ -203,7 +214,7 @@ const char* gg_fp8_status_str(int status) {
     case GG_OK: return "ok";
     case GG_ERR_NULL: return "a required pointer is NULL";
     case GG_ERR_SHAPE: return "invalid or overflowing size argument";
-    case GG_ERR_UNSUPPORTED: return "unsupported shape (N and K must be multiples of 128) or variant";
+    case GG_ERR_UNSUPPORTED: return "unsupported shape (N must be a multiple of 8 and K of 16; some variants and the row kernels need multiples of 128) or variant";
     case GG_ERR_WORKSPACE: return "workspace too small";
     case GG_ERR_HIP: return "HIP runtime error";
     case GG_ERR_OFFSETS: return "group offsets are not non-decreasing within [0, M_total]";
@@ -225,7 +236,7 @@ const char* gg_fp8_variant_name(int variant) {
 int gg_fp8_auto_variant(int G, int64_t M_total, int N, int K) {
   if (G < 0 || M_total < 0 || N <= 0 || K <= 0) return -GG_ERR_SHAPE;
   if (M_total > 0x7FFFFFFFLL || N > (1 << 21) || K > (1 << 22)) return -GG_ERR_SHAPE;
-  if (N % 128 != 0 || K % 128 != 0) return -GG_ERR_UNSUPPORTED;
+  if (N % 8 != 0 || K % 16 != 0) return -GG_ERR_UNSUPPORTED;
   return pick_variant(G, M_total, N, K);
 }
 
@@ -262,7 +273,7 @@ int gg_fp8_pad(const void* A, const float* SA, const int32_t* group_offsets, voi
   if (G < 0 || M_total < 0 || K <= 0 || M_pad_cap < 0) return GG_ERR_SHAPE;
   if (M_total > 0x7FFFFFFFLL || M_pad_cap > 0x7FFFFFFFLL || K > (1 << 22)) return GG_ERR_SHAPE;
   if (M_pad_cap < gg_fp8_padded_rows_cap(G, M_total)) return GG_ERR_SHAPE;
-  if (K % 128 != 0) return GG_ERR_UNSUPPORTED;
+  if (K % 16 != 0) return GG_ERR_UNSUPPORTED;
   if (!padded_offsets || !group_offsets) return GG_ERR_NULL;
   if (M_pad_cap > 0 && (!A_pad || !SA_pad)) return GG_ERR_NULL;
   if (M_total > 0 && (!A || !SA)) return GG_ERR_NULL;
@@ -276,7 +287,7 @@ int gg_fp8_pad(const void* A, const float* SA, const int32_t* group_offsets, voi
   if (grid > nblocks) grid = nblocks;
   hipLaunchKernelGGL(gg::gg_pad_rows_kernel, dim3((unsigned)grid), dim3(gg::PAD_THREADS), 0, s,
                      static_cast<const uint8_t*>(A), SA, group_offsets, padded_offsets, static_cast<uint8_t*>(A_pad),
-                     SA_pad, G, (int)M_total, (int)M_pad_cap, K, K / 128);
+                     SA_pad, G, (int)M_total, (int)M_pad_cap, K, (K + 127) / 128);
   return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
 }
 
@@ -291,7 +302,7 @@ int gg_fp8_unpad(const void* C_pad, const int32_t* group_offsets, const int32_t*
                  int64_t M_total, int N, void* stream) {
   if (G < 0 || M_total < 0 || N <= 0) return GG_ERR_SHAPE;
   if (M_total > 0x7FFFFFFFLL || N > (1 << 21)) return GG_ERR_SHAPE;
-  if (N % 128 != 0) return GG_ERR_UNSUPPORTED;
+  if (N % 8 != 0) return GG_ERR_UNSUPPORTED;
   if (G == 0 || M_total == 0) return GG_OK;
   if (!C_pad || !group_offsets || !padded_offsets || !C) return GG_ERR_NULL;
   const int64_t nblocks = (M_total + gg::PAD_BLOCK_ROWS - 1) / gg::PAD_BLOCK_ROWS;

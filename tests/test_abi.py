@@ -76,8 +76,8 @@ def test_gemm_argument_validation(lib):
     def call(A=p, SA=p, B=p, SB=p, off=p, C=p, G=2, M=100, N=256, K=256):
         return f(A, SA, B, SB, off, C, G, M, N, K, nul, 0, nul)
 
-    assert call(N=200) == GG_ERR_UNSUPPORTED
-    assert call(K=64) == GG_ERR_UNSUPPORTED
+    assert call(N=204) == GG_ERR_UNSUPPORTED      # N must be a multiple of 8 (16-byte stores of C)
+    assert call(K=72) == GG_ERR_UNSUPPORTED       # K must be a multiple of 16 (16-byte fetches)
     assert call(N=0) == GG_ERR_SHAPE
     assert call(K=-128) == GG_ERR_SHAPE
     assert call(G=-1) == GG_ERR_SHAPE

@@ -404,3 +404,75 @@ def test_binary16_output_full_size_sampled_rows():
                                np.searchsorted(off, rows, side="right") - 1, minlength=p["G"]))]),
                            with_abs_sum=True, out="f16")
     assert_parity(f16_bits_of(C[ridx]), ref, what="binary16 gate_up", fmt="f16")
+
+
+# ---------------------------------------------------------------------------------------------- ragged N and K
+@pytest.mark.parametrize("sizes,N,K", [
+    ([70, 0, 129, 5], 200, 208),             # one partial tile, one short K block after a full one
+    ([33, 260], 136, 144),                   # 8 columns and 16 bytes past the first block
+    ([300], 392, 528),                       # 256 + 136 columns: full tile then partial; 4 K blocks + 16 bytes
+    ([17, 1, 140], 8, 16),                   # the smallest legal shape
+    ([64, 64], 648, 4112),                   # K = 4096 + 16
+    ([50, 3], 1032, 128),                    # N ragged only
+    ([50, 3], 256, 1008),                    # K ragged only
+])
+def test_ragged_n_and_k_every_variant_that_takes_them(sizes, N, K):
+    """Ceilings in Table 1 of the paper: the last scale block along K and along N may be short.  The library takes
+    any N % 8 == 0 and K % 16 == 0 (16-byte stores and fetches); raw bytes and uniform scales, hard bound."""
+    rng = np.random.default_rng(900 + N + K)
+    sizes = np.asarray(sizes)
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    M, G = int(off[-1]), len(sizes)
+    KB, NB = -(-K // 128), -(-N // 128)
+    A = rng.integers(0, 256, (M, K), dtype=np.uint8)
+    B = rng.integers(0, 256, (G, N, K), dtype=np.uint8)
+    A[(A & 0x7F) == 0x7F] = 0x35
+    B[(B & 0x7F) == 0x7F] = 0x35
+    A[(A & 0x78) > 0x58] &= 0xBF             # keep magnitudes moderate: no overflow of bf16 with scales up to 4
+    SA = rng.uniform(0.25, 4.0, (M, KB)).astype(np.float32)
+    SB = rng.uniform(0.25, 4.0, (G, NB, KB)).astype(np.float32)
+    ref = orc.grouped_gemm(A, SA, B, SB, off, with_abs_sum=True)
+    dev = tuple(torch.from_numpy(x).to(DEV) for x in (A, SA, B, SB, off))
+    first, supported = None, []
+    for v in [-1] + list(range(gg.num_variants())):
+        C = torch.full((M + 3, N), CANARY, dtype=torch.int16, device=DEV).view(torch.bfloat16)
+        try:
+            gg.grouped_gemm(*dev, C=C[:M], variant=v)
+        except gg.GGError as e:                 # a variant built for whole tiles and whole K blocks only says so
+            assert e.status == 3 and v >= 0
+            continue
+        supported.append(v)
+        torch.cuda.synchronize()
+        bits = bits_of(C)
+        assert (bits[M:] == CANARY).all(), f"variant {v} wrote past the last row"
+        assert_parity(bits[:M], ref, empirical=False, what=f"N={N} K={K} variant {v}")
+        first = bits if first is None else first
+        assert np.array_equal(bits, first), f"variant {v} differs from the others"
+    # the automatic choice and the tiles it draws from always work; the second kernel's variants never do here
+    names = {gg.variant_name(v) for v in supported if v >= 0}
+    assert -1 in supported and {"160x256/2x4w/3s", "128x128/2x4w/4s", "128x256/2x4w/3s", "32x256/1x8w/4s"} <= names
+    assert not any("-rb" in n for n in names)
+
+
+def test_ragged_shapes_pad_path_bitwise_and_exact_case():
+    rng = np.random.default_rng(77)
+    sizes, N, K = [130, 0, 1, 67], 200, 336
+    host, dev = None, None
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    M, G = int(off[-1]), len(sizes)
+    KB, NB = -(-K // 128), -(-N // 128)
+    # small integers and power-of-two scales: every intermediate is exact, the GPU must equal the oracle bit for bit
+    ints = np.array([0x00, 0x38, 0xB8, 0x40, 0xC0, 0x44], dtype=np.uint8)       # 0, 1, -1, 2, -2, 3
+    A = ints[rng.integers(0, len(ints), (M, K))]
+    B = ints[rng.integers(0, len(ints), (G, N, K))]
+    SA = (2.0 ** rng.integers(-2, 3, (M, KB))).astype(np.float32)
+    SB = (2.0 ** rng.integers(-2, 3, (G, NB, KB))).astype(np.float32)
+    ref = orc.grouped_gemm(A, SA, B, SB, off)
+    At, SAt, Bt, SBt, offt = (torch.from_numpy(x).to(DEV) for x in (A, SA, B, SB, off))
+    C1 = gg.grouped_gemm(At, SAt, Bt, SBt, offt)
+    A_pad, SA_pad, poff = gg.pad(At, SAt, offt)
+    C_pad = gg.grouped_gemm_padded(A_pad, SA_pad, Bt, SBt, poff)
+    C2 = gg.unpad(C_pad, offt, poff, M)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(C1), ref["C"])
+    assert np.array_equal(bits_of(C2), ref["C"])
