@@ -219,16 +219,25 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
   const int sbRd = Cfg::A_BYTES + Cfg::B_BYTES + Cfg::SA_BYTES + ((wn * WTN) >> 7) * 4;
 
   // ---- persistent walk over the tile list ---------------------------------------------------------
+  // A workgroup knows its next tile while it works on the current one: in the ring-of-buffers path without the
+  // mid-stream barrier the last STAGES-1 K blocks of a tile, which have nothing left to fetch for it, fetch the
+  // first STAGES-1 K blocks of the next tile instead, so the ring does not run dry across the epilogue.
+  struct Tile {
+    bool valid;
+    int g, n0, rows_valid;
+    int64_t grow;
+  };
   int g = 0, base = 0;
   const int nwg = gridDim.x;
-  for (int it = 0;; ++it) {
+  auto find_tile = [&](int it) __attribute__((always_inline)) -> Tile {
+    Tile t = {false, 0, 0, 0, 0};
     int T;
     if (a.slots > 0) T = (it * 8 + (int)(blockIdx.x & 7)) * a.slots + (int)(blockIdx.x >> 3);
     else T = it * nwg + blockIdx.x;
 
     int row0 = 0, Mg = 0, mtiles = 0;
     for (;;) {
-      if (g >= a.G) return;
+      if (g >= a.G) return t;
       row0 = clampi(a.off[g], 0, a.M_total);
       const int row1 = clampi(a.off[g + 1], row0, a.M_total);
       Mg = row1 - row0;
@@ -249,24 +258,48 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
     const int ntile = nc * a.n_chunk + (rem - mtile * csz);
 
     const int m0 = mtile * BM;
-    const int n0 = ntile * BN;
-    int rows_valid = Mg - m0;
-    rows_valid = rows_valid < BM ? rows_valid : BM;
-    const int64_t grow = (int64_t)row0 + m0;
-
-    // bounded views: nothing past the last valid row of this tile is loaded or stored
-    __amdgpu_buffer_rsrc_t dA = __builtin_amdgcn_make_buffer_rsrc((void*)(a.A + grow * K), 0, rows_valid * K, GG_RSRC_FLAGS);
-    __amdgpu_buffer_rsrc_t dSA = __builtin_amdgcn_make_buffer_rsrc((void*)(a.SA + grow * KB), 0, rows_valid * KB * 4, GG_RSRC_FLAGS);
-    // N not a multiple of the tile width: the weight rows, scale blocks and output columns past N do not exist
-    // (the row part of a weight fetch is in the lane offset, the only part the descriptor's bounds check sees)
-    const int n_rem = N - n0;
-    const int bn_valid = RAGGED && n_rem < BN ? n_rem : BN;
-    const int nb_all = RAGGED ? (N + 127) >> 7 : N >> 7;
-    int nb_valid = nb_all - (n0 >> 7);
+    t.g = g;
+    t.n0 = ntile * BN;
+    t.rows_valid = Mg - m0 < BM ? Mg - m0 : BM;
+    t.grow = (int64_t)row0 + m0;
+    t.valid = true;
+    return t;
+  };
+  // bounded views: nothing past the last valid row of a tile is loaded or stored.
+  // N not a multiple of the tile width: the weight rows, scale blocks and output columns past N do not exist
+  // (the row part of a weight fetch is in the lane offset, the only part the descriptor's bounds check sees)
+  const int nb_all = RAGGED ? (N + 127) >> 7 : N >> 7;
+  // on = false: a view of length zero, through which every fetch is dropped (same instruction count, no traffic)
+  auto desc_a = [&](const Tile& t, bool on) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)(a.A + t.grow * K), 0, on ? t.rows_valid * K : 0, GG_RSRC_FLAGS);
+  };
+  auto desc_sa = [&](const Tile& t, bool on) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)(a.SA + t.grow * KB), 0, on ? t.rows_valid * KB * 4 : 0, GG_RSRC_FLAGS);
+  };
+  auto desc_b = [&](const Tile& t, bool on) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
+    const int n_rem = N - t.n0;
+    return __builtin_amdgcn_make_buffer_rsrc((void*)(a.B + ((int64_t)t.g * N + t.n0) * K), 0, on ? (RAGGED && n_rem < BN ? n_rem : BN) * K : 0, GG_RSRC_FLAGS);
+  };
+  auto desc_sb = [&](const Tile& t, bool on) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
+    int nb_valid = nb_all - (t.n0 >> 7);
     nb_valid = RAGGED && nb_valid < BN / 128 ? nb_valid : BN / 128;
-    __amdgpu_buffer_rsrc_t dB = __builtin_amdgcn_make_buffer_rsrc((void*)(a.B + ((int64_t)g * N + n0) * K), 0, bn_valid * K, GG_RSRC_FLAGS);
-    __amdgpu_buffer_rsrc_t dC = __builtin_amdgcn_make_buffer_rsrc((void*)(a.C + grow * N + n0), 0, rows_valid * N * 2 - n0 * 2, GG_RSRC_FLAGS);
-    __amdgpu_buffer_rsrc_t dSB = __builtin_amdgcn_make_buffer_rsrc((void*)(a.SB + ((int64_t)g * nb_all + (n0 >> 7)) * KB), 0, nb_valid * KB * 4, GG_RSRC_FLAGS);
+    return __builtin_amdgcn_make_buffer_rsrc((void*)(a.SB + ((int64_t)t.g * nb_all + (t.n0 >> 7)) * KB), 0, on ? nb_valid * KB * 4 : 0, GG_RSRC_FLAGS);
+  };
+
+  // cross-tile prefetch needs a full ring's worth of K blocks per tile, and the path that has it
+  const bool xt = !Cfg::XPF && KB >= STAGES - 1;
+  Tile cur = find_tile(0);
+  if (!cur.valid) return;
+  __amdgpu_buffer_rsrc_t dA = desc_a(cur, true), dSA = desc_sa(cur, true), dB = desc_b(cur, true), dSB = desc_sb(cur, true);
+  int rot = k_rotation(a, cur.n0);
+  bool primed = false;      // the first STAGES-1 K blocks of `cur` were already fetched by the previous tile
+  int stage = 0;            // LDS buffer of the current K block; runs on across tiles
+  for (int it = 0;; ++it) {
+    const int n0 = cur.n0, rows_valid = cur.rows_valid;
+    const int n_rem = N - n0;
+    __amdgpu_buffer_rsrc_t dC = __builtin_amdgcn_make_buffer_rsrc((void*)(a.C + cur.grow * N + n0), 0, rows_valid * N * 2 - n0 * 2, GG_RSRC_FLAGS);
+    Tile nxt = {false, 0, 0, 0, 0};
+    bool has_next = false, prefetch = false;   // known once this tile's own fetches are all issued
 
     // ---- global -> LDS DMA of one K block, split so that it can be fed into the MFMA stream --------
     // A wave that issues its 8-9 DMAs back to back sits in the issue stage until the CU's vector-memory
@@ -277,14 +310,13 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
     constexpr int NDMA_ALL = A_FULL + B_FULL;                                  // issued by every wave
     constexpr int NDMA_STREAM = NDMA_ALL < Cfg::MFMAS ? NDMA_ALL : Cfg::MFMAS;  // of those, inside the stream
     constexpr int DMA_GAP = Cfg::GAP > 0 ? Cfg::GAP : Cfg::MFMAS / (NDMA_STREAM > 0 ? NDMA_STREAM : 1);
-    // K blocks are taken in the order rot, rot+1, ..., KB-1, 0, ..., rot-1 (see k_rotation)
-    const int rot = k_rotation(a, n0);
-    auto kphys = [&](int kb) -> int { return k_wrapped(kb + rot, KB); };
-    auto dma_tile = [&](auto idx_c, int kb_l, int stage) {
+    // K blocks are taken in the order rot, rot+1, ..., KB-1, 0, ..., rot-1 (see k_rotation).  dA, dSA, dB, dSB and
+    // rot are those of the current tile until its last fetch has been issued, and those of the next tile from then on.
+    auto dma_tile = [&](auto idx_c, int kb_l, int stg) {
       constexpr int idx = decltype(idx_c)::value;
-      const int kb = kphys(kb_l);
+      const int kb = k_wrapped(kb_l + rot, KB);
       const bool last = kb == KB - 1;
-      uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
+      uint8_t* st = lds + stg * Cfg::STAGE_BYTES;
       if constexpr (idx < A_FULL) {
         __builtin_amdgcn_raw_ptr_buffer_load_lds(dA, GG_LDS_PTR(st + (w + idx * NW) * 1024), 16, (RAGGED && last && a_tail) ? GG_OOB_OFFSET : vA + idx * (NW * 8) * K, kb * 128, 0, 0);
       } else {
@@ -295,10 +327,10 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
           __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(st + Cfg::A_BYTES + (w + i * NW) * 1024), 16, vB, i * (NW * 8) * K + kb * 128, 0, 0);
       }
     };
-    auto dma_head = [&](int kb_l, int stage) {   // everything that is not issued inside the stream
-      const int kb = kphys(kb_l);
+    auto dma_head = [&](int kb_l, int stg) {   // everything that is not issued inside the stream
+      const int kb = k_wrapped(kb_l + rot, KB);
       const bool last = kb == KB - 1;
-      uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
+      uint8_t* st = lds + stg * Cfg::STAGE_BYTES;
       if (w < Cfg::SA_WAVES)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(dSA, GG_LDS_PTR(st + Cfg::A_BYTES + Cfg::B_BYTES + w * 256), 4, vSA, kb * 4, 0, 0);
       if (w == Cfg::SB_WAVE)
@@ -314,9 +346,9 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
                                                    (RAGGED ? 0 : B_FULL * (NW * 8) * K) + kb * 128, 0, 0);
       }
     };
-    auto dma_all = [&](int kb, int stage) {
-      dma_head(kb, stage);
-      static_for<0, NDMA_ALL>([&](auto ic) { dma_tile(ic, kb, stage); });
+    auto dma_all = [&](int kb, int stg) {
+      dma_head(kb, stg);
+      static_for<0, NDMA_ALL>([&](auto ic) { dma_tile(ic, kb, stg); });
     };
 
     v4f acc[TM][TN];
@@ -369,7 +401,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
         sb_c = *(const float*)(st + sbRd);
       }
 
-      int stage = 0;
+      stage = 0;
       auto kstep_x = [&](int kb, auto issue_c, auto last_c) {
         constexpr bool ISSUE = decltype(issue_c)::value, LAST = decltype(last_c)::value;
         const int stage1 = stage + 1 == STAGES ? 0 : stage + 1;                   // buffer of block kb+1
@@ -448,11 +480,18 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
       for (; kb < kb_issue_end; ++kb) kstep_x(kb, std::true_type{}, std::false_type{});
       for (; kb < KB - 1; ++kb) kstep_x(kb, std::false_type{}, std::false_type{});
       kstep_x(kb, std::false_type{}, std::true_type{});
+      nxt = find_tile(it + 1);
+      has_next = nxt.valid;
     } else {
       // ======== ring of 2 buffers (or odd TM): one barrier per K block, at the block boundary ============
+      if (!primed) {
+        int sp = stage;
 #pragma unroll
-      for (int s = 0; s < STAGES - 1; ++s)
-        if (s < KB) dma_all(s, s);
+        for (int s = 0; s < STAGES - 1; ++s) {
+          if (s < KB) dma_all(s, sp);
+          sp = sp + 1 == STAGES ? 0 : sp + 1;
+        }
+      }
 
       // FMAs of the last PIPE MFMAs of a K block are carried into the next block's stream (their
       // accumulators are fixed at compile time), so the matrix pipe does not wait for a VALU tail
@@ -463,17 +502,22 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
 #pragma unroll
       for (int i = 0; i < PIPE; ++i) { pend[i] = (v4f){0.f, 0.f, 0.f, 0.f}; s_pend[i] = 0.f; }
 
-      // One K block.  ISSUE: the DMA of block kb + STAGES - 1 is issued during this block.
-      auto kstep = [&](int kb, auto issue_c) {
-        constexpr bool ISSUE = decltype(issue_c)::value;
-        const int stage = kb % STAGES;
-        const int nstage = (kb + STAGES - 1) % STAGES;
+      // One K block.  MODE 1: the DMA of block kb + STAGES - 1 is issued during this block; MODE 2: this tile has
+      // no such block any more and the DMA of block kb + STAGES - 1 - KB of the next tile is issued instead (through
+      // views of length zero when there is no next tile to fetch for: every K block issues the same fetches).
+      auto kstep = [&](int kb, auto mode_c) {
+        constexpr int MODE = decltype(mode_c)::value;
+        constexpr bool ISSUE = true;
+        int kb_new = MODE == 2 ? kb + STAGES - 1 - KB : kb + STAGES - 1;
+        if (MODE == 2 && kb_new >= KB) kb_new = KB - 1;      // fewer K blocks than ring buffers: dropped anyway
+        const int nstage = stage == 0 ? STAGES - 1 : stage - 1;
         // The DMA of this K block (issued STAGES-1 blocks ago by every wave) must have landed; the newer
-        // blocks may stay in flight.  Loads complete in order, but stores do not order with loads, so
-        // the first block of a tile drains everything (the previous tile's epilogue stores too).
+        // blocks (of this tile, then of the next) may stay in flight.  Loads complete in order, but stores do not
+        // order with loads, so the first block of a tile drains everything (the previous tile's epilogue stores too).
         {
-          int younger = KB - 1 - kb;
-          younger = younger < STAGES - 2 ? younger : STAGES - 2;
+          // every K block issues one group of fetches, so STAGES-2 groups are younger than block kb (KB-1 if the
+          // tile has fewer K blocks than the ring has buffers)
+          int younger = KB - 1 < STAGES - 2 ? KB - 1 : STAGES - 2;
           if (kb == 0) younger = 0;
           wait_all_but<NDMA_ALL, STAGES - 2>(younger, dma_extra);
         }
@@ -498,8 +542,8 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
 #pragma unroll
         for (int mt = 1; mt < TM; ++mt) sa[mt] = *(const float*)(st + saRd + mt * 64);
         if constexpr (ISSUE) {
-          dma_head(kb + STAGES - 1, nstage);
-          static_for<NDMA_STREAM, NDMA_ALL>([&](auto ic) { dma_tile(ic, kb + STAGES - 1, nstage); });
+          dma_head(kb_new, nstage);
+          static_for<NDMA_STREAM, NDMA_ALL>([&](auto ic) { dma_tile(ic, kb_new, nstage); });
         }
         __builtin_amdgcn_sched_barrier(0);   // the reads above keep their order; the stream below is ordered by hand
 
@@ -514,7 +558,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
           if constexpr (j == 0 && mt + 1 < TM) afr[(mt + 1) & 1] = read_a(mt + 1, st);
           p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[j], afr[mt & 1], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
           if constexpr (ISSUE && NDMA_STREAM > 0 && (t + 1) % DMA_GAP == 0 && (t + 1) / DMA_GAP <= NDMA_STREAM)
-            dma_tile(std::integral_constant<int, (t + 1) / DMA_GAP - 1>{}, kb + STAGES - 1, nstage);
+            dma_tile(std::integral_constant<int, (t + 1) / DMA_GAP - 1>{}, kb_new, nstage);
           if constexpr (t < PIPE) {
             constexpr int u = MF - PIPE + t;                 // carried over from the previous K block
             acc[u / TN][u % TN] += pend[t] * s_pend[t];
@@ -535,18 +579,27 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < PIPE; ++i) { pend[i] = p[MF - PIPE + i]; s_pend[i] = s[(MF - PIPE + i) / TN]; }
+        stage = stage + 1 == STAGES ? 0 : stage + 1;
       };
 
       const int kb_issue_end = KB - (STAGES - 1) > 0 ? KB - (STAGES - 1) : 0;
       int kb = 0;
-      for (; kb < kb_issue_end; ++kb) kstep(kb, std::true_type{});
-      for (; kb < KB; ++kb) kstep(kb, std::false_type{});
+      for (; kb < kb_issue_end; ++kb) kstep(kb, std::integral_constant<int, 1>{});
+      // this tile has issued its last fetch: from here on the descriptors are the next tile's
+      nxt = find_tile(it + 1);
+      has_next = nxt.valid;
+      prefetch = has_next && xt;
+      dA = desc_a(nxt, prefetch); dSA = desc_sa(nxt, prefetch); dB = desc_b(nxt, prefetch); dSB = desc_sb(nxt, prefetch);
+      rot = k_rotation(a, nxt.n0);
+      for (; kb < KB; ++kb) kstep(kb, std::integral_constant<int, 2>{});
       static_for<0, PIPE>([&](auto ic) {
         constexpr int u = MF - PIPE + decltype(ic)::value;
         acc[u / TN][u % TN] += pend[decltype(ic)::value] * s_pend[decltype(ic)::value];
       });
     }
-    __syncthreads();  // every wave is done reading LDS before the next tile's prologue overwrites it
+    // every wave is done reading LDS before the next tile's prologue overwrites it; with the next tile's first
+    // blocks already in flight there is no prologue, and the barrier of its first K block does the same job
+    if (!prefetch) __syncthreads();
 
     // ---- epilogue: bf16 (or binary16) RNE, 16-byte bounded stores ---------------------------------------------
 #pragma unroll
@@ -565,6 +618,16 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
         __builtin_amdgcn_raw_buffer_store_b128(out, dC, (!RAGGED || col < n_rem) ? row * N * 2 + col * 2 : GG_OOB_OFFSET, 0, 0);
       }
     }
+    if (!has_next) {
+      wait_vmcnt<0>();     // the dropped fetches of the last K blocks still write zeros into this workgroup's LDS
+      return;
+    }
+    if (!prefetch) {
+      dA = desc_a(nxt, true); dSA = desc_sa(nxt, true); dB = desc_b(nxt, true); dSB = desc_sb(nxt, true);
+      rot = k_rotation(a, nxt.n0);
+    }
+    cur = nxt;
+    primed = prefetch;
   }
 }
 
