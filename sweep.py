@@ -37,6 +37,8 @@ def main():
     ap.add_argument("--cold", action="store_true",
                     help="overwrite a 1 GiB buffer before every timed launch, so that neither the L2s nor the 256 MB "
                          "Infinity Cache hold any input (default: same buffers every launch, caches warm)")
+    ap.add_argument("--free-only", action="store_true",
+                    help="time the padding-free path only (for comparing tile variants; the pad columns repeat its time)")
     ap.add_argument("--seed", type=int, default=20250816)
     ap.add_argument("--out", type=str, default=None, help="write the JSON lines here instead of stdout")
     ap.add_argument("--summary", type=str, default=None, help="write the summary (markdown) here as well as to stderr")
@@ -134,10 +136,13 @@ def main():
                         assert rc == 0
 
                     t_free = timed(free_step)
-                    t_pad = timed(lambda: pad_step(False))
-                    t_pad_unpad = timed(lambda: pad_step(True))
-                    m_pad = int(poff[-1].item())
-                    assert m_pad == int(np.sum(128 * ((sizes + 127) // 128)))
+                    m_pad = int(np.sum(128 * ((sizes + 127) // 128)))
+                    if args.free_only:
+                        t_pad = t_pad_unpad = t_free
+                    else:
+                        t_pad = timed(lambda: pad_step(False))
+                        t_pad_unpad = timed(lambda: pad_step(True))
+                        assert m_pad == int(poff[-1].item())
                     used = args.variant if args.variant >= 0 else gg.auto_variant(G, M, N, K)
                     rec = {
                         "N": N, "K": K, "G": G, "M": M, "M_pad": m_pad,
