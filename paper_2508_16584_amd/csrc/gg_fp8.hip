@@ -192,6 +192,7 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
 
   // upper bound on the number of tiles for any offsets: every group adds at most one partial m-tile
   const int64_t max_tiles = (M_total / v.BM + G) * (int64_t)args.n_tiles;
+  if (max_tiles > 0x7FFFFFFFLL) return GG_ERR_SHAPE;   // the kernels count tiles in 32 bits
   int64_t grid = (int64_t)device_cus() * v.wg_per_cu;
   if (grid > max_tiles) grid = max_tiles;
   if (grid < 1) grid = 1;

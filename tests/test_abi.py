@@ -83,6 +83,7 @@ def test_gemm_argument_validation(lib):
     assert call(G=-1) == GG_ERR_SHAPE
     assert call(M=-1) == GG_ERR_SHAPE
     assert call(M=2 ** 31) == GG_ERR_SHAPE
+    assert call(M=2 ** 31 - 1, N=2 ** 21, K=128) == GG_ERR_SHAPE      # more tiles than the kernels' 32-bit tile index
     for name in ("A", "SA", "B", "SB", "off", "C"):
         assert call(**{name: nul}) == GG_ERR_NULL, name
     # empty problems succeed without touching any pointer

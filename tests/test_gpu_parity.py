@@ -88,6 +88,26 @@ def test_edge_group_sizes_every_variant(sizes, N, K):
         assert_parity(got, ref, empirical=p["M_total"] * N >= 50000, what=f"sizes {sizes} variant {v}")
 
 
+def test_many_empty_groups_and_a_wide_output():
+    rng = np.random.default_rng(61)
+    # 1000 groups of which 988 are empty: the tile walk steps over long runs of zero-row groups
+    sizes = np.zeros(1000, dtype=np.int64)
+    sizes[rng.choice(1000, size=12, replace=False)] = rng.integers(1, 70, size=12)
+    cfg = WorkloadConfig("empties", 53, 1000, 256, 256, 0, "custom", "latency")
+    p = make_problem(cfg, sizes=sizes)
+    ref = orc.grouped_gemm(*np_problem(p), with_abs_sum=True)
+    dev = tuple(p[k].to(DEV) for k in ("A", "SA", "B", "SB", "group_offsets"))
+    for v in (-1, 0, 5, 14):
+        assert_parity(run_gpu(dev, p["M_total"], 256, v), ref, empirical=False, what=f"1000 groups variant {v}")
+    # N = 16384: 64 column tiles per row tile, walked in chunks of 8
+    cfg = WorkloadConfig("wide", 54, 2, 256, 16384, 0, "custom", "latency")
+    p = make_problem(cfg, sizes=np.array([37, 200]))
+    ref = orc.grouped_gemm(*np_problem(p), with_abs_sum=True)
+    dev = tuple(p[k].to(DEV) for k in ("A", "SA", "B", "SB", "group_offsets"))
+    for v in (-1, 1, 2, 12):
+        assert_parity(run_gpu(dev, p["M_total"], 16384, v), ref, what=f"N=16384 variant {v}")
+
+
 def test_rows_outside_the_groups_and_guard_bands_are_untouched():
     # groups cover rows [5, 5+sum) of a larger buffer; C has guard rows before and after
     rng = np.random.default_rng(60)
