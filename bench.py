@@ -141,16 +141,102 @@ def bench_quantize_rows(args, cfg, dev):
     print(json.dumps(out))
 
 
+def bench_expert_mlp(args, cfg, dev):
+    """Forward pass of the experts' MLP on the workload's routing: bf16 tokens [M_total, K] gathered by expert and
+    quantised, GEMM with [G, N, K] (gate | up), silu(gate) * up + quantise, GEMM with [G, K, N/2] (down).  Padding-
+    free: four kernels on M_total rows.  Padded (what a GEMM that needs 128-row groups forces on its neighbours):
+    pad copy after the quantiser, both GEMMs and the activation on the padded rows, un-pad copy at the end."""
+    import ctypes
+    import numpy as np
+    import torch
+
+    import paper_2508_16584_amd as gg
+    from workloads import group_sizes
+    from workloads.quantize import quantize_b
+
+    sizes = group_sizes(cfg, cfg.seed)
+    G, M, K, N = cfg.G, int(np.sum(sizes)), cfg.K, cfg.N
+    inter = N // 2
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg.seed)
+    rng = np.random.default_rng(cfg.seed)
+    off = torch.from_numpy(np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)).to(dev)
+    X = torch.randn((M, K), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    src = torch.from_numpy(rng.permutation(M).astype(np.int32)).to(dev)
+    B1 = torch.empty((G, N, K), dtype=torch.uint8, device=dev)
+    SB1 = torch.empty((G, N // 128, K // 128), dtype=torch.float32, device=dev)
+    B2 = torch.empty((G, K, inter), dtype=torch.uint8, device=dev)
+    SB2 = torch.empty((G, K // 128, inter // 128), dtype=torch.float32, device=dev)
+    for g in range(G):
+        B1[g], SB1[g] = quantize_b(torch.randn((N, K), generator=gen, device=dev) * 0.02)
+        B2[g], SB2[g] = quantize_b(torch.randn((K, inter), generator=gen, device=dev) * 0.02)
+    cap = gg.padded_rows_cap(G, M)
+    A1 = torch.empty((M, K), dtype=torch.uint8, device=dev)
+    SA1 = torch.empty((M, K // 128), dtype=torch.float32, device=dev)
+    H = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    A2 = torch.empty((M, inter), dtype=torch.uint8, device=dev)
+    SA2 = torch.empty((M, inter // 128), dtype=torch.float32, device=dev)
+    Y = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+    H_pad = torch.empty((cap, N), dtype=torch.bfloat16, device=dev)
+    A2_pad = torch.empty((cap, inter), dtype=torch.uint8, device=dev)
+    SA2_pad = torch.empty((cap, inter // 128), dtype=torch.float32, device=dev)
+    Y_pad = torch.empty((cap, K), dtype=torch.bfloat16, device=dev)
+
+    def free_chain():
+        gg.quantize_rows(X, src, A=A1, SA=SA1)
+        gg.grouped_gemm(A1, SA1, B1, SB1, off, C=H)
+        gg.swiglu_quantize_rows(H, A=A2, SA=SA2)
+        gg.grouped_gemm(A2, SA2, B2, SB2, off, C=Y)
+
+    def pad_chain():
+        gg.quantize_rows(X, src, A=A1, SA=SA1)
+        A_pad, SA_pad, poff = gg.pad(A1, SA1, off)
+        gg.grouped_gemm_padded(A_pad, SA_pad, B1, SB1, poff, C_pad=H_pad)
+        gg.swiglu_quantize_rows(H_pad, A=A2_pad, SA=SA2_pad)
+        gg.grouped_gemm_padded(A2_pad, SA2_pad, B2, SB2, poff, C_pad=Y_pad)
+        gg.unpad(Y_pad, off, poff, M, C=Y)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    t_free = timed(free_chain)
+    y_free = Y.clone()
+    t_pad = timed(pad_chain)
+    same = bool(torch.equal(y_free.view(torch.int16), Y.view(torch.int16)))
+    flops = 2.0 * M * N * K + 2.0 * M * K * inter
+    print(json.dumps({
+        "metric": "expert MLP forward (quantise, GEMM, silu*up + quantise, GEMM), FP8 TFLOP/s of the two GEMMs on valid rows",
+        "value": round(flops / (t_free * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(t_free, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 tokens, fp8_e4m3 operands, fp32 accumulate, bf16 out", "data": "synthetic",
+        "config": {"workload": args.workload + " routing", "op": "expert_mlp", "G": G, "M_total": M, "hidden": K,
+                   "intermediate": inter},
+        "padded_chain_ms": round(t_pad, 4), "speedup_vs_padded_chain": round(t_pad / t_free, 4),
+        "padded_chain_output_bitwise_equal": same,
+        "note": "caches warm (same buffers every step); the padded chain adds a pad and an un-pad copy and runs the "
+                "GEMMs and the activation on 128-row padded groups",
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="gate_up")
-    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows", "swiglu_quantize_rows"],
+    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows", "swiglu_quantize_rows", "expert_mlp"],
                     help="grouped_gemm: the hot path (default, the headline metric); quantize_rows: the producer of its "
                          "A operand on the same workload's activation shape; swiglu_quantize_rows: activation + quantiser "
-                         "on the workload's output shape [M_total, N] (N = 2 x intermediate width)")
+                         "on the workload's output shape [M_total, N] (N = 2 x intermediate width); expert_mlp: the whole forward "
+                         "chain quantise -> GEMM -> activation+quantise -> GEMM on the workload's routing, padding-free "
+                         "against the same chain on 128-row padded groups")
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--copies", type=int, default=0, help="input copies to rotate over (0 = enough for 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -178,6 +264,9 @@ def main():
     cfg = CONFIGS[args.workload]
     if args.op in ("quantize_rows", "swiglu_quantize_rows"):
         bench_quantize_rows(args, cfg, dev)
+        return
+    if args.op == "expert_mlp":
+        bench_expert_mlp(args, cfg, dev)
         return
     p = make_problem(cfg, device=dev)
     G, M, N, K = p["G"], p["M_total"], p["N"], p["K"]
