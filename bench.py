@@ -334,6 +334,7 @@ def main():
     vname = gg.variant_name(used)
     roof["kernel"] = ("gg_gemm_rb_kernel<" if "-rb" in vname else "gg_gemm_kernel<") + vname + ">"
     roof["kernel_avg_ms"] = round(kern_avg_ms, 4)
+    roof["kernel_median_ms"] = round(float(np.median(kern_ms)), 4)
     roof["kernel_min_ms"] = round(float(kern_ms.min()), 4)
     roof["algorithmic_bytes"] = int(alg_bytes)
     roof["algorithmic_flops"] = flops
