@@ -122,19 +122,22 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
   const int sbRd = Cfg::A_BYTES + Cfg::SA_BYTES + ((w * 32) >> 7) * 4;
   uint8_t* const bslots = lds + Cfg::B_BASE + w * (Cfg::B_SLOTS * Cfg::B_SLOT_BYTES);   // this wave's weight slots
 
+  // ---- persistent walk over the tile list; a workgroup looks one tile ahead (see "carry" below) -------------
+  struct Tile {
+    bool valid;
+    int g, n0, rows_valid;
+    int64_t grow;
+  };
   int g = 0, base = 0;
   const int nwg = gridDim.x;
-  for (int it = 0;; ++it) {
+  auto find_tile = [&](int it) __attribute__((always_inline)) -> Tile {
+    Tile t = {false, 0, 0, 0, 0};
     int T;
     if (a.slots > 0) T = (it * 8 + (int)(blockIdx.x & 7)) * a.slots + (int)(blockIdx.x >> 3);
     else T = it * nwg + blockIdx.x;
     int row0 = 0, Mg = 0, mtiles = 0;
     for (;;) {
-      if (g >= a.G) {
-        // the out-of-range fetches of the last K blocks write zeros into this workgroup's LDS: let them land
-        wait_vmcnt<0>();
-        return;
-      }
+      if (g >= a.G) return t;
       row0 = clampi(a.off[g], 0, a.M_total);
       const int row1 = clampi(a.off[g + 1], row0, a.M_total);
       Mg = row1 - row0;
@@ -152,49 +155,90 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     csz = csz < a.n_chunk ? csz : a.n_chunk;
     const int mtile = rem / csz;
     const int ntile = nc * a.n_chunk + (rem - mtile * csz);
-    const int m0 = mtile * BM, n0 = ntile * BN;
-    int rows_valid = Mg - m0;
-    rows_valid = rows_valid < BM ? rows_valid : BM;
-    const int64_t grow = (int64_t)row0 + m0;
+    const int m0 = mtile * BM;
+    t.g = g;
+    t.n0 = ntile * BN;
+    t.rows_valid = Mg - m0 < BM ? Mg - m0 : BM;
+    t.grow = (int64_t)row0 + m0;
+    t.valid = true;
+    return t;
+  };
+  // Bounded descriptors: rows past the group's end read as zero and are never written (paper Sec. 2.2:
+  // no padding, no out-of-group access).  on = false: views of length zero (every fetch through them is dropped).
+  // One descriptor per 64-row band of the A tile: a lane's offset inside its band is then the same for every
+  // slab it fetches (one register instead of one per slab).
+  auto band = [&](const Tile& t, int i, bool on) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
+    int rows_i = t.rows_valid - 64 * i;
+    rows_i = rows_i < 0 ? 0 : (rows_i > 64 ? 64 : rows_i);
+    return uniform_rsrc(a.A + (t.grow + 64 * i) * K, on ? rows_i * K : 0);
+  };
+  auto desc_b = [&](const Tile& t, bool on) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
+    return uniform_rsrc(a.B + ((int64_t)t.g * N + t.n0) * K, on ? BN * K : 0);
+  };
+  // this wave's scale source: the activation scales of the tile's rows, or the weight scales of its two column blocks
+  auto desc_s = [&](const Tile& t, bool on) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
+    return sa_wave ? uniform_rsrc(a.SA + t.grow * KB, on ? t.rows_valid * KB * 4 : 0)
+                   : uniform_rsrc(a.SB + ((int64_t)t.g * (N >> 7) + (t.n0 >> 7)) * KB, on ? (BN / 128) * KB * 4 : 0);
+  };
 
-    // Bounded descriptors: rows past the group's end read as zero and are never written (paper Sec. 2.2:
-    // no padding, no out-of-group access).
-    // One descriptor per 64-row band of the A tile: a lane's offset inside its band is then the same for every
-    // slab it fetches (one register instead of one per slab).
-    auto band = [&](int i) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
-      int rows_i = rows_valid - 64 * i;
-      rows_i = rows_i < 0 ? 0 : (rows_i > 64 ? 64 : rows_i);
-      return uniform_rsrc(a.A + (grow + 64 * i) * K, rows_i * K);
-    };
-    __amdgpu_buffer_rsrc_t dA0 = band(0), dA1 = band(1 % Cfg::A_ITERS), dA2 = band(2 % Cfg::A_ITERS), dA3 = band(3 % Cfg::A_ITERS);
-    __amdgpu_buffer_rsrc_t dB = uniform_rsrc(a.B + ((int64_t)g * N + n0) * K, BN * K);
-    // this wave's scale source: the activation scales of the tile's rows, or the weight scales of its two column blocks
-    __amdgpu_buffer_rsrc_t dS = sa_wave ? uniform_rsrc(a.SA + grow * KB, rows_valid * KB * 4)
-                                        : uniform_rsrc(a.SB + ((int64_t)g * (N >> 7) + (n0 >> 7)) * KB, (BN / 128) * KB * 4);
+  // Carry: the fetches a K step issues run two to three K blocks ahead; at the end of a tile those blocks are the
+  // first blocks of the workgroup's next tile.  With an even number of K blocks (the two register sets alternate
+  // by K-block parity) the descriptors are re-pointed to the next tile as its first fetches come up, the K loop
+  // runs on into it, and the state at the end of the last K block IS the state the prologue would have built.
+  // The host only launches this kernel with an even KB >= 4.
+  Tile cur = find_tile(0);
+  if (!cur.valid) return;
+  __amdgpu_buffer_rsrc_t dA0 = band(cur, 0, true), dA1 = band(cur, 1 % Cfg::A_ITERS, true), dA2 = band(cur, 2 % Cfg::A_ITERS, true),
+                         dA3 = band(cur, 3 % Cfg::A_ITERS, true);
+  __amdgpu_buffer_rsrc_t dB = desc_b(cur, true), dB0 = dB;     // dB0: the stream of fragments j = 0, one K block further ahead
+  __amdgpu_buffer_rsrc_t dS = desc_s(cur, true);
+  int rot = k_rotation(a, cur.n0), rot0 = rot;
+  int kbase = 0, kbase0 = 0;      // K-block index at which the tile behind dA.., dB, dS (resp. dB0) starts
+  bool primed = false;
+  v8i bfr[2][TN];                 // weight fragments of K block kb in set kb % 2
+  v8i afr[AFR];
+  float sa[AFR];
+  float sb_next = 0.f;
+  int stage = 0;                  // LDS buffer of block kb
+  int bslot = 2;                  // slot of fragment 2*kb + 2
+  for (int it = 0;; ++it) {
+    const int n0 = cur.n0, rows_valid = cur.rows_valid;
+    const int64_t grow = cur.grow;
+    // The next tile is looked up here, not where it is first needed: the four K steps at the end of the tile must
+    // stay one basic block (with control flow between them the compiler sinks the accumulator updates of a step
+    // into the next block, and every product of the step stays alive across it).
+    const Tile nxt = find_tile(it + 1);
+    const bool has_next = nxt.valid;
 
-    // K blocks are taken in the order rot, rot+1, ..., KB-1, 0, ..., rot-1 (see k_rotation)
-    const int rot = k_rotation(a, n0);
-    // K blocks past the end are "fetched" from an out-of-range offset: same instruction count, no traffic
-    auto dma_a = [&](auto ic, int kb, int stage) __attribute__((always_inline)) {   // one 8-row slab of block kb's A tile
+    // K blocks are taken in the order rot, rot+1, ..., KB-1, 0, ..., rot-1 (see k_rotation).
+    // K blocks past the end of the tile a descriptor points to are "fetched" from an out-of-range offset: same
+    // instruction count, no traffic.
+    auto dma_a = [&](auto ic, int kb_t, int stage) __attribute__((always_inline)) {   // one 8-row slab of block kb's A tile
       constexpr int i = decltype(ic)::value;
+      const int kb = kb_t - kbase;
       const int vo = kb < KB ? vA : GG_OOB_OFFSET;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(i == 0 ? dA0 : i == 1 ? dA1 : i == 2 ? dA2 : dA3, GG_LDS_PTR(lds + stage * Cfg::STAGE_BYTES + (w + i * NW) * 1024), 16, vo,
                                                __builtin_amdgcn_readfirstlane(k_wrapped(kb + rot, KB) * 128), 0, 0);
     };
-    auto dma_scales = [&](int kb, int stage) __attribute__((always_inline)) {     // exactly one DMA in every wave
+    auto dma_scales = [&](int kb_t, int stage) __attribute__((always_inline)) {     // exactly one DMA in every wave
+      const int kb = kb_t - kbase;
       const int vo = kb < KB ? vS : GG_OOB_OFFSET;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(dS, GG_LDS_PTR(lds + stage * Cfg::STAGE_BYTES + ldsS), 4, vo,
                                                __builtin_amdgcn_readfirstlane(k_wrapped(kb + rot, KB) * 4), 0, 0);
     };
     // weight fragment j of block kb into slot `slot` of this wave: two slabs of 8 fragment rows
-    auto dma_b = [&](int kb, int j, int slot) __attribute__((always_inline)) {
+    auto dma_b = [&](int kb_t, auto jc, int slot) __attribute__((always_inline)) {
+      constexpr int j = decltype(jc)::value;
+      const int kb = kb_t - (j == 0 ? kbase0 : kbase);
       const bool in = kb < KB;
       uint8_t* dst = bslots + slot * Cfg::B_SLOT_BYTES;
       // all 256 weight rows of the tile exist: only the lane part of the offset needs the bounds check
-      const int so = __builtin_amdgcn_readfirstlane(k_wrapped(kb + rot, KB) * 128 + j * 4 * K);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(dst), 16, in ? vB0 : GG_OOB_OFFSET, so, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(dst + 1024), 16, in ? vB1 : GG_OOB_OFFSET, so, 0, 0);
+      const int so = __builtin_amdgcn_readfirstlane(k_wrapped(kb + (j == 0 ? rot0 : rot), KB) * 128 + j * 4 * K);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(j == 0 ? dB0 : dB, GG_LDS_PTR(dst), 16, in ? vB0 : GG_OOB_OFFSET, so, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(j == 0 ? dB0 : dB, GG_LDS_PTR(dst + 1024), 16, in ? vB1 : GG_OOB_OFFSET, so, 0, 0);
     };
+    constexpr std::integral_constant<int, 0> J0{};
+    constexpr std::integral_constant<int, 1> J1{};
     auto read_frag = [&](const uint8_t* p) __attribute__((always_inline)) -> v8i {   // 16 rows x 128 B at p -> MFMA operand
       const v4i lo = *(const v4i*)(p + rd0);
       const v4i hi = *(const v4i*)(p + rd1);
@@ -212,35 +256,34 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     // A(1); once A(0) and fragments 0, 1 have landed, copy those to registers and refill their slots with
     // fragments 3 and 4.  That is the state every K block starts from: A(kb+1) and fragment 2kb+2 older than
     // the last 4 fetches, which are the refills with fragments 2kb+3 and 2kb+4.
-    dma_scales(0, 0);
-    static_for<0, Cfg::A_ITERS>([&](auto ic) __attribute__((always_inline)) { dma_a(ic, 0, 0); });
-    dma_b(0, 0, 0);
-    dma_b(0, 1, 1);
-    dma_b(1, 0, 2);
-    dma_scales(1, 1);
-    static_for<0, Cfg::A_ITERS>([&](auto ic) __attribute__((always_inline)) { dma_a(ic, 1, 1); });
-    wait_vmcnt<2 + Cfg::N_A>();
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
+    if (!primed) {
+      dma_scales(0, 0);
+      static_for<0, Cfg::A_ITERS>([&](auto ic) __attribute__((always_inline)) { dma_a(ic, 0, 0); });
+      dma_b(0, J0, 0);
+      dma_b(0, J1, 1);
+      dma_b(1, J0, 2);
+      dma_scales(1, 1);
+      static_for<0, Cfg::A_ITERS>([&](auto ic) __attribute__((always_inline)) { dma_a(ic, 1, 1); });
+      wait_vmcnt<2 + Cfg::N_A>();
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
 
-    v8i bfr[2][TN];                                            // weight fragments of K block kb in set kb % 2
-    bfr[0][0] = read_frag(bslots);
-    bfr[0][1] = read_frag(bslots + Cfg::B_SLOT_BYTES);
-    v8i afr[AFR];
-    float sa[AFR];
+      bfr[0][0] = read_frag(bslots);
+      bfr[0][1] = read_frag(bslots + Cfg::B_SLOT_BYTES);
 #pragma unroll
-    for (int i = 0; i < AFR - 1; ++i) {
-      afr[i] = read_frag(lds + i * 2048);
-      sa[i] = *(const float*)(lds + saRd + i * 64);
-    }
-    // the slot reads must be done before their slots are refilled
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    dma_b(1, 1, 0);
-    dma_b(2, 0, 1);
+      for (int i = 0; i < AFR - 1; ++i) {
+        afr[i] = read_frag(lds + i * 2048);
+        sa[i] = *(const float*)(lds + saRd + i * 64);
+      }
+      // the slot reads must be done before their slots are refilled
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      dma_b(1, J1, 0);
+      dma_b(2, J0, 1);
 
-    float sb_next = *(const float*)(lds + sbRd);               // weight scale of block 0
-    int stage = 0;                                             // LDS buffer of block kb
-    int bslot = 2;                                             // slot of fragment 2*kb + 2
+      sb_next = *(const float*)(lds + sbRd);                   // weight scale of block 0
+      stage = 0;
+      bslot = 2;
+    }
     // One K block; BS = kb % 2 is the register set that holds its weights.
     auto kstep = [&](int kb, auto bs_c) __attribute__((always_inline)) {
       constexpr int BS = decltype(bs_c)::value;
@@ -285,8 +328,8 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
             dma_a(std::integral_constant<int, t - Cfg::T_A0>{}, kb + 2, stageN);
           // refills: fragment F+3 into the slot fragment F was copied from, some MFMAs (and the LDS reads they
           // waited for, which return in order) after that copy
-          if constexpr (t == Cfg::T_R0) dma_b(kb + 2, 1, bslot);        // 2kb+2 -> 2kb+5
-          if constexpr (t == Cfg::T_R1) dma_b(kb + 3, 0, bslot1);       // 2kb+3 -> 2kb+6
+          if constexpr (t == Cfg::T_R0) dma_b(kb + 2, J1, bslot);       // 2kb+2 -> 2kb+5
+          if constexpr (t == Cfg::T_R1) dma_b(kb + 3, J0, bslot1);      // 2kb+3 -> 2kb+6
         }
         if constexpr (t >= PIPE) {
           constexpr int u = t - PIPE;
@@ -333,21 +376,39 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       __builtin_amdgcn_sched_barrier(0);
       stage = stage1;
       bslot = bslot1 + 1 == Cfg::B_SLOTS ? 0 : bslot1 + 1;
+      // The accumulators are "used" here: outside a loop the compiler otherwise sinks a step's accumulator updates
+      // down to their next use in a later basic block, and every product of the step stays alive until there.
+#pragma unroll
+      for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(acc[mt][j]));
     };
 
     // The copies of the block for the two register sets follow each other in a straight line (no if/else over
     // copies: their identical accumulator updates would be merged behind the branches, and all products of a
     // block would be live at once).
-    for (int kb = 0;;) {
-      kstep(kb, std::integral_constant<int, 0>{});
-      if (++kb >= KB) break;
-      kstep(kb, std::integral_constant<int, 1>{});
-      if (++kb >= KB) break;
+    constexpr std::integral_constant<int, 0> SET0{};
+    constexpr std::integral_constant<int, 1> SET1{};
+    for (int kb = 0; kb < KB - 4; kb += 2) {
+      kstep(kb, SET0);
+      kstep(kb + 1, SET1);
     }
-    // Every wave is done reading LDS before the next tile's prologue refills it; the out-of-range DMAs of the
-    // last blocks (zeros) complete, in order, before that prologue's.
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
+    // step KB-4 issues the last fetch of this tile's j = 0 fragments (block KB-1); step KB-3 the last fetches of
+    // its activations, scales and j = 1 fragments.  After each, that stream moves on to the next tile.
+    kstep(KB - 4, SET0);
+    dB0 = desc_b(nxt, has_next);
+    rot0 = k_rotation(a, nxt.n0);
+    kbase0 = KB;
+    kstep(KB - 3, SET1);
+    dA0 = band(nxt, 0, has_next); dA1 = band(nxt, 1 % Cfg::A_ITERS, has_next);
+    dA2 = band(nxt, 2 % Cfg::A_ITERS, has_next); dA3 = band(nxt, 3 % Cfg::A_ITERS, has_next);
+    dB = dB0;
+    dS = desc_s(nxt, has_next);
+    rot = rot0;
+    kbase = KB;
+    kstep(KB - 2, SET0);
+    kstep(KB - 1, SET1);
+    kbase = kbase0 = 0;
 
     // ---- epilogue: bf16 (or binary16) RNE, one bounded 16-byte store per activation block ---------------------------------
 #pragma unroll
@@ -366,6 +427,13 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       __amdgpu_buffer_rsrc_t dC = uniform_rsrc(a.C + (grow + 16 * mt) * N + n0, rows_mt > 0 ? rows_mt * N * 2 - n0 * 2 : 0);
       __builtin_amdgcn_raw_buffer_store_b128(out, dC, r * N * 2 + (w * 32 + 8 * q) * 2, 0, 0);
     }
+    if (!has_next) {
+      // the dropped fetches of the last K blocks still write zeros into this workgroup's LDS: let them land
+      wait_vmcnt<0>();
+      return;
+    }
+    cur = nxt;
+    primed = true;
   }
 }
 

@@ -40,6 +40,7 @@ struct Variant {
   hipError_t (*launch)(const gg::GemmArgs&, int grid, hipStream_t);
   // the same tile for N % BN != 0 or K % 128 != 0 (partial tiles, short last K block); null: whole blocks only
   hipError_t (*launch_ragged)(const gg::GemmArgs&, int grid, hipStream_t) = nullptr;
+  bool even_kb_only = false;   // needs K % 256 == 0 and K >= 512
 };
 
 template <class Cfg, bool RAGGED = false>
@@ -99,10 +100,10 @@ const Variant kVariants[] = {
     GG_VARIANT(128, 128, 2, 4, 4, true, 0, 1),    // 9
     GG_VARIANT(32, 256, 1, 8, 4, true, 0, 1),     // 10
     GG_VARIANT(128, 128, 2, 4, 2, false, 0, 2),   // 11
-    {"256x256/1x8w/3s-rb", 256, 256, gg::RbCfg<256, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, false>>, nullptr},   // 12
-    {"256x256/1x8w/3s-rbk", 256, 256, gg::RbCfg<256, 2, true>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, true>>, nullptr},    // 13
-    {"192x256/1x8w/3s-rb", 192, 256, gg::RbCfg<192, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<192, 2, false>>, nullptr},   // 14
-    {"224x256/1x8w/3s-rb", 224, 256, gg::RbCfg<224, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<224, 2, false>>, nullptr},   // 15
+    {"256x256/1x8w/3s-rb", 256, 256, gg::RbCfg<256, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, false>>, nullptr, true},   // 12
+    {"256x256/1x8w/3s-rbk", 256, 256, gg::RbCfg<256, 2, true>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, true>>, nullptr, true},    // 13
+    {"192x256/1x8w/3s-rb", 192, 256, gg::RbCfg<192, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<192, 2, false>>, nullptr, true},   // 14
+    {"224x256/1x8w/3s-rb", 224, 256, gg::RbCfg<224, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<224, 2, false>>, nullptr, true},   // 15
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -139,7 +140,7 @@ int pick_variant(int G, int64_t M_total, int N, int K) {
     const double whole = std::floor(rounds), frac = rounds - whole;
     return (whole + (frac > 1e-9 ? 0.5 + 0.5 * frac : 0.0)) * BM / eff;
   };
-  const bool long_k = K >= 3072;
+  const bool long_k = K >= 3072 && K % 256 == 0;   // the second kernel also needs an even number of K blocks
   int best = 0;
   double c_best = cost(160, 1.0);
   auto consider = [&](int variant, double c) {
@@ -171,6 +172,8 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
   const Variant& v = kVariants[variant];
   const bool ragged = N % v.BN != 0 || K % 128 != 0;
   if (ragged && !v.launch_ragged) return GG_ERR_UNSUPPORTED;   // this variant takes whole tiles and whole K blocks only
+  // the second kernel runs its K loop on from one tile into the next, two K blocks per turn
+  if (v.even_kb_only && (K % 256 != 0 || K < 512)) return GG_ERR_UNSUPPORTED;
 
   gg::GemmArgs args;
   args.A = static_cast<const uint8_t*>(A);

@@ -18,11 +18,14 @@ DEV = "cuda:0"
 CANARY = 0x7B7B          # bf16 bit pattern that no test result produces in bulk
 
 
-def variants_for(N):
+def variants_for(N, K):
+    """Tile variants that take this shape: N a multiple of the tile width; the second kernel ("-rb") runs its K
+    loop two K blocks per turn and on into the next tile, so it needs K % 256 == 0 and K >= 512."""
     out = []
     for v in range(gg.num_variants()):
-        bn = int(gg.variant_name(v).split("/")[0].split("x")[1])
-        if N % bn == 0:
+        name = gg.variant_name(v)
+        bn = int(name.split("/")[0].split("x")[1])
+        if N % bn == 0 and not ("-rb" in name and (K % 256 != 0 or K < 512)):
             out.append(v)
     return out
 
@@ -54,7 +57,7 @@ def test_tiny_config_every_variant_full_compare():
     ref = orc.grouped_gemm(*host, with_abs_sum=True)
     dev = tuple(p[k].to(DEV) for k in ("A", "SA", "B", "SB", "group_offsets"))
     first = {}
-    for v in [-1] + variants_for(p["N"]):
+    for v in [-1] + variants_for(p["N"], p["K"]):
         got = run_gpu(dev, p["M_total"], p["N"], v)
         assert_parity(got, ref, what=f"tiny variant {v}")
         # The arithmetic per element does not depend on the tiling: all variants of one kernel agree bit for
@@ -83,7 +86,7 @@ def test_edge_group_sizes_every_variant(sizes, N, K):
     host = np_problem(p)
     ref = orc.grouped_gemm(*host, with_abs_sum=True)
     dev = tuple(p[k].to(DEV) for k in ("A", "SA", "B", "SB", "group_offsets"))
-    for v in [-1] + variants_for(N):
+    for v in [-1] + variants_for(N, K):
         got = run_gpu(dev, p["M_total"], N, v)
         assert_parity(got, ref, empirical=p["M_total"] * N >= 50000, what=f"sizes {sizes} variant {v}")
 
@@ -93,14 +96,14 @@ def test_many_empty_groups_and_a_wide_output():
     # 1000 groups of which 988 are empty: the tile walk steps over long runs of zero-row groups
     sizes = np.zeros(1000, dtype=np.int64)
     sizes[rng.choice(1000, size=12, replace=False)] = rng.integers(1, 70, size=12)
-    cfg = WorkloadConfig("empties", 53, 1000, 256, 256, 0, "custom", "latency")
+    cfg = WorkloadConfig("empties", 53, 1000, 512, 256, 0, "custom", "latency")
     p = make_problem(cfg, sizes=sizes)
     ref = orc.grouped_gemm(*np_problem(p), with_abs_sum=True)
     dev = tuple(p[k].to(DEV) for k in ("A", "SA", "B", "SB", "group_offsets"))
     for v in (-1, 0, 5, 14):
         assert_parity(run_gpu(dev, p["M_total"], 256, v), ref, empirical=False, what=f"1000 groups variant {v}")
     # N = 16384: 64 column tiles per row tile, walked in chunks of 8
-    cfg = WorkloadConfig("wide", 54, 2, 256, 16384, 0, "custom", "latency")
+    cfg = WorkloadConfig("wide", 54, 2, 512, 16384, 0, "custom", "latency")
     p = make_problem(cfg, sizes=np.array([37, 200]))
     ref = orc.grouped_gemm(*np_problem(p), with_abs_sum=True)
     dev = tuple(p[k].to(DEV) for k in ("A", "SA", "B", "SB", "group_offsets"))
@@ -111,7 +114,7 @@ def test_many_empty_groups_and_a_wide_output():
 def test_rows_outside_the_groups_and_guard_bands_are_untouched():
     # groups cover rows [5, 5+sum) of a larger buffer; C has guard rows before and after
     rng = np.random.default_rng(60)
-    sizes, N, K = [130, 0, 67], 256, 384
+    sizes, N, K = [130, 0, 67], 256, 512
     host, dev = raw_problem(rng, sizes, N, K, DEV)
     A, SA, B, SB, off = host
     pre, post = 5, 9
@@ -121,7 +124,7 @@ def test_rows_outside_the_groups_and_guard_bands_are_untouched():
     off2 = (off + pre).astype(np.int32)
     ref = orc.grouped_gemm(A2, SA2, B, SB, off2, with_abs_sum=True)
     dev2 = tuple(torch.from_numpy(x).to(DEV) for x in (A2, SA2, B, SB, off2))
-    for v in variants_for(N):
+    for v in variants_for(N, K):
         guard = 64
         buf = torch.full(((M + 2 * guard), N), CANARY, dtype=torch.int16, device=DEV)
         C = buf[guard:guard + M].view(torch.bfloat16)
@@ -138,7 +141,7 @@ def test_raw_bytes_full_dynamic_range_hard_bound():
     sizes, N, K = [77, 200, 3], 256, 512
     host, dev = raw_problem(rng, sizes, N, K, DEV)
     ref = orc.grouped_gemm(*host, with_abs_sum=True)
-    for v in variants_for(N):
+    for v in variants_for(N, K):
         got = run_gpu(dev, int(sum(sizes)), N, v)
         assert_parity(got, ref, empirical=False, what=f"raw bytes variant {v}")
 
@@ -158,9 +161,9 @@ def test_closed_forms_are_exact():
     #     reproduce the oracle bit for bit, not merely within tolerance
     rng = np.random.default_rng(62)
     small = [0x00, 0x38, 0x40, 0x44, 0xB8, 0xC0, 0xC4]        # 0, 1, 2, 3, -1, -2, -3
-    host, dev = raw_problem(rng, [129, 1, 62], 256, 384, DEV, byte_choices=small, scale_pow2=True)
+    host, dev = raw_problem(rng, [129, 1, 62], 256, 512, DEV, byte_choices=small, scale_pow2=True)
     ref = orc.grouped_gemm(*host)
-    for v in variants_for(256):
+    for v in variants_for(256, 512):
         got = run_gpu(dev, 192, 256, v)
         assert np.array_equal(got, ref["C"]), f"variant {v}"
     # (c) subnormal codes only on the A side, B = +-1: products are exact multiples of 2^-9
@@ -226,12 +229,12 @@ def test_nan_stays_in_its_row_and_column():
 def test_untrusted_offsets_never_write_outside_C():
     # decreasing and out-of-range offsets: results are unspecified, but nothing outside C[0:M] is written
     rng = np.random.default_rng(64)
-    host, dev = raw_problem(rng, [100, 100, 100], 256, 384, DEV)
+    host, dev = raw_problem(rng, [100, 100, 100], 256, 512, DEV)
     M = 300
     bad = torch.tensor([-5, 250, 120, 100000], dtype=torch.int32, device=DEV)
     assert gg.check_offsets(bad, M) == 6          # GG_ERR_OFFSETS
     assert gg.check_offsets(dev[4], M) == 0
-    for v in variants_for(256):
+    for v in variants_for(256, 512):
         guard = 300
         buf = torch.full(((M + 2 * guard), 256), CANARY, dtype=torch.int16, device=DEV)
         C = buf[guard:guard + M].view(torch.bfloat16)
@@ -384,7 +387,7 @@ def test_binary16_output_every_variant():
     ref = orc.grouped_gemm(*host, with_abs_sum=True, out="f16")
     dev = tuple(p[k].to(DEV) for k in ("A", "SA", "B", "SB", "group_offsets"))
     first = {}
-    for v in [-1] + variants_for(p["N"]):
+    for v in [-1] + variants_for(p["N"], p["K"]):
         C = torch.full((p["M_total"], p["N"]), 0x7B7B, dtype=torch.int16, device=DEV).view(torch.float16)
         gg.grouped_gemm(*dev, C=C, variant=v)
         torch.cuda.synchronize()
