@@ -18,6 +18,10 @@
 //    scale to fetch use an out-of-range offset: zeros, no traffic), so all s_waitcnt counts are compile-time
 //    constants.  Order inside block kb: scale and A DMAs of block kb+2 first, then the refills of the two
 //    weight slots; the wait at the top of block kb+1 lets exactly the refills stay in flight.
+//  * The K loop is carried from one tile of a workgroup into its next: the fetches of a K step run two to three
+//    K blocks ahead, and past a tile's last K block they fetch the next tile's first blocks (the descriptors are
+//    re-pointed when a fetch stream reaches the end of the tile), so only a workgroup's first tile has a
+//    prologue.  The register sets alternate by K-block parity: the number of K blocks must be even and >= 4.
 //
 // Arithmetic per output element is the same as in the first kernel (one C=0 MFMA per 128-wide scale block,
 // 4 fp32 FMAs with the per-lane scale, the K blocks in the same order), so results are bit-identical to it unless KP is set.
