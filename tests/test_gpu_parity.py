@@ -111,6 +111,29 @@ def test_many_empty_groups_and_a_wide_output():
         assert_parity(run_gpu(dev, p["M_total"], 16384, v), ref, what=f"N=16384 variant {v}")
 
 
+@pytest.mark.parametrize("K", [512, 768])
+def test_several_tiles_per_workgroup_every_element(K):
+    """More tiles than workgroups at a size the oracle can check in full: every workgroup walks through several
+    tiles, which is where both kernels hand their fetch pipeline from one tile to the next (the first kernel's last
+    K blocks fetch for the next tile; the second kernel's K loop runs on into it).  K = 512 is the shortest K loop
+    the second kernel takes (4 K blocks: the hand-over starts in the first K step), K = 768 has a main loop too."""
+    sizes, N = [700, 0, 1300, 37, 1800, 191], 4096
+    cfg = WorkloadConfig("walk", 55, len(sizes), K, N, 0, "custom", "latency")
+    p = make_problem(cfg, sizes=np.array(sizes))
+    ref = orc.grouped_gemm(*np_problem(p), with_abs_sum=True)
+    dev = tuple(p[k].to(DEV) for k in ("A", "SA", "B", "SB", "group_offsets"))
+    first = {}
+    for v in [-1] + variants_for(N, K):
+        bm = 128 if v < 0 else int(gg.variant_name(v).split("x")[0])
+        if v >= 0 and (sum(-(-m // bm) for m in sizes) * (N // 256) <= 256 or bm < 128):
+            continue                                   # fewer tiles than workgroups, or a tile for short groups
+        got = run_gpu(dev, p["M_total"], N, v)
+        assert_parity(got, ref, what=f"K={K} variant {v}")
+        family = "k-permuted" if v >= 0 and gg.variant_name(v).endswith("-rbk") else "plain"
+        first.setdefault(family, got)
+        assert np.array_equal(got, first[family]), f"variant {v} differs from the first of its family"
+
+
 def test_rows_outside_the_groups_and_guard_bands_are_untouched():
     # groups cover rows [5, 5+sum) of a larger buffer; C has guard rows before and after
     rng = np.random.default_rng(60)
