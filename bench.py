@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0             # MI355X HBM3E
 # HBM bytes per launch of the GEMM kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/gemm_kernels_full_size_workloads.md gives the commands and the copy-kernel calibration:
 # FETCH_SIZE counts half of a plain copy's bytes, WRITE_SIZE all of them); None = not measured.
-MEASURED_TRAFFIC_BYTES = {"gate_up": 713820344, "down": 993765665, "decode": 1554026585, "many_small": 8045378172}
+MEASURED_TRAFFIC_BYTES = {"gate_up": 713820344, "down": 1029977334, "decode": 1554026585, "many_small": 8045378172}
 
 
 def algorithmic_bytes(sizes, N, K):

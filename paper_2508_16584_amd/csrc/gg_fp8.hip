@@ -111,20 +111,21 @@ constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 // expected tile count: a group ends in a partial tile half of the time on average, which adds G/2 tiles per
 // column of tiles.  Candidates and their measured character on MI355X:
 //   160x256, ring 3 (variant 0): the safe default; best when groups are short;
-//   256x256, ring 2 (variant 1): fewest bytes per flop, one K block of look-ahead: best on every problem of 24576
-//       rows or more in the paper's grid, and on short K loops;
+//   256x256, ring 2 (variant 1): fewest bytes per flop, one K block of look-ahead: best on the problems of 24576
+//       rows or more with K >= 4096 in the paper's grid;
 //   second kernel at 192, 224 and 256 rows (variants 14, 15, 12): weights through registers, better overlap, K loop
-//       carried from tile to tile: best on the problems of 8192-16384 rows; needs an even number of K blocks, and
-//       is only chosen for K >= 3072.  Three heights, because on a few hundred tiles the number of rounds over the
-//       256 workgroups matters more than anything else (8192 rows in 8 groups, N = 4096: 2.9 rounds at 192 rows,
-//       2.25 at 256, 3.45 at 160);
+//       carried from tile to tile: best on the smaller problems and on every problem with a short K loop (K = 1024
+//       to 2560: the 256-row one is within 2 % of the per-point best everywhere on the paper's size generator, while
+//       with strongly skewed group sizes the heights differ by under 3 %); needs an even number of K blocks.
+//       Three heights, because on a few hundred tiles the number of rounds over the 256 workgroups matters more
+//       than anything else (8192 rows in 8 groups, N = 4096: 2.9 rounds at 192 rows, 2.25 at 256, 3.45 at 160);
 //   128x256 (variant 3): very short groups (weight streaming).
 // Between the candidates allowed for a shape, the estimated time is rounds x tile height / efficiency, where a
 // partly filled last round costs 0.3 + 0.7 x its fill (measured: the workgroups that do run get more of the L2
 // bandwidth) and the efficiency per row is 1 : 1.06 : 1.08 : 1.10 for 160 : 192 : 224 : 256 rows of the kernels
-// named above and 1.04 for the 256x256 ring-2 tile on long K loops (1.10 on short ones).  The constants are a fit
-// to the five candidates on the 576 points of the paper's grid (Sec. 3.1) with caches flushed before every
-// launch: mean loss against the per-point best of the five 0.9 %, against 3.1-8.6 % for any single one.
+// named above and, for the 256x256 ring-2 tile, 1.02 from K = 4096 on and 0.94 below.  The constants are a fit to the
+// five candidates on the paper's grid (Sec. 3.1) extended to K = 1024 ... 8192 (960 points) with caches flushed
+// before every launch: mean loss against the per-point best of the five 0.7 %.
 int pick_variant(int G, int64_t M_total, int N, int K) {
   if (N % 256 != 0 || K % 128 != 0) {
     // partial tiles and a short last K block: first kernel only; the 128-wide tile wastes least on a ragged N
@@ -134,22 +135,22 @@ int pick_variant(int G, int64_t M_total, int N, int K) {
   const double avg = G > 0 ? (double)M_total / G : 0.0;
   if (avg < 64) return 3;
   if (avg < 192) return 0;
-  if (M_total >= 24576) return 1;
+  if (K >= 4096 && M_total >= 24576) return 1;
   auto cost = [&](int BM, double eff) {
     const double rounds = ((double)M_total / BM + 0.5 * G) * (N / 256) / 256.0;   // 256 CUs: the chip this is fitted on
     const double whole = std::floor(rounds), frac = rounds - whole;
     return (whole + (frac > 1e-9 ? 0.3 + 0.7 * frac : 0.0)) * BM / eff;
   };
-  const bool long_k = K >= 3072 && K % 256 == 0;   // the second kernel also needs an even number of K blocks
+  const bool second_kernel = K % 256 == 0 && K >= 512;   // its K loop takes two K blocks per turn
   int best = 0;
   double c_best = cost(160, 1.0);
   auto consider = [&](int variant, double c) {
     if (c < c_best) { c_best = c; best = variant; }
   };
-  if (long_k) consider(14, cost(192, 1.06));
-  if (long_k) consider(15, cost(224, 1.08));
-  if (long_k) consider(12, cost(256, 1.10));
-  consider(1, cost(256, long_k ? 1.04 : 1.10));
+  if (second_kernel) consider(14, cost(192, 1.06));
+  if (second_kernel) consider(15, cost(224, 1.08));
+  if (second_kernel) consider(12, cost(256, 1.10));
+  consider(1, cost(256, K >= 4096 ? 1.02 : 0.94));
   return best;
 }
 
