@@ -98,6 +98,20 @@ int gg_fp8_grouped_gemm_f16(const void* A, const float* SA, const void* B, const
                             const int32_t* group_offsets, void* C, int G, int64_t M_total, int N, int K,
                             void* workspace, size_t workspace_bytes, void* stream, int variant);
 
+/* Options of the _ex entry points (bits of `flags`; any other bit: GG_ERR_UNSUPPORTED).
+ *  GG_OUT_F16    C is IEEE binary16 instead of bfloat16 (as gg_fp8_grouped_gemm_f16).
+ *  GG_SA_KMAJOR  the activation scales are stored K-block-major: SA [ceil(K/128), M_total], the scale of
+ *                (row r, K block kb) at SA[kb * M_total + r].  Table 1 of the paper fixes the shape of the scale
+ *                tensor, not its storage order; in this order the scales that one K block of a tile needs are
+ *                contiguous, a few cache lines instead of one per row.  M_total * ceil(K/128) must stay below 2^29
+ *                (GG_ERR_SHAPE otherwise).  Same arithmetic, bit-identical results. */
+enum { GG_OUT_F16 = 1, GG_SA_KMAJOR = 2 };
+
+/* gg_fp8_grouped_gemm_variant with options (Sec. 2.1, 2.2 as above).  variant = -1 chooses automatically. */
+int gg_fp8_grouped_gemm_ex(const void* A, const float* SA, const void* B, const float* SB,
+                           const int32_t* group_offsets, void* C, int G, int64_t M_total, int N, int K,
+                           void* workspace, size_t workspace_bytes, void* stream, int variant, unsigned flags);
+
 /* ---- the pad-then-GEMM comparison path (the baseline of Sec. 3) ------------
  * Every group is copied to an offset that is a multiple of 128 rows, pad rows
  * are zero, the same GEMM kernels run on the aligned problem, and the valid
@@ -116,6 +130,13 @@ int64_t gg_fp8_padded_rows_cap(int G, int64_t M_total);
 int gg_fp8_pad(const void* A, const float* SA, const int32_t* group_offsets,
                void* A_pad, float* SA_pad, int32_t* padded_offsets,
                int G, int64_t M_total, int64_t M_pad_cap, int K, void* stream);
+
+/* gg_fp8_pad with options: with GG_SA_KMAJOR, SA is [ceil(K/128), M_total] and SA_pad [ceil(K/128), M_pad_cap]
+ * (the padded problem then goes to gg_fp8_grouped_gemm_ex with the same flag, M_total = M_pad_cap and
+ * group_offsets = padded_offsets).  Other flag bits: GG_ERR_UNSUPPORTED. */
+int gg_fp8_pad_ex(const void* A, const float* SA, const int32_t* group_offsets,
+                  void* A_pad, float* SA_pad, int32_t* padded_offsets,
+                  int G, int64_t M_total, int64_t M_pad_cap, int K, void* stream, unsigned flags);
 
 /* The GEMM on the aligned problem: identical to gg_fp8_grouped_gemm with
  * M_total = M_pad_cap and group_offsets = padded_offsets.  Pad rows inside
@@ -151,6 +172,14 @@ int gg_fp8_quantize_rows(const void* X, const int32_t* row_src, void* A, float* 
  * (GG_ERR_UNSUPPORTED otherwise); H, A, act_out 16-byte aligned.  Asynchronous on `stream`. */
 int gg_fp8_swiglu_quantize_rows(const void* H, void* A, float* SA, void* act_out,
                                 int64_t M_total, int I, void* stream);
+
+/* The two row kernels with options: with GG_SA_KMAJOR they write the scales K-block-major, SA [K/128, M_total]
+ * (resp. [I/128, M_total]), the order gg_fp8_grouped_gemm_ex takes with the same flag.  Bytes and scale values are
+ * those of the plain entry points.  Other flag bits: GG_ERR_UNSUPPORTED. */
+int gg_fp8_quantize_rows_ex(const void* X, const int32_t* row_src, void* A, float* SA,
+                            int64_t T, int64_t M_total, int K, void* stream, unsigned flags);
+int gg_fp8_swiglu_quantize_rows_ex(const void* H, void* A, float* SA, void* act_out,
+                                   int64_t M_total, int I, void* stream, unsigned flags);
 
 /* Debug helper, NOT for the hot path: synchronises `stream`, copies the G+1
  * offsets to the host and returns GG_ERR_OFFSETS unless they are non-decreasing

@@ -79,6 +79,14 @@ def load_library() -> ctypes.CDLL:
     lib.gg_fp8_num_variants.restype = i32
     lib.gg_fp8_grouped_gemm_f16.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp, sz, vp, i32]
     lib.gg_fp8_grouped_gemm_f16.restype = i32
+    lib.gg_fp8_grouped_gemm_ex.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp, sz, vp, i32, ctypes.c_uint]
+    lib.gg_fp8_grouped_gemm_ex.restype = i32
+    lib.gg_fp8_pad_ex.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i64, i32, vp, ctypes.c_uint]
+    lib.gg_fp8_pad_ex.restype = i32
+    lib.gg_fp8_quantize_rows_ex.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, ctypes.c_uint]
+    lib.gg_fp8_quantize_rows_ex.restype = i32
+    lib.gg_fp8_swiglu_quantize_rows_ex.argtypes = [vp, vp, vp, vp, i64, i32, vp, ctypes.c_uint]
+    lib.gg_fp8_swiglu_quantize_rows_ex.restype = i32
     lib.gg_fp8_num_variants.argtypes = []
     lib.gg_fp8_variant_name.restype = ctypes.c_char_p
     lib.gg_fp8_variant_name.argtypes = [i32]
@@ -104,8 +112,9 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED_SYMBOLS = [
     "gg_fp8_version", "gg_fp8_status_str", "gg_fp8_workspace_bytes", "gg_fp8_grouped_gemm",
-    "gg_fp8_grouped_gemm_variant", "gg_fp8_grouped_gemm_f16", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_auto_variant", "gg_fp8_padded_rows_cap",
+    "gg_fp8_grouped_gemm_variant", "gg_fp8_grouped_gemm_f16", "gg_fp8_grouped_gemm_ex", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_auto_variant", "gg_fp8_padded_rows_cap",
     "gg_fp8_pad", "gg_fp8_grouped_gemm_padded", "gg_fp8_unpad", "gg_fp8_quantize_rows", "gg_fp8_swiglu_quantize_rows", "gg_fp8_check_offsets",
+    "gg_fp8_pad_ex", "gg_fp8_quantize_rows_ex", "gg_fp8_swiglu_quantize_rows_ex",
 ]
 
 
@@ -138,7 +147,10 @@ def _want(t, name, dtype, ndim):
         raise ValueError(f"{name} must live on the GPU")
 
 
-def _gemm_shapes(A, SA, B, SB, group_offsets):
+GG_OUT_F16, GG_SA_KMAJOR = 1, 2        # flags of the _ex entry points
+
+
+def _gemm_shapes(A, SA, B, SB, group_offsets, sa_kmajor=False):
     _want(A, "A", torch.uint8, 2)
     _want(SA, "SA", torch.float32, 2)
     _want(B, "B", torch.uint8, 3)
@@ -151,8 +163,9 @@ def _gemm_shapes(A, SA, B, SB, group_offsets):
     if group_offsets.shape[0] != G + 1:
         raise ValueError(f"group_offsets must have G+1={G + 1} entries")
     KB, NB = -(-K // 128), -(-N // 128)          # ceilings (Table 1 of the paper)
-    if tuple(SA.shape) != (M_total, KB):
-        raise ValueError(f"SA must be [{M_total}, {KB}]")
+    sa_shape = (KB, M_total) if sa_kmajor else (M_total, KB)
+    if tuple(SA.shape) != sa_shape:
+        raise ValueError(f"SA must be {list(sa_shape)}")
     if tuple(SB.shape) != (G, NB, KB):
         raise ValueError(f"SB must be [{G}, {NB}, {KB}]")
     return G, M_total, N, K
@@ -193,16 +206,16 @@ def _workspace(G, M_total, N, K, device):
     return (torch.empty(n, dtype=torch.uint8, device=device) if n else None), n
 
 
-def grouped_gemm(A, SA, B, SB, group_offsets, C=None, variant: int = -1, stream=None, out_dtype=None):
-    """C[r, :] = round(block-scaled A[r, :] @ B[g]^T) for every row r of every group g (gg_fp8_grouped_gemm,
-    or gg_fp8_grouped_gemm_f16 when C / out_dtype is torch.float16).
+def grouped_gemm(A, SA, B, SB, group_offsets, C=None, variant: int = -1, stream=None, out_dtype=None, sa_kmajor=False):
+    """C[r, :] = round(block-scaled A[r, :] @ B[g]^T) for every row r of every group g (gg_fp8_grouped_gemm_variant,
+    gg_fp8_grouped_gemm_f16 when C / out_dtype is torch.float16, gg_fp8_grouped_gemm_ex when sa_kmajor).
 
-    A uint8 [M_total, K] (e4m3 bytes), SA float32 [M_total, K/128], B uint8 [G, N, K],
+    A uint8 [M_total, K] (e4m3 bytes), SA float32 [M_total, K/128] (sa_kmajor: [K/128, M_total]), B uint8 [G, N, K],
     SB float32 [G, N/128, K/128], group_offsets int32 [G+1]; returns C bfloat16 (default) or float16 [M_total, N]
     (allocated here unless given; rows outside the groups are left as they are).
     """
     lib = load_library()
-    G, M_total, N, K = _gemm_shapes(A, SA, B, SB, group_offsets)
+    G, M_total, N, K = _gemm_shapes(A, SA, B, SB, group_offsets, sa_kmajor)
     if out_dtype is None:
         out_dtype = C.dtype if C is not None else torch.bfloat16
     if out_dtype not in (torch.bfloat16, torch.float16):
@@ -213,9 +226,12 @@ def grouped_gemm(A, SA, B, SB, group_offsets, C=None, variant: int = -1, stream=
     if tuple(C.shape) != (M_total, N):
         raise ValueError(f"C must be [{M_total}, {N}]")
     ws, n = _workspace(G, M_total, N, K, A.device)
-    fn = lib.gg_fp8_grouped_gemm_f16 if out_dtype == torch.float16 else lib.gg_fp8_grouped_gemm_variant
-    _check(fn(_ptr(A), _ptr(SA), _ptr(B), _ptr(SB), _ptr(group_offsets), _ptr(C),
-              G, M_total, N, K, _ptr(ws), n, _stream(stream), int(variant)))
+    args = (_ptr(A), _ptr(SA), _ptr(B), _ptr(SB), _ptr(group_offsets), _ptr(C), G, M_total, N, K, _ptr(ws), n,
+            _stream(stream), int(variant))
+    if sa_kmajor:
+        _check(lib.gg_fp8_grouped_gemm_ex(*args, GG_SA_KMAJOR | (GG_OUT_F16 if out_dtype == torch.float16 else 0)))
+    else:
+        _check((lib.gg_fp8_grouped_gemm_f16 if out_dtype == torch.float16 else lib.gg_fp8_grouped_gemm_variant)(*args))
     return C
 
 
@@ -223,8 +239,9 @@ def padded_rows_cap(G: int, M_total: int) -> int:
     return int(load_library().gg_fp8_padded_rows_cap(G, M_total))
 
 
-def pad(A, SA, group_offsets, M_pad_cap: int | None = None, stream=None):
-    """gg_fp8_pad: returns (A_pad, SA_pad, padded_offsets) with every group at a multiple of 128 rows."""
+def pad(A, SA, group_offsets, M_pad_cap: int | None = None, stream=None, sa_kmajor=False):
+    """gg_fp8_pad (gg_fp8_pad_ex when sa_kmajor: SA [K/128, M_total] -> SA_pad [K/128, M_pad_cap]): returns
+    (A_pad, SA_pad, padded_offsets) with every group at a multiple of 128 rows."""
     lib = load_library()
     _want(A, "A", torch.uint8, 2)
     _want(SA, "SA", torch.float32, 2)
@@ -234,15 +251,22 @@ def pad(A, SA, group_offsets, M_pad_cap: int | None = None, stream=None):
     if M_pad_cap is None:
         M_pad_cap = padded_rows_cap(G, M_total)
     A_pad = torch.empty((M_pad_cap, K), dtype=torch.uint8, device=A.device)
-    SA_pad = torch.empty((M_pad_cap, SA.shape[1]), dtype=torch.float32, device=A.device)
+    KB = -(-K // 128)
+    if tuple(SA.shape) != ((KB, M_total) if sa_kmajor else (M_total, KB)):
+        raise ValueError("SA does not have the shape of its storage order")
+    SA_pad = torch.empty((KB, M_pad_cap) if sa_kmajor else (M_pad_cap, KB), dtype=torch.float32, device=A.device)
     poff = torch.empty(G + 1, dtype=torch.int32, device=A.device)
-    _check(lib.gg_fp8_pad(_ptr(A), _ptr(SA), _ptr(group_offsets), _ptr(A_pad), _ptr(SA_pad), _ptr(poff),
-                          G, M_total, M_pad_cap, K, _stream(stream)))
+    args = (_ptr(A), _ptr(SA), _ptr(group_offsets), _ptr(A_pad), _ptr(SA_pad), _ptr(poff), G, M_total, M_pad_cap, K,
+            _stream(stream))
+    _check(lib.gg_fp8_pad_ex(*args, GG_SA_KMAJOR) if sa_kmajor else lib.gg_fp8_pad(*args))
     return A_pad, SA_pad, poff
 
 
-def grouped_gemm_padded(A_pad, SA_pad, B, SB, padded_offsets, C_pad=None, stream=None):
-    """gg_fp8_grouped_gemm_padded: the same GEMM on the 128-aligned problem; returns C_pad."""
+def grouped_gemm_padded(A_pad, SA_pad, B, SB, padded_offsets, C_pad=None, stream=None, sa_kmajor=False):
+    """gg_fp8_grouped_gemm_padded: the same GEMM on the 128-aligned problem; returns C_pad.  (sa_kmajor: the same
+    through gg_fp8_grouped_gemm_ex, as the header prescribes.)"""
+    if sa_kmajor:
+        return grouped_gemm(A_pad, SA_pad, B, SB, padded_offsets, C=C_pad, stream=stream, sa_kmajor=True)
     lib = load_library()
     G, M_pad_cap, N, K = _gemm_shapes(A_pad, SA_pad, B, SB, padded_offsets)
     if C_pad is None:
@@ -267,9 +291,10 @@ def unpad(C_pad, group_offsets, padded_offsets, M_total: int, C=None, stream=Non
     return C
 
 
-def quantize_rows(X, row_src=None, M_total=None, A=None, SA=None, stream=None):
-    """gg_fp8_quantize_rows: X [T, K] bf16 -> (A uint8 [M_total, K], SA float32 [M_total, K/128]); output row r
-    is input row row_src[r] (int32 [M_total] on the device; None = identity)."""
+def quantize_rows(X, row_src=None, M_total=None, A=None, SA=None, stream=None, sa_kmajor=False):
+    """gg_fp8_quantize_rows(_ex): X [T, K] bf16 -> (A uint8 [M_total, K], SA float32 [M_total, K/128], or
+    [K/128, M_total] with sa_kmajor); output row r is input row row_src[r] (int32 [M_total] on the device;
+    None = identity)."""
     lib = load_library()
     _want(X, "X", torch.bfloat16, 2)
     T, K = X.shape
@@ -281,15 +306,19 @@ def quantize_rows(X, row_src=None, M_total=None, A=None, SA=None, stream=None):
     if A is None:
         A = torch.empty((M_total, K), dtype=torch.uint8, device=X.device)
     if SA is None:
-        SA = torch.empty((M_total, K // 128), dtype=torch.float32, device=X.device)
+        SA = torch.empty((K // 128, M_total) if sa_kmajor else (M_total, K // 128), dtype=torch.float32, device=X.device)
     _want(A, "A", torch.uint8, 2)
     _want(SA, "SA", torch.float32, 2)
-    _check(lib.gg_fp8_quantize_rows(_ptr(X), _ptr(row_src), _ptr(A), _ptr(SA), T, M_total, K, _stream(stream)))
+    if tuple(SA.shape) != ((K // 128, M_total) if sa_kmajor else (M_total, K // 128)) or tuple(A.shape) != (M_total, K):
+        raise ValueError("A or SA does not have the shape of the output")
+    args = (_ptr(X), _ptr(row_src), _ptr(A), _ptr(SA), T, M_total, K, _stream(stream))
+    _check(lib.gg_fp8_quantize_rows_ex(*args, GG_SA_KMAJOR) if sa_kmajor else lib.gg_fp8_quantize_rows(*args))
     return A, SA
 
 
-def swiglu_quantize_rows(H, A=None, SA=None, act_out=None, want_act=False, stream=None):
-    """gg_fp8_swiglu_quantize_rows: H [M, 2I] bf16 -> (A uint8 [M, I], SA float32 [M, I/128], act bf16 [M, I] or None)."""
+def swiglu_quantize_rows(H, A=None, SA=None, act_out=None, want_act=False, stream=None, sa_kmajor=False):
+    """gg_fp8_swiglu_quantize_rows(_ex): H [M, 2I] bf16 -> (A uint8 [M, I], SA float32 [M, I/128], or [I/128, M] with
+    sa_kmajor, act bf16 [M, I] or None)."""
     lib = load_library()
     _want(H, "H", torch.bfloat16, 2)
     M, two_i = H.shape
@@ -299,14 +328,17 @@ def swiglu_quantize_rows(H, A=None, SA=None, act_out=None, want_act=False, strea
     if A is None:
         A = torch.empty((M, inter), dtype=torch.uint8, device=H.device)
     if SA is None:
-        SA = torch.empty((M, inter // 128), dtype=torch.float32, device=H.device)
+        SA = torch.empty((inter // 128, M) if sa_kmajor else (M, inter // 128), dtype=torch.float32, device=H.device)
     if act_out is None and want_act:
         act_out = torch.empty((M, inter), dtype=torch.bfloat16, device=H.device)
     _want(A, "A", torch.uint8, 2)
     _want(SA, "SA", torch.float32, 2)
     if act_out is not None:
         _want(act_out, "act_out", torch.bfloat16, 2)
-    _check(lib.gg_fp8_swiglu_quantize_rows(_ptr(H), _ptr(A), _ptr(SA), _ptr(act_out), M, inter, _stream(stream)))
+    if tuple(SA.shape) != ((inter // 128, M) if sa_kmajor else (M, inter // 128)) or tuple(A.shape) != (M, inter):
+        raise ValueError("A or SA does not have the shape of the output")
+    args = (_ptr(H), _ptr(A), _ptr(SA), _ptr(act_out), M, inter, _stream(stream))
+    _check(lib.gg_fp8_swiglu_quantize_rows_ex(*args, GG_SA_KMAJOR) if sa_kmajor else lib.gg_fp8_swiglu_quantize_rows(*args))
     return A, SA, act_out
 
 

@@ -76,7 +76,21 @@ struct GemmArgs {
   int k_rem;     // bytes of a row that fall into the last K block: K - 128 * (KB - 1), in (0, 128]
   int out_f16;   // 0: C is bfloat16, 1: C is IEEE binary16
   int rot_mul;   // K blocks by which neighbouring 256-column blocks shift the start of their K loop (0: none)
+  // Storage order of SA, in bytes: the scale of (row, K block kb) is at row * sa_row_stride + kb * sa_kb_stride.
+  // Row-major [M_total, KB]: (4 * KB, 4); K-block-major [KB, M_total]: (4, 4 * M_total), where the scales one
+  // K block of a tile needs are contiguous (a few cache lines instead of one per row).
+  int sa_row_stride, sa_kb_stride;
+  int sa_kmajor;   // 1 for the second order
 };
+
+// Length in bytes of the view of SA that starts at the scale of (first row of a tile, K block 0).  The K-block part
+// of a scale's address travels in the scalar offset of the fetch, which the hardware takes off the length before
+// it compares the lane offset with it.  Row-major: rows_valid scale rows, so rows past the group's end read as
+// zero.  K-block-major: everything up to the end of the tensor; a row past the group's end then reads some other
+// row's scale, which only ever meets that row's all-zero activations in an accumulator that is never stored.
+__device__ __forceinline__ int sa_view_bytes(const GemmArgs& a, int64_t grow, int rows_valid) {
+  return a.sa_kmajor ? (int)(((int64_t)a.KB * a.M_total - grow) * 4) : rows_valid * a.sa_row_stride;
+}
 
 template <int BM_, int BN_, int WM_, int WN_, int STAGES_, bool XPF_ = false, int GAP_ = 0, int PIPE_ = 3>
 struct GemmCfg {
@@ -199,7 +213,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
   // byte k_rem of the block belong to the next row; those lanes fetch from an out-of-range offset, i.e. zeros
   const bool a_tail = RAGGED && ((pch ^ keyA_ld) << 4) >= a.k_rem;
   const bool b_tail = RAGGED && ((pch ^ keyB_ld) << 4) >= a.k_rem;
-  const int vSA = (w * 64 + l) * KB * 4;
+  const int vSA = (w * 64 + l) * a.sa_row_stride;
   const int vSB = (l < BN / 128 ? l : BN / 128 - 1) * KB * 4;        // lane -> which 128-wide N block of the tile
 
   // DMAs this wave issues per K block = A_SLABS/NW + B_SLABS/NW + dma_extra (slab remainders, scale fetches)
@@ -274,7 +288,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
     return __builtin_amdgcn_make_buffer_rsrc((void*)(a.A + t.grow * K), 0, on ? t.rows_valid * K : 0, GG_RSRC_FLAGS);
   };
   auto desc_sa = [&](const Tile& t, bool on) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
-    return __builtin_amdgcn_make_buffer_rsrc((void*)(a.SA + t.grow * KB), 0, on ? t.rows_valid * KB * 4 : 0, GG_RSRC_FLAGS);
+    return __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)a.SA + t.grow * a.sa_row_stride), 0, on ? sa_view_bytes(a, t.grow, t.rows_valid) : 0, GG_RSRC_FLAGS);
   };
   auto desc_b = [&](const Tile& t, bool on) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
     const int n_rem = N - t.n0;
@@ -332,7 +346,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
       const bool last = kb == KB - 1;
       uint8_t* st = lds + stg * Cfg::STAGE_BYTES;
       if (w < Cfg::SA_WAVES)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(dSA, GG_LDS_PTR(st + Cfg::A_BYTES + Cfg::B_BYTES + w * 256), 4, vSA, kb * 4, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(dSA, GG_LDS_PTR(st + Cfg::A_BYTES + Cfg::B_BYTES + w * 256), 4, vSA, kb * a.sa_kb_stride, 0, 0);
       if (w == Cfg::SB_WAVE)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(dSB, GG_LDS_PTR(st + Cfg::A_BYTES + Cfg::B_BYTES + Cfg::SA_BYTES), 4, vSB, kb * 4, 0, 0);
       if constexpr (Cfg::A_SLABS % NW != 0) {

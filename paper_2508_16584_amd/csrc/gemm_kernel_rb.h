@@ -116,7 +116,8 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
   // Every wave issues exactly one scale DMA per K block: waves [0, SA_WAVES) fetch 64 activation scales each,
   // wave SB_WAVE the two weight scales, the others an out-of-range offset into a dump area.
   const bool sa_wave = w < Cfg::SA_WAVES, sb_wave = w == Cfg::SB_WAVE;
-  const int vS = sa_wave ? (w * 64 + l) * KB * 4 : sb_wave ? (l < BN / 128 ? l : BN / 128 - 1) * KB * 4 : GG_OOB_OFFSET;
+  const int s_kb_stride = sa_wave ? a.sa_kb_stride : 4;             // bytes from one K block's scale to the next
+  const int vS = sa_wave ? (w * 64 + l) * a.sa_row_stride : sb_wave ? (l < BN / 128 ? l : BN / 128 - 1) * KB * 4 : GG_OOB_OFFSET;
   const int ldsS = Cfg::A_BYTES + (sa_wave ? w * 256 : sb_wave ? Cfg::SA_BYTES : Cfg::SA_BYTES + Cfg::SB_BYTES);
   // operand reads: row r, chunks (2q, 2q+1), or (q, 4+q) with KP
   const int keyR = Cfg::KP ? swz_key_a1(r) : swz_key_a(r);
@@ -181,7 +182,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
   };
   // this wave's scale source: the activation scales of the tile's rows, or the weight scales of its two column blocks
   auto desc_s = [&](const Tile& t, bool on) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
-    return sa_wave ? uniform_rsrc(a.SA + t.grow * KB, on ? t.rows_valid * KB * 4 : 0)
+    return sa_wave ? uniform_rsrc((const uint8_t*)a.SA + t.grow * a.sa_row_stride, on ? sa_view_bytes(a, t.grow, t.rows_valid) : 0)
                    : uniform_rsrc(a.SB + ((int64_t)t.g * (N >> 7) + (t.n0 >> 7)) * KB, on ? (BN / 128) * KB * 4 : 0);
   };
 
@@ -228,7 +229,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       const int kb = kb_t - kbase;
       const int vo = kb < KB ? vS : GG_OOB_OFFSET;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(dS, GG_LDS_PTR(lds + stage * Cfg::STAGE_BYTES + ldsS), 4, vo,
-                                               __builtin_amdgcn_readfirstlane(k_wrapped(kb + rot, KB) * 4), 0, 0);
+                                               __builtin_amdgcn_readfirstlane(k_wrapped(kb + rot, KB) * s_kb_stride), 0, 0);
     };
     // weight fragment j of block kb into slot `slot` of this wave: two slabs of 8 fragment rows
     auto dma_b = [&](int kb_t, auto jc, int slot) __attribute__((always_inline)) {

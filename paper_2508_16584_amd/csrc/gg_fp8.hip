@@ -165,7 +165,8 @@ int validate_gemm(const void* A, const float* SA, const void* B, const float* SB
 }
 
 int run_gemm(const void* A, const float* SA, const void* B, const float* SB, const int32_t* off, void* C,
-             int G, int64_t M_total, int N, int K, void* stream, int variant, bool out_f16 = false) {
+             int G, int64_t M_total, int N, int K, void* stream, int variant, unsigned flags = 0) {
+  if (flags & ~(unsigned)(GG_OUT_F16 | GG_SA_KMAJOR)) return GG_ERR_UNSUPPORTED;
   int st = validate_gemm(A, SA, B, SB, off, C, G, M_total, N, K);
   if (st != GG_OK) return st;
   if (G == 0 || M_total == 0) return GG_OK;
@@ -192,7 +193,18 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
   args.k_rem = K - 128 * (args.KB - 1);
   args.n_tiles = (N + v.BN - 1) / v.BN;
   args.n_chunk = args.n_tiles < 8 ? args.n_tiles : 8;
-  args.out_f16 = out_f16 ? 1 : 0;
+  args.out_f16 = (flags & GG_OUT_F16) ? 1 : 0;
+  if (flags & GG_SA_KMAJOR) {
+    // the K-block part of a scale's address travels in a 32-bit scalar offset
+    if (M_total * 4 * (int64_t)args.KB > 0x7FFFFFFFLL) return GG_ERR_SHAPE;
+    args.sa_row_stride = 4;
+    args.sa_kb_stride = (int)(M_total * 4);
+    args.sa_kmajor = 1;
+  } else {
+    args.sa_kmajor = 0;
+    args.sa_row_stride = 4 * args.KB;
+    args.sa_kb_stride = 4;
+  }
   args.rot_mul = (K % 8192 == 4096) ? 4 : 0;   // 7 * 4 < K / 128; a function of K alone (see k_rotation)
 
   // upper bound on the number of tiles for any offsets: every group adds at most one partial m-tile
@@ -268,7 +280,15 @@ int gg_fp8_grouped_gemm_f16(const void* A, const float* SA, const void* B, const
                             void* workspace, size_t workspace_bytes, void* stream, int variant) {
   (void)workspace;
   if (workspace_bytes < gg_fp8_workspace_bytes(G, M_total, N, K)) return GG_ERR_WORKSPACE;
-  return run_gemm(A, SA, B, SB, group_offsets, C, G, M_total, N, K, stream, variant, true);
+  return run_gemm(A, SA, B, SB, group_offsets, C, G, M_total, N, K, stream, variant, GG_OUT_F16);
+}
+
+int gg_fp8_grouped_gemm_ex(const void* A, const float* SA, const void* B, const float* SB,
+                           const int32_t* group_offsets, void* C, int G, int64_t M_total, int N, int K,
+                           void* workspace, size_t workspace_bytes, void* stream, int variant, unsigned flags) {
+  (void)workspace;
+  if (workspace_bytes < gg_fp8_workspace_bytes(G, M_total, N, K)) return GG_ERR_WORKSPACE;
+  return run_gemm(A, SA, B, SB, group_offsets, C, G, M_total, N, K, stream, variant, flags);
 }
 
 int64_t gg_fp8_padded_rows_cap(int G, int64_t M_total) {
@@ -276,8 +296,9 @@ int64_t gg_fp8_padded_rows_cap(int G, int64_t M_total) {
   return 128 * ((M_total + 127) / 128 + (int64_t)G);
 }
 
-int gg_fp8_pad(const void* A, const float* SA, const int32_t* group_offsets, void* A_pad, float* SA_pad,
-               int32_t* padded_offsets, int G, int64_t M_total, int64_t M_pad_cap, int K, void* stream) {
+int gg_fp8_pad_ex(const void* A, const float* SA, const int32_t* group_offsets, void* A_pad, float* SA_pad,
+                  int32_t* padded_offsets, int G, int64_t M_total, int64_t M_pad_cap, int K, void* stream, unsigned flags) {
+  if (flags & ~(unsigned)GG_SA_KMAJOR) return GG_ERR_UNSUPPORTED;
   if (G < 0 || M_total < 0 || K <= 0 || M_pad_cap < 0) return GG_ERR_SHAPE;
   if (M_total > 0x7FFFFFFFLL || M_pad_cap > 0x7FFFFFFFLL || K > (1 << 22)) return GG_ERR_SHAPE;
   if (M_pad_cap < gg_fp8_padded_rows_cap(G, M_total)) return GG_ERR_SHAPE;
@@ -295,8 +316,13 @@ int gg_fp8_pad(const void* A, const float* SA, const int32_t* group_offsets, voi
   if (grid > nblocks) grid = nblocks;
   hipLaunchKernelGGL(gg::gg_pad_rows_kernel, dim3((unsigned)grid), dim3(gg::PAD_THREADS), 0, s,
                      static_cast<const uint8_t*>(A), SA, group_offsets, padded_offsets, static_cast<uint8_t*>(A_pad),
-                     SA_pad, G, (int)M_total, (int)M_pad_cap, K, (K + 127) / 128);
+                     SA_pad, G, (int)M_total, (int)M_pad_cap, K, (K + 127) / 128, (flags & GG_SA_KMAJOR) ? 1 : 0);
   return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
+}
+
+int gg_fp8_pad(const void* A, const float* SA, const int32_t* group_offsets, void* A_pad, float* SA_pad,
+               int32_t* padded_offsets, int G, int64_t M_total, int64_t M_pad_cap, int K, void* stream) {
+  return gg_fp8_pad_ex(A, SA, group_offsets, A_pad, SA_pad, padded_offsets, G, M_total, M_pad_cap, K, stream, 0);
 }
 
 int gg_fp8_grouped_gemm_padded(const void* A_pad, const float* SA_pad, const void* B, const float* SB,
@@ -322,8 +348,9 @@ int gg_fp8_unpad(const void* C_pad, const int32_t* group_offsets, const int32_t*
   return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
 }
 
-int gg_fp8_quantize_rows(const void* X, const int32_t* row_src, void* A, float* SA, int64_t T, int64_t M_total, int K,
-                         void* stream) {
+int gg_fp8_quantize_rows_ex(const void* X, const int32_t* row_src, void* A, float* SA, int64_t T, int64_t M_total, int K,
+                            void* stream, unsigned flags) {
+  if (flags & ~(unsigned)GG_SA_KMAJOR) return GG_ERR_UNSUPPORTED;
   if (T < 0 || M_total < 0 || K <= 0) return GG_ERR_SHAPE;
   if (M_total > 0x7FFFFFFFLL || T > 0x7FFFFFFFLL || K > (1 << 22)) return GG_ERR_SHAPE;
   if (K % 128 != 0) return GG_ERR_UNSUPPORTED;
@@ -333,11 +360,19 @@ int gg_fp8_quantize_rows(const void* X, const int32_t* row_src, void* A, float* 
   if (grid > (M_total + 1) / 2) grid = (M_total + 1) / 2;     // a workgroup takes rows in pairs
   hipLaunchKernelGGL(gg::gg_quantize_rows_kernel, dim3((unsigned)grid), dim3(gg::Q_THREADS), 0,
                      static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(X), row_src,
-                     static_cast<uint8_t*>(A), SA, T, (int)M_total, K, K / 128);
+                     static_cast<uint8_t*>(A), SA, T, (int)M_total, K, K / 128,
+                     (flags & GG_SA_KMAJOR) ? (int64_t)1 : (int64_t)(K / 128), (flags & GG_SA_KMAJOR) ? M_total : (int64_t)1);
   return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
 }
 
-int gg_fp8_swiglu_quantize_rows(const void* H, void* A, float* SA, void* act_out, int64_t M_total, int I, void* stream) {
+int gg_fp8_quantize_rows(const void* X, const int32_t* row_src, void* A, float* SA, int64_t T, int64_t M_total, int K,
+                         void* stream) {
+  return gg_fp8_quantize_rows_ex(X, row_src, A, SA, T, M_total, K, stream, 0);
+}
+
+int gg_fp8_swiglu_quantize_rows_ex(const void* H, void* A, float* SA, void* act_out, int64_t M_total, int I, void* stream,
+                                   unsigned flags) {
+  if (flags & ~(unsigned)GG_SA_KMAJOR) return GG_ERR_UNSUPPORTED;
   if (M_total < 0 || I <= 0) return GG_ERR_SHAPE;
   if (M_total > 0x7FFFFFFFLL || I > (1 << 21)) return GG_ERR_SHAPE;
   if (I % 128 != 0) return GG_ERR_UNSUPPORTED;
@@ -347,8 +382,13 @@ int gg_fp8_swiglu_quantize_rows(const void* H, void* A, float* SA, void* act_out
   if (grid > (M_total + 1) / 2) grid = (M_total + 1) / 2;     // a workgroup takes rows in pairs
   hipLaunchKernelGGL(gg::gg_swiglu_quantize_rows_kernel, dim3((unsigned)grid), dim3(gg::Q_THREADS), 0,
                      static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(H), static_cast<uint8_t*>(A), SA,
-                     static_cast<uint16_t*>(act_out), (int)M_total, I, I / 128);
+                     static_cast<uint16_t*>(act_out), (int)M_total, I, I / 128,
+                     (flags & GG_SA_KMAJOR) ? (int64_t)1 : (int64_t)(I / 128), (flags & GG_SA_KMAJOR) ? M_total : (int64_t)1);
   return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
+}
+
+int gg_fp8_swiglu_quantize_rows(const void* H, void* A, float* SA, void* act_out, int64_t M_total, int I, void* stream) {
+  return gg_fp8_swiglu_quantize_rows_ex(H, A, SA, act_out, M_total, I, stream, 0);
 }
 
 int gg_fp8_check_offsets(const int32_t* group_offsets, int G, int64_t M_total, void* stream) {

@@ -64,7 +64,7 @@ __device__ __forceinline__ int pad_find_group(const int32_t* __restrict__ poff, 
 __global__ void __launch_bounds__(PAD_THREADS) gg_pad_rows_kernel(const uint8_t* __restrict__ A, const float* __restrict__ SA,
                                                                     const int32_t* __restrict__ off, const int32_t* __restrict__ poff,
                                                                     uint8_t* __restrict__ A_pad, float* __restrict__ SA_pad,
-                                                                    int G, int M_total, int M_pad_cap, int K, int KB) {
+                                                                    int G, int M_total, int M_pad_cap, int K, int KB, int sa_kmajor) {
   const int nblocks = (M_pad_cap + PAD_BLOCK_ROWS - 1) / PAD_BLOCK_ROWS;
   const int chunks = K >> 4;  // 16-byte chunks per row of A
   for (int blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
@@ -97,9 +97,17 @@ __global__ void __launch_bounds__(PAD_THREADS) gg_pad_rows_kernel(const uint8_t*
         if (j < total) __builtin_nontemporal_store(v[u], dst + j);
       }
     }
-    const float* __restrict__ ssrc = SA + (int64_t)src0 * KB;
-    float* __restrict__ sdst = SA_pad + (int64_t)p0 * KB;
-    for (int i = threadIdx.x; i < rows * KB; i += PAD_THREADS) sdst[i] = (i < valid * KB) ? ssrc[i] : 0.f;
+    if (sa_kmajor) {
+      // SA [KB, M_total] -> SA_pad [KB, M_pad_cap]: per K block, the block's 32 rows are contiguous
+      for (int i = threadIdx.x; i < PAD_BLOCK_ROWS * KB; i += PAD_THREADS) {
+        const int kb = i / PAD_BLOCK_ROWS, j = i % PAD_BLOCK_ROWS;
+        if (j < rows) SA_pad[(int64_t)kb * M_pad_cap + p0 + j] = j < valid ? SA[(int64_t)kb * M_total + src0 + j] : 0.f;
+      }
+    } else {
+      const float* __restrict__ ssrc = SA + (int64_t)src0 * KB;
+      float* __restrict__ sdst = SA_pad + (int64_t)p0 * KB;
+      for (int i = threadIdx.x; i < rows * KB; i += PAD_THREADS) sdst[i] = (i < valid * KB) ? ssrc[i] : 0.f;
+    }
   }
 }
 

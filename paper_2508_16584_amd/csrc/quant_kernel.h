@@ -115,7 +115,8 @@ __device__ __forceinline__ RowPairSlot row_pair_slot(int v, int KB, int r, int r
 __global__ void __launch_bounds__(Q_THREADS) gg_quantize_rows_kernel(const uint16_t* __restrict__ X,
                                                                      const int32_t* __restrict__ row_src,
                                                                      uint8_t* __restrict__ A, float* __restrict__ SA,
-                                                                     int64_t T, int M_total, int K, int KB) {
+                                                                     int64_t T, int M_total, int K, int KB,
+                                                                     int64_t sa_rs, int64_t sa_ks) {   // SA[row * sa_rs + blk * sa_ks]
   const int grp = threadIdx.x >> 4, sub = threadIdx.x & 15;
   for (int64_t r64 = blockIdx.x; r64 < M_total; r64 += 2 * (int64_t)gridDim.x) {
     const int r = (int)r64;
@@ -130,8 +131,8 @@ __global__ void __launch_bounds__(Q_THREADS) gg_quantize_rows_kernel(const uint1
       q_v4i rawA = {0, 0, 0, 0}, rawB = {0, 0, 0, 0};
       if (a.valid && sa >= 0 && sa < T) rawA = *(const q_v4i*)(X + sa * K + a.blk * 128 + sub * 8);
       if (b.valid && sb >= 0 && sb < T) rawB = *(const q_v4i*)(X + sb * K + b.blk * 128 + sub * 8);
-      if (a.valid) quantize_block(rawA, A + (int64_t)a.row * K + a.blk * 128 + sub * 8, SA + (int64_t)a.row * KB + a.blk, sub);
-      if (b.valid) quantize_block(rawB, A + (int64_t)b.row * K + b.blk * 128 + sub * 8, SA + (int64_t)b.row * KB + b.blk, sub);
+      if (a.valid) quantize_block(rawA, A + (int64_t)a.row * K + a.blk * 128 + sub * 8, SA + a.row * sa_rs + a.blk * sa_ks, sub);
+      if (b.valid) quantize_block(rawB, A + (int64_t)b.row * K + b.blk * 128 + sub * 8, SA + b.row * sa_rs + b.blk * sa_ks, sub);
     }
   }
 }
@@ -167,7 +168,8 @@ __device__ __forceinline__ q_v4i swiglu8(const q_v4i g_raw, const q_v4i u_raw) {
 __global__ void __launch_bounds__(Q_THREADS) gg_swiglu_quantize_rows_kernel(const uint16_t* __restrict__ H,
                                                                             uint8_t* __restrict__ A, float* __restrict__ SA,
                                                                             uint16_t* __restrict__ act_out,
-                                                                            int M_total, int I, int IB) {
+                                                                            int M_total, int I, int IB,
+                                                                            int64_t sa_rs, int64_t sa_ks) {   // SA[row * sa_rs + blk * sa_ks]
   const int grp = threadIdx.x >> 4, sub = threadIdx.x & 15;
   for (int64_t r64 = blockIdx.x; r64 < M_total; r64 += 2 * (int64_t)gridDim.x) {
     const int r = (int)r64;
@@ -190,13 +192,13 @@ __global__ void __launch_bounds__(Q_THREADS) gg_swiglu_quantize_rows_kernel(cons
         const q_v4i act = swiglu8(gA, uA);
         const int64_t o = (int64_t)a.row * I + a.blk * 128 + sub * 8;
         if (act_out) *(q_v4i*)(act_out + o) = act;
-        quantize_block(act, A + o, SA + (int64_t)a.row * IB + a.blk, sub);
+        quantize_block(act, A + o, SA + a.row * sa_rs + a.blk * sa_ks, sub);
       }
       if (b.valid) {
         const q_v4i act = swiglu8(gB, uB);
         const int64_t o = (int64_t)b.row * I + b.blk * 128 + sub * 8;
         if (act_out) *(q_v4i*)(act_out + o) = act;
-        quantize_block(act, A + o, SA + (int64_t)b.row * IB + b.blk, sub);
+        quantize_block(act, A + o, SA + b.row * sa_rs + b.blk * sa_ks, sub);
       }
     }
   }

@@ -111,12 +111,13 @@ def test_many_empty_groups_and_a_wide_output():
         assert_parity(run_gpu(dev, p["M_total"], 16384, v), ref, what=f"N=16384 variant {v}")
 
 
-@pytest.mark.parametrize("K", [512, 768])
+@pytest.mark.parametrize("K", [512, 768, 1024, 1536])
 def test_several_tiles_per_workgroup_every_element(K):
     """More tiles than workgroups at a size the oracle can check in full: every workgroup walks through several
     tiles, which is where both kernels hand their fetch pipeline from one tile to the next (the first kernel's last
     K blocks fetch for the next tile; the second kernel's K loop runs on into it).  K = 512 is the shortest K loop
-    the second kernel takes (4 K blocks: the hand-over starts in the first K step), K = 768 has a main loop too."""
+    the second kernel takes (4 K blocks: the hand-over starts in the first K step); the others have a main loop too,
+    of one, two and four turns."""
     sizes, N = [700, 0, 1300, 37, 1800, 191], 4096
     cfg = WorkloadConfig("walk", 55, len(sizes), K, N, 0, "custom", "latency")
     p = make_problem(cfg, sizes=np.array(sizes))
