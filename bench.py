@@ -29,7 +29,25 @@ HBM_PEAK_GBS = 8000.0             # MI355X HBM3E
 # HBM bytes per launch of the GEMM kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/gemm_kernels_full_size_workloads.md gives the commands and the copy-kernel calibration:
 # FETCH_SIZE counts half of a plain copy's bytes, WRITE_SIZE all of them); None = not measured.
-MEASURED_TRAFFIC_BYTES = {"gate_up": 713820344, "down": 1029977334, "decode": 1554026585, "many_small": 8045378172}
+MEASURED_TRAFFIC_BYTES = {"gate_up": 700801786, "down": 1030363239, "decode": 1547770438, "many_small": 8038152824}
+# the same with the activation scales row-major (--sa-layout row)
+MEASURED_TRAFFIC_BYTES_ROW_MAJOR = {"gate_up": 713820344, "down": 1029977334, "decode": 1554026585, "many_small": 8045378172}
+
+
+def clock_warmup(step, ms):
+    """Untimed launches of the benchmarked step for about `ms` milliseconds, ahead of the W warm-up steps: after an
+    idle period the GPU needs some 30 ms of load to reach its sustained clock (the first 100 launches of gate_up fall
+    from 277 to 246 us each), and W launches of a 0.3 ms kernel end well inside that ramp.  Returns the launch count."""
+    import torch
+    n, t0 = 0, time.perf_counter()
+    while ms > 0:
+        for _ in range(10):
+            step(n)
+            n += 1
+        torch.cuda.synchronize()
+        if (time.perf_counter() - t0) * 1e3 >= ms:
+            break
+    return n
 
 
 def algorithmic_bytes(sizes, N, K):
@@ -42,8 +60,11 @@ def algorithmic_bytes(sizes, N, K):
 
 
 # the same for the two row kernels (profiles/row_kernels_quantize_and_swiglu.md)
-MEASURED_TRAFFIC_BYTES_QUANT = {"gate_up": 178728308, "many_small": 714945956}
-MEASURED_TRAFFIC_BYTES_SWIGLU = {"gate_up": 84510332, "many_small": 337914328}
+MEASURED_TRAFFIC_BYTES_QUANT = {"gate_up": 191812988, "many_small": 773516892}
+MEASURED_TRAFFIC_BYTES_SWIGLU = {"gate_up": 88188540, "many_small": 353462836}
+# the same with the scales written row-major (--sa-layout row)
+MEASURED_TRAFFIC_BYTES_QUANT_ROW_MAJOR = {"gate_up": 178728308, "many_small": 714945956}
+MEASURED_TRAFFIC_BYTES_SWIGLU_ROW_MAJOR = {"gate_up": 84510332, "many_small": 337914328}
 
 
 def copy_calibration(dev):
@@ -69,6 +90,7 @@ def bench_quantize_rows(args, cfg, dev):
     from workloads import group_sizes
 
     fused = args.op == "swiglu_quantize_rows"
+    km = args.sa_layout == "kmajor"
     sizes = group_sizes(cfg, cfg.seed)
     M = int(np.sum(sizes))
     width_in = cfg.N if fused else cfg.K                      # columns of the bf16 input
@@ -83,15 +105,16 @@ def bench_quantize_rows(args, cfg, dev):
         X = (torch.randn((M, width_in), generator=gen, device=dev, dtype=torch.float32) * (1.7 if fused else 1.0)).to(torch.bfloat16)
         src = None if fused else torch.from_numpy(rng.permutation(M).astype(np.int32)).to(dev)
         sets.append((X, src, torch.empty((M, width_out), dtype=torch.uint8, device=dev),
-                     torch.empty((M, width_out // 128), dtype=torch.float32, device=dev)))
+                     torch.empty((width_out // 128, M) if km else (M, width_out // 128), dtype=torch.float32, device=dev)))
 
     def step(i):
         X, src, A, SA = sets[i % copies]
         if fused:
-            gg.swiglu_quantize_rows(X, A=A, SA=SA)
+            gg.swiglu_quantize_rows(X, A=A, SA=SA, sa_kmajor=km)
         else:
-            gg.quantize_rows(X, src, A=A, SA=SA)
+            gg.quantize_rows(X, src, A=A, SA=SA, sa_kmajor=km)
 
+    n_ramp = clock_warmup(step, args.clock_warmup_ms)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -107,7 +130,10 @@ def bench_quantize_rows(args, cfg, dev):
     if args.copy_calibration:
         copy_calibration(dev)
     achieved = alg_bytes / (float(kern_ms.mean()) * 1e-3) / 1e9
-    traffic = (MEASURED_TRAFFIC_BYTES_SWIGLU if fused else MEASURED_TRAFFIC_BYTES_QUANT).get(args.workload)
+    if km:
+        traffic = (MEASURED_TRAFFIC_BYTES_SWIGLU if fused else MEASURED_TRAFFIC_BYTES_QUANT).get(args.workload)
+    else:
+        traffic = (MEASURED_TRAFFIC_BYTES_SWIGLU_ROW_MAJOR if fused else MEASURED_TRAFFIC_BYTES_QUANT_ROW_MAJOR).get(args.workload)
     out = {
         "metric": "algorithmic GB/s, " + ("bf16 gate|up rows -> silu(gate)*up -> e4m3 + 1x128 scales" if fused else
                                           "bf16 rows -> e4m3 + 1x128 scales gathered into group order"),
@@ -115,7 +141,9 @@ def bench_quantize_rows(args, cfg, dev):
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 in, fp32 arithmetic, e4m3 + fp32 scales out", "data": "synthetic",
         "config": {"workload": args.workload + (" output" if fused else " activations"), "op": args.op, "M_total": M,
-                   "columns_in": width_in, "columns_out": width_out, "input_copies_rotated": copies},
+                   "columns_in": width_in, "columns_out": width_out, "input_copies_rotated": copies,
+                   "clock_warmup_launches": n_ramp,
+                   "sa_layout": "K-block-major [K/128, M_total]" if km else "row-major [M_total, K/128]"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "kernel": "gg_swiglu_quantize_rows_kernel" if fused else "gg_quantize_rows_kernel",
@@ -157,6 +185,8 @@ def bench_expert_mlp(args, cfg, dev):
     sizes = group_sizes(cfg, cfg.seed)
     G, M, K, N = cfg.G, int(np.sum(sizes)), cfg.K, cfg.N
     inter = N // 2
+    km = args.sa_layout == "kmajor"
+    sa_shape = (lambda rows, blocks: (blocks, rows)) if km else (lambda rows, blocks: (rows, blocks))
     gen = torch.Generator(device=dev)
     gen.manual_seed(cfg.seed)
     rng = np.random.default_rng(cfg.seed)
@@ -172,28 +202,28 @@ def bench_expert_mlp(args, cfg, dev):
         B2[g], SB2[g] = quantize_b(torch.randn((K, inter), generator=gen, device=dev) * 0.02)
     cap = gg.padded_rows_cap(G, M)
     A1 = torch.empty((M, K), dtype=torch.uint8, device=dev)
-    SA1 = torch.empty((M, K // 128), dtype=torch.float32, device=dev)
+    SA1 = torch.empty(sa_shape(M, K // 128), dtype=torch.float32, device=dev)
     H = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
     A2 = torch.empty((M, inter), dtype=torch.uint8, device=dev)
-    SA2 = torch.empty((M, inter // 128), dtype=torch.float32, device=dev)
+    SA2 = torch.empty(sa_shape(M, inter // 128), dtype=torch.float32, device=dev)
     Y = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
     H_pad = torch.empty((cap, N), dtype=torch.bfloat16, device=dev)
     A2_pad = torch.empty((cap, inter), dtype=torch.uint8, device=dev)
-    SA2_pad = torch.empty((cap, inter // 128), dtype=torch.float32, device=dev)
+    SA2_pad = torch.empty(sa_shape(cap, inter // 128), dtype=torch.float32, device=dev)
     Y_pad = torch.empty((cap, K), dtype=torch.bfloat16, device=dev)
 
     def free_chain():
-        gg.quantize_rows(X, src, A=A1, SA=SA1)
-        gg.grouped_gemm(A1, SA1, B1, SB1, off, C=H)
-        gg.swiglu_quantize_rows(H, A=A2, SA=SA2)
-        gg.grouped_gemm(A2, SA2, B2, SB2, off, C=Y)
+        gg.quantize_rows(X, src, A=A1, SA=SA1, sa_kmajor=km)
+        gg.grouped_gemm(A1, SA1, B1, SB1, off, C=H, sa_kmajor=km)
+        gg.swiglu_quantize_rows(H, A=A2, SA=SA2, sa_kmajor=km)
+        gg.grouped_gemm(A2, SA2, B2, SB2, off, C=Y, sa_kmajor=km)
 
     def pad_chain():
-        gg.quantize_rows(X, src, A=A1, SA=SA1)
-        A_pad, SA_pad, poff = gg.pad(A1, SA1, off)
-        gg.grouped_gemm_padded(A_pad, SA_pad, B1, SB1, poff, C_pad=H_pad)
-        gg.swiglu_quantize_rows(H_pad, A=A2_pad, SA=SA2_pad)
-        gg.grouped_gemm_padded(A2_pad, SA2_pad, B2, SB2, poff, C_pad=Y_pad)
+        gg.quantize_rows(X, src, A=A1, SA=SA1, sa_kmajor=km)
+        A_pad, SA_pad, poff = gg.pad(A1, SA1, off, sa_kmajor=km)
+        gg.grouped_gemm_padded(A_pad, SA_pad, B1, SB1, poff, C_pad=H_pad, sa_kmajor=km)
+        gg.swiglu_quantize_rows(H_pad, A=A2_pad, SA=SA2_pad, sa_kmajor=km)
+        gg.grouped_gemm_padded(A2_pad, SA2_pad, B2, SB2, poff, C_pad=Y_pad, sa_kmajor=km)
         gg.unpad(Y_pad, off, poff, M, C=Y)
 
     def timed(fn):
@@ -206,6 +236,7 @@ def bench_expert_mlp(args, cfg, dev):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / args.steps
 
+    n_ramp = clock_warmup(lambda i: free_chain(), args.clock_warmup_ms)
     t_free = timed(free_chain)
     y_free = Y.clone()
     t_pad = timed(pad_chain)
@@ -217,7 +248,8 @@ def bench_expert_mlp(args, cfg, dev):
         "warmup": args.warmup, "ms_per_step": round(t_free, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 tokens, fp8_e4m3 operands, fp32 accumulate, bf16 out", "data": "synthetic",
         "config": {"workload": args.workload + " routing", "op": "expert_mlp", "G": G, "M_total": M, "hidden": K,
-                   "intermediate": inter},
+                   "intermediate": inter, "sa_layout": "K-block-major" if km else "row-major",
+                   "clock_warmup_launches": n_ramp},
         "padded_chain_ms": round(t_pad, 4), "speedup_vs_padded_chain": round(t_pad / t_free, 4),
         "padded_chain_output_bitwise_equal": same,
         "note": "caches warm (same buffers every step); the padded chain adds a pad and an un-pad copy and runs the "
@@ -237,10 +269,18 @@ def main():
                          "on the workload's output shape [M_total, N] (N = 2 x intermediate width); expert_mlp: the whole forward "
                          "chain quantise -> GEMM -> activation+quantise -> GEMM on the workload's routing, padding-free "
                          "against the same chain on 128-row padded groups")
+    ap.add_argument("--clock-warmup-ms", type=float, default=150.0,
+                    help="untimed launches for about this long before the W warm-up steps, so that the timed steps run at "
+                         "the GPU's sustained clock (0: none)")
     ap.add_argument("--variant", type=int, default=-1)
+    ap.add_argument("--sa-layout", choices=["kmajor", "row"], default="kmajor",
+                    help="storage order of the activation scales: [K/128, M_total] (GG_SA_KMAJOR, the default: the faster "
+                         "one, and what the row kernels write at no cost) or [M_total, K/128]")
     ap.add_argument("--copies", type=int, default=0, help="input copies to rotate over (0 = enough for 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-pad-path", action="store_true")
+    ap.add_argument("--no-row-major-compare", action="store_true",
+                    help="skip the extra timed loop with row-major activation scales (grouped_gemm with --sa-layout kmajor)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -274,6 +314,7 @@ def main():
     flops = 2.0 * M * N * K
     alg_bytes = algorithmic_bytes(sizes, N, K)
 
+    km = args.sa_layout == "kmajor"
     # ---- input copies to rotate over (cold caches) ---------------------------------------------
     per_set = alg_bytes
     copies = args.copies or max(2, min(8, int(np.ceil(1.0e9 / per_set))))
@@ -283,13 +324,16 @@ def main():
             s = {k: p[k] for k in ("A", "SA", "B", "SB", "group_offsets")}
         else:
             s = {k: p[k].clone() for k in ("A", "SA", "B", "SB", "group_offsets")}
+        if km:
+            s["SA"] = p["SA"].t().contiguous()          # [K/128, M_total]; p["SA"] stays row-major for the oracle
         s["C"] = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
         sets.append(s)
 
     def step(i):
         s = sets[i % copies]
-        gg.grouped_gemm(s["A"], s["SA"], s["B"], s["SB"], s["group_offsets"], C=s["C"], variant=args.variant)
+        gg.grouped_gemm(s["A"], s["SA"], s["B"], s["SB"], s["group_offsets"], C=s["C"], variant=args.variant, sa_kmajor=km)
 
+    n_ramp = clock_warmup(step, args.clock_warmup_ms)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -320,6 +364,29 @@ def main():
     torch.cuda.synchronize()
     hot_ms = h0.elapsed_time(h1) / 20
 
+    # the same launches with the activation scales row-major ([M_total, K/128], what the plain entry points take)
+    row_major = None
+    if km and not args.no_row_major_compare:
+        def step_row(i):
+            s = sets[i % copies]
+            gg.grouped_gemm(s["A"], s["SA_row"], s["B"], s["SB"], s["group_offsets"], C=s["C"], variant=args.variant)
+        for s in sets:
+            s["SA_row"] = s["SA"].t().contiguous()
+        for i in range(args.warmup):
+            step_row(i)
+        torch.cuda.synchronize()
+        ev_row = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        t0 = time.perf_counter()
+        for i in range(args.steps):          # the same loop as the headline's, event pairs included
+            ev_row[i][0].record()
+            step_row(i)
+            ev_row[i][1].record()
+        torch.cuda.synchronize()
+        row_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        row_major = {"value": round(flops / (row_ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "ms_per_step": round(row_ms, 4)}
+        for s in sets:
+            del s["SA_row"]
+
     value = flops / (ms_per_step * 1e-3) / 1e12
     if cfg.bound == "hbm":
         achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
@@ -329,7 +396,7 @@ def main():
         achieved = flops / (kern_avg_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": FP8_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / FP8_MFMA_PEAK_TFLOPS, 4)}
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(args.workload)
+    roof["traffic"] = (MEASURED_TRAFFIC_BYTES if km else MEASURED_TRAFFIC_BYTES_ROW_MAJOR).get(args.workload)
     used = args.variant if args.variant >= 0 else gg.auto_variant(p["G"], p["M_total"], p["N"], p["K"])
     vname = gg.variant_name(used)
     roof["kernel"] = ("gg_gemm_rb_kernel<" if "-rb" in vname else "gg_gemm_kernel<") + vname + ">"
@@ -346,18 +413,23 @@ def main():
         "dtype": "fp8_e4m3 in, fp32 accumulate, bf16 out", "data": "synthetic",
         "config": {"workload": args.workload, "G": G, "M_total": M, "N": N, "K": K,
                    "group_sizes": cfg.sizes, "rows_min": int(sizes.min()), "rows_max": int(sizes.max()),
-                   "input_copies_rotated": copies, "variant": gg.variant_name(args.variant) or "auto"},
+                   "input_copies_rotated": copies, "variant": gg.variant_name(args.variant) or "auto",
+                   "clock_warmup_launches": n_ramp,
+                   "sa_layout": "K-block-major [K/128, M_total] (GG_SA_KMAJOR)" if km else "row-major [M_total, K/128]"},
         "frac_of_fp8_mfma_peak": round(value / FP8_MFMA_PEAK_TFLOPS, 4),
         "hot_cache_ms": round(hot_ms, 4),
         "roofline": roof,
     }
+    if row_major:
+        out["sa_row_major"] = row_major
 
     # ---- pad-then-GEMM comparison path (Sec. 3) -------------------------------------------------
     if not args.no_pad_path:
         cap = gg.padded_rows_cap(G, M)
         s0 = sets[0]
         A_pad = torch.empty((cap, K), dtype=torch.uint8, device=dev)
-        SA_pad = torch.empty((cap, K // 128), dtype=torch.float32, device=dev)
+        SA_pad = torch.empty((K // 128, cap) if km else (cap, K // 128), dtype=torch.float32, device=dev)
+        flags = 2 if km else 0                                   # GG_SA_KMAJOR
         poff = torch.empty(G + 1, dtype=torch.int32, device=dev)
         C_pad = torch.empty((cap, N), dtype=torch.bfloat16, device=dev)
         lib = gg.load_library()
@@ -367,10 +439,10 @@ def main():
 
         def pad_step(i, with_unpad):
             s = sets[i % copies]
-            rc = lib.gg_fp8_pad(vp(s["A"]), vp(s["SA"]), vp(s["group_offsets"]), vp(A_pad), vp(SA_pad), vp(poff),
-                                G, M, cap, K, stream)
-            rc |= lib.gg_fp8_grouped_gemm_padded(vp(A_pad), vp(SA_pad), vp(s["B"]), vp(s["SB"]), vp(poff), vp(C_pad),
-                                                 G, cap, N, K, None, 0, stream)
+            rc = lib.gg_fp8_pad_ex(vp(s["A"]), vp(s["SA"]), vp(s["group_offsets"]), vp(A_pad), vp(SA_pad), vp(poff),
+                                   G, M, cap, K, stream, flags)
+            rc |= lib.gg_fp8_grouped_gemm_ex(vp(A_pad), vp(SA_pad), vp(s["B"]), vp(s["SB"]), vp(poff), vp(C_pad),
+                                             G, cap, N, K, None, 0, stream, -1, flags)
             if with_unpad:
                 rc |= lib.gg_fp8_unpad(vp(C_pad), vp(s["group_offsets"]), vp(poff), vp(s["C"]), G, M, N, stream)
             assert rc == 0

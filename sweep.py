@@ -39,6 +39,8 @@ def main():
                          "Infinity Cache hold any input (default: same buffers every launch, caches warm)")
     ap.add_argument("--free-only", action="store_true",
                     help="time the padding-free path only (for comparing tile variants; the pad columns repeat its time)")
+    ap.add_argument("--sa-layout", choices=["kmajor", "row"], default="kmajor",
+                    help="storage order of the activation scales: [K/128, M] (GG_SA_KMAJOR, default) or [M, K/128]")
     ap.add_argument("--seed", type=int, default=20250816)
     ap.add_argument("--out", type=str, default=None, help="write the JSON lines here instead of stdout")
     ap.add_argument("--summary", type=str, default=None, help="write the summary (markdown) here as well as to stderr")
@@ -63,6 +65,7 @@ def main():
     Ns, Ks, Gs, Ms = pick(args.Ns, Ns), pick(args.Ks, Ks), pick(args.Gs, Gs), pick(args.Ms, Ms)
     Gmax, Mmax = max(Gs), max(Ms)
 
+    flags = 2 if args.sa_layout == "kmajor" else 0        # GG_SA_KMAJOR
     vp = lambda t: ctypes.c_void_p(t.data_ptr())
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
     sink = open(args.out, "w") if args.out else sys.stdout
@@ -121,16 +124,18 @@ def main():
                     off = torch.from_numpy(off_h).to(dev)
                     poff = torch.empty(G + 1, dtype=torch.int32, device=dev)
                     cap = gg.padded_rows_cap(G, M)
+                    # the scales of the first M rows in the chosen order (SA_pad is written in the same order)
+                    SA_M = SA[:M].t().contiguous() if flags else SA
 
                     def free_step():
-                        rc = lib.gg_fp8_grouped_gemm_variant(vp(A), vp(SA), vp(B), vp(SB), vp(off), vp(C), G, M, N, K,
-                                                             None, 0, stream, args.variant)
+                        rc = lib.gg_fp8_grouped_gemm_ex(vp(A), vp(SA_M), vp(B), vp(SB), vp(off), vp(C), G, M, N, K,
+                                                        None, 0, stream, args.variant, flags)
                         assert rc == 0, gg.status_str(rc)
 
                     def pad_step(with_unpad):
-                        rc = lib.gg_fp8_pad(vp(A), vp(SA), vp(off), vp(A_pad), vp(SA_pad), vp(poff), G, M, cap, K, stream)
-                        rc |= lib.gg_fp8_grouped_gemm_variant(vp(A_pad), vp(SA_pad), vp(B), vp(SB), vp(poff), vp(C_pad),
-                                                              G, cap, N, K, None, 0, stream, args.variant)
+                        rc = lib.gg_fp8_pad_ex(vp(A), vp(SA_M), vp(off), vp(A_pad), vp(SA_pad), vp(poff), G, M, cap, K, stream, flags)
+                        rc |= lib.gg_fp8_grouped_gemm_ex(vp(A_pad), vp(SA_pad), vp(B), vp(SB), vp(poff), vp(C_pad),
+                                                         G, cap, N, K, None, 0, stream, args.variant, flags)
                         if with_unpad:
                             rc |= lib.gg_fp8_unpad(vp(C_pad), vp(off), vp(poff), vp(C), G, M, N, stream)
                         assert rc == 0
@@ -176,7 +181,7 @@ def main():
     Nc, Kc, Gc, Mc = col("N"), col("K"), col("G"), col("M")
     lines = [
         f"points: {len(rows_out)}  (N in {Ns}, K in {Ks}, G in {Gs}, M in {Ms}; variant {'auto' if args.variant < 0 else args.variant}; "
-        f"caches {'flushed before every launch' if args.cold else 'warm'})",
+        f"activation scales {'K-block-major' if flags else 'row-major'}; caches {'flushed before every launch' if args.cold else 'warm'})",
         f"TFLOP/s on valid rows: min {tf.min():.0f}  median {np.median(tf):.0f}  max {tf.max():.0f}",
         f"speed-up over pad+GEMM: min {sp.min():.3f}  median {np.median(sp):.3f}  max {sp.max():.3f}",
         f"speed-up over pad+GEMM+unpad: min {spu.min():.3f}  median {np.median(spu):.3f}  max {spu.max():.3f}",

@@ -109,6 +109,32 @@ def test_pad_unpad_argument_validation(lib):
     assert lib.gg_fp8_check_offsets(nul, 2, 100, nul) == GG_ERR_NULL
 
 
+def test_ex_entry_points_validate_flags_and_sizes(lib):
+    p = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
+    nul = ctypes.c_void_p(0)
+    F16, KM = binding.GG_OUT_F16, binding.GG_SA_KMAJOR
+    gemm = lambda flags, M=100, N=256, K=256, A=p: lib.gg_fp8_grouped_gemm_ex(A, p, p, p, p, p, 2, M, N, K, nul, 0, nul, -1, flags)
+    assert gemm(4) == GG_ERR_UNSUPPORTED and gemm(F16 | KM | 8) == GG_ERR_UNSUPPORTED      # unknown flag bits
+    for flags in (0, F16, KM, F16 | KM):
+        assert gemm(flags, N=204) == GG_ERR_UNSUPPORTED
+        assert gemm(flags, M=-1) == GG_ERR_SHAPE
+        assert gemm(flags, A=nul) == GG_ERR_NULL
+        assert gemm(flags, M=0) == GG_OK
+    # K-block-major scales: the K-block part of a scale's address is a 32-bit byte offset
+    assert gemm(KM, M=2 ** 24, N=256, K=128 * 32) == GG_ERR_SHAPE
+    cap = gg.padded_rows_cap(2, 100)
+    assert lib.gg_fp8_pad_ex(p, p, p, p, p, p, 2, 100, cap, 256, nul, F16) == GG_ERR_UNSUPPORTED    # not a pad option
+    assert lib.gg_fp8_pad_ex(p, p, p, p, p, p, 2, 100, cap - 1, 256, nul, KM) == GG_ERR_SHAPE
+    assert lib.gg_fp8_pad_ex(p, p, p, p, p, nul, 2, 100, cap, 256, nul, KM) == GG_ERR_NULL
+    assert lib.gg_fp8_quantize_rows_ex(p, nul, p, p, 10, 10, 256, nul, F16) == GG_ERR_UNSUPPORTED
+    assert lib.gg_fp8_quantize_rows_ex(p, nul, p, p, 10, 10, 200, nul, KM) == GG_ERR_UNSUPPORTED
+    assert lib.gg_fp8_quantize_rows_ex(p, nul, nul, p, 10, 10, 256, nul, KM) == GG_ERR_NULL
+    assert lib.gg_fp8_quantize_rows_ex(nul, nul, nul, nul, 0, 0, 256, nul, KM) == GG_OK
+    assert lib.gg_fp8_swiglu_quantize_rows_ex(p, p, p, nul, 10, 256, nul, 4) == GG_ERR_UNSUPPORTED
+    assert lib.gg_fp8_swiglu_quantize_rows_ex(p, p, nul, nul, 10, 256, nul, KM) == GG_ERR_NULL
+    assert lib.gg_fp8_swiglu_quantize_rows_ex(nul, nul, nul, nul, 0, 256, nul, KM) == GG_OK
+
+
 def test_binding_rejects_wrong_tensors_before_calling_the_library(lib):
     import torch
     A = torch.zeros((4, 256), dtype=torch.uint8)
