@@ -68,6 +68,14 @@ def main():
     flags = 2 if args.sa_layout == "kmajor" else 0        # GG_SA_KMAJOR
     vp = lambda t: ctypes.c_void_p(t.data_ptr())
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    # bring the GPU to its sustained clock before the first grid point (about 150 ms of matrix work)
+    wu = torch.randn((4096, 4096), device=dev, dtype=torch.bfloat16)
+    t_wu = time.perf_counter()
+    while time.perf_counter() - t_wu < 0.15:
+        for _ in range(10):
+            wu @ wu
+        torch.cuda.synchronize()
+    del wu
     sink = open(args.out, "w") if args.out else sys.stdout
     rows_out = []
     t_start = time.perf_counter()
