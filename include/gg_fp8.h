@@ -112,6 +112,22 @@ int gg_fp8_grouped_gemm_ex(const void* A, const float* SA, const void* B, const 
                            const int32_t* group_offsets, void* C, int G, int64_t M_total, int N, int K,
                            void* workspace, size_t workspace_bytes, void* stream, int variant, unsigned flags);
 
+/* The first grouped GEMM of an expert MLP with the activation and the quantiser of the second GEMM's operand in
+ * its epilogue (what gg_fp8_grouped_gemm followed by gg_fp8_swiglu_quantize_rows computes, without the bf16
+ * intermediate [M_total, 2*I] ever reaching memory): B [G, 2*I, K] holds the gate projection in rows [0, I) and the
+ * up projection in rows [I, 2*I) of every group, SB [G, 2*I/128, K/128] their scales;
+ *   h = bf16(the block-scaled sums of Sec. 2.1),  act = bf16( silu(h_gate) * h_up ),
+ * A2 [M_total, I] e4m3 and SA2 [M_total, I/128] from act by the recipe of gg_fp8_quantize_rows; act_out (bf16
+ * [M_total, I]) receives act when it is not NULL.  Only valid rows are read, computed and written (Sec. 2.2), like
+ * every kernel here; this is the "neighbouring kernel" of Sec. 4 moved into the GEMM.  Bit-identical to the
+ * two-call sequence unless K % 8192 == 4096 (there the plain GEMM adds the K blocks in a rotated order).
+ * flags: GG_SA_KMAJOR (applies to SA and to SA2) or 0.  variant: -1, or one of the second kernel's "-rb" variants
+ * with 192, 224 or 256 rows.  I a multiple of 128, K a multiple of 256 and >= 512 (GG_ERR_UNSUPPORTED otherwise:
+ * use the two calls); 2*I*K below 2^31.  A2, act_out 16-byte aligned.  Asynchronous on `stream`. */
+int gg_fp8_grouped_gemm_swiglu(const void* A, const float* SA, const void* B, const float* SB,
+                               const int32_t* group_offsets, void* A2, float* SA2, void* act_out,
+                               int G, int64_t M_total, int I, int K, void* stream, int variant, unsigned flags);
+
 /* ---- the pad-then-GEMM comparison path (the baseline of Sec. 3) ------------
  * Every group is copied to an offset that is a multiple of 128 rows, pad rows
  * are zero, the same GEMM kernels run on the aligned problem, and the valid

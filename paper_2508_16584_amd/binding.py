@@ -81,6 +81,8 @@ def load_library() -> ctypes.CDLL:
     lib.gg_fp8_grouped_gemm_f16.restype = i32
     lib.gg_fp8_grouped_gemm_ex.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp, sz, vp, i32, ctypes.c_uint]
     lib.gg_fp8_grouped_gemm_ex.restype = i32
+    lib.gg_fp8_grouped_gemm_swiglu.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp, i32, ctypes.c_uint]
+    lib.gg_fp8_grouped_gemm_swiglu.restype = i32
     lib.gg_fp8_pad_ex.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i64, i32, vp, ctypes.c_uint]
     lib.gg_fp8_pad_ex.restype = i32
     lib.gg_fp8_quantize_rows_ex.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, ctypes.c_uint]
@@ -114,7 +116,7 @@ EXPORTED_SYMBOLS = [
     "gg_fp8_version", "gg_fp8_status_str", "gg_fp8_workspace_bytes", "gg_fp8_grouped_gemm",
     "gg_fp8_grouped_gemm_variant", "gg_fp8_grouped_gemm_f16", "gg_fp8_grouped_gemm_ex", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_auto_variant", "gg_fp8_padded_rows_cap",
     "gg_fp8_pad", "gg_fp8_grouped_gemm_padded", "gg_fp8_unpad", "gg_fp8_quantize_rows", "gg_fp8_swiglu_quantize_rows", "gg_fp8_check_offsets",
-    "gg_fp8_pad_ex", "gg_fp8_quantize_rows_ex", "gg_fp8_swiglu_quantize_rows_ex",
+    "gg_fp8_pad_ex", "gg_fp8_quantize_rows_ex", "gg_fp8_swiglu_quantize_rows_ex", "gg_fp8_grouped_gemm_swiglu",
 ]
 
 
@@ -233,6 +235,36 @@ def grouped_gemm(A, SA, B, SB, group_offsets, C=None, variant: int = -1, stream=
     else:
         _check((lib.gg_fp8_grouped_gemm_f16 if out_dtype == torch.float16 else lib.gg_fp8_grouped_gemm_variant)(*args))
     return C
+
+
+def grouped_gemm_swiglu(A, SA, B, SB, group_offsets, A2=None, SA2=None, act_out=None, want_act=False, variant: int = -1,
+                        stream=None, sa_kmajor=False):
+    """gg_fp8_grouped_gemm_swiglu: the grouped GEMM with B [G, 2I, K] (gate rows, then up rows), silu(gate) * up and
+    the 1x128 quantiser in one kernel: returns (A2 uint8 [M_total, I], SA2 float32 [M_total, I/128] or
+    [I/128, M_total] with sa_kmajor, act bf16 [M_total, I] or None)."""
+    lib = load_library()
+    G, M_total, N, K = _gemm_shapes(A, SA, B, SB, group_offsets, sa_kmajor)
+    if N % 2:
+        raise ValueError("B must hold an even number of rows per group (gate | up)")
+    inter = N // 2
+    if A2 is None:
+        A2 = torch.empty((M_total, inter), dtype=torch.uint8, device=A.device)
+    if SA2 is None:
+        SA2 = torch.empty((inter // 128, M_total) if sa_kmajor else (M_total, inter // 128), dtype=torch.float32, device=A.device)
+    if act_out is None and want_act:
+        act_out = torch.empty((M_total, inter), dtype=torch.bfloat16, device=A.device)
+    _want(A2, "A2", torch.uint8, 2)
+    _want(SA2, "SA2", torch.float32, 2)
+    if act_out is not None:
+        _want(act_out, "act_out", torch.bfloat16, 2)
+        if tuple(act_out.shape) != (M_total, inter):
+            raise ValueError(f"act_out must be [{M_total}, {inter}]")
+    if tuple(A2.shape) != (M_total, inter) or tuple(SA2.shape) != ((inter // 128, M_total) if sa_kmajor else (M_total, inter // 128)):
+        raise ValueError("A2 or SA2 does not have the shape of the output")
+    _check(lib.gg_fp8_grouped_gemm_swiglu(_ptr(A), _ptr(SA), _ptr(B), _ptr(SB), _ptr(group_offsets), _ptr(A2), _ptr(SA2),
+                                          _ptr(act_out), G, M_total, inter, K, _stream(stream), int(variant),
+                                          GG_SA_KMAJOR if sa_kmajor else 0))
+    return A2, SA2, act_out
 
 
 def padded_rows_cap(G: int, M_total: int) -> int:

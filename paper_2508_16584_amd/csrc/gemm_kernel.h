@@ -42,6 +42,7 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v2f __attribute__((ext_vector_type(2)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
@@ -81,6 +82,13 @@ struct GemmArgs {
   // K block of a tile needs are contiguous (a few cache lines instead of one per row).
   int sa_row_stride, sa_kb_stride;
   int sa_kmajor;   // 1 for the second order
+  // fused activation epilogue of the second kernel (N = 2 * I weight rows: gate rows [0, I), up rows [I, 2I)):
+  // A2 [M_total, I] e4m3, SA2 one scale per (row, 128 activation columns) at row * sa2_row_stride + block *
+  // sa2_kb_stride (elements), act_out [M_total, I] bf16 or null
+  uint8_t* A2;
+  float* SA2;
+  uint16_t* act_out;
+  int64_t sa2_row_stride, sa2_kb_stride;
 };
 
 // Length in bytes of the view of SA that starts at the scale of (first row of a tile, K block 0).  The K-block part

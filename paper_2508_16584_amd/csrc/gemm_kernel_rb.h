@@ -30,12 +30,16 @@
 // product has the same terms, the matrix instruction adds them in another order.
 #pragma once
 #include "gemm_kernel.h"
+#include "quant_kernel.h"
 
 namespace gg {
 
-template <int BM_, int AFR_ = 4, bool KP_ = false>
+// FUSE: the tile's 256 weight rows are 128 rows of the gate projection and the 128 matching rows of the up
+// projection of an expert MLP's first GEMM, and the epilogue turns the two 128-column halves into
+// silu(gate) * up, quantised to e4m3 with one scale per row (see the epilogue).
+template <int BM_, int AFR_ = 4, bool KP_ = false, bool FUSE_ = false>
 struct RbCfg {
-  static constexpr bool KP = KP_;
+  static constexpr bool KP = KP_, FUSE = FUSE_;
   static constexpr int BM = BM_, BN = 256, S = 3;
   static constexpr int NW = 8, NT = 512;
   static constexpr int TM = BM / 16, TN = 2;
@@ -50,7 +54,8 @@ struct RbCfg {
   static constexpr int STAGE_BYTES = A_BYTES + SA_BYTES + SB_BYTES + DUMP_BYTES;
   static constexpr int B_SLOTS = 3, B_SLOT_BYTES = 2048;        // per wave: fragments of 16 rows x 128 B
   static constexpr int B_BASE = S * STAGE_BYTES;
-  static constexpr int LDS_BYTES = B_BASE + NW * B_SLOTS * B_SLOT_BYTES;
+  static constexpr int RED_BASE = B_BASE + NW * B_SLOTS * B_SLOT_BYTES;   // FUSE: per row, the 8 waves' partial maxima
+  static constexpr int LDS_BYTES = RED_BASE + (FUSE ? BM * NW * 4 : 0);
   static constexpr int SB_WAVE = NW - 1;
   static constexpr int MFMAS = TM * TN;
   static constexpr int PIPE = 3;                   // MFMAs in flight before their FMAs are issued
@@ -109,22 +114,26 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
   const int vA = a_row * K + (((l & 7) ^ (Cfg::KP ? swz_key_a1(a_row) : swz_key_a(a_row))) << 4);
   // weight fragment j, fragment row rr (= MFMA row) is tile column 32w + 8*(rr/4) + 4j + rr%4: the 8 outputs
   // a lane ends up with (MFMA rows 4q..4q+3 of both fragments) are then 8 consecutive columns
+  // FUSE: fragment 0 is rows [16w, 16w+16) of the tile's gate rows, fragment 1 the same rows of its up rows, so a
+  // lane ends up with gate and up of the same 4 activation columns 16w + 4q .. + 3
   const int f_row = l >> 3;                                            // slab 0; slab 1 is fragment row f_row + 8
-  const int vBrow = (w * 32 + 8 * (f_row >> 2) + (f_row & 3)) * K;
+  const int vBrow = (Cfg::FUSE ? w * 16 + f_row : w * 32 + 8 * (f_row >> 2) + (f_row & 3)) * K;
   const int vB0 = vBrow + (((l & 7) ^ (Cfg::KP ? swz_key_a1(f_row) : swz_key_a(f_row))) << 4);
-  const int vB1 = vBrow + 16 * K + (((l & 7) ^ (Cfg::KP ? swz_key_a1(f_row + 8) : swz_key_a(f_row + 8))) << 4);
+  const int vB1 = vBrow + (Cfg::FUSE ? 8 : 16) * K + (((l & 7) ^ (Cfg::KP ? swz_key_a1(f_row + 8) : swz_key_a(f_row + 8))) << 4);
+  const int inter = N >> 1;                                            // FUSE: activation columns (N = gate + up rows)
+  const int frag1_off = Cfg::FUSE ? inter * K : 4 * K;                 // from fragment 0's weight rows to fragment 1's
   // Every wave issues exactly one scale DMA per K block: waves [0, SA_WAVES) fetch 64 activation scales each,
   // wave SB_WAVE the two weight scales, the others an out-of-range offset into a dump area.
   const bool sa_wave = w < Cfg::SA_WAVES, sb_wave = w == Cfg::SB_WAVE;
   const int s_kb_stride = sa_wave ? a.sa_kb_stride : 4;             // bytes from one K block's scale to the next
-  const int vS = sa_wave ? (w * 64 + l) * a.sa_row_stride : sb_wave ? (l < BN / 128 ? l : BN / 128 - 1) * KB * 4 : GG_OOB_OFFSET;
+  const int vS = sa_wave ? (w * 64 + l) * a.sa_row_stride : sb_wave ? (l < BN / 128 ? l : BN / 128 - 1) * (Cfg::FUSE ? inter >> 7 : 1) * KB * 4 : GG_OOB_OFFSET;
   const int ldsS = Cfg::A_BYTES + (sa_wave ? w * 256 : sb_wave ? Cfg::SA_BYTES : Cfg::SA_BYTES + Cfg::SB_BYTES);
   // operand reads: row r, chunks (2q, 2q+1), or (q, 4+q) with KP
   const int keyR = Cfg::KP ? swz_key_a1(r) : swz_key_a(r);
   const int rd0 = r * 128 + (((Cfg::KP ? q : 2 * q) ^ keyR) << 4);
   const int rd1 = r * 128 + (((Cfg::KP ? 4 + q : 2 * q + 1) ^ keyR) << 4);
   const int saRd = Cfg::A_BYTES + r * 4;
-  const int sbRd = Cfg::A_BYTES + Cfg::SA_BYTES + ((w * 32) >> 7) * 4;
+  const int sbRd = Cfg::A_BYTES + Cfg::SA_BYTES + (Cfg::FUSE ? 0 : ((w * 32) >> 7) * 4);   // FUSE: gate block, up block at + 4
   uint8_t* const bslots = lds + Cfg::B_BASE + w * (Cfg::B_SLOTS * Cfg::B_SLOT_BYTES);   // this wave's weight slots
 
   // ---- persistent walk over the tile list; a workgroup looks one tile ahead (see "carry" below) -------------
@@ -162,7 +171,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     const int ntile = nc * a.n_chunk + (rem - mtile * csz);
     const int m0 = mtile * BM;
     t.g = g;
-    t.n0 = ntile * BN;
+    t.n0 = ntile * (Cfg::FUSE ? 128 : BN);     // FUSE: first of the tile's 128 activation columns
     t.rows_valid = Mg - m0 < BM ? Mg - m0 : BM;
     t.grow = (int64_t)row0 + m0;
     t.valid = true;
@@ -178,12 +187,13 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     return uniform_rsrc(a.A + (t.grow + 64 * i) * K, on ? rows_i * K : 0);
   };
   auto desc_b = [&](const Tile& t, bool on) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
-    return uniform_rsrc(a.B + ((int64_t)t.g * N + t.n0) * K, on ? BN * K : 0);
+    return uniform_rsrc(a.B + ((int64_t)t.g * N + t.n0) * K, on ? (Cfg::FUSE ? inter + 128 : BN) * K : 0);
   };
   // this wave's scale source: the activation scales of the tile's rows, or the weight scales of its two column blocks
   auto desc_s = [&](const Tile& t, bool on) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
     return sa_wave ? uniform_rsrc((const uint8_t*)a.SA + t.grow * a.sa_row_stride, on ? sa_view_bytes(a, t.grow, t.rows_valid) : 0)
-                   : uniform_rsrc(a.SB + ((int64_t)t.g * (N >> 7) + (t.n0 >> 7)) * KB, on ? (BN / 128) * KB * 4 : 0);
+                   : uniform_rsrc(a.SB + ((int64_t)t.g * (N >> 7) + (t.n0 >> 7)) * KB,
+                                  on ? (Cfg::FUSE ? (inter >> 7) + 1 : BN / 128) * KB * 4 : 0);
   };
 
   // Carry: the fetches a K step issues run two to three K blocks ahead; at the end of a tile those blocks are the
@@ -203,7 +213,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
   v8i bfr[2][TN];                 // weight fragments of K block kb in set kb % 2
   v8i afr[AFR];
   float sa[AFR];
-  float sb_next = 0.f;
+  float sb_next = 0.f, sb_next_up = 0.f;     // FUSE: the weight scales of the gate block and of the up block
   int stage = 0;                  // LDS buffer of block kb
   int bslot = 2;                  // slot of fragment 2*kb + 2
   for (int it = 0;; ++it) {
@@ -238,7 +248,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       const bool in = kb < KB;
       uint8_t* dst = bslots + slot * Cfg::B_SLOT_BYTES;
       // all 256 weight rows of the tile exist: only the lane part of the offset needs the bounds check
-      const int so = __builtin_amdgcn_readfirstlane(k_wrapped(kb + (j == 0 ? rot0 : rot), KB) * 128 + j * 4 * K);
+      const int so = __builtin_amdgcn_readfirstlane(k_wrapped(kb + (j == 0 ? rot0 : rot), KB) * 128 + j * frag1_off);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(j == 0 ? dB0 : dB, GG_LDS_PTR(dst), 16, in ? vB0 : GG_OOB_OFFSET, so, 0, 0);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(j == 0 ? dB0 : dB, GG_LDS_PTR(dst + 1024), 16, in ? vB1 : GG_OOB_OFFSET, so, 0, 0);
     };
@@ -286,6 +296,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       dma_b(2, J0, 1);
 
       sb_next = *(const float*)(lds + sbRd);                   // weight scale of block 0
+      if constexpr (Cfg::FUSE) sb_next_up = *(const float*)(lds + sbRd + 4);
       stage = 0;
       bslot = 2;
     }
@@ -303,19 +314,20 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       // every wave has its part of block kb+1 in LDS and is done reading block kb-1
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      const float sb = sb_next;                                // read a block ago: no LDS wait ahead of the first MFMA
+      const float sb = sb_next, sb_up = sb_next_up;            // read a block ago: no LDS wait ahead of the first MFMA
       bfr[BS ^ 1][0] = read_frag(bslots + bslot * Cfg::B_SLOT_BYTES);
       dma_scales(kb + 2, stageN);
       __builtin_amdgcn_sched_barrier(0);
 
       v4f p[MF];
-      float s[TM];
+      float s[TM], s_up[Cfg::FUSE ? TM : 1];
       auto body = [&](auto tc) __attribute__((always_inline)) {
         constexpr int t = decltype(tc)::value;
         if constexpr (t < MF) {
           constexpr int mt = t / TN, j = t % TN;
           if constexpr (j == 0) {
             s[mt] = sa[mt % AFR] * sb;
+            if constexpr (Cfg::FUSE) s_up[mt] = sa[mt % AFR] * sb_up;
             // fragment of activation block mt + AFR - 1 into the slot block mt - 1 has left; past the end of
             // this K block that is the next K block's, published by the barrier above
             constexpr int nb = mt + AFR - 1;
@@ -325,7 +337,10 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
             } else {
               afr[nb % AFR] = read_frag(st1 + (nb - TM) * 2048);
               sa[nb % AFR] = *(const float*)(st1 + saRd + (nb - TM) * 64);
-              if constexpr (nb == TM) sb_next = *(const float*)(st1 + sbRd);   // next block's weight scale
+              if constexpr (nb == TM) {                                         // next block's weight scale(s)
+                sb_next = *(const float*)(st1 + sbRd);
+                if constexpr (Cfg::FUSE) sb_next_up = *(const float*)(st1 + sbRd + 4);
+              }
             }
           }
           p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[BS][j], afr[mt % AFR], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
@@ -338,7 +353,8 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
         }
         if constexpr (t >= PIPE) {
           constexpr int u = t - PIPE;
-          acc[u / TN][u % TN] += p[u] * s[u / TN];
+          if constexpr (Cfg::FUSE && u % TN == 1) acc[u / TN][1] += p[u] * s_up[u / TN];
+          else acc[u / TN][u % TN] += p[u] * s[u / TN];
         }
       };
       auto order = [&](auto tc) __attribute__((always_inline)) {               // issue order of what body creates
@@ -346,8 +362,8 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
         if constexpr (t < MF) {
           constexpr int j = t % TN;
           if constexpr (j == 0) {
-            __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);                                   // scale product
-            __builtin_amdgcn_sched_group_barrier(0x100, t / TN + AFR - 1 == TM ? 4 : 3, 0);      // 3 (4) DS reads
+            __builtin_amdgcn_sched_group_barrier(0x002, Cfg::FUSE ? 2 : 1, 0);                   // scale product(s)
+            __builtin_amdgcn_sched_group_barrier(0x100, t / TN + AFR - 1 == TM ? (Cfg::FUSE ? 5 : 4) : 3, 0);   // 3 (4, 5) DS reads
           }
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                     // 1 MFMA
           if constexpr (t >= Cfg::T_A0 && t < Cfg::T_A0 + Cfg::A_ITERS) {
@@ -415,6 +431,67 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     kstep(KB - 1, SET1);
     kbase = kbase0 = 0;
 
+    if constexpr (Cfg::FUSE) {
+      // ---- fused epilogue: act = bf16(silu(bf16(gate)) * bf16(up)), then the 1x128 block quantiser on act ------
+      // The two projections are rounded to bfloat16 first, as if the GEMM had stored them, and everything after
+      // that is the arithmetic of the separate activation kernel, so the bytes, scales and activations equal
+      // that kernel's on this GEMM's output bit for bit.  A row's 128 activation columns are spread over the 8
+      // waves (16 columns each: 4 lane groups x 4 values): the block maximum goes through LDS.
+      uint8_t* red = lds + Cfg::RED_BASE;
+#pragma unroll
+      for (int mt = 0; mt < TM; ++mt) {
+        const v4f x = acc[mt][0], y = acc[mt][1];
+        const int a01 = swiglu2(pack2_rne(x[0], x[1], false), pack2_rne(y[0], y[1], false));
+        const int a23 = swiglu2(pack2_rne(x[2], x[3], false), pack2_rne(y[2], y[3], false));
+        const float v[4] = {__builtin_bit_cast(float, a01 << 16), __builtin_bit_cast(float, a01 & (int)0xFFFF0000),
+                            __builtin_bit_cast(float, a23 << 16), __builtin_bit_cast(float, a23 & (int)0xFFFF0000)};
+        unsigned top = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const unsigned t = amax_bits_of(v[i]);
+          top = top > t ? top : t;
+        }
+        unsigned o = (unsigned)__shfl_xor((int)top, 16);
+        top = top > o ? top : o;
+        o = (unsigned)__shfl_xor((int)top, 32);
+        top = top > o ? top : o;
+        if (q == 0) *(unsigned*)(red + ((mt * 16 + r) * NW + w) * 4) = top;
+        acc[mt][0] = (v4f){v[0], v[1], v[2], v[3]};                  // keep the activations, drop the projections
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      const int ntile = n0 >> 7;
+#pragma unroll
+      for (int mt = 0; mt < TM; ++mt) {
+        const v4i m0 = *(const v4i*)(red + (mt * 16 + r) * NW * 4);
+        const v4i m1 = *(const v4i*)(red + (mt * 16 + r) * NW * 4 + 16);
+        unsigned top = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          top = top > (unsigned)m0[i] ? top : (unsigned)m0[i];
+          top = top > (unsigned)m1[i] ? top : (unsigned)m1[i];
+        }
+        const float amax = block_amax(top);
+        const float scale = amax / 448.0f;
+        const float inv = 448.0f / amax;
+        const float v[4] = {acc[mt][0][0], acc[mt][0][1], acc[mt][0][2], acc[mt][0][3]};
+        const int bytes = e4m3x4_of(v, inv);
+        int rows_mt = rows_valid - 16 * mt;
+        rows_mt = rows_mt < 0 ? 0 : rows_mt;
+        // bounded views of 16 rows, as for C below; a lane's 4 columns are 16w + 4q .. + 3 of the tile's 128
+        __amdgpu_buffer_rsrc_t dQ = uniform_rsrc(a.A2 + (grow + 16 * mt) * inter + n0, rows_mt > 0 ? rows_mt * inter - n0 : 0);
+        __builtin_amdgcn_raw_buffer_store_b32(bytes, dQ, r * inter + w * 16 + 4 * q, 0, 0);
+        if (a.act_out) {
+          __amdgpu_buffer_rsrc_t dAct = uniform_rsrc(a.act_out + (grow + 16 * mt) * inter + n0, rows_mt > 0 ? (rows_mt * inter - n0) * 2 : 0);
+          // the activations are bfloat16 values held as floats: their upper halves are the bits to store
+          const v2i pk = {(int)((__builtin_bit_cast(unsigned, v[0]) >> 16) | (__builtin_bit_cast(unsigned, v[1]) & 0xFFFF0000u)),
+                          (int)((__builtin_bit_cast(unsigned, v[2]) >> 16) | (__builtin_bit_cast(unsigned, v[3]) & 0xFFFF0000u))};
+          __builtin_amdgcn_raw_buffer_store_b64(pk, dAct, (r * inter + w * 16 + 4 * q) * 2, 0, 0);
+        }
+        if (w == 0 && q == 0 && r < rows_mt) a.SA2[(grow + 16 * mt + r) * a.sa2_row_stride + (int64_t)ntile * a.sa2_kb_stride] = scale;
+      }
+    } else {
     // ---- epilogue: bf16 (or binary16) RNE, one bounded 16-byte store per activation block ---------------------------------
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt) {
@@ -431,6 +508,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       rows_mt = rows_mt < 0 ? 0 : rows_mt;
       __amdgpu_buffer_rsrc_t dC = uniform_rsrc(a.C + (grow + 16 * mt) * N + n0, rows_mt > 0 ? rows_mt * N * 2 - n0 * 2 : 0);
       __builtin_amdgcn_raw_buffer_store_b128(out, dC, r * N * 2 + (w * 32 + 8 * q) * 2, 0, 0);
+    }
     }
     if (!has_next) {
       // the dropped fetches of the last K blocks still write zeros into this workgroup's LDS: let them land

@@ -107,6 +107,18 @@ const Variant kVariants[] = {
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
+// The second kernel with the activation epilogue (gg_fp8_grouped_gemm_swiglu): same tiles as variants 14, 15, 12.
+struct FusedVariant {
+  int variant;   // the plain variant it is the twin of
+  int BM;
+  hipError_t (*launch)(const gg::GemmArgs&, int, hipStream_t);
+};
+const FusedVariant kFused[] = {
+    {14, 192, &launch_gemm_rb<gg::RbCfg<192, 2, false, true>>},
+    {15, 224, &launch_gemm_rb<gg::RbCfg<224, 2, false, true>>},
+    {12, 256, &launch_gemm_rb<gg::RbCfg<256, 2, false, true>>},
+};
+
 // Automatic choice.  The host sees only sizes (the offsets stay on the device), so the choice works with the
 // expected tile count: a group ends in a partial tile half of the time on average, which adds G/2 tiles per
 // column of tiles.  Candidates and their measured character on MI355X:
@@ -193,6 +205,10 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
   args.k_rem = K - 128 * (args.KB - 1);
   args.n_tiles = (N + v.BN - 1) / v.BN;
   args.n_chunk = args.n_tiles < 8 ? args.n_tiles : 8;
+  args.A2 = nullptr;
+  args.SA2 = nullptr;
+  args.act_out = nullptr;
+  args.sa2_row_stride = args.sa2_kb_stride = 0;
   args.out_f16 = (flags & GG_OUT_F16) ? 1 : 0;
   if (flags & GG_SA_KMAJOR) {
     // the K-block part of a scale's address travels in a 32-bit scalar offset
@@ -289,6 +305,75 @@ int gg_fp8_grouped_gemm_ex(const void* A, const float* SA, const void* B, const 
   (void)workspace;
   if (workspace_bytes < gg_fp8_workspace_bytes(G, M_total, N, K)) return GG_ERR_WORKSPACE;
   return run_gemm(A, SA, B, SB, group_offsets, C, G, M_total, N, K, stream, variant, flags);
+}
+
+int gg_fp8_grouped_gemm_swiglu(const void* A, const float* SA, const void* B, const float* SB,
+                               const int32_t* group_offsets, void* A2, float* SA2, void* act_out,
+                               int G, int64_t M_total, int I, int K, void* stream, int variant, unsigned flags) {
+  if (flags & ~(unsigned)GG_SA_KMAJOR) return GG_ERR_UNSUPPORTED;
+  if (G < 0 || M_total < 0 || I <= 0 || K <= 0) return GG_ERR_SHAPE;
+  if (M_total > 0x7FFFFFFFLL || I > (1 << 20) || K > (1 << 22)) return GG_ERR_SHAPE;
+  // whole 128-column blocks of activations; the second kernel's K loop (two K blocks per turn, carried)
+  if (I % 128 != 0 || K % 256 != 0 || K < 512) return GG_ERR_UNSUPPORTED;
+  if ((int64_t)2 * I * K > 0x7FFFFFFFLL) return GG_ERR_SHAPE;       // an expert's weights are addressed with 32-bit offsets
+  if (G == 0 || M_total == 0) return GG_OK;
+  if (!A || !SA || !B || !SB || !group_offsets || !A2 || !SA2) return GG_ERR_NULL;
+  const int N = 2 * I;
+  const FusedVariant* fv = nullptr;
+  if (variant < 0) {
+    // the cheapest of the three tile heights under the cost model of the automatic choice
+    double c_best = 0;
+    const double eff[3] = {1.06, 1.08, 1.10};
+    for (int i = 0; i < 3; ++i) {
+      const double rounds = ((double)M_total / kFused[i].BM + 0.5 * G) * (I / 128) / 256.0;
+      const double whole = std::floor(rounds), frac = rounds - whole;
+      const double c = (whole + (frac > 1e-9 ? 0.3 + 0.7 * frac : 0.0)) * kFused[i].BM / eff[i];
+      if (!fv || c < c_best) { c_best = c; fv = &kFused[i]; }
+    }
+  } else {
+    for (const FusedVariant& f : kFused)
+      if (f.variant == variant) fv = &f;
+    if (!fv) return GG_ERR_UNSUPPORTED;
+  }
+  gg::GemmArgs args;
+  args.A = static_cast<const uint8_t*>(A);
+  args.SA = SA;
+  args.B = static_cast<const uint8_t*>(B);
+  args.SB = SB;
+  args.off = group_offsets;
+  args.C = nullptr;
+  args.G = G;
+  args.M_total = (int)M_total;
+  args.N = N;
+  args.K = K;
+  args.KB = K / 128;
+  args.k_rem = 128;
+  args.n_tiles = I / 128;
+  args.n_chunk = args.n_tiles < 8 ? args.n_tiles : 8;
+  args.out_f16 = 0;
+  args.rot_mul = 0;      // a tile holds columns of two far-apart column blocks: every K loop starts at block 0
+  const bool km = (flags & GG_SA_KMAJOR) != 0;
+  if (km && M_total * 4 * (int64_t)args.KB > 0x7FFFFFFFLL) return GG_ERR_SHAPE;
+  args.sa_row_stride = km ? 4 : 4 * args.KB;
+  args.sa_kb_stride = km ? (int)(M_total * 4) : 4;
+  args.sa_kmajor = km ? 1 : 0;
+  args.A2 = static_cast<uint8_t*>(A2);
+  args.SA2 = SA2;
+  args.act_out = static_cast<uint16_t*>(act_out);
+  args.sa2_row_stride = km ? 1 : I / 128;
+  args.sa2_kb_stride = km ? M_total : 1;
+  const int64_t max_tiles = (M_total / fv->BM + G) * (int64_t)args.n_tiles;
+  if (max_tiles > 0x7FFFFFFFLL) return GG_ERR_SHAPE;
+  int64_t grid = device_cus();
+  if (grid > max_tiles) grid = max_tiles;
+  if (grid < 1) grid = 1;
+  if (grid >= kXcds) {
+    grid -= grid % kXcds;
+    args.slots = (int)(grid / kXcds);
+  } else {
+    args.slots = 0;
+  }
+  return fv->launch(args, (int)grid, static_cast<hipStream_t>(stream)) == hipSuccess ? GG_OK : GG_ERR_HIP;
 }
 
 int64_t gg_fp8_padded_rows_cap(int G, int64_t M_total) {

@@ -142,27 +142,59 @@ __global__ void __launch_bounds__(Q_THREADS) gg_quantize_rows_kernel(const uint1
 //     act = bf16_rne( silu(gate) * up ),  silu(g) = g / (1 + exp(-g))   in fp32
 // and then exactly quantize_block on the bf16 bits of act.  act is also written out when act_out is not null.
 // Same mapping: 16 lanes own one block of 128 activation columns, a lane loads 8 gate and 8 up values.
+// two (gate, up) pairs, each a dword of two bf16 -> one dword of two bf16 activations
+__device__ __forceinline__ int swiglu2(const int g_raw, const int u_raw) {
+  float g[2] = {__builtin_bit_cast(float, g_raw << 16), __builtin_bit_cast(float, g_raw & (int)0xFFFF0000)};
+  float u[2] = {__builtin_bit_cast(float, u_raw << 16), __builtin_bit_cast(float, u_raw & (int)0xFFFF0000)};
+  float a[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    // sigmoid through t = exp(-|g|) in [0, 1]: no overflow for any g; the hardware exponential (a few fp32
+    // ulps, denormal results flushed: t = 0 below g = -87.3) and reciprocal are far inside the bf16 rounding
+    const float t = __expf(-__builtin_fabsf(g[h]));
+    const float sig = __fdividef(g[h] >= 0.f ? 1.0f : t, 1.0f + t);
+    a[h] = g[h] * sig * u[h];
+  }
+  typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+  typedef float f2 __attribute__((ext_vector_type(2)));
+  const bf2 r = __builtin_convertvector((f2){a[0], a[1]}, bf2);     // round to nearest even
+  return __builtin_bit_cast(int, r);
+}
+
 __device__ __forceinline__ q_v4i swiglu8(const q_v4i g_raw, const q_v4i u_raw) {
   q_v4i out;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    float g[2] = {__builtin_bit_cast(float, g_raw[i] << 16), __builtin_bit_cast(float, g_raw[i] & (int)0xFFFF0000)};
-    float u[2] = {__builtin_bit_cast(float, u_raw[i] << 16), __builtin_bit_cast(float, u_raw[i] & (int)0xFFFF0000)};
-    float a[2];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      // sigmoid through t = exp(-|g|) in [0, 1]: no overflow for any g; the hardware exponential (a few fp32
-      // ulps, denormal results flushed: t = 0 below g = -87.3) and reciprocal are far inside the bf16 rounding
-      const float t = __expf(-__builtin_fabsf(g[h]));
-      const float sig = __fdividef(g[h] >= 0.f ? 1.0f : t, 1.0f + t);
-      a[h] = g[h] * sig * u[h];
-    }
-    typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
-    typedef float f2 __attribute__((ext_vector_type(2)));
-    const bf2 r = __builtin_convertvector((f2){a[0], a[1]}, bf2);     // round to nearest even
-    out[i] = __builtin_bit_cast(int, r);
-  }
+  for (int i = 0; i < 4; ++i) out[i] = swiglu2(g_raw[i], u_raw[i]);
   return out;
+}
+
+// The block quantiser's arithmetic for callers that hold a block's values spread over lanes in another way than
+// quantize_block's 16 x 8: amax_bits_of() of every value, reduced by the caller with an integer max, then
+// block_scale() and e4m3_of().  Same results as quantize_block, bit for bit (its fast path and its NaN/inf path
+// agree on ordinary values; this is the general path throughout).
+__device__ __forceinline__ unsigned amax_bits_of(float v) {
+  const unsigned u = __builtin_bit_cast(unsigned, v) & 0x7FFFFFFFu;
+  return u > 0x7F800000u ? 0u : u;                             // a NaN counts as zero
+}
+__device__ __forceinline__ float block_amax(unsigned top) {
+  top = top > 0x0D800000u ? top : 0x0D800000u;                 // floor 2^-100
+  return __builtin_bit_cast(float, top);
+}
+// four values -> four e4m3 bytes in a dword (value 0 in the low byte)
+__device__ __forceinline__ int e4m3x4_of(const float* v, float inv) {
+  float y[4];
+  unsigned nan = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float t = v[i] * inv;
+    const bool is_nan = t != t;
+    y[i] = is_nan ? 0.f : __builtin_fminf(__builtin_fmaxf(t, -448.0f), 448.0f);
+    nan |= is_nan ? (0x7Fu << (8 * i)) : 0u;
+  }
+  int w = 0;
+  w = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], w, false);
+  w = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], w, true);
+  return w | (int)nan;
 }
 
 __global__ void __launch_bounds__(Q_THREADS) gg_swiglu_quantize_rows_kernel(const uint16_t* __restrict__ H,

@@ -125,3 +125,25 @@ def raw_problem(rng, sizes, N, K, device, byte_choices=None, scale_pow2=False):
     host = (A, SA, B, SB, off)
     dev = tuple(torch.from_numpy(x).to(device) for x in host)
     return host, dev
+
+
+def assert_swiglu_act(hb: np.ndarray, actb: np.ndarray, min_equal=0.995):
+    """GPU activations (bf16 bits) of H = [gate | up] (bf16 bits) against the oracle's: within one bf16 ulp of the
+    float64 value plus |gate * up| * 2^-126 (fp32 evaluation on the GPU; below gate = -87.3 the fp32 sigmoid is flushed
+    to 0), NaNs and infinities in the same places, and nearly all of them bit-equal."""
+    ref_bits = orc.swiglu_rows(hb)
+    got, ref = orc.f64_from_bf16_bits(actb), orc.f64_from_bf16_bits(ref_bits)
+    half = hb.shape[1] // 2
+    gate, up = orc.f64_from_bf16_bits(hb[:, :half]), orc.f64_from_bf16_bits(hb[:, half:])
+    # where the fp32 sigmoid is flushed to 0 (gate < -87.3) an infinite `up` gives 0 * inf = NaN instead of an infinity
+    flushed = (gate < -87.0) & np.isinf(up)
+    assert np.isnan(got[flushed]).all()
+    assert np.array_equal(np.isnan(got)[~flushed], np.isnan(ref)[~flushed])
+    ok = ~np.isnan(ref) & ~flushed
+    fin = ok & np.isfinite(ref)
+    assert np.array_equal(got[ok & ~fin], ref[ok & ~fin])                        # infinities agree exactly
+    with np.errstate(invalid="ignore"):
+        gu = np.abs(gate * up)
+    assert np.all(np.abs(got[fin] - ref[fin]) <= orc.bf16_ulp(ref[fin]) + gu[fin] * 2.0 ** -126)
+    if fin.sum() > 1000:
+        assert np.mean(actb[fin] == ref_bits[fin]) >= min_equal

@@ -135,6 +135,21 @@ def test_ex_entry_points_validate_flags_and_sizes(lib):
     assert lib.gg_fp8_swiglu_quantize_rows_ex(nul, nul, nul, nul, 0, 256, nul, KM) == GG_OK
 
 
+def test_fused_gemm_argument_validation(lib):
+    p = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
+    nul = ctypes.c_void_p(0)
+    f = lambda I=256, K=512, M=100, A2=p, variant=-1, flags=0: lib.gg_fp8_grouped_gemm_swiglu(
+        p, p, p, p, p, A2, p, nul, 2, M, I, K, nul, variant, flags)
+    assert f(I=192) == GG_ERR_UNSUPPORTED          # whole 128-column blocks of activations
+    assert f(K=384) == GG_ERR_UNSUPPORTED and f(K=256) == GG_ERR_UNSUPPORTED    # K % 256 == 0, K >= 512
+    assert f(variant=0) == GG_ERR_UNSUPPORTED and f(variant=13) == GG_ERR_UNSUPPORTED and f(variant=99) == GG_ERR_UNSUPPORTED
+    assert f(flags=binding.GG_OUT_F16) == GG_ERR_UNSUPPORTED
+    assert f(I=0) == GG_ERR_SHAPE and f(M=-1) == GG_ERR_SHAPE
+    assert f(I=2 ** 19, K=4096) == GG_ERR_SHAPE     # an expert's weights beyond 32-bit offsets
+    assert f(A2=nul) == GG_ERR_NULL
+    assert f(M=0, A2=nul) == GG_OK
+
+
 def test_binding_rejects_wrong_tensors_before_calling_the_library(lib):
     import torch
     A = torch.zeros((4, 256), dtype=torch.uint8)

@@ -10,6 +10,7 @@ import torch
 
 import paper_2508_16584_amd as gg
 from oracle import gg_oracle as orc
+from gg_testlib import assert_swiglu_act
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -168,22 +169,7 @@ def check_swiglu(hb: np.ndarray, min_equal=0.995):
     actb = act.view(torch.int16).cpu().numpy().view(np.uint16)
     A, SA = A.cpu().numpy(), SA.cpu().numpy()
     assert np.array_equal(A, A2.cpu().numpy()) and np.array_equal(SA, SA2.cpu().numpy())
-    ref_bits = orc.swiglu_rows(hb)
-    got, ref = orc.f64_from_bf16_bits(actb), orc.f64_from_bf16_bits(ref_bits)
-    half = hb.shape[1] // 2
-    gate, up = orc.f64_from_bf16_bits(hb[:, :half]), orc.f64_from_bf16_bits(hb[:, half:])
-    # where the fp32 sigmoid is flushed to 0 (gate < -87.3) an infinite `up` gives 0 * inf = NaN instead of an infinity
-    flushed = (gate < -87.0) & np.isinf(up)
-    assert np.isnan(got[flushed]).all()
-    assert np.array_equal(np.isnan(got)[~flushed], np.isnan(ref)[~flushed])
-    ok = ~np.isnan(ref) & ~flushed
-    fin = ok & np.isfinite(ref)
-    assert np.array_equal(got[ok & ~fin], ref[ok & ~fin])                        # infinities agree exactly
-    with np.errstate(invalid="ignore"):
-        gu = np.abs(gate * up)
-    assert np.all(np.abs(got[fin] - ref[fin]) <= orc.bf16_ulp(ref[fin]) + gu[fin] * 2.0 ** -126)
-    if fin.sum() > 1000:
-        assert np.mean(actb[fin] == ref_bits[fin]) >= min_equal
+    assert_swiglu_act(hb, actb, min_equal)
     A_ref, SA_ref = orc.quantize_rows(actb)
     assert np.array_equal(SA.view(np.uint32), SA_ref.view(np.uint32))
     assert np.array_equal(A, A_ref)

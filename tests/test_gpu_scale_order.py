@@ -96,8 +96,8 @@ def test_kmajor_binary16_output_and_untrusted_offsets():
     c1 = gg.grouped_gemm(dA, SAk, dB, dSB, good, out_dtype=torch.float16, sa_kmajor=True)
     torch.cuda.synchronize()
     assert torch.equal(c0.view(torch.int16), c1.view(torch.int16))
-    # offsets that leave [0, M_total] or decrease: nothing outside C is written, and the two orders still agree
-    # (both clamp the offsets the same way)
+    # offsets that leave [0, M_total] or decrease: nothing outside C is written, and where the clamped groups do not
+    # overlap the two orders still agree (both clamp the offsets the same way)
     for bad in ([-50, 100, 200, 5000], [0, 250, 100, 300], [290, 295, 300, 1 << 30]):
         boff = torch.tensor(bad, dtype=torch.int32, device=DEV)
         for v in (-1, 0, 3, 12):
@@ -107,7 +107,8 @@ def test_kmajor_binary16_output_and_untrusted_offsets():
             torch.cuda.synchronize()
             b0, b1 = bits_of(C0), bits_of(C1)
             assert (b1[:2] == CANARY).all() and (b1[2 + M:] == CANARY).all()
-            assert np.array_equal(b0, b1)
+            if bad[2] >= bad[1]:          # decreasing offsets make two groups claim the same rows: the last writer wins
+                assert np.array_equal(b0, b1)
 
 
 @pytest.mark.parametrize("sizes,N,K", [([5, 300, 64], 256, 512), ([130, 0, 1, 67], 200, 336), ([0, 0, 7], 512, 4096)])
