@@ -166,6 +166,20 @@ int pick_variant(int G, int64_t M_total, int N, int K) {
   return best;
 }
 
+// Grid of the row kernels (a workgroup takes rows in pairs).  With K-block-major scales and at least 8 workgroups the
+// pairs are dealt out by XCD (see pair_of in quant_kernel.h), which needs a grid that is a multiple of 8.
+int64_t row_kernel_grid(int64_t M_total, bool kmajor, int* by_xcd) {
+  int64_t grid = (int64_t)device_cus() * 8;
+  const int64_t npairs = (M_total + 1) / 2;
+  if (grid > npairs) grid = npairs;
+  *by_xcd = 0;
+  if (kmajor && grid >= kXcds) {
+    grid -= grid % kXcds;
+    *by_xcd = 1;
+  }
+  return grid < 1 ? 1 : grid;
+}
+
 int validate_gemm(const void* A, const float* SA, const void* B, const float* SB, const int32_t* off, void* C,
                   int G, int64_t M_total, int N, int K) {
   if (G < 0 || M_total < 0 || N <= 0 || K <= 0) return GG_ERR_SHAPE;
@@ -441,12 +455,13 @@ int gg_fp8_quantize_rows_ex(const void* X, const int32_t* row_src, void* A, floa
   if (K % 128 != 0) return GG_ERR_UNSUPPORTED;
   if (M_total == 0) return GG_OK;
   if (!A || !SA || (!X && T > 0)) return GG_ERR_NULL;
-  int64_t grid = (int64_t)device_cus() * 8;
-  if (grid > (M_total + 1) / 2) grid = (M_total + 1) / 2;     // a workgroup takes rows in pairs
+  int by_xcd = 0;
+  const int64_t grid = row_kernel_grid(M_total, (flags & GG_SA_KMAJOR) != 0, &by_xcd);
   hipLaunchKernelGGL(gg::gg_quantize_rows_kernel, dim3((unsigned)grid), dim3(gg::Q_THREADS), 0,
                      static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(X), row_src,
                      static_cast<uint8_t*>(A), SA, T, (int)M_total, K, K / 128,
-                     (flags & GG_SA_KMAJOR) ? (int64_t)1 : (int64_t)(K / 128), (flags & GG_SA_KMAJOR) ? M_total : (int64_t)1);
+                     (flags & GG_SA_KMAJOR) ? (int64_t)1 : (int64_t)(K / 128), (flags & GG_SA_KMAJOR) ? M_total : (int64_t)1,
+                     by_xcd);
   return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
 }
 
@@ -463,12 +478,13 @@ int gg_fp8_swiglu_quantize_rows_ex(const void* H, void* A, float* SA, void* act_
   if (I % 128 != 0) return GG_ERR_UNSUPPORTED;
   if (M_total == 0) return GG_OK;
   if (!H || !A || !SA) return GG_ERR_NULL;
-  int64_t grid = (int64_t)device_cus() * 8;
-  if (grid > (M_total + 1) / 2) grid = (M_total + 1) / 2;     // a workgroup takes rows in pairs
+  int by_xcd = 0;
+  const int64_t grid = row_kernel_grid(M_total, (flags & GG_SA_KMAJOR) != 0, &by_xcd);
   hipLaunchKernelGGL(gg::gg_swiglu_quantize_rows_kernel, dim3((unsigned)grid), dim3(gg::Q_THREADS), 0,
                      static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(H), static_cast<uint8_t*>(A), SA,
                      static_cast<uint16_t*>(act_out), (int)M_total, I, I / 128,
-                     (flags & GG_SA_KMAJOR) ? (int64_t)1 : (int64_t)(I / 128), (flags & GG_SA_KMAJOR) ? M_total : (int64_t)1);
+                     (flags & GG_SA_KMAJOR) ? (int64_t)1 : (int64_t)(I / 128), (flags & GG_SA_KMAJOR) ? M_total : (int64_t)1,
+                     by_xcd);
   return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
 }
 

@@ -97,8 +97,29 @@ __device__ __forceinline__ void quantize_block(const q_v4i raw, uint8_t* dst, fl
   if (sub == 0) *dst_scale = scale;
 }
 
-// A workgroup works on two rows at a time (r and r + gridDim.x): their 2 * KB blocks are numbered through and
+// A workgroup works on two adjacent rows at a time.  Pair t of workgroup b (t = 0, 1, ...):
+//   by_xcd = 0: pair number b + t * grid (pairs dealt out round-robin);
+//   by_xcd = 1 (grid a multiple of 8): the eight rows of a "sector" (8 adjacent rows: with K-block-major scales their
+//     eight 4-byte scale stores of one K block make up one 32-byte piece of memory) go to four workgroups in
+//     neighbouring slots of ONE XCD (workgroup b runs on XCD b % 8), which run at the same time, so the pieces leave
+//     that XCD's L2 as whole writes.  Dealt out round-robin they come from four XCDs, and each L2 writes a masked
+//     32-byte piece for its 8 bytes.
+// pair_of() returns the pair number, -1 when the workgroup is done, -2 for a pair to skip.  The 2 * KB blocks of a
+// pair are numbered through and
 // taken 32 per pass, so that short rows (KB <= 16) still fill both load slots of every lane.
+__device__ __forceinline__ int64_t pair_of(int64_t t, int64_t npairs, int by_xcd) {
+  const int64_t b = blockIdx.x, grid = gridDim.x;
+  if (!by_xcd) {
+    const int64_t p = b + t * grid;
+    return p < npairs ? p : -1;
+  }
+  const int64_t u = b / 8 + t * (grid / 8);          // position in this XCD's list of pairs: 4 per sector
+  const int64_t sector = (u / 4) * 8 + b % 8;
+  const int64_t p = sector * 4 + u % 4;
+  if (sector * 4 >= npairs) return -1;               // sectors only grow with t
+  return p < npairs ? p : -2;                        // a pair past the end inside the last sector
+}
+
 struct RowPairSlot {
   bool valid;     // this 16-lane group has a block in this pass
   int row, blk;
@@ -116,11 +137,17 @@ __global__ void __launch_bounds__(Q_THREADS) gg_quantize_rows_kernel(const uint1
                                                                      const int32_t* __restrict__ row_src,
                                                                      uint8_t* __restrict__ A, float* __restrict__ SA,
                                                                      int64_t T, int M_total, int K, int KB,
-                                                                     int64_t sa_rs, int64_t sa_ks) {   // SA[row * sa_rs + blk * sa_ks]
+                                                                     int64_t sa_rs, int64_t sa_ks,     // SA[row * sa_rs + blk * sa_ks]
+                                                                     int by_xcd) {
   const int grp = threadIdx.x >> 4, sub = threadIdx.x & 15;
-  for (int64_t r64 = blockIdx.x; r64 < M_total; r64 += 2 * (int64_t)gridDim.x) {
+  const int64_t npairs = ((int64_t)M_total + 1) / 2;
+  for (int64_t t = 0;; ++t) {
+    const int64_t pr = pair_of(t, npairs, by_xcd);
+    if (pr == -1) break;
+    if (pr < 0) continue;
+    const int64_t r64 = 2 * pr;
     const int r = (int)r64;
-    const int r2 = r64 + gridDim.x < M_total ? (int)(r64 + gridDim.x) : M_total;     // M_total = no second row
+    const int r2 = r64 + 1 < M_total ? (int)(r64 + 1) : M_total;     // M_total = no second row
     const int64_t s1 = row_src ? (int64_t)row_src[r] : (int64_t)r;
     const int64_t s2 = r2 < M_total ? (row_src ? (int64_t)row_src[r2] : (int64_t)r2) : -1;
     for (int v0 = 0; v0 < 2 * KB; v0 += 32) {
@@ -201,11 +228,17 @@ __global__ void __launch_bounds__(Q_THREADS) gg_swiglu_quantize_rows_kernel(cons
                                                                             uint8_t* __restrict__ A, float* __restrict__ SA,
                                                                             uint16_t* __restrict__ act_out,
                                                                             int M_total, int I, int IB,
-                                                                            int64_t sa_rs, int64_t sa_ks) {   // SA[row * sa_rs + blk * sa_ks]
+                                                                            int64_t sa_rs, int64_t sa_ks,     // SA[row * sa_rs + blk * sa_ks]
+                                                                            int by_xcd) {
   const int grp = threadIdx.x >> 4, sub = threadIdx.x & 15;
-  for (int64_t r64 = blockIdx.x; r64 < M_total; r64 += 2 * (int64_t)gridDim.x) {
+  const int64_t npairs = ((int64_t)M_total + 1) / 2;
+  for (int64_t t = 0;; ++t) {
+    const int64_t pr = pair_of(t, npairs, by_xcd);
+    if (pr == -1) break;
+    if (pr < 0) continue;
+    const int64_t r64 = 2 * pr;
     const int r = (int)r64;
-    const int r2 = r64 + gridDim.x < M_total ? (int)(r64 + gridDim.x) : M_total;
+    const int r2 = r64 + 1 < M_total ? (int)(r64 + 1) : M_total;
     for (int v0 = 0; v0 < 2 * IB; v0 += 32) {
       const RowPairSlot a = row_pair_slot(v0 + grp, IB, r, r2, M_total);
       const RowPairSlot b = row_pair_slot(v0 + 16 + grp, IB, r, r2, M_total);
