@@ -141,3 +141,34 @@ def test_fused_full_size_equals_the_two_calls_bitwise():
     assert_swiglu_act(u16(H[ridx]), act_s)
     A2o, S2o = orc.quantize_rows(act_s)
     assert np.array_equal(A2r.cpu().numpy()[rows], A2o) and np.array_equal(S2r.cpu().numpy()[rows].view(np.uint32), S2o.view(np.uint32))
+
+
+def test_fused_at_the_largest_weight_offsets():
+    """One expert with 2 * I * K = 2^30 bytes of weights (the entry point takes up to 2^31 - 1): the up rows start
+    2^29 bytes after the gate rows, the largest 32-bit scalar offset the kernel forms.  Raw bytes, few rows."""
+    rng = np.random.default_rng(5300)
+    M, inter, K = 40, 32768, 16384
+    KB, NB = K // 128, 2 * inter // 128
+    A = rng.integers(0, 256, (M, K), dtype=np.uint8)
+    A[(A & 0x7F) == 0x7F] = 0x35
+    A[(A & 0x78) > 0x58] &= 0xBF
+    B = torch.randint(0, 256, (1, 2 * inter, K), dtype=torch.uint8, generator=torch.Generator().manual_seed(5300))
+    B[(B & 0x7F) == 0x7F] = 0x35
+    B[(B & 0x78) > 0x50] &= 0xBF
+    SA = rng.uniform(0.25, 4.0, (M, KB)).astype(np.float32)
+    SB = rng.uniform(0.25, 4.0, (1, NB, KB)).astype(np.float32)
+    off = np.array([0, M], dtype=np.int32)
+    dA, dSA, dSB, doff = (torch.from_numpy(x).to(DEV) for x in (A, SA, SB, off))
+    dB = B.to(DEV)
+    H = gg.grouped_gemm(dA, dSA, dB, dSB, doff)
+    A2r, S2r, actr = gg.swiglu_quantize_rows(H, want_act=True)
+    A2, S2, act = gg.grouped_gemm_swiglu(dA, dSA, dB, dSB, doff, want_act=True)
+    torch.cuda.synchronize()
+    assert torch.equal(A2, A2r) and torch.equal(S2.view(torch.int32), S2r.view(torch.int32))
+    assert torch.equal(act.view(torch.int16), actr.view(torch.int16))
+    # the plain GEMM's H against the oracle on the columns at both ends of the two projections
+    cols = np.r_[0:128, inter - 128:inter + 128, 2 * inter - 128:2 * inter]
+    Bs = B[0, torch.from_numpy(cols)].numpy()[None]
+    blk = cols[::128] // 128                                           # the 128-column blocks these columns come from
+    ref = orc.grouped_gemm(A, SA, Bs, np.ascontiguousarray(SB[:, blk]), off, with_abs_sum=True)
+    assert_parity(u16(H[:, torch.from_numpy(cols).to(DEV)]), ref, empirical=False, what="H at the ends of gate and up")
