@@ -362,6 +362,7 @@ def test_full_size_configs_sampled_rows(name, max_groups, every):
     (3072, 8192, 4, 8192),
     (8192, 3072, 32, 8192),
     (5120, 6144, 16, 16384),
+    (7168, 4096, 32, 65536),
 ])
 def test_paper_grid_points_with_the_papers_size_generator(N, K, G, M):
     """Points of the paper's sweep grid (Sec. 3.1) with group sizes from its generator (App. C.1): sampled rows
@@ -398,6 +399,16 @@ def test_paper_grid_points_with_the_papers_size_generator(N, K, G, M):
     torch.cuda.synchronize()
     assert int(poff[-1].item()) == int(np.sum(128 * ((sizes + 127) // 128)))
     assert torch.equal(C.view(torch.int16), C2.view(torch.int16))
+    # the same two paths with the activation scales stored K-block-major (what the sweep times by default)
+    SAk = p["SA"].t().contiguous()
+    C3 = canary_C(M, N)
+    gg.grouped_gemm(p["A"], SAk, p["B"], p["SB"], p["group_offsets"], C=C3, sa_kmajor=True)
+    A_pad, SA_pad, poff = gg.pad(p["A"], SAk, p["group_offsets"], cap, sa_kmajor=True)
+    gg.grouped_gemm_padded(A_pad, SA_pad, p["B"], p["SB"], poff, C_pad, sa_kmajor=True)
+    C4 = canary_C(M, N)
+    gg.unpad(C_pad, p["group_offsets"], poff, M, C=C4)
+    torch.cuda.synchronize()
+    assert torch.equal(C.view(torch.int16), C3.view(torch.int16)) and torch.equal(C.view(torch.int16), C4.view(torch.int16))
 
 
 # ---------------------------------------------------------------------------------------------- binary16 output
