@@ -50,6 +50,37 @@ def clock_warmup(step, ms):
     return n
 
 
+def timed_region(step, steps):
+    """Exactly `steps` launches back to back between two synchronisations.  Returns (wall-clock ms per step, ms per
+    step between two HIP events recorded on the launch stream around the region): the second is the kernel's average
+    launch duration as the stream sees it, gaps between launches included."""
+    import torch
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()                    # HIP events on the stream the kernel is launched on (torch's current stream)
+    for i in range(steps):
+        step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def per_launch_ms(step, steps):
+    """The same launches again, each between its own pair of HIP events (untimed for the headline: the event pairs
+    keep consecutive launches apart and add a few microseconds each): for median, minimum and maximum."""
+    import numpy as np
+    import torch
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for i in range(steps):
+        ev[i][0].record()
+        step(i)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    return np.array([a.elapsed_time(b) for a, b in ev])
+
+
 def algorithmic_bytes(sizes, N, K):
     """A + SA + B (non-empty groups only) + SB + C, each touched once."""
     import numpy as np
@@ -118,18 +149,11 @@ def bench_quantize_rows(args, cfg, dev):
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        ev[i][0].record()
-        step(i)
-        ev[i][1].record()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    kern_ms = np.array([a.elapsed_time(b) for a, b in ev])
+    ms_per_step, kern_avg_ms = timed_region(step, args.steps)
+    kern_ms = per_launch_ms(step, args.steps)
     if args.copy_calibration:
         copy_calibration(dev)
-    achieved = alg_bytes / (float(kern_ms.mean()) * 1e-3) / 1e9
+    achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
     if km:
         traffic = (MEASURED_TRAFFIC_BYTES_SWIGLU if fused else MEASURED_TRAFFIC_BYTES_QUANT).get(args.workload)
     else:
@@ -147,7 +171,8 @@ def bench_quantize_rows(args, cfg, dev):
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "kernel": "gg_swiglu_quantize_rows_kernel" if fused else "gg_quantize_rows_kernel",
-                     "kernel_avg_ms": round(float(kern_ms.mean()), 4), "kernel_min_ms": round(float(kern_ms.min()), 4),
+                     "kernel_avg_ms": round(kern_avg_ms, 4), "kernel_median_ms": round(float(np.median(kern_ms)), 4),
+                     "kernel_min_ms": round(float(kern_ms.min()), 4),
                      "algorithmic_bytes": int(alg_bytes)},
     }
     if not args.no_cpu_baseline:
@@ -348,17 +373,8 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        ev[i][0].record()          # HIP events on the stream the kernel is launched on (torch's current stream)
-        step(i)
-        ev[i][1].record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-    kern_ms = np.array([a.elapsed_time(b) for a, b in ev])
-    kern_avg_ms = float(kern_ms.mean())
+    ms_per_step, kern_avg_ms = timed_region(step, args.steps)
+    kern_ms = per_launch_ms(step, args.steps)
 
     if args.copy_calibration:
         copy_calibration(dev)
@@ -385,15 +401,7 @@ def main():
             s["SA_row"] = s["SA"].t().contiguous()
         for i in range(args.warmup):
             step_row(i)
-        torch.cuda.synchronize()
-        ev_row = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-        t0 = time.perf_counter()
-        for i in range(args.steps):          # the same loop as the headline's, event pairs included
-            ev_row[i][0].record()
-            step_row(i)
-            ev_row[i][1].record()
-        torch.cuda.synchronize()
-        row_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        row_ms, _ = timed_region(step_row, args.steps)       # the same timed region as the headline's
         row_major = {"value": round(flops / (row_ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "ms_per_step": round(row_ms, 4)}
         for s in sets:
             del s["SA_row"]
