@@ -91,8 +91,8 @@ def algorithmic_bytes(sizes, N, K):
 
 
 # the same for the two row kernels (profiles/row_kernels_quantize_and_swiglu.md)
-MEASURED_TRAFFIC_BYTES_QUANT = {"gate_up": 179910152, "many_small": 722231880}
-MEASURED_TRAFFIC_BYTES_SWIGLU = {"gate_up": 84573272, "many_small": 338159576}
+MEASURED_TRAFFIC_BYTES_QUANT = {"gate_up": 179908976, "many_small": 722131561}
+MEASURED_TRAFFIC_BYTES_SWIGLU = {"gate_up": 84573778, "many_small": 338136982}
 # the same with the scales written row-major (--sa-layout row)
 MEASURED_TRAFFIC_BYTES_QUANT_ROW_MAJOR = {"gate_up": 178728308, "many_small": 714945956}
 MEASURED_TRAFFIC_BYTES_SWIGLU_ROW_MAJOR = {"gate_up": 84510332, "many_small": 337914328}
