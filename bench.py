@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0             # MI355X HBM3E
 # HBM bytes per launch of the GEMM kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/gemm_kernels_full_size_workloads.md gives the commands and the copy-kernel calibration:
 # FETCH_SIZE counts half of a plain copy's bytes, WRITE_SIZE all of them); None = not measured.
-MEASURED_TRAFFIC_BYTES = {"gate_up": 700812759, "down": 1028999271, "decode": 1547659413, "many_small": 8041009970}
+MEASURED_TRAFFIC_BYTES = {"gate_up": 700801429, "down": 1028754724, "decode": 1547376910, "many_small": 8037192685}
 # the same with the activation scales row-major (--sa-layout row)
 MEASURED_TRAFFIC_BYTES_ROW_MAJOR = {"gate_up": 713820344, "down": 1029977334, "decode": 1554026585, "many_small": 8045378172}
 
