@@ -21,7 +21,9 @@
  *  - Every data pointer is a DEVICE pointer owned by the caller.  The library
  *    never allocates, frees or synchronises (except gg_fp8_check_offsets) and
  *    keeps no state between calls; calls are asynchronous on `stream`
- *    (a hipStream_t passed as void*, NULL = the default stream).
+ *    (a hipStream_t passed as void*, NULL = the default stream).  Nothing but kernel launches is enqueued: the
+ *    calls may be recorded into a HIP graph by stream capture (after one ordinary call per kernel on the device,
+ *    which sets the kernel's shared-memory limit).
  *  - All matrices are row-major and dense (leading dimension = row length).
  *    A, B, C, A_pad, C_pad must be 16-byte aligned; SA, SB, offsets 4-byte.
  *  - N must be a positive multiple of 8 and K of 16 (16-byte stores and fetches; GG_ERR_UNSUPPORTED otherwise).
