@@ -273,6 +273,13 @@ def bench_expert_mlp(args, cfg, dev):
     if inter % 128 == 0 and K % 256 == 0 and K >= 512 and 2 * inter * K < 2 ** 31:
         t_fused = timed(fused_chain)
         fused_same = bool(torch.equal(y_free.view(torch.int16), Y.view(torch.int16)))
+    # the four-kernel padding-free chain recorded once into a HIP graph and replayed (the library only enqueues kernel
+    # launches, so stream capture takes it as it is): what is left of the host's launch cost
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        free_chain()
+    t_graph = timed(graph.replay)
+    graph_same = bool(torch.equal(y_free.view(torch.int16), Y.view(torch.int16)))
     t_pad = timed(pad_chain)
     same = bool(torch.equal(y_free.view(torch.int16), Y.view(torch.int16)))
     flops = 2.0 * M * N * K + 2.0 * M * K * inter
@@ -284,6 +291,7 @@ def bench_expert_mlp(args, cfg, dev):
         "config": {"workload": args.workload + " routing", "op": "expert_mlp", "G": G, "M_total": M, "hidden": K,
                    "intermediate": inter, "sa_layout": "K-block-major" if km else "row-major",
                    "clock_warmup_launches": n_ramp},
+        "graph_replay_ms": round(t_graph, 4), "graph_replay_output_bitwise_equal": graph_same,
         "fused_chain_ms": None if t_fused is None else round(t_fused, 4),
         "fused_chain_output_bitwise_equal": fused_same,
         "padded_chain_ms": round(t_pad, 4), "speedup_vs_padded_chain": round(t_pad / t_free, 4),
