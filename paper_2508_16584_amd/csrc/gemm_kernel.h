@@ -92,8 +92,8 @@ struct GemmArgs {
 };
 
 // Length in bytes of the view of SA that starts at the scale of (first row of a tile, K block 0).  The K-block part
-// of a scale's address travels in the scalar offset of the fetch, which the hardware takes off the length before
-// it compares the lane offset with it.  Row-major: rows_valid scale rows, so rows past the group's end read as
+// of a scale's address travels in the scalar offset of the fetch, which the range check adds to the lane offset
+// before it compares with the length.  Row-major: rows_valid scale rows, so rows past the group's end read as
 // zero.  K-block-major: everything up to the end of the tensor; a row past the group's end then reads some other
 // row's scale, which only ever meets that row's all-zero activations in an accumulator that is never stored.
 __device__ __forceinline__ int sa_view_bytes(const GemmArgs& a, int64_t grow, int rows_valid) {
@@ -289,7 +289,8 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
   };
   // bounded views: nothing past the last valid row of a tile is loaded or stored.
   // N not a multiple of the tile width: the weight rows, scale blocks and output columns past N do not exist
-  // (the row part of a weight fetch is in the lane offset, the only part the descriptor's bounds check sees)
+  // (the range check compares lane offset + scalar offset + access size with the view's length, so a view that
+  // ends after the last existing row refuses exactly the fetches past it)
   const int nb_all = RAGGED ? (N + 127) >> 7 : N >> 7;
   // on = false: a view of length zero, through which every fetch is dropped (same instruction count, no traffic)
   auto desc_a = [&](const Tile& t, bool on) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
