@@ -26,12 +26,27 @@ sys.path.insert(0, ROOT)
 FP8_MFMA_PEAK_TFLOPS = 5033.0     # MI355X dense FP8: 256 CU x 8192 flop/clk/CU x 2.4 GHz
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E
 
-# HBM bytes per launch of the GEMM kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/gemm_kernels_full_size_workloads.md gives the commands and the copy-kernel calibration:
-# FETCH_SIZE counts half of a plain copy's bytes, WRITE_SIZE all of them); None = not measured.
-MEASURED_TRAFFIC_BYTES = {"gate_up": 700801429, "down": 1028754724, "decode": 1547376910, "many_small": 8037192685}
-# the same with the activation scales row-major (--sa-layout row)
-MEASURED_TRAFFIC_BYTES_ROW_MAJOR = {"gate_up": 713820344, "down": 1029977334, "decode": 1554026585, "many_small": 8045378172}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+
+
+def profiled_traffic(op, workload, layout, kernel):
+    """HBM bytes per launch from the table under profiles/ that earlier rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+    this script wrote (each row: op, workload, scale layout, kernel, read bytes, written bytes, total; the file gives
+    the commands and the copy-kernel calibration).  It is NOT a measurement of the present run: the JSON line says so
+    in `traffic_source`, and a row is only used when it was taken with the same kernel variant.  None if there is
+    no such row."""
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            for line in f:
+                c = [x.strip().strip("`") for x in line.strip().strip("|").split("|")]
+                if len(c) >= 7 and c[0] == op and c[1] == workload and c[2] == layout and c[3] == kernel:
+                    return int(c[6])
+    except (OSError, ValueError):
+        pass
+    return None
+
+
+TRAFFIC_SOURCE = "profiles/hbm_traffic.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command on an earlier box, not this run"
 
 
 def clock_warmup(step, ms):
@@ -90,12 +105,6 @@ def algorithmic_bytes(sizes, N, K):
     return M * K + M * KB * 4 + nonempty * N * K + nonempty * NB * KB * 4 + M * N * 2
 
 
-# the same for the two row kernels (profiles/row_kernels_quantize_and_swiglu.md)
-MEASURED_TRAFFIC_BYTES_QUANT = {"gate_up": 179908976, "many_small": 722131561}
-MEASURED_TRAFFIC_BYTES_SWIGLU = {"gate_up": 84573778, "many_small": 338136982}
-# the same with the scales written row-major (--sa-layout row)
-MEASURED_TRAFFIC_BYTES_QUANT_ROW_MAJOR = {"gate_up": 178728308, "many_small": 714945956}
-MEASURED_TRAFFIC_BYTES_SWIGLU_ROW_MAJOR = {"gate_up": 84510332, "many_small": 337914328}
 
 
 def copy_calibration(dev):
@@ -154,10 +163,8 @@ def bench_quantize_rows(args, cfg, dev):
     if args.copy_calibration:
         copy_calibration(dev)
     achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
-    if km:
-        traffic = (MEASURED_TRAFFIC_BYTES_SWIGLU if fused else MEASURED_TRAFFIC_BYTES_QUANT).get(args.workload)
-    else:
-        traffic = (MEASURED_TRAFFIC_BYTES_SWIGLU_ROW_MAJOR if fused else MEASURED_TRAFFIC_BYTES_QUANT_ROW_MAJOR).get(args.workload)
+    kname = "gg_swiglu_quantize_rows_kernel" if fused else "gg_quantize_rows_kernel"
+    traffic = profiled_traffic(args.op, args.workload, args.sa_layout, kname)
     out = {
         "metric": "algorithmic GB/s, " + ("bf16 gate|up rows -> silu(gate)*up -> e4m3 + 1x128 scales" if fused else
                                           "bf16 rows -> e4m3 + 1x128 scales gathered into group order"),
@@ -170,7 +177,7 @@ def bench_quantize_rows(args, cfg, dev):
                    "sa_layout": "K-block-major [K/128, M_total]" if km else "row-major [M_total, K/128]"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "kernel": "gg_swiglu_quantize_rows_kernel" if fused else "gg_quantize_rows_kernel",
+                     "traffic_source": TRAFFIC_SOURCE if traffic is not None else None, "kernel": kname,
                      "kernel_avg_ms": round(kern_avg_ms, 4), "kernel_median_ms": round(float(np.median(kern_ms)), 4),
                      "kernel_min_ms": round(float(kern_ms.min()), 4),
                      "algorithmic_bytes": int(alg_bytes)},
@@ -317,14 +324,15 @@ def main():
                     help="untimed launches for about this long before the W warm-up steps, so that the timed steps run at "
                          "the GPU's sustained clock (0: none)")
     ap.add_argument("--variant", type=int, default=-1)
-    ap.add_argument("--sa-layout", choices=["kmajor", "row"], default="kmajor",
-                    help="storage order of the activation scales: [K/128, M_total] (GG_SA_KMAJOR, the default: the faster "
-                         "one, and what the row kernels write at no cost) or [M_total, K/128]")
+    ap.add_argument("--sa-layout", choices=["kmajor", "row"], default="row",
+                    help="storage order of the activation scales: row = [M_total, K/128], what the problem statement's "
+                         "call gg_fp8_grouped_gemm takes (the default and the headline); kmajor = [K/128, M_total] "
+                         "(GG_SA_KMAJOR of the _ex entry points: a few per cent faster, timed beside the headline)")
     ap.add_argument("--copies", type=int, default=0, help="input copies to rotate over (0 = enough for 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-pad-path", action="store_true")
-    ap.add_argument("--no-row-major-compare", action="store_true",
-                    help="skip the extra timed loop with row-major activation scales (grouped_gemm with --sa-layout kmajor)")
+    ap.add_argument("--no-other-layout", "--no-row-major-compare", dest="no_other_layout", action="store_true",
+                    help="skip the second timed loop with the other storage order of the activation scales")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -360,23 +368,33 @@ def main():
 
     km = args.sa_layout == "kmajor"
     # ---- input copies to rotate over (cold caches) ---------------------------------------------
+    # The headline is the call of the problem statement, gg_fp8_grouped_gemm, whose activation scales are row-major
+    # [M_total, K/128] (Table 1 / App. A); --sa-layout kmajor times gg_fp8_grouped_gemm_ex with GG_SA_KMAJOR instead.
+    # Whichever is not the headline is timed in a second loop of the same shape and reported beside it.
     per_set = alg_bytes
     copies = args.copies or max(2, min(8, int(np.ceil(1.0e9 / per_set))))
+    ws_bytes = gg.workspace_bytes(G, M, N, K)
     sets = []
     for i in range(copies):
         if i == 0:
             s = {k: p[k] for k in ("A", "SA", "B", "SB", "group_offsets")}
         else:
             s = {k: p[k].clone() for k in ("A", "SA", "B", "SB", "group_offsets")}
-        if km:
-            s["SA"] = p["SA"].t().contiguous()          # [K/128, M_total]; p["SA"] stays row-major for the oracle
+        s["SA_row"] = s.pop("SA")                          # [M_total, K/128]
+        s["SA_km"] = s["SA_row"].t().contiguous()          # [K/128, M_total]
         s["C"] = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
         sets.append(s)
+    ws = torch.zeros(max(ws_bytes, 1), dtype=torch.uint8, device=dev)
 
-    def step(i):
-        s = sets[i % copies]
-        gg.grouped_gemm(s["A"], s["SA"], s["B"], s["SB"], s["group_offsets"], C=s["C"], variant=args.variant, sa_kmajor=km)
+    def make_step(kmajor):
+        def step(i):
+            s = sets[i % copies]
+            gg.grouped_gemm(s["A"], s["SA_km" if kmajor else "SA_row"], s["B"], s["SB"],
+                            s["group_offsets"], C=s["C"], variant=args.variant, sa_kmajor=kmajor, workspace=ws)
+        return step
 
+    step = make_step(km)
+    torch.cuda.reset_peak_memory_stats()
     n_ramp = clock_warmup(step, args.clock_warmup_ms)
     for i in range(args.warmup):
         step(i)
@@ -399,20 +417,17 @@ def main():
     torch.cuda.synchronize()
     hot_ms = h0.elapsed_time(h1) / 20
 
-    # the same launches with the activation scales row-major ([M_total, K/128], what the plain entry points take)
-    row_major = None
-    if km and not args.no_row_major_compare:
-        def step_row(i):
-            s = sets[i % copies]
-            gg.grouped_gemm(s["A"], s["SA_row"], s["B"], s["SB"], s["group_offsets"], C=s["C"], variant=args.variant)
-        for s in sets:
-            s["SA_row"] = s["SA"].t().contiguous()
+    # the same launches with the other storage order of the activation scales
+    other = None
+    if not args.no_other_layout:
+        step_o = make_step(not km)
         for i in range(args.warmup):
-            step_row(i)
-        row_ms, _ = timed_region(step_row, args.steps)       # the same timed region as the headline's
-        row_major = {"value": round(flops / (row_ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "ms_per_step": round(row_ms, 4)}
-        for s in sets:
-            del s["SA_row"]
+            step_o(i)
+        o_ms, o_kern_ms = timed_region(step_o, args.steps)       # the same timed region as the headline's
+        other = {"entry_point": "gg_fp8_grouped_gemm_ex + GG_SA_KMAJOR" if not km else "gg_fp8_grouped_gemm",
+                 "value": round(flops / (o_ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "ms_per_step": round(o_ms, 4),
+                 "frac_of_fp8_mfma_peak": round(flops / (o_kern_ms * 1e-3) / 1e12 / FP8_MFMA_PEAK_TFLOPS, 4)}
+        step(0)                                             # C of set 0 is the headline layout's again (bitwise the same)
 
     value = flops / (ms_per_step * 1e-3) / 1e12
     if cfg.bound == "hbm":
@@ -423,9 +438,11 @@ def main():
         achieved = flops / (kern_avg_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": FP8_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / FP8_MFMA_PEAK_TFLOPS, 4)}
-    roof["traffic"] = (MEASURED_TRAFFIC_BYTES if km else MEASURED_TRAFFIC_BYTES_ROW_MAJOR).get(args.workload)
     used = args.variant if args.variant >= 0 else gg.auto_variant(p["G"], p["M_total"], p["N"], p["K"])
     vname = gg.variant_name(used)
+    roof["traffic"] = profiled_traffic("grouped_gemm", args.workload, args.sa_layout, vname)
+    roof["traffic_source"] = TRAFFIC_SOURCE if roof["traffic"] is not None else None
+    # the variant the library reports for these sizes (gg_fp8_auto_variant), or the one asked for
     roof["kernel"] = ("gg_gemm_rb_kernel<" if "-rb" in vname else "gg_gemm_kernel<") + vname + ">"
     roof["kernel_avg_ms"] = round(kern_avg_ms, 4)
     roof["kernel_median_ms"] = round(float(np.median(kern_ms)), 4)
@@ -442,23 +459,29 @@ def main():
                    "group_sizes": cfg.sizes, "rows_min": int(sizes.min()), "rows_max": int(sizes.max()),
                    "input_copies_rotated": copies, "variant": gg.variant_name(args.variant) or "auto",
                    "clock_warmup_launches": n_ramp,
-                   "sa_layout": "K-block-major [K/128, M_total] (GG_SA_KMAJOR)" if km else "row-major [M_total, K/128]"},
+                   "entry_point": "gg_fp8_grouped_gemm_ex + GG_SA_KMAJOR" if km else
+                                  ("gg_fp8_grouped_gemm" if args.variant < 0 else "gg_fp8_grouped_gemm_variant"),
+                   "sa_layout": "K-block-major [K/128, M_total] (GG_SA_KMAJOR)" if km else "row-major [M_total, K/128]",
+                   "workspace_bytes": int(ws_bytes)},
         "frac_of_fp8_mfma_peak": round(value / FP8_MFMA_PEAK_TFLOPS, 4),
         "hot_cache_ms": round(hot_ms, 4),
         "roofline": roof,
     }
-    if row_major:
-        out["sa_row_major"] = row_major
+    if other:
+        out["sa_kmajor" if not km else "sa_row_major"] = other
 
     # ---- pad-then-GEMM comparison path (Sec. 3) -------------------------------------------------
     if not args.no_pad_path:
         cap = gg.padded_rows_cap(G, M)
-        s0 = sets[0]
+        mem0 = torch.cuda.memory_allocated()
         A_pad = torch.empty((cap, K), dtype=torch.uint8, device=dev)
         SA_pad = torch.empty((K // 128, cap) if km else (cap, K // 128), dtype=torch.float32, device=dev)
         flags = 2 if km else 0                                   # GG_SA_KMAJOR
         poff = torch.empty(G + 1, dtype=torch.int32, device=dev)
         C_pad = torch.empty((cap, N), dtype=torch.bfloat16, device=dev)
+        ws_pad = torch.zeros(max(gg.workspace_bytes(G, cap, N, K), 1), dtype=torch.uint8, device=dev)
+        GG_PADDED_GROUPS = 4      # what gg_fp8_grouped_gemm_padded passes: every group is a multiple of 128 rows
+        pad_alloc = torch.cuda.memory_allocated() - mem0 - ws_pad.numel()
         lib = gg.load_library()
         import ctypes
         vp = lambda t: ctypes.c_void_p(t.data_ptr())
@@ -466,10 +489,10 @@ def main():
 
         def pad_step(i, with_unpad):
             s = sets[i % copies]
-            rc = lib.gg_fp8_pad_ex(vp(s["A"]), vp(s["SA"]), vp(s["group_offsets"]), vp(A_pad), vp(SA_pad), vp(poff),
+            rc = lib.gg_fp8_pad_ex(vp(s["A"]), vp(s["SA_km" if km else "SA_row"]), vp(s["group_offsets"]), vp(A_pad), vp(SA_pad), vp(poff),
                                    G, M, cap, K, stream, flags)
             rc |= lib.gg_fp8_grouped_gemm_ex(vp(A_pad), vp(SA_pad), vp(s["B"]), vp(s["SB"]), vp(poff), vp(C_pad),
-                                             G, cap, N, K, None, 0, stream, -1, flags)
+                                             G, cap, N, K, vp(ws_pad), ws_pad.numel(), stream, -1, flags | GG_PADDED_GROUPS)
             if with_unpad:
                 rc |= lib.gg_fp8_unpad(vp(C_pad), vp(s["group_offsets"]), vp(poff), vp(s["C"]), G, M, N, stream)
             assert rc == 0
@@ -496,6 +519,10 @@ def main():
             "mem_saving_row_tensors": round(1 - M / m_pad, 4),          # 1 - bytes(A,SA,C)/bytes(A_pad,SA_pad,C_pad)
             "peak_bytes_padding_free": int(M * row_bytes + weights),
             "peak_bytes_pad_path": int(M * (K + 4 * KB) + m_pad * row_bytes + weights),
+            # what the pad path's own buffers took in this run (torch's allocator, capacity M_pad_cap rows), next to
+            # the analytic figure for the same buffers
+            "pad_buffers_allocated_bytes": int(pad_alloc), "pad_buffers_analytic_bytes": int(cap * row_bytes + 4 * (G + 1)),
+            "padded_gemm_variant": gg.variant_name(gg.auto_variant_padded(G, cap, N, K)),
             "paper_context": "1.7%-20.4% speed-up, up to 23.8% memory reduction on H800 (abstract)",
         }
         del A_pad, SA_pad, C_pad
@@ -518,6 +545,13 @@ def main():
         ref = gg_oracle.grouped_gemm(A_s, SA_s, B_s, SB_s, off_s)
         cpu_s = time.perf_counter() - t0
         got = sets[0]["C"][ridx].cpu().view(torch.int16).numpy().view(np.uint16)
+        # the tolerance of the parity tests, asserted on this sample (the abs-sum S is a second, untimed oracle pass):
+        # |gpu - D| <= max(ulp, ulp/2 + 2^-10 S) for every element
+        S = gg_oracle.grouped_gemm(A_s, SA_s, B_s, SB_s, off_s, with_abs_sum=True)["S"]
+        err = np.abs(gg_oracle.f64_from_bf16_bits(got) - ref["D"])
+        ulp = gg_oracle.bf16_ulp(ref["D"])
+        bound = np.maximum(ulp, 0.5 * ulp + 2.0 ** -10 * S)
+        assert np.all(err <= bound), f"bench.py: {int(np.sum(err > bound))} sampled outputs outside the tolerance"
         threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         try:
             from threadpoolctl import threadpool_info
@@ -532,6 +566,9 @@ def main():
             "sample": f"first {per_group} rows of {len(groups)} groups ({len(rows)} rows x N={N} x K={K}), "
                       f"NumPy float64 oracle, {cpu_s:.1f} s",
             "gpu_bits_equal_oracle_on_sample": round(float(np.mean(got == ref["C"])), 5),
+            "tolerance_asserted": "|gpu - D| <= max(ulp_bf16(D), ulp_bf16(D)/2 + 2^-10 S) on every sampled output",
+            "max_err_ulp": round(float(np.max(err / ulp)), 3),
+            "outputs_that_needed_the_floor": int(np.sum(err > ulp)), "outputs_compared": int(err.size),
         }
 
     print(json.dumps(out))

@@ -67,7 +67,7 @@ struct RbCfg {
   static constexpr int T_A0 = 0;                   // A DMAs after MFMAs T_A0 .. T_A0 + A_ITERS - 1
   static constexpr int T_R0 = A_ITERS + 2;         // refill of the slot read at the top of the block
   static constexpr int T_MID = MFMAS / 2 + 2;      // wait for and read of the second fragment of the next block
-  static constexpr int T_R1 = T_MID + 4;           // refill of that slot
+  static constexpr int T_R1 = T_MID + 6 <= MFMAS ? T_MID + 4 : MFMAS - 2;   // refill of that slot
   // in flight across the top of a block: the 4 refill DMAs of the previous block
   static constexpr int W_TOP = 4;
   // in flight across the mid-block wait: the later refill of the previous block (2), this block's scale and A
@@ -75,7 +75,7 @@ struct RbCfg {
   static constexpr int W_MID = 2 + N_A + 2;
   static_assert(BM % 16 == 0 && BM <= 256 && AFR_ >= 2 && TM % AFR_ == 0, "BM a multiple of 16, fragment ring a divisor of BM/16");
   static_assert(SA_WAVES <= SB_WAVE, "scale fetchers must be distinct waves");
-  static_assert(T_R0 + 2 <= T_MID && T_R1 + 2 <= MFMAS && T_MID % TN == 0, "issue slots must fit the MFMA stream");
+  static_assert(T_R0 + 2 <= T_MID && T_R1 >= T_MID + 2 && T_R1 + 2 <= MFMAS && T_MID % TN == 0, "issue slots must fit the MFMA stream");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 

@@ -105,6 +105,9 @@ const Variant kVariants[] = {
     // ring of 4 activation fragments at 192 rows: 1 % faster than 2 there, no gain (and 249 VGPRs) at 256 rows
     {"192x256/1x8w/3s-rb", 192, 256, gg::RbCfg<192, 4, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<192, 4, false>>, nullptr, true},   // 14
     {"224x256/1x8w/3s-rb", 224, 256, gg::RbCfg<224, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<224, 2, false>>, nullptr, true},   // 15
+    {"128x256/1x8w/3s-rb", 128, 256, gg::RbCfg<128, 4, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<128, 4, false>>, nullptr, true},   // 16
+    {"160x256/1x8w/3s-rb", 160, 256, gg::RbCfg<160, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<160, 2, false>>, nullptr, true},   // 17
+    {"96x256/1x8w/3s-rb", 96, 256, gg::RbCfg<96, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<96, 2, false>>, nullptr, true},   // 18
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
