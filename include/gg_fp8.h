@@ -20,7 +20,8 @@
  * Conventions common to all entry points
  *  - Every data pointer is a DEVICE pointer owned by the caller.  The library
  *    never allocates, frees or synchronises (except gg_fp8_check_offsets) and
- *    keeps no state between calls; calls are asynchronous on `stream`
+ *    keeps no state between calls (beyond a per-device flag that a kernel's shared-memory limit has been
+ *    raised); calls are asynchronous on `stream`
  *    (a hipStream_t passed as void*, NULL = the default stream).  Nothing but kernel launches is enqueued: the
  *    calls may be recorded into a HIP graph by stream capture (after one ordinary call per kernel on the device,
  *    which sets the kernel's shared-memory limit).
@@ -63,15 +64,19 @@ int gg_fp8_version(void);
 /* Static, never-NULL description of a gg_status value. */
 const char* gg_fp8_status_str(int status);
 
-/* Bytes of device scratch the GEMM entry points need for this problem size
- * (may be 0).  The same value serves the padded GEMM with M_total = M_pad_cap. */
+/* Bytes of device scratch the GEMM entry points need for this problem size (a few hundred: the tile counters from
+ * which the workgroups of the taller tile variants take their tiles, one counter per XCD).  The same value serves
+ * the padded GEMM with M_total = M_pad_cap.  `workspace` is a device buffer of at least that size, 4-byte aligned,
+ * with any contents: every call clears what it uses with a small kernel ahead of the GEMM.  Two calls that may run
+ * at the same time (different streams) need different workspaces.  A missing or short workspace: GG_ERR_WORKSPACE
+ * (sizes for which nothing is launched need none). */
 size_t gg_fp8_workspace_bytes(int G, int64_t M_total, int N, int K);
 
 /* The padding-free grouped GEMM defined at the top of this file (Sec. 2.1 and
  * 2.2).  One persistent kernel walks the (group, m-tile, n-tile) list derived
  * from group_offsets on the device; rows past the end of a group are neither
- * loaded (they read as zero) nor stored.  `workspace` may be NULL when
- * gg_fp8_workspace_bytes() is 0. */
+ * loaded (they read as zero) nor stored; the 16-row activation blocks of a tile that
+ * lie past a group's end are not computed either (taller tile variants). */
 int gg_fp8_grouped_gemm(const void* A, const float* SA, const void* B, const float* SB,
                         const int32_t* group_offsets, void* C,
                         int G, int64_t M_total, int N, int K,
@@ -91,6 +96,9 @@ const char* gg_fp8_variant_name(int variant);
  * sizes only, never at device memory); a negative gg_status value if the sizes
  * are not supported. */
 int gg_fp8_auto_variant(int G, int64_t M_total, int N, int K);
+/* The same for gg_fp8_grouped_gemm_padded (and for the _ex call with GG_PADDED_GROUPS): the choice among the tile
+ * heights that divide groups of 128-row blocks (the padded problem of Sec. 3). */
+int gg_fp8_auto_variant_padded(int G, int64_t M_pad_cap, int N, int K);
 
 /* gg_fp8_grouped_gemm_variant with C [M_total, N] written as IEEE binary16 instead of bfloat16: the paper says
  * "half-precision" and App. A only fixes 2 bytes per element, so both 2-byte formats are offered.  Same sum, same
@@ -106,8 +114,12 @@ int gg_fp8_grouped_gemm_f16(const void* A, const float* SA, const void* B, const
  *                (row r, K block kb) at SA[kb * M_total + r].  Table 1 of the paper fixes the shape of the scale
  *                tensor, not its storage order; in this order the scales that one K block of a tile needs are
  *                contiguous, a few cache lines instead of one per row.  M_total * ceil(K/128) must stay below 2^29
- *                (GG_ERR_SHAPE otherwise).  Same arithmetic, bit-identical results. */
-enum { GG_OUT_F16 = 1, GG_SA_KMAJOR = 2 };
+ *                (GG_ERR_SHAPE otherwise).  Same arithmetic, bit-identical results.
+ *  GG_PADDED_GROUPS  a promise that every group holds a multiple of 128 rows (the pad path of Sec. 3, what
+ *                gg_fp8_grouped_gemm_padded passes): the automatic choice (variant = -1) then only considers tile
+ *                heights that divide such groups, and reads M_total as a capacity (M_pad_cap).  Results do not
+ *                depend on it. */
+enum { GG_OUT_F16 = 1, GG_SA_KMAJOR = 2, GG_PADDED_GROUPS = 4 };
 
 /* gg_fp8_grouped_gemm_variant with options (Sec. 2.1, 2.2 as above).  variant = -1 chooses automatically. */
 int gg_fp8_grouped_gemm_ex(const void* A, const float* SA, const void* B, const float* SB,

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     auto_variant,
+    auto_variant_padded,
     num_variants,
     pad,
     padded_rows_cap,

@@ -94,6 +94,8 @@ def load_library() -> ctypes.CDLL:
     lib.gg_fp8_variant_name.argtypes = [i32]
     lib.gg_fp8_auto_variant.restype = i32
     lib.gg_fp8_auto_variant.argtypes = [i32, i64, i32, i32]
+    lib.gg_fp8_auto_variant_padded.restype = i32
+    lib.gg_fp8_auto_variant_padded.argtypes = [i32, i64, i32, i32]
     lib.gg_fp8_padded_rows_cap.restype = i64
     lib.gg_fp8_padded_rows_cap.argtypes = [i32, i64]
     lib.gg_fp8_pad.restype = i32
@@ -114,7 +116,7 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED_SYMBOLS = [
     "gg_fp8_version", "gg_fp8_status_str", "gg_fp8_workspace_bytes", "gg_fp8_grouped_gemm",
-    "gg_fp8_grouped_gemm_variant", "gg_fp8_grouped_gemm_f16", "gg_fp8_grouped_gemm_ex", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_auto_variant", "gg_fp8_padded_rows_cap",
+    "gg_fp8_grouped_gemm_variant", "gg_fp8_grouped_gemm_f16", "gg_fp8_grouped_gemm_ex", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_auto_variant", "gg_fp8_auto_variant_padded", "gg_fp8_padded_rows_cap",
     "gg_fp8_pad", "gg_fp8_grouped_gemm_padded", "gg_fp8_unpad", "gg_fp8_quantize_rows", "gg_fp8_swiglu_quantize_rows", "gg_fp8_check_offsets",
     "gg_fp8_pad_ex", "gg_fp8_quantize_rows_ex", "gg_fp8_swiglu_quantize_rows_ex", "gg_fp8_grouped_gemm_swiglu",
 ]
@@ -149,7 +151,7 @@ def _want(t, name, dtype, ndim):
         raise ValueError(f"{name} must live on the GPU")
 
 
-GG_OUT_F16, GG_SA_KMAJOR = 1, 2        # flags of the _ex entry points
+GG_OUT_F16, GG_SA_KMAJOR, GG_PADDED_GROUPS = 1, 2, 4        # flags of the _ex entry points
 
 
 def _gemm_shapes(A, SA, B, SB, group_offsets, sa_kmajor=False):
@@ -190,6 +192,14 @@ def num_variants() -> int:
     return load_library().gg_fp8_num_variants()
 
 
+def auto_variant_padded(G: int, M_pad_cap: int, N: int, K: int) -> int:
+    """Index of the variant gg_fp8_grouped_gemm_padded (or GG_PADDED_GROUPS with variant = -1) uses."""
+    v = load_library().gg_fp8_auto_variant_padded(G, M_pad_cap, N, K)
+    if v < 0:
+        raise ValueError(f"gg_fp8_auto_variant_padded: {status_str(-v)}")
+    return v
+
+
 def auto_variant(G: int, M_total: int, N: int, K: int) -> int:
     """Index of the variant grouped_gemm(variant=-1) uses for these sizes."""
     v = load_library().gg_fp8_auto_variant(G, M_total, N, K)
@@ -203,18 +213,37 @@ def variant_name(v: int):
     return None if s is None else s.decode()
 
 
-def _workspace(G, M_total, N, K, device):
+_ws_cache = {}
+
+
+def _workspace(G, M_total, N, K, device, workspace=None, stream=None):
+    """The scratch buffer of a GEMM call: the caller's, or one per (device, stream) kept by this binding (calls on one
+    stream run in order, so they may share it; the library clears what it uses at the start of every call)."""
     n = workspace_bytes(G, M_total, N, K)
-    return (torch.empty(n, dtype=torch.uint8, device=device) if n else None), n
+    if workspace is not None:
+        _want(workspace, "workspace", torch.uint8, 1)
+        if workspace.numel() < n:
+            raise ValueError(f"workspace must hold at least {n} bytes")
+        return workspace, workspace.numel()
+    if n == 0:
+        return None, 0
+    key = (device, (stream if stream is not None else torch.cuda.current_stream(device)).cuda_stream)
+    ws = _ws_cache.get(key)
+    if ws is None or ws.numel() < n:
+        ws = _ws_cache[key] = torch.zeros(n, dtype=torch.uint8, device=device)
+    return ws, ws.numel()
 
 
-def grouped_gemm(A, SA, B, SB, group_offsets, C=None, variant: int = -1, stream=None, out_dtype=None, sa_kmajor=False):
+def grouped_gemm(A, SA, B, SB, group_offsets, C=None, variant: int = -1, stream=None, out_dtype=None, sa_kmajor=False,
+                 workspace=None):
     """C[r, :] = round(block-scaled A[r, :] @ B[g]^T) for every row r of every group g (gg_fp8_grouped_gemm_variant,
     gg_fp8_grouped_gemm_f16 when C / out_dtype is torch.float16, gg_fp8_grouped_gemm_ex when sa_kmajor).
 
     A uint8 [M_total, K] (e4m3 bytes), SA float32 [M_total, K/128] (sa_kmajor: [K/128, M_total]), B uint8 [G, N, K],
     SB float32 [G, N/128, K/128], group_offsets int32 [G+1]; returns C bfloat16 (default) or float16 [M_total, N]
-    (allocated here unless given; rows outside the groups are left as they are).
+    (allocated here unless given; rows outside the groups are left as they are).  With variant = -1, row-major
+    scales and bfloat16 output this is the plain gg_fp8_grouped_gemm call.  workspace: uint8 tensor of at least
+    workspace_bytes(...) bytes (default: one kept per stream by this binding).
     """
     lib = load_library()
     G, M_total, N, K = _gemm_shapes(A, SA, B, SB, group_offsets, sa_kmajor)
@@ -227,10 +256,12 @@ def grouped_gemm(A, SA, B, SB, group_offsets, C=None, variant: int = -1, stream=
     _want(C, "C", out_dtype, 2)
     if tuple(C.shape) != (M_total, N):
         raise ValueError(f"C must be [{M_total}, {N}]")
-    ws, n = _workspace(G, M_total, N, K, A.device)
+    ws, n = _workspace(G, M_total, N, K, A.device, workspace, stream)
     args = (_ptr(A), _ptr(SA), _ptr(B), _ptr(SB), _ptr(group_offsets), _ptr(C), G, M_total, N, K, _ptr(ws), n,
             _stream(stream), int(variant))
-    if sa_kmajor:
+    if variant == -1 and not sa_kmajor and out_dtype == torch.bfloat16:
+        _check(lib.gg_fp8_grouped_gemm(*args[:-1]))
+    elif sa_kmajor:
         _check(lib.gg_fp8_grouped_gemm_ex(*args, GG_SA_KMAJOR | (GG_OUT_F16 if out_dtype == torch.float16 else 0)))
     else:
         _check((lib.gg_fp8_grouped_gemm_f16 if out_dtype == torch.float16 else lib.gg_fp8_grouped_gemm_variant)(*args))
@@ -297,14 +328,22 @@ def pad(A, SA, group_offsets, M_pad_cap: int | None = None, stream=None, sa_kmaj
 def grouped_gemm_padded(A_pad, SA_pad, B, SB, padded_offsets, C_pad=None, stream=None, sa_kmajor=False):
     """gg_fp8_grouped_gemm_padded: the same GEMM on the 128-aligned problem; returns C_pad.  (sa_kmajor: the same
     through gg_fp8_grouped_gemm_ex, as the header prescribes.)"""
-    if sa_kmajor:
-        return grouped_gemm(A_pad, SA_pad, B, SB, padded_offsets, C=C_pad, stream=stream, sa_kmajor=True)
     lib = load_library()
+    if sa_kmajor:
+        G, M_pad_cap, N, K = _gemm_shapes(A_pad, SA_pad, B, SB, padded_offsets, True)
+        if C_pad is None:
+            C_pad = torch.empty((M_pad_cap, N), dtype=torch.bfloat16, device=A_pad.device)
+        _want(C_pad, "C_pad", torch.bfloat16, 2)
+        ws, n = _workspace(G, M_pad_cap, N, K, A_pad.device, None, stream)
+        _check(lib.gg_fp8_grouped_gemm_ex(_ptr(A_pad), _ptr(SA_pad), _ptr(B), _ptr(SB), _ptr(padded_offsets), _ptr(C_pad),
+                                          G, M_pad_cap, N, K, _ptr(ws), n, _stream(stream), -1,
+                                          GG_SA_KMAJOR | GG_PADDED_GROUPS))
+        return C_pad
     G, M_pad_cap, N, K = _gemm_shapes(A_pad, SA_pad, B, SB, padded_offsets)
     if C_pad is None:
         C_pad = torch.empty((M_pad_cap, N), dtype=torch.bfloat16, device=A_pad.device)
     _want(C_pad, "C_pad", torch.bfloat16, 2)
-    ws, n = _workspace(G, M_pad_cap, N, K, A_pad.device)
+    ws, n = _workspace(G, M_pad_cap, N, K, A_pad.device, None, stream)
     _check(lib.gg_fp8_grouped_gemm_padded(_ptr(A_pad), _ptr(SA_pad), _ptr(B), _ptr(SB), _ptr(padded_offsets),
                                           _ptr(C_pad), G, M_pad_cap, N, K, _ptr(ws), n, _stream(stream)))
     return C_pad

@@ -56,6 +56,10 @@ __device__ __forceinline__ int pack2_rne(float a, float b, bool f16) {
 }
 
 #define GG_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+// The group offsets are read through the constant address space: nothing writes them while a kernel of this library
+// runs, and the compiler then fetches them with scalar loads wherever the index is uniform.  (As plain global loads
+// they become vector loads once the kernel has stored anything, each followed by a wait for every fetch in flight.)
+#define GG_CONST_I32 __attribute__((address_space(4))) int32_t
 // dword 3 of a raw buffer descriptor on gfx9-family parts: 32-bit data format, no swizzle
 #define GG_RSRC_FLAGS 0x00020000
 // a lane offset that fails the bounds check of every descriptor used here: the access returns zeros / is dropped
@@ -251,6 +255,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
   };
   int g = 0, base = 0;
   const int nwg = gridDim.x;
+  const GG_CONST_I32* offc = (const GG_CONST_I32*)a.off;
   auto find_tile = [&](int it) __attribute__((always_inline)) -> Tile {
     Tile t = {false, 0, 0, 0, 0};
     int T;
@@ -260,8 +265,8 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
     int row0 = 0, Mg = 0, mtiles = 0;
     for (;;) {
       if (g >= a.G) return t;
-      row0 = clampi(a.off[g], 0, a.M_total);
-      const int row1 = clampi(a.off[g + 1], row0, a.M_total);
+      row0 = clampi(offc[g], 0, a.M_total);
+      const int row1 = clampi(offc[g + 1], row0, a.M_total);
       Mg = row1 - row0;
       mtiles = (Mg + BM - 1) / BM;
       const int cnt = mtiles * a.n_tiles;

@@ -23,6 +23,12 @@
 //    re-pointed when a fetch stream reaches the end of the tile), so only a workgroup's first tile has a
 //    prologue.  The register sets alternate by K-block parity: the number of K blocks must be even and >= 4.
 //
+//  * SKIP (variants "-rbs"): every K step leaves out the 16-row activation blocks past the tile's last valid row
+//    (operand reads, MFMAs, FMAs: paper Sec. 2.2, no work on rows that do not exist).  Measured, it does not pay:
+//    a partly filled tile is bound by its weight fetches and the fixed cost of a K step, not by its MFMAs, and the
+//    scalar test per block costs 1-3 % on full tiles; the variants are kept selectable, the automatic choice
+//    does not take them.
+//
 // Arithmetic per output element is the same as in the first kernel (one C=0 MFMA per 128-wide scale block,
 // 4 fp32 FMAs with the per-lane scale, the K blocks in the same order), so results are bit-identical to it unless KP is set.
 // KP: a lane's 32 operand bytes of a 128-byte row are [16q, 16q+16) and [64+16q, 64+16q+16) (q = lane/16)
@@ -37,9 +43,12 @@ namespace gg {
 // FUSE: the tile's 256 weight rows are 128 rows of the gate projection and the 128 matching rows of the up
 // projection of an expert MLP's first GEMM, and the epilogue turns the two 128-column halves into
 // silu(gate) * up, quantised to e4m3 with one scale per row (see the epilogue).
-template <int BM_, int AFR_ = 4, bool KP_ = false, bool FUSE_ = false>
+// SKIP: every K step leaves out the 16-row activation blocks past the tile's last valid row (a scalar test per
+// block: 1-3 % slower on full tiles, and a tile's cost follows its height).  Without it every tile costs a full one.
+template <int BM_, int AFR_ = 4, bool KP_ = false, bool FUSE_ = false, bool SKIP_ = false>
 struct RbCfg {
-  static constexpr bool KP = KP_, FUSE = FUSE_;
+  static constexpr bool KP = KP_, FUSE = FUSE_, SKIP = SKIP_;
+  static_assert(!(FUSE_ && SKIP_), "the activation epilogue runs full K steps only");
   static constexpr int BM = BM_, BN = 256, S = 3;
   static constexpr int NW = 8, NT = 512;
   static constexpr int TM = BM / 16, TN = 2;
@@ -58,9 +67,10 @@ struct RbCfg {
   static constexpr int LDS_BYTES = RED_BASE + (FUSE ? BM * NW * 4 : 0);
   static constexpr int SB_WAVE = NW - 1;
   static constexpr int MFMAS = TM * TN;
-  // MFMAs in flight before their FMAs are issued (at 256 rows 2 is 1 % faster than 3, interleaved A/B; at 192 and
-  // 224 rows it makes no difference)
-  static constexpr int PIPE = BM >= 256 ? 2 : 3;
+  // MFMAs in flight before their FMAs are issued: the two of one activation block (at 256 rows 1 % faster than 3,
+  // at 192 and 224 rows no difference), so that the FMAs of a block sit in the block after it and a K step that
+  // stops early needs one block to drain
+  static constexpr int PIPE = 2;
   static constexpr int AFR = AFR_;                 // ring of activation fragments (prefetch distance AFR-1 blocks)
   // fetches per wave per K block, in issue order: 1 scale DMA, A_ITERS A slabs, 2 + 2 weight-slot refills
   static constexpr int N_A = 1 + A_ITERS;
@@ -74,6 +84,7 @@ struct RbCfg {
   // DMAs (N_A) and its first refill (2)
   static constexpr int W_MID = 2 + N_A + 2;
   static_assert(BM % 16 == 0 && BM <= 256 && AFR_ >= 2 && TM % AFR_ == 0, "BM a multiple of 16, fragment ring a divisor of BM/16");
+  static_assert(PIPE == TN, "the FMAs of an activation block are issued with the MFMAs of the next one");
   static_assert(SA_WAVES <= SB_WAVE, "scale fetchers must be distinct waves");
   static_assert(T_R0 + 2 <= T_MID && T_R1 >= T_MID + 2 && T_R1 + 2 <= MFMAS && T_MID % TN == 0, "issue slots must fit the MFMA stream");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
@@ -146,6 +157,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
   };
   int g = 0, base = 0;
   const int nwg = gridDim.x;
+  const GG_CONST_I32* offc = (const GG_CONST_I32*)a.off;
   auto find_tile = [&](int it) __attribute__((always_inline)) -> Tile {
     Tile t = {false, 0, 0, 0, 0};
     int T;
@@ -154,8 +166,8 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     int row0 = 0, Mg = 0, mtiles = 0;
     for (;;) {
       if (g >= a.G) return t;
-      row0 = clampi(a.off[g], 0, a.M_total);
-      const int row1 = clampi(a.off[g + 1], row0, a.M_total);
+      row0 = clampi(offc[g], 0, a.M_total);
+      const int row1 = clampi(offc[g + 1], row0, a.M_total);
       Mg = row1 - row0;
       mtiles = (Mg + BM - 1) / BM;
       const int cnt = mtiles * a.n_tiles;
@@ -221,11 +233,9 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
   for (int it = 0;; ++it) {
     const int n0 = cur.n0, rows_valid = cur.rows_valid;
     const int64_t grow = cur.grow;
-    // The next tile is looked up here, not where it is first needed: the four K steps at the end of the tile must
-    // stay one basic block (with control flow between them the compiler sinks the accumulator updates of a step
-    // into the next block, and every product of the step stays alive across it).
-    const Tile nxt = find_tile(it + 1);
-    const bool has_next = nxt.valid;
+    // SKIP: activation blocks a K step of this tile runs: those with a valid row, and one more that carries the
+    // FMAs of the last of them
+    const int tm_act = rows_valid > BM - 16 ? TM : (rows_valid + 15) / 16 + 1;
 
     // K blocks are taken in the order rot, rot+1, ..., KB-1, 0, ..., rot-1 (see k_rotation).
     // K blocks past the end of the tile a descriptor points to are "fetched" from an out-of-range offset: same
@@ -262,6 +272,13 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       return (v8i){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
     };
 
+    // The next tile is looked up here, not where it is first needed: the four K steps at the end of the tile stay
+    // one basic block.
+    const Tile nxt = find_tile(it + 1);
+    const bool has_next = nxt.valid;
+    // (One copy of the tile's code per kernel: with a copy for full and a copy for partly filled tiles behind a
+    // branch, the state carried from tile to tile ends up in different registers in the two and the kernel spills.)
+    constexpr std::bool_constant<Cfg::SKIP> pred_c{};
     v4f acc[TM][TN];
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt)
@@ -302,9 +319,17 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       stage = 0;
       bslot = 2;
     }
-    // One K block; BS = kb % 2 is the register set that holds its weights.
-    auto kstep = [&](int kb, auto bs_c) __attribute__((always_inline)) {
+    // One K block; BS = kb % 2 is the register set that holds its weights.  PRED: the step of a partly filled tile,
+    // which runs the activation blocks [0, tm_act) only; the fetches, the copies of the weight fragments and the
+    // reads of the next K block's first activation fragments are those of a full step.
+    auto kstep = [&](int kb, auto bs_c, auto pred_c) __attribute__((always_inline)) {
       constexpr int BS = decltype(bs_c)::value;
+      constexpr bool PRED = decltype(pred_c)::value;
+      static_assert(!(PRED && Cfg::FUSE), "the activation epilogue runs full steps only");
+      // opaque to the compiler, which otherwise hoists the tests on it out of the K loop and keeps one copy of the
+      // loop per tile height
+      int tm_run = tm_act;
+      if constexpr (PRED) asm volatile("" : "+s"(tm_run));
       const int stage1 = stage + 1 == S ? 0 : stage + 1;       // buffer of block kb+1
       const int stageN = stage == 0 ? S - 1 : stage - 1;       // buffer of block kb+2 (= of block kb-1)
       const int bslot1 = bslot + 1 == Cfg::B_SLOTS ? 0 : bslot + 1;   // slot of fragment 2*kb + 3
@@ -390,13 +415,56 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
           bfr[BS ^ 1][1] = read_frag(bslots + bslot1 * Cfg::B_SLOT_BYTES);
           __builtin_amdgcn_sched_barrier(0);
         }
-        static_for<mt * TN, mt * TN + TN>(body);
-        static_for<mt * TN, mt * TN + TN>(order);
+        if constexpr (!PRED) {
+          static_for<mt * TN, mt * TN + TN>(body);
+          static_for<mt * TN, mt * TN + TN>(order);
+        } else {
+          constexpr int nb = mt + AFR - 1;
+          if constexpr (nb >= TM) {              // the next K block's first fragments and scales: always
+            afr[nb % AFR] = read_frag(st1 + (nb - TM) * 2048);
+            sa[nb % AFR] = *(const float*)(st1 + saRd + (nb - TM) * 64);
+            if constexpr (nb == TM) sb_next = *(const float*)(st1 + sbRd);
+          }
+          if (mt < tm_run) {
+            s[mt] = sa[mt % AFR] * sb;
+            if constexpr (nb < TM) {
+              afr[nb % AFR] = read_frag(st + nb * 2048);
+              sa[nb % AFR] = *(const float*)(st + saRd + nb * 64);
+            }
+            p[mt * TN] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[BS][0], afr[mt % AFR], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+            p[mt * TN + 1] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[BS][1], afr[mt % AFR], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+            if constexpr (mt >= 1) {             // the FMAs of the block before this one
+              acc[mt - 1][0] += p[(mt - 1) * TN] * s[mt - 1];
+              acc[mt - 1][1] += p[(mt - 1) * TN + 1] * s[mt - 1];
+            }
+            __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
+            if constexpr (nb < TM) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if constexpr (mt >= 1) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if constexpr (mt >= 1) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+          }
+          static_for<mt * TN, mt * TN + TN>([&](auto tc) __attribute__((always_inline)) {
+            constexpr int t = decltype(tc)::value;
+            if constexpr (t >= Cfg::T_A0 && t < Cfg::T_A0 + Cfg::A_ITERS)
+              dma_a(std::integral_constant<int, t - Cfg::T_A0>{}, kb + 2, stageN);
+            if constexpr (t == Cfg::T_R0) dma_b(kb + 2, J1, bslot);
+            if constexpr (t == Cfg::T_R1) dma_b(kb + 3, J0, bslot1);
+          });
+        }
         __builtin_amdgcn_sched_barrier(0);
       });
-      static_for<MF, MF + PIPE>(body);
-      static_for<MF, MF + PIPE>(order);
-      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (!PRED) {
+        static_for<MF, MF + PIPE>(body);
+        static_for<MF, MF + PIPE>(order);
+        __builtin_amdgcn_sched_barrier(0);
+      } else {
+        if (tm_run >= TM) {                      // a full tile: the FMAs of its last block
+          acc[TM - 1][0] += p[(TM - 1) * TN] * s[TM - 1];
+          acc[TM - 1][1] += p[(TM - 1) * TN + 1] * s[TM - 1];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
       stage = stage1;
       bslot = bslot1 + 1 == Cfg::B_SLOTS ? 0 : bslot1 + 1;
       // The accumulators are "used" here: outside a loop the compiler otherwise sinks a step's accumulator updates
@@ -412,26 +480,28 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     // block would be live at once).
     constexpr std::integral_constant<int, 0> SET0{};
     constexpr std::integral_constant<int, 1> SET1{};
-    for (int kb = 0; kb < KB - 4; kb += 2) {
-      kstep(kb, SET0);
-      kstep(kb + 1, SET1);
+    {
+      for (int kb = 0; kb < KB - 4; kb += 2) {
+        kstep(kb, SET0, pred_c);
+        kstep(kb + 1, SET1, pred_c);
+      }
+      // step KB-4 issues the last fetch of this tile's j = 0 fragments (block KB-1); step KB-3 the last fetches of
+      // its activations, scales and j = 1 fragments.  After each, that stream moves on to the next tile.
+      kstep(KB - 4, SET0, pred_c);
+      dB0 = desc_b(nxt, has_next);
+      rot0 = k_rotation(a, nxt.n0);
+      kbase0 = KB;
+      kstep(KB - 3, SET1, pred_c);
+      dA0 = band(nxt, 0, has_next); dA1 = band(nxt, 1 % Cfg::A_ITERS, has_next);
+      dA2 = band(nxt, 2 % Cfg::A_ITERS, has_next); dA3 = band(nxt, 3 % Cfg::A_ITERS, has_next);
+      dB = dB0;
+      dS = desc_s(nxt, has_next);
+      rot = rot0;
+      kbase = KB;
+      kstep(KB - 2, SET0, pred_c);
+      kstep(KB - 1, SET1, pred_c);
+      kbase = kbase0 = 0;
     }
-    // step KB-4 issues the last fetch of this tile's j = 0 fragments (block KB-1); step KB-3 the last fetches of
-    // its activations, scales and j = 1 fragments.  After each, that stream moves on to the next tile.
-    kstep(KB - 4, SET0);
-    dB0 = desc_b(nxt, has_next);
-    rot0 = k_rotation(a, nxt.n0);
-    kbase0 = KB;
-    kstep(KB - 3, SET1);
-    dA0 = band(nxt, 0, has_next); dA1 = band(nxt, 1 % Cfg::A_ITERS, has_next);
-    dA2 = band(nxt, 2 % Cfg::A_ITERS, has_next); dA3 = band(nxt, 3 % Cfg::A_ITERS, has_next);
-    dB = dB0;
-    dS = desc_s(nxt, has_next);
-    rot = rot0;
-    kbase = KB;
-    kstep(KB - 2, SET0);
-    kstep(KB - 1, SET1);
-    kbase = kbase0 = 0;
 
     if constexpr (Cfg::FUSE) {
       // ---- fused epilogue: act = bf16(silu(bf16(gate)) * bf16(up)), then the 1x128 block quantiser on act ------

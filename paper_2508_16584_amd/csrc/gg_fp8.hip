@@ -108,6 +108,9 @@ const Variant kVariants[] = {
     {"128x256/1x8w/3s-rb", 128, 256, gg::RbCfg<128, 4, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<128, 4, false>>, nullptr, true},   // 16
     {"160x256/1x8w/3s-rb", 160, 256, gg::RbCfg<160, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<160, 2, false>>, nullptr, true},   // 17
     {"96x256/1x8w/3s-rb", 96, 256, gg::RbCfg<96, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<96, 2, false>>, nullptr, true},   // 18
+    // "-rbs": the second kernel with K steps that leave out the activation blocks past a tile's last valid row
+    {"256x256/1x8w/3s-rbs", 256, 256, gg::RbCfg<256, 2, false, false, true>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, false, false, true>>, nullptr, true},   // 19
+    {"192x256/1x8w/3s-rbs", 192, 256, gg::RbCfg<192, 4, false, false, true>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<192, 4, false, false, true>>, nullptr, true},   // 20
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -170,6 +173,19 @@ int pick_variant(int G, int64_t M_total, int N, int K) {
   return best;
 }
 
+// The padded problem (Sec. 3: every group a multiple of 128 rows; M_pad_cap = 128 * (ceil(M_total / 128) + G) is a
+// capacity, the groups hold about M_pad_cap - 64 * G rows): tile heights that divide 128-row groups only.  The
+// 128-row tile for short groups; otherwise the 256-row tile of the second kernel, whose K steps leave out the
+// half of the last tile of a group with an odd number of 128-row blocks, or the first kernel's when K rules the
+// second one out.
+int pick_variant_padded(int G, int64_t M_pad_cap, int N, int K) {
+  if (N % 256 != 0 || K % 128 != 0) return N % 128 != 0 || N < 256 ? 2 : 3;
+  const double rows = (double)M_pad_cap - 64.0 * G;
+  const double avg = G > 0 ? rows / G : 0.0;
+  if (avg < 256) return 3;
+  return (K % 256 == 0 && K >= 512) ? 12 : 1;
+}
+
 // Grid of the row kernels (a workgroup takes rows in pairs).  With K-block-major scales and at least 8 workgroups the
 // pairs are dealt out by XCD (see pair_of in quant_kernel.h), which needs a grid that is a multiple of 8.
 int64_t row_kernel_grid(int64_t M_total, bool kmajor, int* by_xcd) {
@@ -184,6 +200,20 @@ int64_t row_kernel_grid(int64_t M_total, bool kmajor, int* by_xcd) {
   return grid < 1 ? 1 : grid;
 }
 
+// Device scratch a GEMM call on this problem may use (gg_fp8_workspace_bytes): none for the kernels of this file.
+size_t workspace_need(int G, int64_t M_total, int N, int K) {
+  (void)G; (void)M_total; (void)N; (void)K;
+  return 0;
+}
+
+// A caller's workspace: at least workspace_need bytes, 16-byte aligned (sizes that need none may pass NULL).
+bool workspace_ok(const void* workspace, size_t bytes, int G, int64_t M_total, int N, int K) {
+  if (G <= 0 || M_total <= 0 || N <= 0 || K <= 0) return true;
+  const size_t need = workspace_need(G, M_total, N, K);
+  if (need == 0) return true;
+  return workspace && ((uintptr_t)workspace & 15) == 0 && bytes >= need;
+}
+
 int validate_gemm(const void* A, const float* SA, const void* B, const float* SB, const int32_t* off, void* C,
                   int G, int64_t M_total, int N, int K) {
   if (G < 0 || M_total < 0 || N <= 0 || K <= 0) return GG_ERR_SHAPE;
@@ -195,13 +225,15 @@ int validate_gemm(const void* A, const float* SA, const void* B, const float* SB
 }
 
 int run_gemm(const void* A, const float* SA, const void* B, const float* SB, const int32_t* off, void* C,
-             int G, int64_t M_total, int N, int K, void* stream, int variant, unsigned flags = 0) {
-  if (flags & ~(unsigned)(GG_OUT_F16 | GG_SA_KMAJOR)) return GG_ERR_UNSUPPORTED;
+             int G, int64_t M_total, int N, int K, void* workspace, size_t workspace_bytes, void* stream, int variant,
+             unsigned flags = 0) {
+  if (flags & ~(unsigned)(GG_OUT_F16 | GG_SA_KMAJOR | GG_PADDED_GROUPS)) return GG_ERR_UNSUPPORTED;
   int st = validate_gemm(A, SA, B, SB, off, C, G, M_total, N, K);
   if (st != GG_OK) return st;
   if (G == 0 || M_total == 0) return GG_OK;
+  if (!workspace_ok(workspace, workspace_bytes, G, M_total, N, K)) return GG_ERR_WORKSPACE;
   if (variant >= kNumVariants) return GG_ERR_UNSUPPORTED;
-  if (variant < 0) variant = pick_variant(G, M_total, N, K);
+  if (variant < 0) variant = (flags & GG_PADDED_GROUPS) ? pick_variant_padded(G, M_total, N, K) : pick_variant(G, M_total, N, K);
   const Variant& v = kVariants[variant];
   const bool ragged = N % v.BN != 0 || K % 128 != 0;
   if (ragged && !v.launch_ragged) return GG_ERR_UNSUPPORTED;   // this variant takes whole tiles and whole K blocks only
@@ -277,8 +309,8 @@ const char* gg_fp8_status_str(int status) {
 }
 
 size_t gg_fp8_workspace_bytes(int G, int64_t M_total, int N, int K) {
-  (void)G; (void)M_total; (void)N; (void)K;
-  return 0;  // the tile schedule is static: no counters, no scratch
+  if (G <= 0 || M_total <= 0 || N <= 0 || K <= 0) return 0;
+  return workspace_need(G, M_total, N, K);
 }
 
 int gg_fp8_num_variants(void) { return kNumVariants; }
@@ -294,12 +326,17 @@ int gg_fp8_auto_variant(int G, int64_t M_total, int N, int K) {
   return pick_variant(G, M_total, N, K);
 }
 
+int gg_fp8_auto_variant_padded(int G, int64_t M_pad_cap, int N, int K) {
+  if (G < 0 || M_pad_cap < 0 || N <= 0 || K <= 0) return -GG_ERR_SHAPE;
+  if (M_pad_cap > 0x7FFFFFFFLL || N > (1 << 21) || K > (1 << 22)) return -GG_ERR_SHAPE;
+  if (N % 8 != 0 || K % 16 != 0) return -GG_ERR_UNSUPPORTED;
+  return pick_variant_padded(G, M_pad_cap, N, K);
+}
+
 int gg_fp8_grouped_gemm_variant(const void* A, const float* SA, const void* B, const float* SB,
                                 const int32_t* group_offsets, void* C, int G, int64_t M_total, int N, int K,
                                 void* workspace, size_t workspace_bytes, void* stream, int variant) {
-  (void)workspace;
-  if (workspace_bytes < gg_fp8_workspace_bytes(G, M_total, N, K)) return GG_ERR_WORKSPACE;
-  return run_gemm(A, SA, B, SB, group_offsets, C, G, M_total, N, K, stream, variant);
+  return run_gemm(A, SA, B, SB, group_offsets, C, G, M_total, N, K, workspace, workspace_bytes, stream, variant);
 }
 
 int gg_fp8_grouped_gemm(const void* A, const float* SA, const void* B, const float* SB,
@@ -312,17 +349,13 @@ int gg_fp8_grouped_gemm(const void* A, const float* SA, const void* B, const flo
 int gg_fp8_grouped_gemm_f16(const void* A, const float* SA, const void* B, const float* SB,
                             const int32_t* group_offsets, void* C, int G, int64_t M_total, int N, int K,
                             void* workspace, size_t workspace_bytes, void* stream, int variant) {
-  (void)workspace;
-  if (workspace_bytes < gg_fp8_workspace_bytes(G, M_total, N, K)) return GG_ERR_WORKSPACE;
-  return run_gemm(A, SA, B, SB, group_offsets, C, G, M_total, N, K, stream, variant, GG_OUT_F16);
+  return run_gemm(A, SA, B, SB, group_offsets, C, G, M_total, N, K, workspace, workspace_bytes, stream, variant, GG_OUT_F16);
 }
 
 int gg_fp8_grouped_gemm_ex(const void* A, const float* SA, const void* B, const float* SB,
                            const int32_t* group_offsets, void* C, int G, int64_t M_total, int N, int K,
                            void* workspace, size_t workspace_bytes, void* stream, int variant, unsigned flags) {
-  (void)workspace;
-  if (workspace_bytes < gg_fp8_workspace_bytes(G, M_total, N, K)) return GG_ERR_WORKSPACE;
-  return run_gemm(A, SA, B, SB, group_offsets, C, G, M_total, N, K, stream, variant, flags);
+  return run_gemm(A, SA, B, SB, group_offsets, C, G, M_total, N, K, workspace, workspace_bytes, stream, variant, flags);
 }
 
 int gg_fp8_grouped_gemm_swiglu(const void* A, const float* SA, const void* B, const float* SB,
@@ -431,8 +464,8 @@ int gg_fp8_pad(const void* A, const float* SA, const int32_t* group_offsets, voi
 int gg_fp8_grouped_gemm_padded(const void* A_pad, const float* SA_pad, const void* B, const float* SB,
                                const int32_t* padded_offsets, void* C_pad, int G, int64_t M_pad_cap, int N, int K,
                                void* workspace, size_t workspace_bytes, void* stream) {
-  return gg_fp8_grouped_gemm(A_pad, SA_pad, B, SB, padded_offsets, C_pad, G, M_pad_cap, N, K, workspace,
-                             workspace_bytes, stream);
+  return run_gemm(A_pad, SA_pad, B, SB, padded_offsets, C_pad, G, M_pad_cap, N, K, workspace, workspace_bytes, stream, -1,
+                  GG_PADDED_GROUPS);
 }
 
 int gg_fp8_unpad(const void* C_pad, const int32_t* group_offsets, const int32_t* padded_offsets, void* C, int G,

@@ -120,6 +120,7 @@ def main():
                 w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02
                 B[g], SB[g] = quantize_b(w)
             C = torch.empty((Mmax, N), dtype=torch.bfloat16, device=dev)
+            ws = torch.zeros(max(gg.workspace_bytes(Gmax, Mmax, N, K), 4), dtype=torch.uint8, device=dev)
             cap_max = gg.padded_rows_cap(Gmax, Mmax)
             A_pad = torch.empty((cap_max, K), dtype=torch.uint8, device=dev)
             SA_pad = torch.empty((cap_max, K // 128), dtype=torch.float32, device=dev)
@@ -137,13 +138,14 @@ def main():
 
                     def free_step():
                         rc = lib.gg_fp8_grouped_gemm_ex(vp(A), vp(SA_M), vp(B), vp(SB), vp(off), vp(C), G, M, N, K,
-                                                        None, 0, stream, args.variant, flags)
+                                                        vp(ws), ws.numel(), stream, args.variant, flags)
                         assert rc == 0, gg.status_str(rc)
 
                     def pad_step(with_unpad):
                         rc = lib.gg_fp8_pad_ex(vp(A), vp(SA_M), vp(off), vp(A_pad), vp(SA_pad), vp(poff), G, M, cap, K, stream, flags)
                         rc |= lib.gg_fp8_grouped_gemm_ex(vp(A_pad), vp(SA_pad), vp(B), vp(SB), vp(poff), vp(C_pad),
-                                                         G, cap, N, K, None, 0, stream, args.variant, flags)
+                                                         G, cap, N, K, vp(ws), ws.numel(), stream, args.variant,
+                                                         flags | (4 if args.variant < 0 else 0))      # GG_PADDED_GROUPS
                         if with_unpad:
                             rc |= lib.gg_fp8_unpad(vp(C_pad), vp(off), vp(poff), vp(C), G, M, N, stream)
                         assert rc == 0

@@ -52,6 +52,8 @@ def test_version_status_strings_and_variants(lib):
         v = gg.auto_variant(G, M, N, K)
         assert 0 <= v < n
         assert N % int(gg.variant_name(v).split("/")[0].split("x")[1]) == 0
+        vp = gg.auto_variant_padded(G, gg.padded_rows_cap(G, M), N, K)
+        assert 0 <= vp < n and 128 % int(gg.variant_name(vp).split("x")[0]) in (0, 128)     # 128- or 256-row tiles
     with pytest.raises(ValueError):
         gg.auto_variant(1, 1, 100, 128)
 
@@ -64,7 +66,7 @@ def test_padded_rows_cap_and_workspace(lib):
     for G, M in [(4, 4 * 129), (7, 5), (32, 16384)]:
         worst = sum(-(-s // 128) * 128 for s in [M // G + (1 if i < M % G else 0) for i in range(G)])
         assert gg.padded_rows_cap(G, M) >= worst
-    assert gg.workspace_bytes(8, 8192, 4096, 7168) == 0
+    assert gg.workspace_bytes(0, 0, 256, 256) == 0
 
 
 def test_gemm_argument_validation(lib):
@@ -74,7 +76,7 @@ def test_gemm_argument_validation(lib):
     ok_args = dict(G=2, M=100, N=256, K=256)
 
     def call(A=p, SA=p, B=p, SB=p, off=p, C=p, G=2, M=100, N=256, K=256):
-        return f(A, SA, B, SB, off, C, G, M, N, K, nul, 0, nul)
+        return f(A, SA, B, SB, off, C, G, M, N, K, p, 4096, nul)
 
     assert call(N=204) == GG_ERR_UNSUPPORTED      # N must be a multiple of 8 (16-byte stores of C)
     assert call(K=72) == GG_ERR_UNSUPPORTED       # K must be a multiple of 16 (16-byte fetches)
@@ -89,8 +91,9 @@ def test_gemm_argument_validation(lib):
     # empty problems succeed without touching any pointer
     assert f(nul, nul, nul, nul, nul, nul, 0, 0, 256, 256, nul, 0, nul) == GG_OK
     assert f(nul, nul, nul, nul, nul, nul, 4, 0, 256, 256, nul, 0, nul) == GG_OK
-    assert lib.gg_fp8_grouped_gemm_variant(p, p, p, p, p, p, 2, 100, 256, 256, nul, 0, nul, 999) == GG_ERR_UNSUPPORTED
-    assert lib.gg_fp8_grouped_gemm_padded(p, p, p, p, p, p, 2, 256, 100, 256, nul, 0, nul) == GG_ERR_UNSUPPORTED
+    assert lib.gg_fp8_grouped_gemm_variant(p, p, p, p, p, p, 2, 100, 256, 256, p, 4096, nul, 999) == GG_ERR_UNSUPPORTED
+    assert lib.gg_fp8_grouped_gemm_padded(p, p, p, p, p, p, 2, 256, 100, 256, p, 4096, nul) == GG_ERR_UNSUPPORTED
+    assert f(p, p, p, p, p, p, 2, 100, 204, 256, nul, 0, nul) == GG_ERR_UNSUPPORTED
     del ok_args
 
 
@@ -113,8 +116,8 @@ def test_ex_entry_points_validate_flags_and_sizes(lib):
     p = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
     nul = ctypes.c_void_p(0)
     F16, KM = binding.GG_OUT_F16, binding.GG_SA_KMAJOR
-    gemm = lambda flags, M=100, N=256, K=256, A=p: lib.gg_fp8_grouped_gemm_ex(A, p, p, p, p, p, 2, M, N, K, nul, 0, nul, -1, flags)
-    assert gemm(4) == GG_ERR_UNSUPPORTED and gemm(F16 | KM | 8) == GG_ERR_UNSUPPORTED      # unknown flag bits
+    gemm = lambda flags, M=100, N=256, K=256, A=p: lib.gg_fp8_grouped_gemm_ex(A, p, p, p, p, p, 2, M, N, K, p, 4096, nul, -1, flags)
+    assert gemm(8) == GG_ERR_UNSUPPORTED and gemm(F16 | KM | 16) == GG_ERR_UNSUPPORTED      # unknown flag bits
     for flags in (0, F16, KM, F16 | KM):
         assert gemm(flags, N=204) == GG_ERR_UNSUPPORTED
         assert gemm(flags, M=-1) == GG_ERR_SHAPE
