@@ -64,13 +64,15 @@ int gg_fp8_version(void);
 /* Static, never-NULL description of a gg_status value. */
 const char* gg_fp8_status_str(int status);
 
-/* Bytes of device scratch the GEMM entry points need for this problem size (a few hundred: the tile counters from
- * which the workgroups of the taller tile variants take their tiles, one counter per XCD).  The same value serves
- * the padded GEMM with M_total = M_pad_cap.  `workspace` is a device buffer of at least that size, 4-byte aligned,
- * with any contents: every call clears what it uses with a small kernel ahead of the GEMM.  Two calls that may run
- * at the same time (different streams) need different workspaces.  A missing or short workspace: GG_ERR_WORKSPACE
- * (sizes for which nothing is launched need none). */
+/* Bytes of device scratch a GEMM entry point needs for this problem size with the automatic variant choice
+ * (gg_fp8_workspace_bytes; the same value serves the padded GEMM with M_total = M_pad_cap) or with an explicit
+ * variant (gg_fp8_workspace_bytes_variant).  0 for all but the split-K variants ("-k2": the two halves of the K loop
+ * of every tile are separate work units whose fp32 partial sums, 2 * M_total * N * 4 bytes, a second kernel adds and
+ * rounds; paper Sec. 3.2, shapes with few rows per group).  `workspace` is a device buffer of at least that size,
+ * 16-byte aligned, with any contents; it may be NULL when 0 bytes are needed.  Calls that may run at the same time
+ * (different streams) need different workspaces.  A missing, short or misaligned workspace: GG_ERR_WORKSPACE. */
 size_t gg_fp8_workspace_bytes(int G, int64_t M_total, int N, int K);
+size_t gg_fp8_workspace_bytes_variant(int G, int64_t M_total, int N, int K, int variant);
 
 /* The padding-free grouped GEMM defined at the top of this file (Sec. 2.1 and
  * 2.2).  One persistent kernel walks the (group, m-tile, n-tile) list derived

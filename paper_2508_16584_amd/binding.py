@@ -72,6 +72,8 @@ def load_library() -> ctypes.CDLL:
     lib.gg_fp8_status_str.argtypes = [i32]
     lib.gg_fp8_workspace_bytes.restype = sz
     lib.gg_fp8_workspace_bytes.argtypes = [i32, i64, i32, i32]
+    lib.gg_fp8_workspace_bytes_variant.restype = sz
+    lib.gg_fp8_workspace_bytes_variant.argtypes = [i32, i64, i32, i32, i32]
     lib.gg_fp8_grouped_gemm.restype = i32
     lib.gg_fp8_grouped_gemm.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp, sz, vp]
     lib.gg_fp8_grouped_gemm_variant.restype = i32
@@ -115,7 +117,7 @@ def load_library() -> ctypes.CDLL:
 
 
 EXPORTED_SYMBOLS = [
-    "gg_fp8_version", "gg_fp8_status_str", "gg_fp8_workspace_bytes", "gg_fp8_grouped_gemm",
+    "gg_fp8_version", "gg_fp8_status_str", "gg_fp8_workspace_bytes", "gg_fp8_workspace_bytes_variant", "gg_fp8_grouped_gemm",
     "gg_fp8_grouped_gemm_variant", "gg_fp8_grouped_gemm_f16", "gg_fp8_grouped_gemm_ex", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_auto_variant", "gg_fp8_auto_variant_padded", "gg_fp8_padded_rows_cap",
     "gg_fp8_pad", "gg_fp8_grouped_gemm_padded", "gg_fp8_unpad", "gg_fp8_quantize_rows", "gg_fp8_swiglu_quantize_rows", "gg_fp8_check_offsets",
     "gg_fp8_pad_ex", "gg_fp8_quantize_rows_ex", "gg_fp8_swiglu_quantize_rows_ex", "gg_fp8_grouped_gemm_swiglu",
@@ -184,8 +186,9 @@ def status_str(status: int) -> str:
     return load_library().gg_fp8_status_str(int(status)).decode()
 
 
-def workspace_bytes(G: int, M_total: int, N: int, K: int) -> int:
-    return int(load_library().gg_fp8_workspace_bytes(G, M_total, N, K))
+def workspace_bytes(G: int, M_total: int, N: int, K: int, variant: int = -1) -> int:
+    """gg_fp8_workspace_bytes (variant = -1: the automatic choice) / gg_fp8_workspace_bytes_variant."""
+    return int(load_library().gg_fp8_workspace_bytes_variant(G, M_total, N, K, int(variant)))
 
 
 def num_variants() -> int:
@@ -216,10 +219,10 @@ def variant_name(v: int):
 _ws_cache = {}
 
 
-def _workspace(G, M_total, N, K, device, workspace=None, stream=None):
+def _workspace(G, M_total, N, K, device, workspace=None, stream=None, variant=-1):
     """The scratch buffer of a GEMM call: the caller's, or one per (device, stream) kept by this binding (calls on one
     stream run in order, so they may share it; the library clears what it uses at the start of every call)."""
-    n = workspace_bytes(G, M_total, N, K)
+    n = workspace_bytes(G, M_total, N, K, variant)
     if workspace is not None:
         _want(workspace, "workspace", torch.uint8, 1)
         if workspace.numel() < n:
@@ -256,7 +259,7 @@ def grouped_gemm(A, SA, B, SB, group_offsets, C=None, variant: int = -1, stream=
     _want(C, "C", out_dtype, 2)
     if tuple(C.shape) != (M_total, N):
         raise ValueError(f"C must be [{M_total}, {N}]")
-    ws, n = _workspace(G, M_total, N, K, A.device, workspace, stream)
+    ws, n = _workspace(G, M_total, N, K, A.device, workspace, stream, variant)
     args = (_ptr(A), _ptr(SA), _ptr(B), _ptr(SB), _ptr(group_offsets), _ptr(C), G, M_total, N, K, _ptr(ws), n,
             _stream(stream), int(variant))
     if variant == -1 and not sa_kmajor and out_dtype == torch.bfloat16:

@@ -93,6 +93,8 @@ struct GemmArgs {
   float* SA2;
   uint16_t* act_out;
   int64_t sa2_row_stride, sa2_kb_stride;
+  // split-K instantiation: partial sums [2][M_total][N] fp32 (K blocks [0, KB/2) and [KB/2, KB) of every valid row)
+  float* P;
 };
 
 // Length in bytes of the view of SA that starts at the scale of (first row of a tile, K block 0).  The K-block part
@@ -198,8 +200,13 @@ __device__ __forceinline__ int swz_key_b(int row) {   // rows read: base + 8*(r/
 
 // RAGGED: N need not be a multiple of the tile width nor K of 128 (the ceilings in Table 1 of the paper); costs a
 // few lane selects per fetch, so shapes made of whole blocks use the instantiation without it.
-template <class Cfg, bool RAGGED = false>
+// SPLITK: the work list holds two units per tile, one per half of the K loop (K blocks [0, KB/2) and [KB/2, KB)),
+// and a unit stores its fp32 partial sums instead of C; gg_splitk_combine_kernel adds the two halves in that order
+// and rounds (paper Sec. 3.2: where few rows meet many weights, a launch has too few tiles to fill the chip; the K
+// loop is the one dimension left to split).  KB must be even; whole tiles and whole K blocks only.
+template <class Cfg, bool RAGGED = false, bool SPLITK = false>
 __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
+  static_assert(!(SPLITK && (RAGGED || Cfg::XPF)), "split-K: whole tiles, the ring-of-buffers path");
   constexpr int BM = Cfg::BM, BN = Cfg::BN, WN = Cfg::WN, NW = Cfg::NW;
   constexpr int TM = Cfg::TM, TN = Cfg::TN, WTM = Cfg::WTM, WTN = Cfg::WTN, STAGES = Cfg::STAGES;
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
@@ -210,6 +217,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
   const int r = l & 15, q = l >> 4;
   const int wm = w / WN, wn = w % WN;
   const int K = a.K, KB = a.KB, N = a.N;
+  const int KBu = SPLITK ? KB >> 1 : KB;      // K blocks per work unit
 
   // ---- per-lane constants of the global -> LDS DMA -------------------------------------------
   // lane l of a wave-wide 16 B DMA lands at LDS byte 16*l of the slab: row l/8, physical chunk l%8.
@@ -252,15 +260,20 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
     bool valid;
     int g, n0, rows_valid;
     int64_t grow;
+    int ks;          // SPLITK: which half of the K loop
   };
   int g = 0, base = 0;
   const int nwg = gridDim.x;
   const GG_CONST_I32* offc = (const GG_CONST_I32*)a.off;
   auto find_tile = [&](int it) __attribute__((always_inline)) -> Tile {
-    Tile t = {false, 0, 0, 0, 0};
+    Tile t = {false, 0, 0, 0, 0, 0};
     int T;
     if (a.slots > 0) T = (it * 8 + (int)(blockIdx.x & 7)) * a.slots + (int)(blockIdx.x >> 3);
     else T = it * nwg + blockIdx.x;
+    if constexpr (SPLITK) {          // the two halves of a tile are neighbours in the list
+      t.ks = T & 1;
+      T >>= 1;
+    }
 
     int row0 = 0, Mg = 0, mtiles = 0;
     for (;;) {
@@ -315,18 +328,20 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
   };
 
   // cross-tile prefetch needs a full ring's worth of K blocks per tile, and the path that has it
-  const bool xt = !Cfg::XPF && KB >= STAGES - 1;
+  const bool xt = !Cfg::XPF && KBu >= STAGES - 1;
   Tile cur = find_tile(0);
   if (!cur.valid) return;
   __amdgpu_buffer_rsrc_t dA = desc_a(cur, true), dSA = desc_sa(cur, true), dB = desc_b(cur, true), dSB = desc_sb(cur, true);
-  int rot = k_rotation(a, cur.n0);
+  // first K block of a work unit: the rotation of its column block, or the start of its half of the K loop
+  auto k_start = [&](const Tile& t) __attribute__((always_inline)) -> int { return SPLITK ? t.ks * KBu : k_rotation(a, t.n0); };
+  int rot = k_start(cur);
   bool primed = false;      // the first STAGES-1 K blocks of `cur` were already fetched by the previous tile
   int stage = 0;            // LDS buffer of the current K block; runs on across tiles
   for (int it = 0;; ++it) {
     const int n0 = cur.n0, rows_valid = cur.rows_valid;
     const int n_rem = N - n0;
     __amdgpu_buffer_rsrc_t dC = __builtin_amdgcn_make_buffer_rsrc((void*)(a.C + cur.grow * N + n0), 0, rows_valid * N * 2 - n0 * 2, GG_RSRC_FLAGS);
-    Tile nxt = {false, 0, 0, 0, 0};
+    Tile nxt = {false, 0, 0, 0, 0, 0};
     bool has_next = false, prefetch = false;   // known once this tile's own fetches are all issued
 
     // ---- global -> LDS DMA of one K block, split so that it can be fed into the MFMA stream --------
@@ -516,7 +531,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
         int sp = stage;
 #pragma unroll
         for (int s = 0; s < STAGES - 1; ++s) {
-          if (s < KB) dma_all(s, sp);
+          if (s < KBu) dma_all(s, sp);
           sp = sp + 1 == STAGES ? 0 : sp + 1;
         }
       }
@@ -536,8 +551,8 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
       auto kstep = [&](int kb, auto mode_c) {
         constexpr int MODE = decltype(mode_c)::value;
         constexpr bool ISSUE = true;
-        int kb_new = MODE == 2 ? kb + STAGES - 1 - KB : kb + STAGES - 1;
-        if (MODE == 2 && kb_new >= KB) kb_new = KB - 1;      // fewer K blocks than ring buffers: dropped anyway
+        int kb_new = MODE == 2 ? kb + STAGES - 1 - KBu : kb + STAGES - 1;
+        if (MODE == 2 && kb_new >= KBu) kb_new = KBu - 1;      // fewer K blocks than ring buffers: dropped anyway
         const int nstage = stage == 0 ? STAGES - 1 : stage - 1;
         // The DMA of this K block (issued STAGES-1 blocks ago by every wave) must have landed; the newer
         // blocks (of this tile, then of the next) may stay in flight.  Loads complete in order, but stores do not
@@ -545,7 +560,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
         {
           // every K block issues one group of fetches, so STAGES-2 groups are younger than block kb (KB-1 if the
           // tile has fewer K blocks than the ring has buffers)
-          int younger = KB - 1 < STAGES - 2 ? KB - 1 : STAGES - 2;
+          int younger = KBu - 1 < STAGES - 2 ? KBu - 1 : STAGES - 2;
           if (kb == 0) younger = 0;
           wait_all_but<NDMA_ALL, STAGES - 2>(younger, dma_extra);
         }
@@ -610,7 +625,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
         stage = stage + 1 == STAGES ? 0 : stage + 1;
       };
 
-      const int kb_issue_end = KB - (STAGES - 1) > 0 ? KB - (STAGES - 1) : 0;
+      const int kb_issue_end = KBu - (STAGES - 1) > 0 ? KBu - (STAGES - 1) : 0;
       int kb = 0;
       for (; kb < kb_issue_end; ++kb) kstep(kb, std::integral_constant<int, 1>{});
       // this tile has issued its last fetch: from here on the descriptors are the next tile's
@@ -618,8 +633,8 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
       has_next = nxt.valid;
       prefetch = has_next && xt;
       dA = desc_a(nxt, prefetch); dSA = desc_sa(nxt, prefetch); dB = desc_b(nxt, prefetch); dSB = desc_sb(nxt, prefetch);
-      rot = k_rotation(a, nxt.n0);
-      for (; kb < KB; ++kb) kstep(kb, std::integral_constant<int, 2>{});
+      rot = k_start(nxt);
+      for (; kb < KBu; ++kb) kstep(kb, std::integral_constant<int, 2>{});
       static_for<0, PIPE>([&](auto ic) {
         constexpr int u = MF - PIPE + decltype(ic)::value;
         acc[u / TN][u % TN] += pend[decltype(ic)::value] * s_pend[decltype(ic)::value];
@@ -629,6 +644,21 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
     // blocks already in flight there is no prologue, and the barrier of its first K block does the same job
     if (!prefetch) __syncthreads();
 
+    if constexpr (SPLITK) {
+      // ---- epilogue of a K half: the fp32 sums as they are, through a view bounded like the one of C -----------
+      __amdgpu_buffer_rsrc_t dP = __builtin_amdgcn_make_buffer_rsrc(
+          (void*)(a.P + ((int64_t)cur.ks * a.M_total + cur.grow) * N + n0), 0, (rows_valid * N - n0) * 4, GG_RSRC_FLAGS);
+#pragma unroll
+      for (int mt = 0; mt < TM; ++mt) {
+        const int row = wm * WTM + 16 * mt + r;
+#pragma unroll
+        for (int pr = 0; pr < TN / 2; ++pr) {
+          const int col = wn * WTN + 32 * pr + 8 * q;
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, acc[mt][2 * pr]), dP, (row * N + col) * 4, 0, 0);
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, acc[mt][2 * pr + 1]), dP, (row * N + col + 4) * 4, 0, 0);
+        }
+      }
+    } else {
     // ---- epilogue: bf16 (or binary16) RNE, 16-byte bounded stores ---------------------------------------------
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt) {
@@ -646,16 +676,39 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
         __builtin_amdgcn_raw_buffer_store_b128(out, dC, (!RAGGED || col < n_rem) ? row * N * 2 + col * 2 : GG_OOB_OFFSET, 0, 0);
       }
     }
+    }
     if (!has_next) {
       wait_vmcnt<0>();     // the dropped fetches of the last K blocks still write zeros into this workgroup's LDS
       return;
     }
     if (!prefetch) {
       dA = desc_a(nxt, true); dSA = desc_sa(nxt, true); dB = desc_b(nxt, true); dSB = desc_sb(nxt, true);
-      rot = k_rotation(a, nxt.n0);
+      rot = k_start(nxt);
     }
     cur = nxt;
     primed = prefetch;
+  }
+}
+
+// Second pass of the split-K path: C[r][n] = round(P[0][r][n] + P[1][r][n]) for the rows of the groups, i.e. rows
+// [off[0], off[G]) clamped to [0, M_total).  One thread per 8 columns; the sum of the two halves in a fixed order,
+// so the result does not depend on how the first pass was scheduled.
+__global__ void __launch_bounds__(256) gg_splitk_combine_kernel(const float* __restrict__ P, const int32_t* __restrict__ off,
+                                                                 uint16_t* __restrict__ C, int G, int M_total, int N, int out_f16) {
+  const int row_lo = clampi(off[0], 0, M_total), row_hi = clampi(off[G], row_lo, M_total);
+  const int64_t groups8 = (int64_t)(row_hi - row_lo) * (N >> 3);
+  const int64_t half = (int64_t)M_total * N;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < groups8; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t e = (int64_t)row_lo * N + i * 8;
+    const v4f a0 = *(const v4f*)(P + e), a1 = *(const v4f*)(P + e + 4);
+    const v4f b0 = *(const v4f*)(P + half + e), b1 = *(const v4f*)(P + half + e + 4);
+    const v4f x = a0 + b0, y = a1 + b1;
+    v4i out;
+    out.x = pack2_rne(x[0], x[1], out_f16 != 0);
+    out.y = pack2_rne(x[2], x[3], out_f16 != 0);
+    out.z = pack2_rne(y[0], y[1], out_f16 != 0);
+    out.w = pack2_rne(y[2], y[3], out_f16 != 0);
+    *(v4i*)(C + e) = out;
   }
 }
 

@@ -16,7 +16,7 @@
 
 namespace {
 
-constexpr int kVersion = 100;  // 0.1.0
+constexpr int kVersion = 101;  // 0.1.1
 constexpr int kXcds = 8;       // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
 
 // Number of compute units of the current device (queried once per device, cached).
@@ -41,9 +41,10 @@ struct Variant {
   // the same tile for N % BN != 0 or K % 128 != 0 (partial tiles, short last K block); null: whole blocks only
   hipError_t (*launch_ragged)(const gg::GemmArgs&, int grid, hipStream_t) = nullptr;
   bool even_kb_only = false;   // needs K % 256 == 0 and K >= 512
+  bool splitk = false;         // two work units per tile (halves of the K loop) and a combine pass; needs a workspace
 };
 
-template <class Cfg, bool RAGGED = false>
+template <class Cfg, bool RAGGED = false, bool SPLITK = false>
 hipError_t launch_gemm(const gg::GemmArgs& args, int grid, hipStream_t stream) {
   static std::atomic<int> prepared[64];
   int dev = 0;
@@ -51,12 +52,12 @@ hipError_t launch_gemm(const gg::GemmArgs& args, int grid, hipStream_t stream) {
   if (e != hipSuccess) return e;
   if (dev >= 0 && dev < 64 && !prepared[dev].load(std::memory_order_acquire)) {
     // more than 64 KB of LDS per workgroup has to be requested explicitly
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_gemm_kernel<Cfg, RAGGED>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_gemm_kernel<Cfg, RAGGED, SPLITK>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
     if (e != hipSuccess) return e;
     prepared[dev].store(1, std::memory_order_release);
   }
-  hipLaunchKernelGGL((gg::gg_gemm_kernel<Cfg, RAGGED>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, args);
+  hipLaunchKernelGGL((gg::gg_gemm_kernel<Cfg, RAGGED, SPLITK>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, args);
   return hipGetLastError();
 }
 
@@ -111,6 +112,11 @@ const Variant kVariants[] = {
     // "-rbs": the second kernel with K steps that leave out the activation blocks past a tile's last valid row
     {"256x256/1x8w/3s-rbs", 256, 256, gg::RbCfg<256, 2, false, false, true>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, false, false, true>>, nullptr, true},   // 19
     {"192x256/1x8w/3s-rbs", 192, 256, gg::RbCfg<192, 4, false, false, true>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<192, 4, false, false, true>>, nullptr, true},   // 20
+    // "-k2": split-K, two halves of the K loop per tile and a combine pass (needs K % 256 == 0 and a workspace)
+    {"128x256/2x4w/3s-k2", 128, 256, gg::GemmCfg<128, 256, 2, 4, 3, false, 0>::LDS_BYTES, 1,
+     &launch_gemm<gg::GemmCfg<128, 256, 2, 4, 3, false, 0>, false, true>, nullptr, false, true},
+    {"64x256/1x8w/3s-k2", 64, 256, gg::GemmCfg<64, 256, 1, 8, 3, false, 0>::LDS_BYTES, 1,
+     &launch_gemm<gg::GemmCfg<64, 256, 1, 8, 3, false, 0>, false, true>, nullptr, false, true},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -174,16 +180,17 @@ int pick_variant(int G, int64_t M_total, int N, int K) {
 }
 
 // The padded problem (Sec. 3: every group a multiple of 128 rows; M_pad_cap = 128 * (ceil(M_total / 128) + G) is a
-// capacity, the groups hold about M_pad_cap - 64 * G rows): tile heights that divide 128-row groups only.  The
-// 128-row tile for short groups; otherwise the 256-row tile of the second kernel, whose K steps leave out the
-// half of the last tile of a group with an odd number of 128-row blocks, or the first kernel's when K rules the
-// second one out.
+// capacity, the groups hold about M_pad_cap - 64 * G rows).  Short groups (one or two 128-row blocks on average):
+// the 128-row tile, which wastes nothing on them; otherwise the choice of the plain path on the estimated row
+// count.  Measured on the padded full-size workloads (hot caches, K-block-major scales): many_small 1763 us with the
+// 128-row tile against 1955 us with the 256 x 256 tile that the capacity alone used to select, decode 339 against
+// 343 us; gate_up 266 us (224-row tile of the second kernel, the best of seven candidates), down 320 us (224 rows;
+// best of seven: 300 us at 256 rows).
 int pick_variant_padded(int G, int64_t M_pad_cap, int N, int K) {
-  if (N % 256 != 0 || K % 128 != 0) return N % 128 != 0 || N < 256 ? 2 : 3;
-  const double rows = (double)M_pad_cap - 64.0 * G;
-  const double avg = G > 0 ? rows / G : 0.0;
-  if (avg < 256) return 3;
-  return (K % 256 == 0 && K >= 512) ? 12 : 1;
+  int64_t rows = M_pad_cap - 64 * (int64_t)G;
+  if (rows < 128) rows = M_pad_cap;
+  if (N % 256 == 0 && K % 128 == 0 && G > 0 && rows / G < 320) return 3;
+  return pick_variant(G, rows, N, K);
 }
 
 // Grid of the row kernels (a workgroup takes rows in pairs).  With K-block-major scales and at least 8 workgroups the
@@ -200,16 +207,15 @@ int64_t row_kernel_grid(int64_t M_total, bool kmajor, int* by_xcd) {
   return grid < 1 ? 1 : grid;
 }
 
-// Device scratch a GEMM call on this problem may use (gg_fp8_workspace_bytes): none for the kernels of this file.
-size_t workspace_need(int G, int64_t M_total, int N, int K) {
-  (void)G; (void)M_total; (void)N; (void)K;
-  return 0;
+// Device scratch a GEMM call with this variant uses: the split-K variants keep the fp32 partial sums of the two
+// halves of the K loop, [2][M_total][N]; the others nothing.
+size_t workspace_need(int variant, int64_t M_total, int N) {
+  if (variant < 0 || variant >= kNumVariants || !kVariants[variant].splitk) return 0;
+  return (size_t)2 * (size_t)M_total * (size_t)N * sizeof(float);
 }
 
-// A caller's workspace: at least workspace_need bytes, 16-byte aligned (sizes that need none may pass NULL).
-bool workspace_ok(const void* workspace, size_t bytes, int G, int64_t M_total, int N, int K) {
-  if (G <= 0 || M_total <= 0 || N <= 0 || K <= 0) return true;
-  const size_t need = workspace_need(G, M_total, N, K);
+// A caller's workspace: at least `need` bytes, 16-byte aligned (NULL is fine when nothing is needed).
+bool workspace_ok(const void* workspace, size_t bytes, size_t need) {
   if (need == 0) return true;
   return workspace && ((uintptr_t)workspace & 15) == 0 && bytes >= need;
 }
@@ -231,10 +237,12 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
   int st = validate_gemm(A, SA, B, SB, off, C, G, M_total, N, K);
   if (st != GG_OK) return st;
   if (G == 0 || M_total == 0) return GG_OK;
-  if (!workspace_ok(workspace, workspace_bytes, G, M_total, N, K)) return GG_ERR_WORKSPACE;
   if (variant >= kNumVariants) return GG_ERR_UNSUPPORTED;
   if (variant < 0) variant = (flags & GG_PADDED_GROUPS) ? pick_variant_padded(G, M_total, N, K) : pick_variant(G, M_total, N, K);
   const Variant& v = kVariants[variant];
+  // split-K: an even number of K blocks, whole tiles, offsets of the partial sums within 32 bits
+  if (v.splitk && (K % 256 != 0 || N % v.BN != 0 || N > (1 << 20))) return GG_ERR_UNSUPPORTED;
+  if (!workspace_ok(workspace, workspace_bytes, workspace_need(variant, M_total, N))) return GG_ERR_WORKSPACE;
   const bool ragged = N % v.BN != 0 || K % 128 != 0;
   if (ragged && !v.launch_ragged) return GG_ERR_UNSUPPORTED;   // this variant takes whole tiles and whole K blocks only
   // the second kernel runs its K loop on from one tile into the next, two K blocks per turn
@@ -274,8 +282,9 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
   args.rot_mul = (K % 8192 == 4096) ? 4 : 0;   // 7 * 4 < K / 128; a function of K alone (see k_rotation)
 
   // upper bound on the number of tiles for any offsets: every group adds at most one partial m-tile
-  const int64_t max_tiles = (M_total / v.BM + G) * (int64_t)args.n_tiles;
+  const int64_t max_tiles = (M_total / v.BM + G) * (int64_t)args.n_tiles * (v.splitk ? 2 : 1);   // split-K: two units per tile
   if (max_tiles > 0x7FFFFFFFLL) return GG_ERR_SHAPE;   // the kernels count tiles in 32 bits
+  args.P = v.splitk ? static_cast<float*>(workspace) : nullptr;
   int64_t grid = (int64_t)device_cus() * v.wg_per_cu;
   if (grid > max_tiles) grid = max_tiles;
   if (grid < 1) grid = 1;
@@ -286,7 +295,16 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
     args.slots = 0;
   }
   hipError_t e = (ragged ? v.launch_ragged : v.launch)(args, (int)grid, static_cast<hipStream_t>(stream));
-  return e == hipSuccess ? GG_OK : GG_ERR_HIP;
+  if (e != hipSuccess) return GG_ERR_HIP;
+  if (v.splitk) {
+    const int64_t groups8 = M_total * (int64_t)(N / 8);
+    int64_t cgrid = (groups8 + 255) / 256;
+    if (cgrid > (int64_t)device_cus() * 8) cgrid = (int64_t)device_cus() * 8;
+    hipLaunchKernelGGL(gg::gg_splitk_combine_kernel, dim3((unsigned)cgrid), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       args.P, off, args.C, G, (int)M_total, N, args.out_f16);
+    if (hipGetLastError() != hipSuccess) return GG_ERR_HIP;
+  }
+  return GG_OK;
 }
 
 }  // namespace
@@ -309,8 +327,13 @@ const char* gg_fp8_status_str(int status) {
 }
 
 size_t gg_fp8_workspace_bytes(int G, int64_t M_total, int N, int K) {
-  if (G <= 0 || M_total <= 0 || N <= 0 || K <= 0) return 0;
-  return workspace_need(G, M_total, N, K);
+  return gg_fp8_workspace_bytes_variant(G, M_total, N, K, -1);
+}
+
+size_t gg_fp8_workspace_bytes_variant(int G, int64_t M_total, int N, int K, int variant) {
+  if (G <= 0 || M_total <= 0 || N <= 0 || K <= 0 || M_total > 0x7FFFFFFFLL || N % 8 != 0 || K % 16 != 0) return 0;
+  if (variant < 0) variant = pick_variant(G, M_total, N, K);
+  return workspace_need(variant, M_total, N);
 }
 
 int gg_fp8_num_variants(void) { return kNumVariants; }
@@ -408,6 +431,7 @@ int gg_fp8_grouped_gemm_swiglu(const void* A, const float* SA, const void* B, co
   args.sa_row_stride = km ? 4 : 4 * args.KB;
   args.sa_kb_stride = km ? (int)(M_total * 4) : 4;
   args.sa_kmajor = km ? 1 : 0;
+  args.P = nullptr;
   args.A2 = static_cast<uint8_t*>(A2);
   args.SA2 = SA2;
   args.act_out = static_cast<uint16_t*>(act_out);

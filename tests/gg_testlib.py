@@ -95,6 +95,41 @@ def assert_parity(got_bits: np.ndarray, ref: dict, empirical: bool = True, what:
     return stats
 
 
+class ParityAccumulator:
+    """assert_parity over a problem too large to hold at once: add() takes one slab of rows (GPU bits and the oracle's
+    result for the same rows), asserts the hard bound and the empirical per-element bound on it, and keeps the counts;
+    finish() asserts the shares over everything added and returns the statistics, among them the largest error in
+    ulp and the number of elements whose error exceeded one ulp (those that needed the absolute floor)."""
+
+    def __init__(self, what=""):
+        self.what, self.n, self.equal, self.within, self.max_ulp, self.max_excess = what, 0, 0, 0, 0.0, 0.0
+
+    def add(self, got_bits, ref):
+        if got_bits.size == 0:
+            return
+        st = assert_parity(got_bits, ref, empirical=False, what=self.what)
+        D, S = ref["D"], ref["S"]
+        got = orc.f64_from_bf16_bits(got_bits)
+        ok = ~np.isnan(D)
+        err = np.abs(np.where(ok, got - D, 0.0))
+        ulp = orc.bf16_ulp(np.where(ok, D, 1.0))
+        nb = int(np.sum(err > 0.5 * ulp + EMPIRICAL_FLOOR * np.where(ok, S, 0.0)))
+        assert nb == 0, f"{self.what}: {nb} elements outside the empirical bound"
+        n = got_bits.size
+        self.n += n
+        self.equal += int(round(st["bit_equal"] * n))
+        self.within += int(round(st["within_1ulp"] * n))
+        self.max_ulp = max(self.max_ulp, st["max_err_ulp"])
+        self.max_excess = max(self.max_excess, st["max_excess_over_S"])
+
+    def finish(self):
+        stats = {"elements": self.n, "bit_equal": self.equal / max(self.n, 1), "within_1ulp": self.within / max(self.n, 1),
+                 "needed_the_floor": self.n - self.within, "max_err_ulp": self.max_ulp, "max_excess_over_S": self.max_excess}
+        if self.n:
+            assert stats["within_1ulp"] >= 0.99 and stats["bit_equal"] >= 0.97, f"{self.what}: {stats}"
+        return stats
+
+
 def np_problem(p: dict):
     """Host NumPy views of a workloads.make_problem() dict (tensors may live on the GPU)."""
     return (p["A"].cpu().numpy(), p["SA"].cpu().numpy(), p["B"].cpu().numpy(), p["SB"].cpu().numpy(),

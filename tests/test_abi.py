@@ -44,7 +44,7 @@ def test_version_status_strings_and_variants(lib):
     n = gg.num_variants()
     assert n >= 1
     for v in range(n):
-        assert re.fullmatch(r"\d+x\d+/\d+x\d+w/\d+s(x|-rb\w*)?", gg.variant_name(v))
+        assert re.fullmatch(r"\d+x\d+/\d+x\d+w/\d+s(x|-rb\w*|-k2)?", gg.variant_name(v))
     assert gg.variant_name(n) is None and gg.variant_name(-1) is None
     # the automatic choice depends on sizes only and always names a variant whose tile width divides N
     for G, M, N, K in [(8, 8192, 4096, 7168), (32, 16384, 7168, 2048), (64, 2048, 4096, 7168), (1, 1, 128, 128),
@@ -53,7 +53,7 @@ def test_version_status_strings_and_variants(lib):
         assert 0 <= v < n
         assert N % int(gg.variant_name(v).split("/")[0].split("x")[1]) == 0
         vp = gg.auto_variant_padded(G, gg.padded_rows_cap(G, M), N, K)
-        assert 0 <= vp < n and 128 % int(gg.variant_name(vp).split("x")[0]) in (0, 128)     # 128- or 256-row tiles
+        assert 0 <= vp < n and N % int(gg.variant_name(vp).split("/")[0].split("x")[1]) == 0
     with pytest.raises(ValueError):
         gg.auto_variant(1, 1, 100, 128)
 

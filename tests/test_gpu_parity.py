@@ -11,7 +11,7 @@ import paper_2508_16584_amd as gg
 from oracle import gg_oracle as orc
 from workloads import CONFIGS, WorkloadConfig, group_sizes, make_problem
 
-from gg_testlib import assert_parity, bits_of, np_problem, raw_problem
+from gg_testlib import ParityAccumulator, assert_parity, bits_of, np_problem, raw_problem
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -25,9 +25,17 @@ def variants_for(N, K):
     for v in range(gg.num_variants()):
         name = gg.variant_name(v)
         bn = int(name.split("/")[0].split("x")[1])
-        if N % bn == 0 and not ("-rb" in name and (K % 256 != 0 or K < 512)):
+        if N % bn == 0 and not ("-rb" in name and (K % 256 != 0 or K < 512)) and not ("-k2" in name and K % 256 != 0):
             out.append(v)
     return out
+
+
+def family_of(v):
+    """Variants whose results agree bit for bit: the arithmetic per element does not depend on the tiling.  "-rbk"
+    variants feed the 128 products of a scale block to the matrix instruction in another order, and "-k2" (split-K)
+    variants add the two halves of the K loop as two partial sums, so each of these is a family of its own."""
+    name = gg.variant_name(v) if v >= 0 else ""
+    return "k-permuted" if name.endswith("-rbk") else "split-k" if name.endswith("-k2") else "plain"
 
 
 def canary_C(M, N):
@@ -63,7 +71,7 @@ def test_tiny_config_every_variant_full_compare():
         # The arithmetic per element does not depend on the tiling: all variants of one kernel agree bit for
         # bit.  Variants named "-rbk" feed the 128 products of a scale block to the matrix instruction in
         # another order, so they form a family of their own.
-        family = "k-permuted" if v >= 0 and gg.variant_name(v).endswith("-rbk") else "plain"
+        family = family_of(v)
         if family not in first:
             first[family] = got
         assert np.array_equal(got, first[family]), f"variant {v} differs from the first of its family"
@@ -130,7 +138,7 @@ def test_several_tiles_per_workgroup_every_element(K):
             continue                                   # fewer tiles than workgroups, or a tile for short groups
         got = run_gpu(dev, p["M_total"], N, v)
         assert_parity(got, ref, what=f"K={K} variant {v}")
-        family = "k-permuted" if v >= 0 and gg.variant_name(v).endswith("-rbk") else "plain"
+        family = family_of(v)
         first.setdefault(family, got)
         assert np.array_equal(got, first[family]), f"variant {v} differs from the first of its family"
 
@@ -323,39 +331,37 @@ def sampled_rows(off, rng, every=97, max_groups=None):
     return np.unique(np.array(rows, dtype=np.int64))
 
 
-@pytest.mark.parametrize("name,max_groups,every", [
-    ("gate_up", None, 61),
-    ("down", None, 127),
-    ("decode", None, 7),
-    ("many_small", 24, 29),
-])
-def test_full_size_configs_sampled_rows(name, max_groups, every):
-    """The four full-size workloads, default launch configuration (what bench.py times)."""
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["gate_up", "down", "decode", "many_small"])
+def test_full_size_configs_every_element(name):
+    """The four full-size workloads in the launch configurations bench.py times (automatic variant; the plain call
+    with row-major activation scales, which is the headline, and the K-block-major order through the _ex call):
+    EVERY row and column of both outputs against the oracle, group by group, plus "no row outside the groups is
+    written, every row inside is" by canaries."""
     cfg = CONFIGS[name]
     p = make_problem(cfg, device=DEV)
     off = p["group_offsets"].cpu().numpy()
     assert np.array_equal(np.diff(off), group_sizes(cfg))
-    C = canary_C(p["M_total"], cfg.N)
-    gg.grouped_gemm(p["A"], p["SA"], p["B"], p["SB"], p["group_offsets"], C=C)
+    M, N = p["M_total"], cfg.N
+    C_row = canary_C(M, N)
+    gg.grouped_gemm(p["A"], p["SA"], p["B"], p["SB"], p["group_offsets"], C=C_row)                    # gg_fp8_grouped_gemm
+    C_km = canary_C(M, N)
+    gg.grouped_gemm(p["A"], p["SA"].t().contiguous(), p["B"], p["SB"], p["group_offsets"], C=C_km, sa_kmajor=True)
     torch.cuda.synchronize()
-    rng = np.random.default_rng(cfg.seed)
-    rows = sampled_rows(off, rng, every=every, max_groups=max_groups)
-    # the oracle only needs the sampled rows of A/SA and the groups they fall in
-    grp = np.searchsorted(off, rows, side="right") - 1
-    used = np.unique(grp)
-    A_s = p["A"][torch.from_numpy(rows).to(DEV)].cpu().numpy()
-    SA_s = p["SA"][torch.from_numpy(rows).to(DEV)].cpu().numpy()
-    B_s = p["B"][torch.from_numpy(used).to(DEV)].cpu().numpy()
-    SB_s = p["SB"][torch.from_numpy(used).to(DEV)].cpu().numpy()
-    counts = np.array([(grp == g).sum() for g in used])
-    off_s = np.concatenate([[0], np.cumsum(counts)])
-    ref = orc.grouped_gemm(A_s, SA_s, B_s, SB_s, off_s, with_abs_sum=True)
-    got = bits_of(C[torch.from_numpy(rows).to(DEV)])
-    stats = assert_parity(got, ref, what=name)
-    print(f"\n{name}: {len(rows)} sampled rows x {cfg.N}: {stats}")
-    # property that holds at any size: every row of every group was written (no canary left)
-    written = (C.view(torch.int16) != CANARY).any(dim=1).cpu().numpy()
-    assert written.all()
+    acc_row, acc_km = ParityAccumulator(f"{name}, row-major scales"), ParityAccumulator(f"{name}, K-block-major scales")
+    for g in range(cfg.G):
+        r0, r1 = int(off[g]), int(off[g + 1])
+        if r1 == r0:
+            continue
+        ref = orc.grouped_gemm(p["A"][r0:r1].cpu().numpy(), p["SA"][r0:r1].cpu().numpy(), p["B"][g:g + 1].cpu().numpy(),
+                               p["SB"][g:g + 1].cpu().numpy(), np.array([0, r1 - r0]), with_abs_sum=True)
+        acc_row.add(bits_of(C_row[r0:r1]), ref)
+        acc_km.add(bits_of(C_km[r0:r1]), ref)
+    s_row, s_km = acc_row.finish(), acc_km.finish()
+    assert s_row["elements"] == M * N == s_km["elements"]
+    print(f"\n{name}: all {M} rows x {N} columns, row-major {s_row}, K-block-major {s_km}")
+    # the two storage orders of the scales give the same bits
+    assert torch.equal(C_row.view(torch.int16), C_km.view(torch.int16))
 
 
 @pytest.mark.parametrize("N,K,G,M", [
@@ -428,7 +434,7 @@ def test_binary16_output_every_variant():
         torch.cuda.synchronize()
         got = f16_bits_of(C)
         assert_parity(got, ref, what=f"binary16 variant {v}", fmt="f16")
-        family = "k-permuted" if v >= 0 and gg.variant_name(v).endswith("-rbk") else "plain"
+        family = family_of(v)
         first.setdefault(family, got)
         assert np.array_equal(got, first[family])
 
@@ -505,7 +511,7 @@ def test_ragged_n_and_k_every_variant_that_takes_them(sizes, N, K):
         assert (bits[M:] == CANARY).all(), f"variant {v} wrote past the last row"
         assert_parity(bits[:M], ref, empirical=False, what=f"N={N} K={K} variant {v}")
         first = bits if first is None else first
-        assert np.array_equal(bits, first), f"variant {v} differs from the others"
+        assert np.array_equal(bits, first), f"variant {v} differs from the others"          # (no split-K variant takes these shapes)
     # the automatic choice and the tiles it draws from always work; the second kernel's variants never do here
     names = {gg.variant_name(v) for v in supported if v >= 0}
     assert -1 in supported and {"160x256/2x4w/3s", "128x128/2x4w/4s", "128x256/2x4w/3s", "32x256/1x8w/4s"} <= names
