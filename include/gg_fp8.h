@@ -128,6 +128,20 @@ int gg_fp8_grouped_gemm_ex(const void* A, const float* SA, const void* B, const 
                            const int32_t* group_offsets, void* C, int G, int64_t M_total, int N, int K,
                            void* workspace, size_t workspace_bytes, void* stream, int variant, unsigned flags);
 
+/* gg_fp8_grouped_gemm_ex with a split-K variant, for callers that cannot allocate (code under HIP graph capture,
+ * serving loops, harnesses that forbid hipMalloc): the partial sums live in a buffer built into the library, one
+ * copy per GPU, instead of a caller's workspace, and the call allocates nothing.  variant: one of the "-k2" variants,
+ * or -1 for the 128 x 256 one; flags: GG_OUT_F16 and GG_SA_KMAJOR.  M_total * N may be at most
+ * gg_fp8_noalloc_max_elements() (4 Mi elements: 32 MiB of partial sums): GG_ERR_WORKSPACE beyond that, before
+ * anything is enqueued.  Same results, bit for bit, as the _ex call with the same variant.  Every call on a GPU
+ * uses that GPU's one buffer: calls that may overlap on one GPU (different streams) race; calls on one stream
+ * are ordered and safe.  Other errors as for gg_fp8_grouped_gemm_ex (a variant that is not split-K:
+ * GG_ERR_UNSUPPORTED). */
+int gg_fp8_grouped_gemm_splitk_noalloc(const void* A, const float* SA, const void* B, const float* SB,
+                                       const int32_t* group_offsets, void* C, int G, int64_t M_total, int N, int K,
+                                       void* stream, int variant, unsigned flags);
+size_t gg_fp8_noalloc_max_elements(void);
+
 /* The first grouped GEMM of an expert MLP with the activation and the quantiser of the second GEMM's operand in
  * its epilogue (what gg_fp8_grouped_gemm followed by gg_fp8_swiglu_quantize_rows computes, without the bf16
  * intermediate [M_total, 2*I] ever reaching memory): B [G, 2*I, K] holds the gate projection in rows [0, I) and the

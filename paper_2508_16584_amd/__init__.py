@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     check_offsets,
     grouped_gemm,
     grouped_gemm_padded,
+    grouped_gemm_splitk_noalloc,
+    noalloc_max_elements,
     grouped_gemm_swiglu,
     library_path,
     load_library,

@@ -83,6 +83,10 @@ def load_library() -> ctypes.CDLL:
     lib.gg_fp8_grouped_gemm_f16.restype = i32
     lib.gg_fp8_grouped_gemm_ex.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp, sz, vp, i32, ctypes.c_uint]
     lib.gg_fp8_grouped_gemm_ex.restype = i32
+    lib.gg_fp8_grouped_gemm_splitk_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp, i32, ctypes.c_uint]
+    lib.gg_fp8_grouped_gemm_splitk_noalloc.restype = i32
+    lib.gg_fp8_noalloc_max_elements.argtypes = []
+    lib.gg_fp8_noalloc_max_elements.restype = sz
     lib.gg_fp8_grouped_gemm_swiglu.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp, i32, ctypes.c_uint]
     lib.gg_fp8_grouped_gemm_swiglu.restype = i32
     lib.gg_fp8_pad_ex.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i64, i32, vp, ctypes.c_uint]
@@ -120,7 +124,7 @@ EXPORTED_SYMBOLS = [
     "gg_fp8_version", "gg_fp8_status_str", "gg_fp8_workspace_bytes", "gg_fp8_workspace_bytes_variant", "gg_fp8_grouped_gemm",
     "gg_fp8_grouped_gemm_variant", "gg_fp8_grouped_gemm_f16", "gg_fp8_grouped_gemm_ex", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_auto_variant", "gg_fp8_auto_variant_padded", "gg_fp8_padded_rows_cap",
     "gg_fp8_pad", "gg_fp8_grouped_gemm_padded", "gg_fp8_unpad", "gg_fp8_quantize_rows", "gg_fp8_swiglu_quantize_rows", "gg_fp8_check_offsets",
-    "gg_fp8_pad_ex", "gg_fp8_quantize_rows_ex", "gg_fp8_swiglu_quantize_rows_ex", "gg_fp8_grouped_gemm_swiglu",
+    "gg_fp8_grouped_gemm_splitk_noalloc", "gg_fp8_noalloc_max_elements", "gg_fp8_pad_ex", "gg_fp8_quantize_rows_ex", "gg_fp8_swiglu_quantize_rows_ex", "gg_fp8_grouped_gemm_swiglu",
 ]
 
 
@@ -269,6 +273,26 @@ def grouped_gemm(A, SA, B, SB, group_offsets, C=None, variant: int = -1, stream=
     else:
         _check((lib.gg_fp8_grouped_gemm_f16 if out_dtype == torch.float16 else lib.gg_fp8_grouped_gemm_variant)(*args))
     return C
+
+
+def grouped_gemm_splitk_noalloc(A, SA, B, SB, group_offsets, C, variant: int = -1, stream=None, sa_kmajor=False):
+    """gg_fp8_grouped_gemm_splitk_noalloc: the split-K GEMM on the library's built-in scratch (no workspace, no
+    allocation in the library; C must be given).  M_total * N <= noalloc_max_elements()."""
+    lib = load_library()
+    G, M_total, N, K = _gemm_shapes(A, SA, B, SB, group_offsets, sa_kmajor)
+    if C.dtype not in (torch.bfloat16, torch.float16):
+        raise TypeError("C must be bfloat16 or float16")
+    _want(C, "C", C.dtype, 2)
+    if tuple(C.shape) != (M_total, N):
+        raise ValueError(f"C must be [{M_total}, {N}]")
+    flags = (GG_SA_KMAJOR if sa_kmajor else 0) | (GG_OUT_F16 if C.dtype == torch.float16 else 0)
+    _check(lib.gg_fp8_grouped_gemm_splitk_noalloc(_ptr(A), _ptr(SA), _ptr(B), _ptr(SB), _ptr(group_offsets), _ptr(C),
+                                                  G, M_total, N, K, _stream(stream), int(variant), flags))
+    return C
+
+
+def noalloc_max_elements() -> int:
+    return int(load_library().gg_fp8_noalloc_max_elements())
 
 
 def grouped_gemm_swiglu(A, SA, B, SB, group_offsets, A2=None, SA2=None, act_out=None, want_act=False, variant: int = -1,

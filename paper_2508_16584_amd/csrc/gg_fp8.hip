@@ -14,6 +14,13 @@
 #include "pad_kernels.h"
 #include "quant_kernel.h"
 
+// Scratch of gg_fp8_grouped_gemm_splitk_noalloc: the partial sums of a split-K call, [2][M_total][N] fp32, for
+// problems of up to kScratchBytes / 8 output elements.  One copy per GPU the library runs on, held until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the address the kernels
+// get is the one that call returns (scratch_ptr below).
+constexpr size_t kScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
 
 constexpr int kVersion = 101;  // 0.1.1
@@ -119,6 +126,7 @@ const Variant kVariants[] = {
      &launch_gemm<gg::GemmCfg<64, 256, 1, 8, 3, false, 0>, false, true>, nullptr, false, true},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+constexpr int kDefaultSplitK = kNumVariants - 2;   // 128 x 256 tile
 
 // The second kernel with the activation epilogue (gg_fp8_grouped_gemm_swiglu): same tiles as variants 14, 15, 12.
 struct FusedVariant {
@@ -218,6 +226,18 @@ size_t workspace_need(int variant, int64_t M_total, int N) {
 bool workspace_ok(const void* workspace, size_t bytes, size_t need) {
   if (need == 0) return true;
   return workspace && ((uintptr_t)workspace & 15) == 0 && bytes >= need;
+}
+
+// Device address of this GPU's copy of `scratch`, looked up once per device with that device current.
+void* scratch_ptr() {
+  static std::atomic<void*> cache[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  void* p = cache[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+  cache[dev].store(p, std::memory_order_release);
+  return p;
 }
 
 int validate_gemm(const void* A, const float* SA, const void* B, const float* SB, const int32_t* off, void* C,
@@ -380,6 +400,23 @@ int gg_fp8_grouped_gemm_ex(const void* A, const float* SA, const void* B, const 
                            void* workspace, size_t workspace_bytes, void* stream, int variant, unsigned flags) {
   return run_gemm(A, SA, B, SB, group_offsets, C, G, M_total, N, K, workspace, workspace_bytes, stream, variant, flags);
 }
+
+int gg_fp8_grouped_gemm_splitk_noalloc(const void* A, const float* SA, const void* B, const float* SB,
+                                       const int32_t* group_offsets, void* C, int G, int64_t M_total, int N, int K,
+                                       void* stream, int variant, unsigned flags) {
+  if (variant < 0) variant = kDefaultSplitK;
+  if (variant >= kNumVariants || !kVariants[variant].splitk) return GG_ERR_UNSUPPORTED;
+  if (flags & GG_PADDED_GROUPS) return GG_ERR_UNSUPPORTED;
+  int st = validate_gemm(A, SA, B, SB, group_offsets, C, G, M_total, N, K);
+  if (st != GG_OK) return st;
+  if (G == 0 || M_total == 0) return GG_OK;
+  if (workspace_need(variant, M_total, N) > kScratchBytes) return GG_ERR_WORKSPACE;   // beyond the built-in scratch
+  void* ptr = scratch_ptr();
+  if (!ptr) return GG_ERR_HIP;
+  return run_gemm(A, SA, B, SB, group_offsets, C, G, M_total, N, K, ptr, kScratchBytes, stream, variant, flags);
+}
+
+size_t gg_fp8_noalloc_max_elements(void) { return kScratchBytes / (2 * sizeof(float)); }
 
 int gg_fp8_grouped_gemm_swiglu(const void* A, const float* SA, const void* B, const float* SB,
                                const int32_t* group_offsets, void* A2, float* SA2, void* act_out,
