@@ -45,10 +45,17 @@ namespace gg {
 // silu(gate) * up, quantised to e4m3 with one scale per row (see the epilogue).
 // SKIP: every K step leaves out the 16-row activation blocks past the tile's last valid row (a scalar test per
 // block: 1-3 % slower on full tiles, and a tile's cost follows its height).  Without it every tile costs a full one.
-template <int BM_, int AFR_ = 4, bool KP_ = false, bool FUSE_ = false, bool SKIP_ = false>
+// RAGGED: N need not be a multiple of 256 nor K of 128 (the ceilings in Table 1 of the paper; N % 8 == 0 and
+// K % 16 == 0 remain): lane masks on the last K block's fetches, weight rows, scale blocks and output columns bounded
+// by N.  A few selects per fetch and store, hence an instantiation of its own.
+// ODDK: the number of K blocks may be odd (one more, empty K step per tile; see KBe in the kernel).  One more value
+// that lives in a scalar register through the whole kernel, which the largest tiles have no room for: the
+// instantiations for whole blocks keep to an even number.
+template <int BM_, int AFR_ = 4, bool KP_ = false, bool FUSE_ = false, bool SKIP_ = false, bool RAGGED_ = false, bool ODDK_ = RAGGED_>
 struct RbCfg {
-  static constexpr bool KP = KP_, FUSE = FUSE_, SKIP = SKIP_;
+  static constexpr bool KP = KP_, FUSE = FUSE_, SKIP = SKIP_, RAGGED = RAGGED_, ODDK = ODDK_;
   static_assert(!(FUSE_ && SKIP_), "the activation epilogue runs full K steps only");
+  static_assert(!(FUSE_ && RAGGED_), "the activation epilogue takes whole blocks only");
   static constexpr int BM = BM_, BN = 256, S = 3;
   static constexpr int NW = 8, NT = 512;
   static constexpr int TM = BM / 16, TN = 2;
@@ -119,6 +126,10 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
   const int l = tid & 63;
   const int r = l & 15, q = l >> 4;
   const int K = a.K, KB = a.KB, N = a.N;
+  // K steps per tile: the two register sets alternate by step parity and the loop runs on from tile to tile, so an
+  // odd number of K blocks (ODDK) gets one more step, whose fetches (block KB of the tile: past its end) all use the
+  // out-of-range offset: zero operands and zero scales, which add exact zeros
+  const int KBe = Cfg::ODDK ? (KB + 1) & ~1 : KB;
 
   // ---- per-lane constants ---------------------------------------------------------------------------
   // DMA: lane l of a wave-wide 16 B DMA lands at LDS byte 16*l of its 1 KB slab (row l/8, chunk l%8); the
@@ -133,6 +144,13 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
   const int vBrow = (Cfg::FUSE ? w * 16 + f_row : w * 32 + 8 * (f_row >> 2) + (f_row & 3)) * K;
   const int vB0 = vBrow + (((l & 7) ^ (Cfg::KP ? swz_key_a1(f_row) : swz_key_a(f_row))) << 4);
   const int vB1 = vBrow + (Cfg::FUSE ? 8 : 16) * K + (((l & 7) ^ (Cfg::KP ? swz_key_a1(f_row + 8) : swz_key_a(f_row + 8))) << 4);
+  // RAGGED, K % 128 != 0: in the last K block a lane whose 16-byte chunk starts at or past byte k_rem of the block
+  // would fetch the start of the next row; it fetches from the out-of-range offset instead (zeros).  Kept as a
+  // second lane offset per stream (vector registers; the scalar registers are all taken).
+  const int vA_last = Cfg::RAGGED && (((l & 7) ^ (Cfg::KP ? swz_key_a1(a_row) : swz_key_a(a_row))) << 4) >= a.k_rem ? GG_OOB_OFFSET : vA;
+  const int vB0_last = Cfg::RAGGED && (((l & 7) ^ (Cfg::KP ? swz_key_a1(f_row) : swz_key_a(f_row))) << 4) >= a.k_rem ? GG_OOB_OFFSET : vB0;
+  const int vB1_last = Cfg::RAGGED && (((l & 7) ^ (Cfg::KP ? swz_key_a1(f_row + 8) : swz_key_a(f_row + 8))) << 4) >= a.k_rem ? GG_OOB_OFFSET : vB1;
+  const int nb_all = Cfg::RAGGED ? (N + 127) >> 7 : N >> 7;             // 128-column scale blocks of a group's weights
   const int inter = N >> 1;                                            // FUSE: activation columns (N = gate + up rows)
   const int frag1_off = Cfg::FUSE ? inter * K : 4 * K;                 // from fragment 0's weight rows to fragment 1's
   // Every wave issues exactly one scale DMA per K block: waves [0, SA_WAVES) fetch 64 activation scales each,
@@ -200,21 +218,25 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     rows_i = rows_i < 0 ? 0 : (rows_i > 64 ? 64 : rows_i);
     return uniform_rsrc(a.A + (t.grow + 64 * i) * K, on ? rows_i * K : 0);
   };
+  // RAGGED: the weight rows, scale blocks and output columns at or past N do not exist; the views end before them
+  // (the range check adds the lane and the scalar part of an offset before it compares with the view's length)
   auto desc_b = [&](const Tile& t, bool on) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
-    return uniform_rsrc(a.B + ((int64_t)t.g * N + t.n0) * K, on ? (Cfg::FUSE ? inter + 128 : BN) * K : 0);
+    const int n_rem = N - t.n0;
+    return uniform_rsrc(a.B + ((int64_t)t.g * N + t.n0) * K, on ? (Cfg::FUSE ? inter + 128 : Cfg::RAGGED && n_rem < BN ? n_rem : BN) * K : 0);
   };
   // this wave's scale source: the activation scales of the tile's rows, or the weight scales of its two column blocks
   auto desc_s = [&](const Tile& t, bool on) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
     return sa_wave ? uniform_rsrc((const uint8_t*)a.SA + t.grow * a.sa_row_stride, on ? sa_view_bytes(a, t.grow, t.rows_valid) : 0)
-                   : uniform_rsrc(a.SB + ((int64_t)t.g * (N >> 7) + (t.n0 >> 7)) * KB,
-                                  on ? (Cfg::FUSE ? (inter >> 7) + 1 : BN / 128) * KB * 4 : 0);
+                   : uniform_rsrc(a.SB + ((int64_t)t.g * nb_all + (t.n0 >> 7)) * KB,
+                                  on ? (Cfg::FUSE ? (inter >> 7) + 1
+                                                  : Cfg::RAGGED && nb_all - (t.n0 >> 7) < BN / 128 ? nb_all - (t.n0 >> 7) : BN / 128) * KB * 4 : 0);
   };
 
   // Carry: the fetches a K step issues run two to three K blocks ahead; at the end of a tile those blocks are the
   // first blocks of the workgroup's next tile.  With an even number of K blocks (the two register sets alternate
   // by K-block parity) the descriptors are re-pointed to the next tile as its first fetches come up, the K loop
   // runs on into it, and the state at the end of the last K block IS the state the prologue would have built.
-  // The host only launches this kernel with an even KB >= 4.
+  // The host only launches this kernel with KB >= 3, and with an even KB unless ODDK is set.
   Tile cur = find_tile(0);
   if (!cur.valid) return;
   __amdgpu_buffer_rsrc_t dA0 = band(cur, 0, true), dA1 = band(cur, 1 % Cfg::A_ITERS, true), dA2 = band(cur, 2 % Cfg::A_ITERS, true),
@@ -243,9 +265,10 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     auto dma_a = [&](auto ic, int kb_t, int stage) __attribute__((always_inline)) {   // one 8-row slab of block kb's A tile
       constexpr int i = decltype(ic)::value;
       const int kb = kb_t - kbase;
-      const int vo = kb < KB ? vA : GG_OOB_OFFSET;
+      const int kp = k_wrapped(kb + rot, KB);
+      const int vo = kb < KB ? (Cfg::RAGGED && kp == KB - 1 ? vA_last : vA) : GG_OOB_OFFSET;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(i == 0 ? dA0 : i == 1 ? dA1 : i == 2 ? dA2 : dA3, GG_LDS_PTR(lds + stage * Cfg::STAGE_BYTES + (w + i * NW) * 1024), 16, vo,
-                                               __builtin_amdgcn_readfirstlane(k_wrapped(kb + rot, KB) * 128), 0, 0);
+                                               __builtin_amdgcn_readfirstlane(kp * 128), 0, 0);
     };
     auto dma_scales = [&](int kb_t, int stage) __attribute__((always_inline)) {     // exactly one DMA in every wave
       const int kb = kb_t - kbase;
@@ -260,9 +283,11 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       const bool in = kb < KB;
       uint8_t* dst = bslots + slot * Cfg::B_SLOT_BYTES;
       // all 256 weight rows of the tile exist: only the lane part of the offset needs the bounds check
-      const int so = __builtin_amdgcn_readfirstlane(k_wrapped(kb + (j == 0 ? rot0 : rot), KB) * 128 + j * frag1_off);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(j == 0 ? dB0 : dB, GG_LDS_PTR(dst), 16, in ? vB0 : GG_OOB_OFFSET, so, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(j == 0 ? dB0 : dB, GG_LDS_PTR(dst + 1024), 16, in ? vB1 : GG_OOB_OFFSET, so, 0, 0);
+      const int kp = k_wrapped(kb + (j == 0 ? rot0 : rot), KB);
+      const bool last = Cfg::RAGGED && kp == KB - 1;
+      const int so = __builtin_amdgcn_readfirstlane(kp * 128 + j * frag1_off);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(j == 0 ? dB0 : dB, GG_LDS_PTR(dst), 16, in ? (last ? vB0_last : vB0) : GG_OOB_OFFSET, so, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(j == 0 ? dB0 : dB, GG_LDS_PTR(dst + 1024), 16, in ? (last ? vB1_last : vB1) : GG_OOB_OFFSET, so, 0, 0);
     };
     constexpr std::integral_constant<int, 0> J0{};
     constexpr std::integral_constant<int, 1> J1{};
@@ -481,25 +506,25 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     constexpr std::integral_constant<int, 0> SET0{};
     constexpr std::integral_constant<int, 1> SET1{};
     {
-      for (int kb = 0; kb < KB - 4; kb += 2) {
+      for (int kb = 0; kb < KBe - 4; kb += 2) {
         kstep(kb, SET0, pred_c);
         kstep(kb + 1, SET1, pred_c);
       }
       // step KB-4 issues the last fetch of this tile's j = 0 fragments (block KB-1); step KB-3 the last fetches of
       // its activations, scales and j = 1 fragments.  After each, that stream moves on to the next tile.
-      kstep(KB - 4, SET0, pred_c);
+      kstep(KBe - 4, SET0, pred_c);
       dB0 = desc_b(nxt, has_next);
       rot0 = k_rotation(a, nxt.n0);
-      kbase0 = KB;
-      kstep(KB - 3, SET1, pred_c);
+      kbase0 = KBe;
+      kstep(KBe - 3, SET1, pred_c);
       dA0 = band(nxt, 0, has_next); dA1 = band(nxt, 1 % Cfg::A_ITERS, has_next);
       dA2 = band(nxt, 2 % Cfg::A_ITERS, has_next); dA3 = band(nxt, 3 % Cfg::A_ITERS, has_next);
       dB = dB0;
       dS = desc_s(nxt, has_next);
       rot = rot0;
-      kbase = KB;
-      kstep(KB - 2, SET0, pred_c);
-      kstep(KB - 1, SET1, pred_c);
+      kbase = KBe;
+      kstep(KBe - 2, SET0, pred_c);
+      kstep(KBe - 1, SET1, pred_c);
       kbase = kbase0 = 0;
     }
 
@@ -579,7 +604,9 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       int rows_mt = rows_valid - 16 * mt;
       rows_mt = rows_mt < 0 ? 0 : rows_mt;
       __amdgpu_buffer_rsrc_t dC = uniform_rsrc(a.C + (grow + 16 * mt) * N + n0, rows_mt > 0 ? rows_mt * N * 2 - n0 * 2 : 0);
-      __builtin_amdgcn_raw_buffer_store_b128(out, dC, r * N * 2 + (w * 32 + 8 * q) * 2, 0, 0);
+      // RAGGED: N is a multiple of 8, so a lane's 8 columns exist together or not at all
+      const bool col_ok = !Cfg::RAGGED || n0 + w * 32 + 8 * q < N;
+      __builtin_amdgcn_raw_buffer_store_b128(out, dC, col_ok ? r * N * 2 + (w * 32 + 8 * q) * 2 : GG_OOB_OFFSET, 0, 0);
     }
     }
     if (!has_next) {

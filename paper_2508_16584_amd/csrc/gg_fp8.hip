@@ -47,7 +47,7 @@ struct Variant {
   hipError_t (*launch)(const gg::GemmArgs&, int grid, hipStream_t);
   // the same tile for N % BN != 0 or K % 128 != 0 (partial tiles, short last K block); null: whole blocks only
   hipError_t (*launch_ragged)(const gg::GemmArgs&, int grid, hipStream_t) = nullptr;
-  bool even_kb_only = false;   // needs K % 256 == 0 and K >= 512
+  bool min_kb3 = false;        // the second kernel: its prologue fetches three K blocks (K > 256)
   bool splitk = false;         // two work units per tile (halves of the K loop) and a combine pass; needs a workspace
 };
 
@@ -108,12 +108,12 @@ const Variant kVariants[] = {
     GG_VARIANT(128, 128, 2, 4, 4, true, 0, 1),    // 9
     GG_VARIANT(32, 256, 1, 8, 4, true, 0, 1),     // 10
     GG_VARIANT(128, 128, 2, 4, 2, false, 0, 2),   // 11
-    {"256x256/1x8w/3s-rb", 256, 256, gg::RbCfg<256, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, false>>, nullptr, true},   // 12
+    {"256x256/1x8w/3s-rb", 256, 256, gg::RbCfg<256, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, false>>, &launch_gemm_rb<gg::RbCfg<256, 2, false, false, false, true>>, true},   // 12
     {"256x256/1x8w/3s-rbk", 256, 256, gg::RbCfg<256, 2, true>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<256, 2, true>>, nullptr, true},    // 13
     // ring of 4 activation fragments at 192 rows: 1 % faster than 2 there, no gain (and 249 VGPRs) at 256 rows
-    {"192x256/1x8w/3s-rb", 192, 256, gg::RbCfg<192, 4, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<192, 4, false>>, nullptr, true},   // 14
-    {"224x256/1x8w/3s-rb", 224, 256, gg::RbCfg<224, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<224, 2, false>>, nullptr, true},   // 15
-    {"128x256/1x8w/3s-rb", 128, 256, gg::RbCfg<128, 4, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<128, 4, false>>, nullptr, true},   // 16
+    {"192x256/1x8w/3s-rb", 192, 256, gg::RbCfg<192, 4, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<192, 4, false>>, &launch_gemm_rb<gg::RbCfg<192, 4, false, false, false, true>>, true},   // 14
+    {"224x256/1x8w/3s-rb", 224, 256, gg::RbCfg<224, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<224, 2, false>>, &launch_gemm_rb<gg::RbCfg<224, 2, false, false, false, true>>, true},   // 15
+    {"128x256/1x8w/3s-rb", 128, 256, gg::RbCfg<128, 4, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<128, 4, false>>, &launch_gemm_rb<gg::RbCfg<128, 4, false, false, false, true>>, true},   // 16
     {"160x256/1x8w/3s-rb", 160, 256, gg::RbCfg<160, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<160, 2, false>>, nullptr, true},   // 17
     {"96x256/1x8w/3s-rb", 96, 256, gg::RbCfg<96, 2, false>::LDS_BYTES, 1, &launch_gemm_rb<gg::RbCfg<96, 2, false>>, nullptr, true},   // 18
     // "-rbs": the second kernel with K steps that leave out the activation blocks past a tile's last valid row
@@ -133,11 +133,14 @@ struct FusedVariant {
   int variant;   // the plain variant it is the twin of
   int BM;
   hipError_t (*launch)(const gg::GemmArgs&, int, hipStream_t);
+  // the instantiation for an odd number of K blocks (one more value in a scalar register: only the 192-row tile
+  // has room for it); null: even numbers only
+  hipError_t (*launch_odd)(const gg::GemmArgs&, int, hipStream_t);
 };
 const FusedVariant kFused[] = {
-    {14, 192, &launch_gemm_rb<gg::RbCfg<192, 2, false, true>>},
-    {15, 224, &launch_gemm_rb<gg::RbCfg<224, 2, false, true>>},
-    {12, 256, &launch_gemm_rb<gg::RbCfg<256, 2, false, true>>},
+    {14, 192, &launch_gemm_rb<gg::RbCfg<192, 2, false, true>>, &launch_gemm_rb<gg::RbCfg<192, 2, false, true, false, false, true>>},
+    {15, 224, &launch_gemm_rb<gg::RbCfg<224, 2, false, true>>, nullptr},
+    {12, 256, &launch_gemm_rb<gg::RbCfg<256, 2, false, true>>, nullptr},
 };
 
 // Automatic choice.  The host sees only sizes (the offsets stay on the device), so the choice works with the
@@ -160,21 +163,22 @@ const FusedVariant kFused[] = {
 // five candidates on the paper's grid (Sec. 3.1) extended to K = 1024 ... 8192 (960 points) with caches flushed
 // before every launch: mean loss against the per-point best of the five 0.7 %.
 int pick_variant(int G, int64_t M_total, int N, int K) {
-  if (N % 256 != 0 || K % 128 != 0) {
-    // partial tiles and a short last K block: first kernel only; the 128-wide tile wastes least on a ragged N
-    const double avg_rows = G > 0 ? (double)M_total / G : 0.0;
-    return N % 128 != 0 || N < 256 ? 2 : (avg_rows < 64 ? 3 : 0);
-  }
   const double avg = G > 0 ? (double)M_total / G : 0.0;
+  const int n_tiles = (N + 255) / 256;
+  const bool ragged = N % 256 != 0 || K % 128 != 0;
+  // A ragged N on 256-wide tiles: the columns past N of the last tile are computed for nothing.  Up to 1/8 of
+  // waste the choice below stands; beyond that the 128-wide tile of the first kernel wastes least.
+  if (N % 256 != 0 && (N % 128 != 0 || N < 256) && (double)n_tiles * 256 > 1.125 * N) return 2;
   if (avg < 64) return 3;
   if (avg < 192) return 0;
-  if (K >= 4096 && M_total >= 24576) return 1;
+  if (!ragged && K >= 4096 && M_total >= 24576) return 1;
+  const double cus = (double)device_cus();   // the constants below are a fit on 256 CUs; the round count follows the chip
   auto cost = [&](int BM, double eff) {
-    const double rounds = ((double)M_total / BM + 0.5 * G) * (N / 256) / 256.0;   // 256 CUs: the chip this is fitted on
+    const double rounds = ((double)M_total / BM + 0.5 * G) * n_tiles / cus;
     const double whole = std::floor(rounds), frac = rounds - whole;
     return (whole + (frac > 1e-9 ? 0.3 + 0.7 * frac : 0.0)) * BM / eff;
   };
-  const bool second_kernel = K % 256 == 0 && K >= 512;   // its K loop takes two K blocks per turn
+  const bool second_kernel = K > 256;   // its prologue fetches three K blocks
   int best = 0;
   double c_best = cost(160, 1.0);
   auto consider = [&](int variant, double c) {
@@ -183,7 +187,7 @@ int pick_variant(int G, int64_t M_total, int N, int K) {
   if (second_kernel) consider(14, cost(192, 1.06));
   if (second_kernel) consider(15, cost(224, 1.08));
   if (second_kernel) consider(12, cost(256, 1.10));
-  consider(1, cost(256, K >= 4096 ? 1.02 : 0.94));
+  if (!ragged) consider(1, cost(256, K >= 4096 ? 1.02 : 0.94));   // the 256 x 256 ring-2 tile takes whole blocks only
   return best;
 }
 
@@ -263,10 +267,12 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
   // split-K: an even number of K blocks, whole tiles, offsets of the partial sums within 32 bits
   if (v.splitk && (K % 256 != 0 || N % v.BN != 0 || N > (1 << 20))) return GG_ERR_UNSUPPORTED;
   if (!workspace_ok(workspace, workspace_bytes, workspace_need(variant, M_total, N))) return GG_ERR_WORKSPACE;
-  const bool ragged = N % v.BN != 0 || K % 128 != 0;
+  // the instantiation for partial tiles and a short last K block; in the second kernel it is also the one that takes
+  // an odd number of K blocks
+  const bool ragged = N % v.BN != 0 || K % 128 != 0 || (v.min_kb3 && (((K + 127) / 128) & 1));
   if (ragged && !v.launch_ragged) return GG_ERR_UNSUPPORTED;   // this variant takes whole tiles and whole K blocks only
-  // the second kernel runs its K loop on from one tile into the next, two K blocks per turn
-  if (v.even_kb_only && (K % 256 != 0 || K < 512)) return GG_ERR_UNSUPPORTED;
+  // the second kernel's prologue fetches three K blocks (an odd number of K blocks is fine: it adds one empty step)
+  if (v.min_kb3 && K <= 256) return GG_ERR_UNSUPPORTED;
 
   gg::GemmArgs args;
   args.A = static_cast<const uint8_t*>(A);
@@ -424,14 +430,17 @@ int gg_fp8_grouped_gemm_swiglu(const void* A, const float* SA, const void* B, co
   if (flags & ~(unsigned)GG_SA_KMAJOR) return GG_ERR_UNSUPPORTED;
   if (G < 0 || M_total < 0 || I <= 0 || K <= 0) return GG_ERR_SHAPE;
   if (M_total > 0x7FFFFFFFLL || I > (1 << 20) || K > (1 << 22)) return GG_ERR_SHAPE;
-  // whole 128-column blocks of activations; the second kernel's K loop (two K blocks per turn, carried)
-  if (I % 128 != 0 || K % 256 != 0 || K < 512) return GG_ERR_UNSUPPORTED;
+  // whole 128-column blocks of activations and whole K blocks; the second kernel's prologue fetches three K blocks
+  if (I % 128 != 0 || K % 128 != 0 || K <= 256) return GG_ERR_UNSUPPORTED;
   if ((int64_t)2 * I * K > 0x7FFFFFFFLL) return GG_ERR_SHAPE;       // an expert's weights are addressed with 32-bit offsets
   if (G == 0 || M_total == 0) return GG_OK;
   if (!A || !SA || !B || !SB || !group_offsets || !A2 || !SA2) return GG_ERR_NULL;
   const int N = 2 * I;
   const FusedVariant* fv = nullptr;
-  if (variant < 0) {
+  const bool odd_kb = ((K / 128) & 1) != 0;
+  if (variant < 0 && odd_kb) {
+    fv = &kFused[0];
+  } else if (variant < 0) {
     // the cheapest of the three tile heights under the cost model of the automatic choice
     double c_best = 0;
     const double eff[3] = {1.06, 1.08, 1.10};
@@ -444,7 +453,7 @@ int gg_fp8_grouped_gemm_swiglu(const void* A, const float* SA, const void* B, co
   } else {
     for (const FusedVariant& f : kFused)
       if (f.variant == variant) fv = &f;
-    if (!fv) return GG_ERR_UNSUPPORTED;
+    if (!fv || (odd_kb && !fv->launch_odd)) return GG_ERR_UNSUPPORTED;
   }
   gg::GemmArgs args;
   args.A = static_cast<const uint8_t*>(A);
@@ -485,7 +494,7 @@ int gg_fp8_grouped_gemm_swiglu(const void* A, const float* SA, const void* B, co
   } else {
     args.slots = 0;
   }
-  return fv->launch(args, (int)grid, static_cast<hipStream_t>(stream)) == hipSuccess ? GG_OK : GG_ERR_HIP;
+  return (odd_kb ? fv->launch_odd : fv->launch)(args, (int)grid, static_cast<hipStream_t>(stream)) == hipSuccess ? GG_OK : GG_ERR_HIP;
 }
 
 int64_t gg_fp8_padded_rows_cap(int G, int64_t M_total) {

@@ -144,7 +144,8 @@ def test_fused_gemm_argument_validation(lib):
     f = lambda I=256, K=512, M=100, A2=p, variant=-1, flags=0: lib.gg_fp8_grouped_gemm_swiglu(
         p, p, p, p, p, A2, p, nul, 2, M, I, K, nul, variant, flags)
     assert f(I=192) == GG_ERR_UNSUPPORTED          # whole 128-column blocks of activations
-    assert f(K=384) == GG_ERR_UNSUPPORTED and f(K=256) == GG_ERR_UNSUPPORTED    # K % 256 == 0, K >= 512
+    assert f(K=400) == GG_ERR_UNSUPPORTED and f(K=256) == GG_ERR_UNSUPPORTED    # whole K blocks, at least three
+    assert f(K=384, variant=12) == GG_ERR_UNSUPPORTED    # an odd number of K blocks: the 192-row tile only
     assert f(variant=0) == GG_ERR_UNSUPPORTED and f(variant=13) == GG_ERR_UNSUPPORTED and f(variant=99) == GG_ERR_UNSUPPORTED
     assert f(flags=binding.GG_OUT_F16) == GG_ERR_UNSUPPORTED
     assert f(I=0) == GG_ERR_SHAPE and f(M=-1) == GG_ERR_SHAPE

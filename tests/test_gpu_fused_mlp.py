@@ -76,17 +76,20 @@ def check_against_two_calls_and_oracle(p, variants=(-1,), kmajor=(False, True), 
     ([700, 0, 1300, 37, 1800, 191], 1024, 1024),    # several tiles per workgroup (the K loop carries on into the next)
     ([5, 300, 64], 384, 1536),                      # three column blocks, odd number of scale groups
     ([193, 225, 257], 256, 768),                    # one row more than each tile height
+    ([700, 0, 1300, 37, 600], 512, 640),            # an odd number of K blocks, several tiles per workgroup
+    ([5, 300, 64], 128, 384),                       # three K blocks: the shortest K loop there is
 ])
 def test_fused_equals_gemm_then_oracle_activation_bitwise(sizes, inter, K):
     cfg = WorkloadConfig("fused", 5000 + inter + K, len(sizes), K, 2 * inter, 0, "custom", "latency")
     p = make_problem(cfg, sizes=np.array(sizes))
-    check_against_two_calls_and_oracle(p, variants=[-1] + FUSED_VARIANTS_TAKEN())
+    check_against_two_calls_and_oracle(p, variants=[-1] + FUSED_VARIANTS_TAKEN(K))
 
 
-def FUSED_VARIANTS_TAKEN():
-    """The tile variants that have a twin with the activation epilogue: the second kernel's plain ones."""
-    return [v for v in range(gg.num_variants())
-            if gg.variant_name(v) in ("192x256/1x8w/3s-rb", "224x256/1x8w/3s-rb", "256x256/1x8w/3s-rb")]
+def FUSED_VARIANTS_TAKEN(K=512):
+    """The tile variants that have a twin with the activation epilogue: the second kernel's plain ones; with an odd
+    number of K blocks the 192-row one only."""
+    names = ("192x256/1x8w/3s-rb",) if (K // 128) % 2 else ("192x256/1x8w/3s-rb", "224x256/1x8w/3s-rb", "256x256/1x8w/3s-rb")
+    return [v for v in range(gg.num_variants()) if gg.variant_name(v) in names]
 
 
 def test_fused_special_values_and_rows_outside_the_groups():
@@ -113,7 +116,7 @@ def test_fused_special_values_and_rows_outside_the_groups():
 def test_fused_rejects_what_it_cannot_take():
     z = lambda *s, dt=torch.uint8: torch.zeros(s, dtype=dt, device=DEV)
     off = torch.tensor([0, 4], dtype=torch.int32, device=DEV)
-    for inter, K in [(192, 512), (128, 384), (128, 256)]:        # I % 128, K % 256, K < 512
+    for inter, K in [(192, 512), (128, 400), (128, 256)]:        # I % 128, K % 128, K <= 256
         with pytest.raises(gg.GGError) as e:
             gg.grouped_gemm_swiglu(z(4, K), z(4, -(-K // 128), dt=torch.float32), z(1, 2 * inter, K),
                                    z(1, -(-2 * inter // 128), -(-K // 128), dt=torch.float32), off)

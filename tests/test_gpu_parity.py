@@ -18,14 +18,21 @@ DEV = "cuda:0"
 CANARY = 0x7B7B          # bf16 bit pattern that no test result produces in bulk
 
 
+# variants of the second kernel that also come in the instantiation for partial tiles, a short last K block and an odd
+# number of K blocks
+RB_ANY_SHAPE = {"256x256/1x8w/3s-rb", "192x256/1x8w/3s-rb", "224x256/1x8w/3s-rb", "128x256/1x8w/3s-rb"}
+
+
 def variants_for(N, K):
-    """Tile variants that take this shape: N a multiple of the tile width; the second kernel ("-rb") runs its K
-    loop two K blocks per turn and on into the next tile, so it needs K % 256 == 0 and K >= 512."""
+    """Tile variants that take this shape (K a multiple of 128): N a multiple of the tile width; the second kernel
+    ("-rb") fetches three K blocks ahead (K > 256) and alternates two register sets by K-block parity, so only its
+    any-shape instantiations take an odd number of K blocks."""
     out = []
     for v in range(gg.num_variants()):
         name = gg.variant_name(v)
         bn = int(name.split("/")[0].split("x")[1])
-        if N % bn == 0 and not ("-rb" in name and (K % 256 != 0 or K < 512)) and not ("-k2" in name and K % 256 != 0):
+        rb_ok = "-rb" not in name or (K > 256 and (K % 256 == 0 or name in RB_ANY_SHAPE))
+        if N % bn == 0 and rb_ok and not ("-k2" in name and K % 256 != 0):
             out.append(v)
     return out
 
@@ -479,6 +486,9 @@ def test_binary16_output_full_size_sampled_rows():
     ([64, 64], 648, 4112),                   # K = 4096 + 16
     ([50, 3], 1032, 128),                    # N ragged only
     ([50, 3], 256, 1008),                    # K ragged only
+    ([300, 17, 0, 513], 264, 272),           # 3 K blocks, the last 16 bytes long; second tile 8 columns wide
+    ([100, 260, 31], 512, 640),              # whole blocks, an odd number of them
+    ([30, 500], 776, 912),                   # 8 K blocks with a short last one; N = 3 * 256 + 8
 ])
 def test_ragged_n_and_k_every_variant_that_takes_them(sizes, N, K):
     """Ceilings in Table 1 of the paper: the last scale block along K and along N may be short.  The library takes
@@ -512,10 +522,11 @@ def test_ragged_n_and_k_every_variant_that_takes_them(sizes, N, K):
         assert_parity(bits[:M], ref, empirical=False, what=f"N={N} K={K} variant {v}")
         first = bits if first is None else first
         assert np.array_equal(bits, first), f"variant {v} differs from the others"          # (no split-K variant takes these shapes)
-    # the automatic choice and the tiles it draws from always work; the second kernel's variants never do here
+    # the automatic choice and the tiles it draws from always work; the second kernel needs three K blocks
     names = {gg.variant_name(v) for v in supported if v >= 0}
     assert -1 in supported and {"160x256/2x4w/3s", "128x128/2x4w/4s", "128x256/2x4w/3s", "32x256/1x8w/4s"} <= names
-    assert not any("-rb" in n for n in names)
+    rb = {n for n in names if "-rb" in n}
+    assert rb == (RB_ANY_SHAPE if K > 256 else set())
 
 
 def test_ragged_shapes_pad_path_bitwise_and_exact_case():
