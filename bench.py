@@ -308,18 +308,60 @@ def bench_expert_mlp(args, cfg, dev):
     }))
 
 
+def bench_ceilings():
+    """What this GPU sustains with the kernels' own instructions and nothing around them (include/gg_probe.h): one
+    JSON line.  Each matrix loop runs for about 10 ms, long enough for the sustained clock."""
+    import paper_2508_16584_amd as gg
+    modes = ["16x16x128 accumulating", "16x16x128 from zero + 4 FMA (this algorithm's inner loop)",
+             "32x32x64 accumulating", "2 x 32x32x64 per scale block + 16 FMA"]
+    kinds = ["constant 1.0", "normal-like e4m3", "uniform random bytes"]
+    mfma = {m: {k: round(gg.probe_mfma(mi, ki, 20000), 1) for ki, k in enumerate(kinds)} for mi, m in enumerate(modes)}
+    hbm = {"read_GBps": round(gg.probe_hbm(0), 1), "copy_GBps": round(gg.probe_hbm(1), 1)}
+    patterns = ["L2-resident contiguous 64 KB", "L2-resident column blocks [256 rows x 128 B] x 2",
+                "kernel stream (4 x 8 tiles per die, K = 7168)"]
+    fetch = {}
+    for pi, pn in enumerate(patterns):
+        fetch[pn] = {}
+        for depth in (1, 2, 3, 4, 6):
+            gbps, bpc = gg.probe_lds_fetch(pi, depth, 20)
+            fetch[pn][f"depth {depth}"] = {"GBps": round(gbps, 1), "B_per_clk_per_CU_at_nominal_clock": round(bpc, 2)}
+    print(json.dumps({"op": "ceilings", "mfma_fp8_TFLOPs": mfma, "hbm": hbm, "l2_to_lds_fetch": fetch,
+                      "peaks": {"mfma_fp8_dense_TFLOPs": 5000.0, "hbm_GBps": 8000.0}}))
+
+
+def pmc_summary(folder):
+    """Per kernel and counter, the mean over the dispatches in rocprofv3's `*counter_collection.csv` files under
+    `folder` (one row per dispatch and counter), as a markdown table: what the summaries under profiles/ are made of."""
+    import csv
+    import glob
+    acc = {}
+    for path in sorted(glob.glob(os.path.join(folder, "**", "*counter_collection.csv"), recursive=True)):
+        with open(path, newline="") as f:
+            for row in csv.DictReader(f):
+                key = (row["Kernel_Name"], row["Counter_Name"])
+                acc.setdefault(key, []).append(float(row["Counter_Value"]))
+                # the dispatch's duration as the profiler saw it (longer than an unprofiled launch)
+                dur = (row["Kernel_Name"], "dispatch duration under the profiler, us (" + row["Counter_Name"] + " run)")
+                acc.setdefault(dur, []).append((int(row["End_Timestamp"]) - int(row["Start_Timestamp"])) / 1e3)
+    print("| kernel | counter | dispatches | mean | min | max |")
+    print("|---|---|---|---|---|---|")
+    for (kernel, counter), v in sorted(acc.items()):
+        print(f"| `{kernel[:110]}` | {counter} | {len(v)} | {sum(v) / len(v):.1f} | {min(v):.1f} | {max(v):.1f} |")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="gate_up")
-    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows", "swiglu_quantize_rows", "expert_mlp"],
+    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows", "swiglu_quantize_rows", "expert_mlp", "ceilings"],
                     help="grouped_gemm: the hot path (default, the headline metric); quantize_rows: the producer of its "
                          "A operand on the same workload's activation shape; swiglu_quantize_rows: activation + quantiser "
                          "on the workload's output shape [M_total, N] (N = 2 x intermediate width); expert_mlp: the whole forward "
                          "chain quantise -> GEMM -> activation+quantise -> GEMM on the workload's routing, padding-free "
-                         "against the same chain on 128-row padded groups")
+                         "against the same chain on 128-row padded groups; ceilings: no workload, the probes of "
+                         "include/gg_probe.h (register-only matrix loops, HBM streams, the L2 -> LDS fetch stream)")
     ap.add_argument("--clock-warmup-ms", type=float, default=150.0,
                     help="untimed launches for about this long before the W warm-up steps, so that the timed steps run at "
                          "the GPU's sustained clock (0: none)")
@@ -335,7 +377,12 @@ def main():
                     help="skip the second timed loop with the other storage order of the activation scales")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--pmc-summary", metavar="DIR", default=None,
+                    help="no GPU work: print per-kernel means of the counters in rocprofv3's counter_collection.csv files under DIR")
     args = ap.parse_args()
+    if args.pmc_summary:
+        pmc_summary(args.pmc_summary)
+        return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (groups shard by expert across GPUs with no exchange inside the "
               "GEMM; nothing here uses a second GPU). Run with --gpus 1.", file=sys.stderr)
@@ -353,6 +400,9 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.op == "ceilings":
+        bench_ceilings()
+        return
     cfg = CONFIGS[args.workload]
     if args.op in ("quantize_rows", "swiglu_quantize_rows"):
         bench_quantize_rows(args, cfg, dev)

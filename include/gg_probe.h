@@ -1,0 +1,62 @@
+/* libgg_probe: measurement probes for gfx950 (MI355X).  NOT part of the hot path and never called by it.
+ *
+ * The grouped GEMM of libgg_fp8 (paper Sec. 2.1, Table 1) is judged against what this chip sustains, and the
+ * datasheet gives only the matrix pipe's and HBM's peaks.  These calls measure the other ceilings the kernels
+ * run into, with the same instructions and access shapes the kernels use and nothing else around them:
+ *   - the matrix instruction in a register-only loop, alone and with the scale fusion of Sec. 2.1 behind it
+ *     (one product per 128-wide scale block, started from zero, then 4 fp32 FMAs per 16x16 block);
+ *   - a plain HBM read and a plain HBM copy;
+ *   - the L2 -> LDS fetch stream (16 bytes per lane, straight into LDS) with no compute behind it.
+ *
+ * Every call is synchronous: it allocates its own device buffers, launches on the null stream, waits, frees, and
+ * returns 0 or the hipError_t that stopped it (nothing is left allocated).  Results are written through host
+ * pointers.  One GPU (the current device); not re-entrant.  `python bench.py --op ceilings` prints all of them.
+ */
+#ifndef GG_PROBE_H_
+#define GG_PROBE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Register-only loop of FP8 (e4m3) matrix instructions on every SIMD of the chip: 8 waves per compute unit, no
+ * memory access inside the loop.
+ *   mode 0: v_mfma_f32_16x16x128_f8f6f4, each product added to its accumulator by the instruction itself
+ *   mode 1: the same instruction started from zero, then acc += product * scale (4 fp32 FMAs): the inner loop of
+ *           the block-scaled GEMM
+ *   mode 2: v_mfma_f32_32x32x64_f8f6f4 accumulating
+ *   mode 3: two v_mfma_f32_32x32x64_f8f6f4 per 128-wide scale block (the first from zero, the second on top of
+ *           it), then 16 fp32 FMAs
+ *   data_kind 0: every operand byte 0x38 (1.0); 1: bytes like e4m3-quantised normal samples scaled to the
+ *           format's range; 2: uniformly random bytes (NaN codes replaced).  The chip's clock depends on how
+ *           many operand bits toggle, so the three differ.
+ * iters: loop trips per wave (each trip: 16 instructions of the 16x16x128 shape, or 8 of the 32x32x64 shape:
+ *        the same 2 * 64 * 64 * 128 flop per trip per wave); > 0.
+ * tflops_out (host): 1e-12 * flop / seconds of the timed launch (a warm-up launch precedes it). */
+int gg_probe_mfma(int mode, int data_kind, int iters, double* tflops_out);
+
+/* HBM streams over `bytes` (a multiple of 4096, larger than the caches for a meaningful figure).
+ *   kind 0: read (16 bytes per lane, summed so the loads cannot be dropped)
+ *   kind 1: copy (read `bytes`, write `bytes`)
+ * gbytes_per_s_out (host): 1e-9 * bytes moved (kind 1: 2 * bytes) / seconds, best of `reps` >= 1 launches. */
+int gg_probe_hbm(int kind, size_t bytes, int reps, double* gbytes_per_s_out);
+
+/* The fetch stream of the GEMM kernels without their compute: 512-thread workgroups, one per compute unit, each
+ * moving 64 KB per step (a K block of a 256 x 256 tile: 256 rows x 128 B of A and as much of B) into LDS with
+ * 16-byte-per-lane buffer loads, `depth` steps in flight (1..7).
+ *   pattern 0: every workgroup re-reads one contiguous 64 KB chunk (L2 hits, full cache lines in address order)
+ *   pattern 1: every workgroup re-reads the same two column blocks [256 rows x 128 B, row pitch K] (L2 hits)
+ *   pattern 2: the kernels' stream: per accelerator die 32 workgroups take a 4 x 8 block of tiles of a problem
+ *              with K = 7168 and walk its 56 K blocks, so an A tile is fetched by 8 workgroups and a B tile by 4
+ *              at about the same time: 12 of 64 fetches miss L2
+ * gbytes_per_s_out: 1e-9 * bytes landed in LDS / seconds over the chip; bytes_per_clk_cu_out: the same per
+ * compute unit and cycle of the nominal shader clock (hipDeviceAttributeClockRate). */
+int gg_probe_lds_fetch(int pattern, int depth, int reps, double* gbytes_per_s_out, double* bytes_per_clk_cu_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -16,6 +16,11 @@ from .binding import (  # noqa: F401
     grouped_gemm_swiglu,
     library_path,
     load_library,
+    load_probe_library,
+    probe_hbm,
+    probe_lds_fetch,
+    probe_library_path,
+    probe_mfma,
     auto_variant,
     auto_variant_padded,
     num_variants,

@@ -37,10 +37,7 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile csrc/gg_fp8.hip for gfx950 into the package directory (needs hipcc, no GPU)."""
-    src = os.path.join(_PKG_DIR, "csrc", "gg_fp8.hip")
-    out = library_path()
+def _hipcc(src: str, out: str, verbose: bool) -> None:
     tmp = out + ".tmp"
     cmd = ["hipcc", *HIPCC_FLAGS, "-I", os.path.join(_ROOT, "include"), "-o", tmp, src]
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -49,9 +46,68 @@ def build_library(verbose: bool = False) -> str:
     if verbose:
         print(res.stderr)
     os.replace(tmp, out)
-    global _lib
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile csrc/gg_fp8.hip (the library) and csrc/gg_probe.hip (the measurement probes of include/gg_probe.h)
+    for gfx950 into the package directory (needs hipcc, no GPU).  Returns the path of the library."""
+    out = library_path()
+    _hipcc(os.path.join(_PKG_DIR, "csrc", "gg_fp8.hip"), out, verbose)
+    _hipcc(os.path.join(_PKG_DIR, "csrc", "gg_probe.hip"), probe_library_path(), verbose)
+    global _lib, _probe
     _lib = None
+    _probe = None
     return out
+
+
+def probe_library_path() -> str:
+    return os.path.join(_PKG_DIR, "libgg_probe.so")
+
+
+_probe = None
+
+
+def load_probe_library() -> ctypes.CDLL:
+    """The measurement probes (include/gg_probe.h); never needed by the hot path."""
+    global _probe
+    if _probe is not None:
+        return _probe
+    path = probe_library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = ctypes.CDLL(path)
+    i32, dp = ctypes.c_int, ctypes.POINTER(ctypes.c_double)
+    lib.gg_probe_mfma.restype = i32
+    lib.gg_probe_mfma.argtypes = [i32, i32, i32, dp]
+    lib.gg_probe_hbm.restype = i32
+    lib.gg_probe_hbm.argtypes = [i32, ctypes.c_size_t, i32, dp]
+    lib.gg_probe_lds_fetch.restype = i32
+    lib.gg_probe_lds_fetch.argtypes = [i32, i32, i32, dp, dp]
+    _probe = lib
+    return lib
+
+
+def _probe_call(fn, *args, n_out=1):
+    outs = [ctypes.c_double(0.0) for _ in range(n_out)]
+    rc = fn(*args, *[ctypes.byref(o) for o in outs])
+    if rc != 0:
+        raise RuntimeError(f"{fn.__name__} failed with hipError_t {rc}")
+    return outs[0].value if n_out == 1 else tuple(o.value for o in outs)
+
+
+def probe_mfma(mode: int, data_kind: int, iters: int = 20000) -> float:
+    """TFLOP/s of a register-only loop of FP8 matrix instructions (gg_probe_mfma)."""
+    return _probe_call(load_probe_library().gg_probe_mfma, mode, data_kind, iters)
+
+
+def probe_hbm(kind: int, nbytes: int = 2 << 30, reps: int = 3) -> float:
+    """GB/s of a plain HBM read (kind 0) or copy (kind 1) (gg_probe_hbm)."""
+    return _probe_call(load_probe_library().gg_probe_hbm, kind, nbytes, reps)
+
+
+def probe_lds_fetch(pattern: int, depth: int = 3, reps: int = 20):
+    """(GB/s over the chip, bytes per clock and compute unit) of the L2 -> LDS fetch stream (gg_probe_lds_fetch)."""
+    return _probe_call(load_probe_library().gg_probe_lds_fetch, pattern, depth, reps, n_out=2)
 
 
 def load_library() -> ctypes.CDLL:

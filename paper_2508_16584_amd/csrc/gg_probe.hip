@@ -1,0 +1,369 @@
+// libgg_probe: the ceilings the grouped GEMM kernels run into, measured with the kernels' own instructions and access
+// shapes and nothing around them (see include/gg_probe.h).  Not part of the hot path.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <vector>
+
+#include "gg_probe.h"
+#include "gemm_kernel.h"   // operand vector types, buffer descriptor flags, wait_vmcnt
+
+namespace {
+
+using gg::v4f;
+using gg::v4i;
+using gg::v8i;
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+#define PROBE_TRY(x)                 \
+  do {                               \
+    hipError_t e_ = (x);             \
+    if (e_ != hipSuccess) {          \
+      cleanup();                     \
+      return (int)e_;                \
+    }                                \
+  } while (0)
+
+int cus() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
+  return n;
+}
+
+// ---------------------------------------------------------------------------------------------- matrix pipe
+// Every wave holds 4 + 4 operand fragments (64 rows x 128 B of each side) and 64 x 64 fp32 accumulators, as a wave
+// of the GEMM kernels does, and multiplies them over and over.  The empty asm per trip keeps the compiler from
+// hoisting the products out of the loop.
+template <int MODE>
+__global__ void __launch_bounds__(512) mfma_loop_kernel(const v8i* __restrict__ src, const float* __restrict__ scales, float* out, int iters) {
+  v8i a[4], b[4];
+  for (int j = 0; j < 4; ++j) {
+    a[j] = src[j * 512 + threadIdx.x];
+    b[j] = src[(4 + j) * 512 + threadIdx.x];
+  }
+  float s[4];
+  for (int j = 0; j < 4; ++j) s[j] = scales[j * 64 + threadIdx.x % 64];
+  float total = 0.f;
+  if constexpr (MODE < 2) {
+    v4f acc[4][4];
+    for (int j = 0; j < 4; ++j)
+      for (int n = 0; n < 4; ++n) acc[j][n] = (v4f){0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+      asm volatile("" : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));
+      v4f p[16];
+      // the FMAs of a product are issued three matrix instructions after it, as in the kernels
+#pragma unroll
+      for (int t = 0; t < 16 + 3; ++t) {
+        if (t < 16) {
+          if (MODE == 1) p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b[t % 4], a[t / 4], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+          else acc[t / 4][t % 4] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b[t % 4], a[t / 4], acc[t / 4][t % 4], 0, 0, 0, 0, 0, 0);
+        }
+        if (MODE == 1 && t >= 3) {
+          const int u = t - 3;
+          acc[u / 4][u % 4] += p[u] * s[u / 4];
+        }
+      }
+      if (MODE == 1) {
+#pragma unroll
+        for (int t = 0; t < 16 + 3; ++t) {
+          if (t < 16) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (t >= 3) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+        }
+      }
+    }
+    for (int j = 0; j < 4; ++j)
+      for (int n = 0; n < 4; ++n) total += acc[j][n][0] + acc[j][n][1] + acc[j][n][2] + acc[j][n][3];
+  } else {
+    // 2 x 2 blocks of 32 x 32 outputs; operands a[2 * block + half], b[2 * block + half] for the two 64-wide halves
+    // of a 128-wide scale block
+    v16f acc[2][2];
+    for (int j = 0; j < 2; ++j)
+      for (int n = 0; n < 2; ++n)
+        for (int i = 0; i < 16; ++i) acc[j][n][i] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+      asm volatile("" : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));
+      if constexpr (MODE == 2) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          acc[u / 2][u % 2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[2 * (u % 2)], a[2 * (u / 2)], acc[u / 2][u % 2], 0, 0, 0, 0, 0, 0);
+          acc[u / 2][u % 2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[2 * (u % 2) + 1], a[2 * (u / 2) + 1], acc[u / 2][u % 2], 0, 0, 0, 0, 0, 0);
+        }
+      } else {
+        v16f p[4];
+        v16f zero;
+        for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+#pragma unroll
+        for (int u = 0; u < 4 + 1; ++u) {
+          if (u < 4) {
+            p[u] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[2 * (u % 2)], a[2 * (u / 2)], zero, 0, 0, 0, 0, 0, 0);
+            p[u] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[2 * (u % 2) + 1], a[2 * (u / 2) + 1], p[u], 0, 0, 0, 0, 0, 0);
+          }
+          if (u >= 1) {
+            const int v = u - 1;
+            acc[v / 2][v % 2] += p[v] * s[v / 2];
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4 + 1; ++u) {
+          if (u < 4) __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+          if (u >= 1) __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);
+        }
+      }
+    }
+    for (int j = 0; j < 2; ++j)
+      for (int n = 0; n < 2; ++n)
+        for (int i = 0; i < 16; ++i) total += acc[j][n][i];
+  }
+  out[blockIdx.x * 512 + threadIdx.x] = total;
+}
+
+// e4m3 code of a float, round to nearest (ties away: operand statistics are all that matters here)
+uint8_t e4m3_of(float v) {
+  const float av = std::fabs(v);
+  if (av < 0.0009765625f) return 0;
+  int e = 0;
+  const float m = std::frexp(av, &e);   // av = m * 2^e, m in [0.5, 1)
+  int E = e - 1 + 7;
+  int mant = (int)std::lround((m * 2.f - 1.f) * 8.f);
+  if (mant == 8) {
+    mant = 0;
+    ++E;
+  }
+  if (E < 1) {
+    E = 0;
+    mant = (int)std::lround(av * 512.f);
+    if (mant > 7) {
+      E = 1;
+      mant = 0;
+    }
+  }
+  if (E > 15 || (E == 15 && mant > 6)) {
+    E = 15;
+    mant = 6;
+  }
+  return (uint8_t)((v < 0 ? 0x80 : 0) | (E << 3) | mant);
+}
+
+// ---------------------------------------------------------------------------------------------- HBM streams
+__global__ void __launch_bounds__(256) hbm_read_kernel(const v4i* __restrict__ src, size_t n16, int* out) {
+  int acc = 0;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
+    const v4i v = __builtin_nontemporal_load(src + i);
+    acc += v.x ^ v.y ^ v.z ^ v.w;
+  }
+  if (acc == 0x5EEDBEEF) out[0] = acc;   // practically never: keeps the loads alive
+}
+__global__ void __launch_bounds__(256) hbm_copy_kernel(const v4i* __restrict__ src, v4i* __restrict__ dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+// ---------------------------------------------------------------------------------------------- L2 -> LDS fetch stream
+// One step = 8 fetch instructions per wave (4 slabs of 8 rows x 128 B of "A", 4 of "B"): 64 KB per workgroup.  All
+// steps land in the same 64 KB of LDS (nobody reads it); how many steps are in flight is set by the wait alone.
+constexpr int kFetchK = 7168, kFetchKB = kFetchK / 128;
+constexpr size_t kFetchABytes = (size_t)8 * 4 * 256 * kFetchK;   // per die: 4 tiles of 256 rows
+constexpr size_t kFetchBBytes = (size_t)8 * 8 * 256 * kFetchK;   // per die: 8 tiles of 256 rows
+
+template <int DEPTH>
+__global__ void __launch_bounds__(512) lds_fetch_kernel(const uint8_t* A, const uint8_t* B, int pattern, int steps) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l = threadIdx.x & 63;
+  const int b = blockIdx.x;
+  const int xcd = b & 7, slot = (b >> 3) & 31;
+  const __amdgpu_buffer_rsrc_t dA = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, (int)kFetchABytes, GG_RSRC_FLAGS);
+  const __amdgpu_buffer_rsrc_t dB = __builtin_amdgcn_make_buffer_rsrc((void*)B, 0, (int)kFetchBBytes, GG_RSRC_FLAGS);
+  int vA, vB, pitch_rows;     // lane offsets of slab 0; a slab further down is pitch_rows bytes on
+  const int row = w * 8 + (l >> 3), chunk = (l & 7) << 4;
+  if (pattern == 0) {
+    // contiguous: "rows" of 128 B one after the other, 32 KB from each buffer
+    vA = b * 32768 + row * 128 + chunk;
+    vB = vA;
+    pitch_rows = 64 * 128;
+  } else if (pattern == 1) {
+    vA = (b & 31) * 256 * kFetchK + (b % kFetchKB) * 128 + row * kFetchK + chunk;
+    vB = (b & 63) * 256 * kFetchK + (b % kFetchKB) * 128 + row * kFetchK + chunk;
+    pitch_rows = 64 * kFetchK;
+  } else {
+    vA = (xcd * 4 + (slot >> 3)) * 256 * kFetchK + row * kFetchK + chunk;
+    vB = (xcd * 8 + (slot & 7)) * 256 * kFetchK + row * kFetchK + chunk;
+    pitch_rows = 64 * kFetchK;
+  }
+  int kb = 0;
+  for (int s = 0; s < steps; ++s) {
+    const int so = pattern == 2 ? kb * 128 : 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dA, GG_LDS_PTR(lds + (w + i * 8) * 1024), 16, vA + i * pitch_rows, so, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(lds + 32768 + (w + i * 8) * 1024), 16, vB + i * pitch_rows, so, 0, 0);
+    gg::wait_vmcnt<(DEPTH - 1) * 8>();
+    __builtin_amdgcn_s_barrier();     // the kernels synchronise once per K block
+    kb = kb + 1 == kFetchKB ? 0 : kb + 1;
+  }
+  gg::wait_vmcnt<0>();
+}
+
+template <int DEPTH>
+hipError_t launch_fetch(const uint8_t* A, const uint8_t* B, int pattern, int steps, int grid) {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lds_fetch_kernel<DEPTH>), hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(lds_fetch_kernel<DEPTH>, dim3(grid), dim3(512), 65536, 0, A, B, pattern, steps);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+extern "C" {
+
+int gg_probe_mfma(int mode, int data_kind, int iters, double* tflops_out) {
+  if (mode < 0 || mode > 3 || data_kind < 0 || data_kind > 2 || iters <= 0 || !tflops_out) return (int)hipErrorInvalidValue;
+  v8i* src = nullptr;
+  float *scales = nullptr, *out = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  auto cleanup = [&] {
+    if (src) (void)hipFree(src);
+    if (scales) (void)hipFree(scales);
+    if (out) (void)hipFree(out);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+  };
+  const int blocks = cus();
+  std::vector<uint8_t> h((size_t)8 * 512 * 32);
+  unsigned x = 777u;
+  for (uint8_t& byte : h) {
+    x = x * 1664525u + 1013904223u;
+    if (data_kind == 0) {
+      byte = 0x38;
+    } else if (data_kind == 2) {
+      byte = (uint8_t)(x >> 24);
+      if ((byte & 0x7F) == 0x7F) byte = 0x40;
+    } else {
+      // sum of 4 uniforms: close enough to a normal sample; 3 sigma at the format's largest value
+      unsigned y = x;
+      float g = 0.f;
+      for (int i = 0; i < 4; ++i) {
+        y = y * 1664525u + 1013904223u;
+        g += (y >> 8) / 16777216.0f - 0.5f;
+      }
+      byte = e4m3_of(g * 1.7320508f * (448.0f / 3.0f));
+    }
+  }
+  std::vector<float> ones(256, 1.0f);
+  PROBE_TRY(hipMalloc(&src, h.size()));
+  PROBE_TRY(hipMalloc(&scales, ones.size() * 4));
+  PROBE_TRY(hipMalloc(&out, (size_t)blocks * 512 * 4));
+  PROBE_TRY(hipMemcpy(src, h.data(), h.size(), hipMemcpyHostToDevice));
+  PROBE_TRY(hipMemcpy(scales, ones.data(), ones.size() * 4, hipMemcpyHostToDevice));
+  PROBE_TRY(hipEventCreate(&e0));
+  PROBE_TRY(hipEventCreate(&e1));
+  for (int rep = 0; rep < 2; ++rep) {   // the first launch warms up
+    PROBE_TRY(hipEventRecord(e0, 0));
+    if (mode == 0) hipLaunchKernelGGL(mfma_loop_kernel<0>, dim3(blocks), dim3(512), 0, 0, src, scales, out, iters);
+    else if (mode == 1) hipLaunchKernelGGL(mfma_loop_kernel<1>, dim3(blocks), dim3(512), 0, 0, src, scales, out, iters);
+    else if (mode == 2) hipLaunchKernelGGL(mfma_loop_kernel<2>, dim3(blocks), dim3(512), 0, 0, src, scales, out, iters);
+    else hipLaunchKernelGGL(mfma_loop_kernel<3>, dim3(blocks), dim3(512), 0, 0, src, scales, out, iters);
+    PROBE_TRY(hipGetLastError());
+    PROBE_TRY(hipEventRecord(e1, 0));
+    PROBE_TRY(hipEventSynchronize(e1));
+  }
+  float ms = 0.f;
+  PROBE_TRY(hipEventElapsedTime(&ms, e0, e1));
+  const double flop = 2.0 * 64 * 64 * 128 * (double)iters * blocks * 8.0;
+  *tflops_out = flop / ((double)ms * 1e-3) * 1e-12;
+  cleanup();
+  return 0;
+}
+
+int gg_probe_hbm(int kind, size_t bytes, int reps, double* gbytes_per_s_out) {
+  if (kind < 0 || kind > 1 || bytes == 0 || bytes % 4096 != 0 || reps < 1 || !gbytes_per_s_out) return (int)hipErrorInvalidValue;
+  v4i *src = nullptr, *dst = nullptr;
+  int* flag = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  auto cleanup = [&] {
+    if (src) (void)hipFree(src);
+    if (dst) (void)hipFree(dst);
+    if (flag) (void)hipFree(flag);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+  };
+  PROBE_TRY(hipMalloc(&src, bytes));
+  if (kind == 1) PROBE_TRY(hipMalloc(&dst, bytes));
+  PROBE_TRY(hipMalloc(&flag, 4));
+  PROBE_TRY(hipMemset(src, 1, bytes));
+  PROBE_TRY(hipEventCreate(&e0));
+  PROBE_TRY(hipEventCreate(&e1));
+  const int grid = cus() * 8;
+  float best = 0.f;
+  for (int rep = 0; rep < reps + 1; ++rep) {   // the first launch warms up
+    PROBE_TRY(hipEventRecord(e0, 0));
+    if (kind == 0) hipLaunchKernelGGL(hbm_read_kernel, dim3(grid), dim3(256), 0, 0, src, bytes / 16, flag);
+    else hipLaunchKernelGGL(hbm_copy_kernel, dim3(grid), dim3(256), 0, 0, src, dst, bytes / 16);
+    PROBE_TRY(hipGetLastError());
+    PROBE_TRY(hipEventRecord(e1, 0));
+    PROBE_TRY(hipEventSynchronize(e1));
+    float ms = 0.f;
+    PROBE_TRY(hipEventElapsedTime(&ms, e0, e1));
+    if (rep > 0 && (best == 0.f || ms < best)) best = ms;
+  }
+  *gbytes_per_s_out = (double)bytes * (kind == 1 ? 2.0 : 1.0) / ((double)best * 1e-3) * 1e-9;
+  cleanup();
+  return 0;
+}
+
+int gg_probe_lds_fetch(int pattern, int depth, int reps, double* gbytes_per_s_out, double* bytes_per_clk_cu_out) {
+  if (pattern < 0 || pattern > 2 || depth < 1 || depth > 7 || reps < 1 || !gbytes_per_s_out || !bytes_per_clk_cu_out) return (int)hipErrorInvalidValue;
+  uint8_t *A = nullptr, *B = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  auto cleanup = [&] {
+    if (A) (void)hipFree(A);
+    if (B) (void)hipFree(B);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+  };
+  // one workgroup per compute unit, at most the 256 the patterns are laid out for (every offset stays inside the
+  // two buffers for any such grid: pattern 0 reaches 256 * 32 KB, the others tile (8 * 4 or 8 * 8) * 256 rows)
+  int grid = cus();
+  if (grid > 256) grid = 256;
+  grid -= grid % 8;
+  if (grid < 8) return (int)hipErrorInvalidValue;
+  PROBE_TRY(hipMalloc(&A, kFetchABytes));
+  PROBE_TRY(hipMalloc(&B, kFetchBBytes));
+  PROBE_TRY(hipMemset(A, 0x38, kFetchABytes));
+  PROBE_TRY(hipMemset(B, 0x38, kFetchBBytes));
+  PROBE_TRY(hipEventCreate(&e0));
+  PROBE_TRY(hipEventCreate(&e1));
+  const int steps = reps * kFetchKB;
+  for (int rep = 0; rep < 2; ++rep) {   // the first launch warms up
+    PROBE_TRY(hipEventRecord(e0, 0));
+    hipError_t e = hipSuccess;
+    switch (depth) {
+      case 1: e = launch_fetch<1>(A, B, pattern, steps, grid); break;
+      case 2: e = launch_fetch<2>(A, B, pattern, steps, grid); break;
+      case 3: e = launch_fetch<3>(A, B, pattern, steps, grid); break;
+      case 4: e = launch_fetch<4>(A, B, pattern, steps, grid); break;
+      case 5: e = launch_fetch<5>(A, B, pattern, steps, grid); break;
+      case 6: e = launch_fetch<6>(A, B, pattern, steps, grid); break;
+      default: e = launch_fetch<7>(A, B, pattern, steps, grid); break;
+    }
+    PROBE_TRY(e);
+    PROBE_TRY(hipEventRecord(e1, 0));
+    PROBE_TRY(hipEventSynchronize(e1));
+  }
+  float ms = 0.f;
+  PROBE_TRY(hipEventElapsedTime(&ms, e0, e1));
+  int dev = 0, khz = 0;
+  PROBE_TRY(hipGetDevice(&dev));
+  PROBE_TRY(hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, dev));
+  const double bytes = 65536.0 * steps * grid, sec = (double)ms * 1e-3;
+  *gbytes_per_s_out = bytes / sec * 1e-9;
+  *bytes_per_clk_cu_out = khz > 0 ? bytes / sec / ((double)khz * 1e3) / grid : 0.0;
+  cleanup();
+  return 0;
+}
+
+}  // extern "C"

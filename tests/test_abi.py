@@ -36,6 +36,25 @@ def test_every_declared_symbol_is_exported(lib):
     assert sorted(binding.EXPORTED_SYMBOLS) == names
 
 
+def test_probe_library_exports_what_its_header_declares():
+    """include/gg_probe.h: the measurement probes live in a library of their own (no compute call without a GPU)."""
+    header = os.path.join(os.path.dirname(HEADER), "gg_probe.h")
+    text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(gg_probe_\w+)\s*\(", text)))
+    assert names == ["gg_probe_hbm", "gg_probe_lds_fetch", "gg_probe_mfma"]
+    if not os.path.exists(gg.probe_library_path()):
+        gg.build_library()
+    probe = gg.load_probe_library()
+    for n in names:
+        assert hasattr(probe, n), f"{n} is declared in gg_probe.h but not exported"
+    # argument checks come before any GPU call
+    out = ctypes.c_double(0.0)
+    assert probe.gg_probe_mfma(4, 0, 10, ctypes.byref(out)) != 0 and probe.gg_probe_mfma(0, 0, 0, ctypes.byref(out)) != 0
+    assert probe.gg_probe_hbm(2, 4096, 1, ctypes.byref(out)) != 0 and probe.gg_probe_hbm(0, 100, 1, ctypes.byref(out)) != 0
+    assert probe.gg_probe_lds_fetch(3, 3, 1, ctypes.byref(out), ctypes.byref(out)) != 0
+    assert probe.gg_probe_lds_fetch(0, 8, 1, ctypes.byref(out), ctypes.byref(out)) != 0
+
+
 def test_version_status_strings_and_variants(lib):
     assert gg.version() >= 100
     texts = {gg.status_str(s) for s in range(7)}
