@@ -329,6 +329,83 @@ def bench_ceilings():
                       "peaks": {"mfma_fp8_dense_TFLOPs": 5000.0, "hbm_GBps": 8000.0}}))
 
 
+def bench_pad_path(args, cfg, dev):
+    """The comparison path of Sec. 3 step by step: pad (offsets + row copies), the GEMM on the padded problem, unpad.
+    Each step is timed alone, `steps` launches back to back over rotating buffer sets (cold caches); the copies are
+    HBM-bound: algorithmic bytes = what the step must read plus what it must write, each once."""
+    import numpy as np
+    import torch
+
+    import paper_2508_16584_amd as gg
+    from workloads import make_problem
+    km = args.sa_layout == "kmajor"
+    p = make_problem(cfg, device=dev)
+    G, M, N, K = p["G"], p["M_total"], p["N"], p["K"]
+    KB = K // 128
+    cap = gg.padded_rows_cap(G, M)
+    off = p["group_offsets"]
+    SA = p["SA"].t().contiguous() if km else p["SA"]
+    copies = args.copies or max(2, min(6, int(np.ceil(1.0e9 / (cap * (K + 2 * N))))))
+    sets = []
+    for i in range(copies):
+        sets.append({
+            "A": p["A"] if i == 0 else p["A"].clone(), "SA": SA if i == 0 else SA.clone(),
+            "A_pad": torch.empty((cap, K), dtype=torch.uint8, device=dev),
+            "SA_pad": torch.empty((KB, cap) if km else (cap, KB), dtype=torch.float32, device=dev),
+            "C_pad": torch.empty((cap, N), dtype=torch.bfloat16, device=dev),
+            "C": torch.empty((M, N), dtype=torch.bfloat16, device=dev)})
+    poff = None
+    for s_ in sets:      # every set holds a valid padded problem before anything is timed
+        _, _, poff = gg.pad(s_["A"], s_["SA"], off, cap, sa_kmajor=km, A_pad=s_["A_pad"], SA_pad=s_["SA_pad"])
+        gg.grouped_gemm_padded(s_["A_pad"], s_["SA_pad"], p["B"], p["SB"], poff, s_["C_pad"], sa_kmajor=km)
+    torch.cuda.synchronize()
+    m_pad = int(poff[-1].item())
+
+    def pad_step(i):
+        s_ = sets[i % copies]
+        gg.pad(s_["A"], s_["SA"], off, cap, sa_kmajor=km, A_pad=s_["A_pad"], SA_pad=s_["SA_pad"])
+
+    def gemm_step(i):
+        s_ = sets[i % copies]
+        gg.grouped_gemm_padded(s_["A_pad"], s_["SA_pad"], p["B"], p["SB"], poff, s_["C_pad"], sa_kmajor=km)
+
+    def unpad_step(i):
+        s_ = sets[i % copies]
+        gg.unpad(s_["C_pad"], off, poff, M, C=s_["C"])
+
+    row = K + 4 * KB
+    steps_out = {}
+    for name, fn, alg in (("pad", pad_step, M * row + m_pad * row + 8 * (G + 1)),
+                          ("padded_gemm", gemm_step, None),
+                          ("unpad", unpad_step, 2 * M * 2 * N)):
+        clock_warmup(fn, args.clock_warmup_ms / 3)
+        for i in range(args.warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        wall_ms, ev_ms = timed_region(fn, args.steps)
+        entry = {"ms_per_step": round(wall_ms, 4), "kernel_avg_ms": round(ev_ms, 4)}
+        if alg is not None:
+            ach = alg / (ev_ms * 1e-3) / 1e9
+            entry["roofline"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": 8000.0, "unit": "GB/s",
+                                 "frac": round(ach / 8000.0, 4), "algorithmic_bytes": int(alg), "traffic": None}
+        else:
+            entry["TFLOPs_on_valid_rows"] = round(2.0 * M * N * K / (wall_ms * 1e-3) / 1e12, 1)
+            entry["variant"] = gg.variant_name(gg.auto_variant_padded(G, cap, N, K))
+        steps_out[name] = entry
+    total = sum(v["ms_per_step"] for v in steps_out.values())
+    print(json.dumps({
+        "metric": "pad-then-GEMM comparison path (Sec. 3), each step timed alone", "value": round(total, 4), "unit": "ms",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(total, 4), "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8 / fp32 / bf16 copies; fp8 e4m3 x e4m3 -> fp32 -> bf16 GEMM",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "op": "pad_path", "G": G, "M_total": M, "M_pad": m_pad, "M_pad_cap": cap,
+                   "N": N, "K": K, "sa_layout": args.sa_layout, "buffer_sets_rotated": copies},
+        "pad": steps_out["pad"], "padded_gemm": steps_out["padded_gemm"], "unpad": steps_out["unpad"],
+        "note": "pad = gg_pad_offsets_kernel + gg_pad_rows_kernel (reads the valid rows of A and S_A, writes the M_pad rows "
+                "of the padded problem); unpad reads and writes the valid rows of the output",
+    }))
+
+
 def pmc_summary(folder):
     """Per kernel and counter, the mean over the dispatches in rocprofv3's `*counter_collection.csv` files under
     `folder` (one row per dispatch and counter), as a markdown table: what the summaries under profiles/ are made of."""
@@ -355,12 +432,13 @@ def main():
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="gate_up")
-    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows", "swiglu_quantize_rows", "expert_mlp", "ceilings"],
+    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows", "swiglu_quantize_rows", "expert_mlp", "ceilings", "pad_path"],
                     help="grouped_gemm: the hot path (default, the headline metric); quantize_rows: the producer of its "
                          "A operand on the same workload's activation shape; swiglu_quantize_rows: activation + quantiser "
                          "on the workload's output shape [M_total, N] (N = 2 x intermediate width); expert_mlp: the whole forward "
                          "chain quantise -> GEMM -> activation+quantise -> GEMM on the workload's routing, padding-free "
-                         "against the same chain on 128-row padded groups; ceilings: no workload, the probes of "
+                         "against the same chain on 128-row padded groups; pad_path: the three steps of the pad-then-GEMM comparison path "
+                         "(Sec. 3) each timed alone, the two copies against the HBM roofline; ceilings: no workload, the probes of "
                          "include/gg_probe.h (register-only matrix loops, HBM streams, the L2 -> LDS fetch stream)")
     ap.add_argument("--clock-warmup-ms", type=float, default=150.0,
                     help="untimed launches for about this long before the W warm-up steps, so that the timed steps run at "
@@ -409,6 +487,9 @@ def main():
         return
     if args.op == "expert_mlp":
         bench_expert_mlp(args, cfg, dev)
+        return
+    if args.op == "pad_path":
+        bench_pad_path(args, cfg, dev)
         return
     p = make_problem(cfg, device=dev)
     G, M, N, K = p["G"], p["M_total"], p["N"], p["K"]

@@ -171,8 +171,13 @@ int64_t gg_fp8_padded_rows_cap(int G, int64_t M_total);
 /* Writes padded_offsets[G+1] (padded_offsets[0] = 0, each group rounded up to a
  * multiple of 128 rows), copies the valid rows of A [M_total,K] and SA
  * [M_total,K/128] to A_pad [M_pad_cap,K] and SA_pad [M_pad_cap,K/128] and
- * zero-fills every other row up to M_pad_cap.  M_pad_cap must be at least
- * gg_fp8_padded_rows_cap(G, M_total) (GG_ERR_SHAPE otherwise). */
+ * zero-fills the pad rows of every group, i.e. every other row of
+ * [0, padded_offsets[G]) (Sec. 3: the baseline allocates and fills the padded
+ * problem, M_pad rows).  Rows from padded_offsets[G] up to M_pad_cap exist only
+ * because the host cannot know M_pad without a synchronisation: they belong to
+ * no group, no call of this library reads them, and they are left untouched.
+ * M_pad_cap must be at least gg_fp8_padded_rows_cap(G, M_total) (GG_ERR_SHAPE
+ * otherwise). */
 int gg_fp8_pad(const void* A, const float* SA, const int32_t* group_offsets,
                void* A_pad, float* SA_pad, int32_t* padded_offsets,
                int G, int64_t M_total, int64_t M_pad_cap, int K, void* stream);

@@ -385,9 +385,10 @@ def padded_rows_cap(G: int, M_total: int) -> int:
     return int(load_library().gg_fp8_padded_rows_cap(G, M_total))
 
 
-def pad(A, SA, group_offsets, M_pad_cap: int | None = None, stream=None, sa_kmajor=False):
+def pad(A, SA, group_offsets, M_pad_cap: int | None = None, stream=None, sa_kmajor=False, A_pad=None, SA_pad=None):
     """gg_fp8_pad (gg_fp8_pad_ex when sa_kmajor: SA [K/128, M_total] -> SA_pad [K/128, M_pad_cap]): returns
-    (A_pad, SA_pad, padded_offsets) with every group at a multiple of 128 rows."""
+    (A_pad, SA_pad, padded_offsets) with every group at a multiple of 128 rows.  Rows past the last padded group are
+    not written (the buffers come from torch.empty unless the caller passes A_pad and SA_pad)."""
     lib = load_library()
     _want(A, "A", torch.uint8, 2)
     _want(SA, "SA", torch.float32, 2)
@@ -396,11 +397,18 @@ def pad(A, SA, group_offsets, M_pad_cap: int | None = None, stream=None, sa_kmaj
     G = group_offsets.shape[0] - 1
     if M_pad_cap is None:
         M_pad_cap = padded_rows_cap(G, M_total)
-    A_pad = torch.empty((M_pad_cap, K), dtype=torch.uint8, device=A.device)
     KB = -(-K // 128)
     if tuple(SA.shape) != ((KB, M_total) if sa_kmajor else (M_total, KB)):
         raise ValueError("SA does not have the shape of its storage order")
-    SA_pad = torch.empty((KB, M_pad_cap) if sa_kmajor else (M_pad_cap, KB), dtype=torch.float32, device=A.device)
+    sa_pad_shape = (KB, M_pad_cap) if sa_kmajor else (M_pad_cap, KB)
+    if A_pad is None:
+        A_pad = torch.empty((M_pad_cap, K), dtype=torch.uint8, device=A.device)
+    if SA_pad is None:
+        SA_pad = torch.empty(sa_pad_shape, dtype=torch.float32, device=A.device)
+    _want(A_pad, "A_pad", torch.uint8, 2)
+    _want(SA_pad, "SA_pad", torch.float32, 2)
+    if tuple(A_pad.shape) != (M_pad_cap, K) or tuple(SA_pad.shape) != sa_pad_shape:
+        raise ValueError("A_pad / SA_pad do not have M_pad_cap rows of the inputs' width")
     poff = torch.empty(G + 1, dtype=torch.int32, device=A.device)
     args = (_ptr(A), _ptr(SA), _ptr(group_offsets), _ptr(A_pad), _ptr(SA_pad), _ptr(poff), G, M_total, M_pad_cap, K,
             _stream(stream))

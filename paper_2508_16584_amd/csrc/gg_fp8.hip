@@ -545,7 +545,7 @@ int gg_fp8_unpad(const void* C_pad, const int32_t* group_offsets, const int32_t*
   if (N % 8 != 0) return GG_ERR_UNSUPPORTED;
   if (G == 0 || M_total == 0) return GG_OK;
   if (!C_pad || !group_offsets || !padded_offsets || !C) return GG_ERR_NULL;
-  const int64_t nblocks = (M_total + gg::PAD_BLOCK_ROWS - 1) / gg::PAD_BLOCK_ROWS;
+  const int64_t nblocks = (M_total + gg::UNPAD_BLOCK_ROWS - 1) / gg::UNPAD_BLOCK_ROWS;
   int64_t grid = (int64_t)device_cus() * 8;
   if (grid > nblocks) grid = nblocks;
   hipLaunchKernelGGL(gg::gg_unpad_rows_kernel, dim3((unsigned)grid), dim3(gg::PAD_THREADS), 0,

@@ -177,9 +177,11 @@ __device__ __forceinline__ int swiglu2(const int g_raw, const int u_raw) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     // sigmoid through t = exp(-|g|) in [0, 1]: no overflow for any g; the hardware exponential (a few fp32
-    // ulps, denormal results flushed: t = 0 below g = -87.3) and reciprocal are far inside the bf16 rounding
+    // ulps, denormal results flushed: t = 0 below g = -87.3) and the hardware reciprocal (1 ulp; 1 + t lies in
+    // [1, 2]) are far inside the bf16 rounding.  A division here compiles to the 10-instruction correctly
+    // rounded sequence, which made this kernel bound by vector arithmetic.
     const float t = __expf(-__builtin_fabsf(g[h]));
-    const float sig = __fdividef(g[h] >= 0.f ? 1.0f : t, 1.0f + t);
+    const float sig = (g[h] >= 0.f ? 1.0f : t) * __builtin_amdgcn_rcpf(1.0f + t);
     a[h] = g[h] * sig * u[h];
   }
   typedef __bf16 bf2 __attribute__((ext_vector_type(2)));

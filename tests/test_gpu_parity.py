@@ -299,11 +299,23 @@ def test_pad_path_equals_padding_free_path_bitwise(sizes, N, K):
     assert cap == 128 * (-(-M // 128) + len(sizes))
     A_pad, SA_pad, poff = gg.pad(A, SA, off)
     torch.cuda.synchronize()
-    # pad kernel against the oracle's pad (bytes, scales and offsets exactly)
-    A_ref, SA_ref, poff_ref = orc.pad(A_h, SA_h, off_h, rows_cap=cap)
+    # pad kernel against the oracle's pad (bytes, scales and offsets exactly) on the rows of the padded problem
+    A_ref, SA_ref, poff_ref = orc.pad(A_h, SA_h, off_h)
+    m_pad = int(poff_ref[-1])
     assert np.array_equal(poff.cpu().numpy(), poff_ref.astype(np.int32))
-    assert np.array_equal(A_pad.cpu().numpy(), A_ref)
-    assert np.array_equal(SA_pad.cpu().numpy(), SA_ref)
+    assert np.array_equal(A_pad.cpu().numpy()[:m_pad], A_ref)
+    assert np.array_equal(SA_pad.cpu().numpy()[:m_pad], SA_ref)
+    # rows between the padded problem's end and the capacity belong to no group and keep what the caller put there,
+    # in both storage orders of the scales
+    K = A.shape[1]
+    for km in (False, True):
+        A_can = torch.full((cap, K), 0xA5, dtype=torch.uint8, device=DEV)
+        SA_can = torch.full((K // 128, cap) if km else (cap, K // 128), -7.0, dtype=torch.float32, device=DEV)
+        gg.pad(A, SA.t().contiguous() if km else SA, off, cap, sa_kmajor=km, A_pad=A_can, SA_pad=SA_can)
+        torch.cuda.synchronize()
+        sa_rows = SA_can.t() if km else SA_can
+        assert np.array_equal(A_can.cpu().numpy()[:m_pad], A_ref) and np.array_equal(sa_rows.cpu().numpy()[:m_pad], SA_ref)
+        assert m_pad < cap and (A_can[m_pad:] == 0xA5).all() and (sa_rows[m_pad:] == -7.0).all()
     # padded GEMM + unpad against the padding-free GEMM: bitwise equal on valid rows (Sec. 3.2)
     C_pad = gg.grouped_gemm_padded(A_pad, SA_pad, B, SB, poff)
     C2 = gg.unpad(C_pad, off, poff, M)

@@ -122,8 +122,9 @@ def test_kmajor_pad_path_bitwise(sizes, N, K):
     A_pad0, SA_pad0, poff0 = gg.pad(dA, dSA, doff)
     A_pad, SA_pad, poff = gg.pad(dA, SAk, doff, sa_kmajor=True)
     torch.cuda.synchronize()
-    assert torch.equal(poff, poff0) and torch.equal(A_pad, A_pad0)
-    assert torch.equal(SA_pad.view(torch.int32), SA_pad0.t().contiguous().view(torch.int32)), "padded scales differ between the orders"
+    m_pad = int(poff[-1].item())          # rows past the last padded group are not written
+    assert torch.equal(poff, poff0) and torch.equal(A_pad[:m_pad], A_pad0[:m_pad])
+    assert torch.equal(SA_pad[:, :m_pad].contiguous().view(torch.int32), SA_pad0[:m_pad].t().contiguous().view(torch.int32)), "padded scales differ between the orders"
     C_pad = gg.grouped_gemm_padded(A_pad, SA_pad, dB, dSB, poff, sa_kmajor=True)
     C_back = gg.unpad(C_pad, doff, poff, M)
     C_row = gg.grouped_gemm(dA, dSA, dB, dSB, doff)
