@@ -628,16 +628,20 @@ def main():
                 rc |= lib.gg_fp8_unpad(vp(C_pad), vp(s["group_offsets"]), vp(poff), vp(s["C"]), G, M, N, stream)
             assert rc == 0
 
+        # the two loops alternate twice and each keeps its faster pass: the first loop after the headline's tends to run
+        # in another clock state than the second, which once made the path WITH the extra copy the faster of the two
         res = {}
-        for with_unpad in (False, True):
-            for i in range(max(3, args.warmup // 2)):
-                pad_step(i, with_unpad)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for i in range(args.steps):
-                pad_step(i, with_unpad)
-            torch.cuda.synchronize()
-            res[with_unpad] = (time.perf_counter() - t0) * 1e3 / args.steps
+        for rnd in range(2):
+            for with_unpad in (False, True):
+                for i in range(max(3, args.warmup // 2)):
+                    pad_step(i, with_unpad)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for i in range(args.steps):
+                    pad_step(i, with_unpad)
+                torch.cuda.synchronize()
+                t = (time.perf_counter() - t0) * 1e3 / args.steps
+                res[with_unpad] = min(t, res.get(with_unpad, t))
         m_pad = int(poff[-1].item())
         KB = K // 128
         row_bytes = K + 4 * KB + 2 * N                      # A, SA and C bytes per row
@@ -698,7 +702,11 @@ def main():
                       f"NumPy float64 oracle, {cpu_s:.1f} s",
             "gpu_bits_equal_oracle_on_sample": round(float(np.mean(got == ref["C"])), 5),
             "tolerance_asserted": "|gpu - D| <= max(ulp_bf16(D), ulp_bf16(D)/2 + 2^-10 S) on every sampled output",
+            # in ulps of D: large only where D is a cancelled sum far below its terms (those outputs are judged by
+            # the 2^-10 S term); max_err_over_bound is the worst ratio of error to tolerance (<= 1 by the assertion)
             "max_err_ulp": round(float(np.max(err / ulp)), 3),
+            "max_err_over_bound": round(float(np.max(err / bound)), 4),
+            "max_err_ulp_where_D_exceeds_S_over_1024": round(float(np.max((err / ulp)[np.abs(ref["D"]) >= S / 1024.0])), 3),
             "outputs_that_needed_the_floor": int(np.sum(err > ulp)), "outputs_compared": int(err.size),
         }
 
