@@ -316,6 +316,8 @@ def bench_ceilings():
              "32x32x64 accumulating", "2 x 32x32x64 per scale block + 16 FMA"]
     kinds = ["constant 1.0", "normal-like e4m3", "uniform random bytes"]
     mfma = {m: {k: round(gg.probe_mfma(mi, ki, 20000), 1) for ki, k in enumerate(kinds)} for mi, m in enumerate(modes)}
+    mixes = [(0, 0, 0), (2, 0, 0), (4, 0, 0), (8, 0, 0), (0, 1, 0), (0, 2, 0), (0, 0, 1), (0, 0, 2), (2, 1, 1), (2, 1, 2)]
+    issue = {f"+{a} scalar +{b} vector +{c} LDS reads per matrix instruction": round(gg.probe_issue_mix(a, b, c), 1) for a, b, c in mixes}
     hbm = {"read_GBps": round(gg.probe_hbm(0), 1), "copy_GBps": round(gg.probe_hbm(1), 1)}
     patterns = ["L2-resident contiguous 64 KB", "L2-resident column blocks [256 rows x 128 B] x 2",
                 "kernel stream (4 x 8 tiles per die, K = 7168)"]
@@ -325,7 +327,8 @@ def bench_ceilings():
         for depth in (1, 2, 3, 4, 6):
             gbps, bpc = gg.probe_lds_fetch(pi, depth, 20)
             fetch[pn][f"depth {depth}"] = {"GBps": round(gbps, 1), "B_per_clk_per_CU_at_nominal_clock": round(bpc, 2)}
-    print(json.dumps({"op": "ceilings", "mfma_fp8_TFLOPs": mfma, "hbm": hbm, "l2_to_lds_fetch": fetch,
+    print(json.dumps({"op": "ceilings", "mfma_fp8_TFLOPs": mfma,
+                      "block_scaled_loop_on_constant_operands_with_more_instructions_TFLOPs": issue, "hbm": hbm, "l2_to_lds_fetch": fetch,
                       "peaks": {"mfma_fp8_dense_TFLOPs": 5000.0, "hbm_GBps": 8000.0}}))
 
 

@@ -5,6 +5,7 @@
  * run into, with the same instructions and access shapes the kernels use and nothing else around them:
  *   - the matrix instruction in a register-only loop, alone and with the scale fusion of Sec. 2.1 behind it
  *     (one product per 128-wide scale block, started from zero, then 4 fp32 FMAs per 16x16 block);
+ *   - the same loop with further scalar, vector and LDS instructions per matrix instruction;
  *   - a plain HBM read and a plain HBM copy;
  *   - the L2 -> LDS fetch stream (16 bytes per lane, straight into LDS) with no compute behind it.
  *
@@ -37,6 +38,14 @@ extern "C" {
  *        the same 2 * 64 * 64 * 128 flop per trip per wave); > 0.
  * tflops_out (host): 1e-12 * flop / seconds of the timed launch (a warm-up launch precedes it). */
 int gg_probe_mfma(int mode, int data_kind, int iters, double* tflops_out);
+
+/* The loop of gg_probe_mfma mode 1 (16x16x128 from zero + 4 FMAs) on constant operands with further instructions
+ * per matrix instruction that do no useful work: `extra_salu` scalar additions, `extra_valu` vector additions,
+ * `extra_lds_reads` 16-byte LDS reads (conflict-free).  What each instruction a kernel puts beside the matrix
+ * instruction costs in matrix-pipe time; with 8 waves per compute unit, as in the GEMM kernels.  Built combinations
+ * (salu, valu, lds): (0,0,0) (2,0,0) (4,0,0) (8,0,0) (0,1,0) (0,2,0) (0,0,1) (0,0,2) (2,1,1) (2,1,2); anything else:
+ * hipErrorInvalidValue. */
+int gg_probe_issue_mix(int extra_salu, int extra_valu, int extra_lds_reads, int iters, double* tflops_out);
 
 /* HBM streams over `bytes` (a multiple of 4096, larger than the caches for a meaningful figure).
  *   kind 0: read (16 bytes per lane, summed so the loads cannot be dropped)

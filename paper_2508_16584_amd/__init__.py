@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     load_library,
     load_probe_library,
     probe_hbm,
+    probe_issue_mix,
     probe_lds_fetch,
     probe_library_path,
     probe_mfma,

@@ -79,6 +79,8 @@ def load_probe_library() -> ctypes.CDLL:
     i32, dp = ctypes.c_int, ctypes.POINTER(ctypes.c_double)
     lib.gg_probe_mfma.restype = i32
     lib.gg_probe_mfma.argtypes = [i32, i32, i32, dp]
+    lib.gg_probe_issue_mix.restype = i32
+    lib.gg_probe_issue_mix.argtypes = [i32, i32, i32, i32, dp]
     lib.gg_probe_hbm.restype = i32
     lib.gg_probe_hbm.argtypes = [i32, ctypes.c_size_t, i32, dp]
     lib.gg_probe_lds_fetch.restype = i32
@@ -98,6 +100,11 @@ def _probe_call(fn, *args, n_out=1):
 def probe_mfma(mode: int, data_kind: int, iters: int = 20000) -> float:
     """TFLOP/s of a register-only loop of FP8 matrix instructions (gg_probe_mfma)."""
     return _probe_call(load_probe_library().gg_probe_mfma, mode, data_kind, iters)
+
+
+def probe_issue_mix(extra_salu: int, extra_valu: int, extra_lds_reads: int, iters: int = 10000) -> float:
+    """TFLOP/s of the block-scaled inner loop with further instructions per matrix instruction (gg_probe_issue_mix)."""
+    return _probe_call(load_probe_library().gg_probe_issue_mix, extra_salu, extra_valu, extra_lds_reads, iters)
 
 
 def probe_hbm(kind: int, nbytes: int = 2 << 30, reps: int = 3) -> float:

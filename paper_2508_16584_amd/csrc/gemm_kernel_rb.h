@@ -260,19 +260,21 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     const int tm_act = rows_valid > BM - 16 ? TM : (rows_valid + 15) / 16 + 1;
 
     // K blocks are taken in the order rot, rot+1, ..., KB-1, 0, ..., rot-1 (see k_rotation).
-    // K blocks past the end of the tile a descriptor points to are "fetched" from an out-of-range offset: same
-    // instruction count, no traffic.
+    // A fetch stream reaches K block KB of the tile its descriptor points to only in the empty step that ODDK adds
+    // (every stream is re-pointed to the next tile right after its fetch of block KB-1, and with no next tile the
+    // descriptors have length zero).  That block is "fetched" from an out-of-range offset: same instruction count,
+    // no traffic.  Without ODDK the test would never fire and is left out.
     auto dma_a = [&](auto ic, int kb_t, int stage) __attribute__((always_inline)) {   // one 8-row slab of block kb's A tile
       constexpr int i = decltype(ic)::value;
       const int kb = kb_t - kbase;
       const int kp = k_wrapped(kb + rot, KB);
-      const int vo = kb < KB ? (Cfg::RAGGED && kp == KB - 1 ? vA_last : vA) : GG_OOB_OFFSET;
+      const int vo = !Cfg::ODDK || kb < KB ? (Cfg::RAGGED && kp == KB - 1 ? vA_last : vA) : GG_OOB_OFFSET;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(i == 0 ? dA0 : i == 1 ? dA1 : i == 2 ? dA2 : dA3, GG_LDS_PTR(lds + stage * Cfg::STAGE_BYTES + (w + i * NW) * 1024), 16, vo,
                                                __builtin_amdgcn_readfirstlane(kp * 128), 0, 0);
     };
     auto dma_scales = [&](int kb_t, int stage) __attribute__((always_inline)) {     // exactly one DMA in every wave
       const int kb = kb_t - kbase;
-      const int vo = kb < KB ? vS : GG_OOB_OFFSET;
+      const int vo = !Cfg::ODDK || kb < KB ? vS : GG_OOB_OFFSET;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(dS, GG_LDS_PTR(lds + stage * Cfg::STAGE_BYTES + ldsS), 4, vo,
                                                __builtin_amdgcn_readfirstlane(k_wrapped(kb + rot, KB) * s_kb_stride), 0, 0);
     };
@@ -280,7 +282,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     auto dma_b = [&](int kb_t, auto jc, int slot) __attribute__((always_inline)) {
       constexpr int j = decltype(jc)::value;
       const int kb = kb_t - (j == 0 ? kbase0 : kbase);
-      const bool in = kb < KB;
+      const bool in = !Cfg::ODDK || kb < KB;
       uint8_t* dst = bslots + slot * Cfg::B_SLOT_BYTES;
       // all 256 weight rows of the tile exist: only the lane part of the offset needs the bounds check
       const int kp = k_wrapped(kb + (j == 0 ? rot0 : rot), KB);

@@ -119,6 +119,58 @@ __global__ void __launch_bounds__(512) mfma_loop_kernel(const v8i* __restrict__ 
   out[blockIdx.x * 512 + threadIdx.x] = total;
 }
 
+// The matrix loop of mode 1 with NS scalar, NV vector and NL LDS-read instructions more per matrix instruction: what
+// each instruction beside the matrix instruction and its 4 FMAs costs in matrix-pipe time.  The extra instructions do
+// nothing useful (counters, reads of a conflict-free 16 KB whose results are only waited for once per trip).
+template <int NS, int NV, int NL>
+__global__ void __launch_bounds__(512) issue_mix_kernel(const v8i* __restrict__ src, const float* __restrict__ scales, float* out, int iters) {
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[16384];
+  for (int i = threadIdx.x; i < 4096; i += 512) ((int*)lds)[i] = i;
+  __syncthreads();
+  v8i a[4], b[4];
+  for (int j = 0; j < 4; ++j) {
+    a[j] = src[j * 512 + threadIdx.x];
+    b[j] = src[(4 + j) * 512 + threadIdx.x];
+  }
+  float s[4];
+  for (int j = 0; j < 4; ++j) s[j] = scales[j * 64 + threadIdx.x % 64];
+  v4f acc[4][4];
+  for (int j = 0; j < 4; ++j)
+    for (int n = 0; n < 4; ++n) acc[j][n] = (v4f){0.f, 0.f, 0.f, 0.f};
+  int sx = iters, vx = threadIdx.x;
+  // every lane reads its own 16 bytes of its wave's 1 KB: no bank conflicts
+  const unsigned rd = (unsigned)(size_t)GG_LDS_PTR(lds) + (threadIdx.x & 63) * 16 + (threadIdx.x >> 6) * 2048;
+  for (int it = 0; it < iters; ++it) {
+    asm volatile("" : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));
+    v4f p[16];
+#pragma unroll
+    for (int t = 0; t < 16 + 3; ++t) {
+      if (t < 16) {
+        p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b[t % 4], a[t / 4], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+#pragma unroll
+        for (int q = 0; q < NS; ++q) asm volatile("s_add_u32 %0, %0, 3" : "+s"(sx) : : "scc");
+#pragma unroll
+        for (int q = 0; q < NV; ++q) asm volatile("v_add_u32 %0, %0, 3" : "+v"(vx));
+#pragma unroll
+        for (int q = 0; q < NL; ++q) {
+          v4i r;
+          asm volatile("ds_read_b128 %0, %1" : "=v"(r) : "v"(rd));
+          asm volatile("" : : "v"(r));
+        }
+      }
+      if (t >= 3) {
+        const int u = t - 3;
+        acc[u / 4][u % 4] += p[u] * s[u / 4];
+      }
+    }
+    if (NL) asm volatile("s_waitcnt lgkmcnt(0)");
+  }
+  float total = (float)(sx + vx);
+  for (int j = 0; j < 4; ++j)
+    for (int n = 0; n < 4; ++n) total += acc[j][n][0] + acc[j][n][1] + acc[j][n][2] + acc[j][n][3];
+  out[blockIdx.x * 512 + threadIdx.x] = total;
+}
+
 // e4m3 code of a float, round to nearest (ties away: operand statistics are all that matters here)
 uint8_t e4m3_of(float v) {
   const float av = std::fabs(v);
@@ -275,6 +327,60 @@ int gg_probe_mfma(int mode, int data_kind, int iters, double* tflops_out) {
   PROBE_TRY(hipEventElapsedTime(&ms, e0, e1));
   const double flop = 2.0 * 64 * 64 * 128 * (double)iters * blocks * 8.0;
   *tflops_out = flop / ((double)ms * 1e-3) * 1e-12;
+  cleanup();
+  return 0;
+}
+
+int gg_probe_issue_mix(int extra_salu, int extra_valu, int extra_lds_reads, int iters, double* tflops_out) {
+  if (iters <= 0 || !tflops_out) return (int)hipErrorInvalidValue;
+  // the combinations that are built
+  const int key = extra_salu * 100 + extra_valu * 10 + extra_lds_reads;
+  v8i* src = nullptr;
+  float *scales = nullptr, *out = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  auto cleanup = [&] {
+    if (src) (void)hipFree(src);
+    if (scales) (void)hipFree(scales);
+    if (out) (void)hipFree(out);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+  };
+  switch (key) {
+    case 0: case 200: case 400: case 800: case 10: case 20: case 1: case 2: case 211: case 212: break;
+    default: return (int)hipErrorInvalidValue;
+  }
+  const int blocks = cus();
+  std::vector<float> ones(256, 1.0f);
+  PROBE_TRY(hipMalloc(&src, (size_t)8 * 512 * 32));
+  PROBE_TRY(hipMalloc(&scales, ones.size() * 4));
+  PROBE_TRY(hipMalloc(&out, (size_t)blocks * 512 * 4));
+  PROBE_TRY(hipMemset(src, 0x38, (size_t)8 * 512 * 32));   // every operand byte 1.0: the clock stays up, so times compare as cycles
+  PROBE_TRY(hipMemcpy(scales, ones.data(), ones.size() * 4, hipMemcpyHostToDevice));
+  PROBE_TRY(hipEventCreate(&e0));
+  PROBE_TRY(hipEventCreate(&e1));
+  for (int rep = 0; rep < 2; ++rep) {   // the first launch warms up
+    PROBE_TRY(hipEventRecord(e0, 0));
+#define GG_MIX(S, V, L) hipLaunchKernelGGL((issue_mix_kernel<S, V, L>), dim3(blocks), dim3(512), 0, 0, src, scales, out, iters)
+    switch (key) {
+      case 0: GG_MIX(0, 0, 0); break;
+      case 200: GG_MIX(2, 0, 0); break;
+      case 400: GG_MIX(4, 0, 0); break;
+      case 800: GG_MIX(8, 0, 0); break;
+      case 10: GG_MIX(0, 1, 0); break;
+      case 20: GG_MIX(0, 2, 0); break;
+      case 1: GG_MIX(0, 0, 1); break;
+      case 2: GG_MIX(0, 0, 2); break;
+      case 211: GG_MIX(2, 1, 1); break;
+      default: GG_MIX(2, 1, 2); break;
+    }
+#undef GG_MIX
+    PROBE_TRY(hipGetLastError());
+    PROBE_TRY(hipEventRecord(e1, 0));
+    PROBE_TRY(hipEventSynchronize(e1));
+  }
+  float ms = 0.f;
+  PROBE_TRY(hipEventElapsedTime(&ms, e0, e1));
+  *tflops_out = 2.0 * 64 * 64 * 128 * (double)iters * blocks * 8.0 / ((double)ms * 1e-3) * 1e-12;
   cleanup();
   return 0;
 }

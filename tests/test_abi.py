@@ -41,7 +41,7 @@ def test_probe_library_exports_what_its_header_declares():
     header = os.path.join(os.path.dirname(HEADER), "gg_probe.h")
     text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
     names = sorted(set(re.findall(r"\b(gg_probe_\w+)\s*\(", text)))
-    assert names == ["gg_probe_hbm", "gg_probe_lds_fetch", "gg_probe_mfma"]
+    assert names == ["gg_probe_hbm", "gg_probe_issue_mix", "gg_probe_lds_fetch", "gg_probe_mfma"]
     if not os.path.exists(gg.probe_library_path()):
         gg.build_library()
     probe = gg.load_probe_library()
@@ -50,6 +50,7 @@ def test_probe_library_exports_what_its_header_declares():
     # argument checks come before any GPU call
     out = ctypes.c_double(0.0)
     assert probe.gg_probe_mfma(4, 0, 10, ctypes.byref(out)) != 0 and probe.gg_probe_mfma(0, 0, 0, ctypes.byref(out)) != 0
+    assert probe.gg_probe_issue_mix(1, 1, 1, 10, ctypes.byref(out)) != 0 and probe.gg_probe_issue_mix(0, 0, 0, 0, ctypes.byref(out)) != 0
     assert probe.gg_probe_hbm(2, 4096, 1, ctypes.byref(out)) != 0 and probe.gg_probe_hbm(0, 100, 1, ctypes.byref(out)) != 0
     assert probe.gg_probe_lds_fetch(3, 3, 1, ctypes.byref(out), ctypes.byref(out)) != 0
     assert probe.gg_probe_lds_fetch(0, 8, 1, ctypes.byref(out), ctypes.byref(out)) != 0

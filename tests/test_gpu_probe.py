@@ -15,6 +15,12 @@ def test_matrix_loops_report_plausible_rates():
     assert rates[1] < 1.05 * rates[0]
 
 
+def test_issue_mix_loops_run_and_more_instructions_are_not_faster():
+    base = gg.probe_issue_mix(0, 0, 0, 2000)
+    heavy = gg.probe_issue_mix(2, 1, 2, 2000)
+    assert 500.0 < heavy < 1.05 * base < 5400.0, (base, heavy)
+
+
 def test_hbm_and_fetch_streams_report_plausible_rates():
     read = gg.probe_hbm(0, 512 << 20, 2)
     copy = gg.probe_hbm(1, 512 << 20, 2)
