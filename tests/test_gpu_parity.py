@@ -126,6 +126,62 @@ def test_many_empty_groups_and_a_wide_output():
         assert_parity(run_gpu(dev, p["M_total"], 16384, v), ref, what=f"N=16384 variant {v}")
 
 
+@pytest.mark.timeout(600)
+def test_largest_k_and_largest_n_the_library_takes():
+    """K = 2^22 and N = 2^21, the limits of the argument check (32-bit offsets inside a tile).  The oracle evaluates
+    the columns of one 128-column block at a time (16 columns of each of two blocks), every row."""
+    def references(A, SA, B, SB, off, blocks):
+        refs = []
+        for blk in blocks:
+            cols = np.arange(blk * 128, blk * 128 + 8)
+            cols = np.concatenate([cols, cols + 120])
+            refs.append((blk, cols, orc.grouped_gemm(A, SA, np.ascontiguousarray(B[:, cols, :]), SB[:, blk:blk + 1, :], off,
+                                                     with_abs_sum=True)))
+        return refs
+
+    def check_columns(refs, got, what):
+        for blk, cols, ref in refs:
+            assert_parity(got[:, cols], ref, empirical=False, what=f"{what}, column block {blk}")
+
+    rng = np.random.default_rng(71)
+    # ---- K = 2^22: 32768 K blocks, 4 MB per row
+    sizes, N, K = [3, 0, 14], 256, 1 << 22
+    G, M, KB = len(sizes), sum(sizes), K // 128
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    A = rng.integers(0x20, 0x48, (M, K), dtype=np.uint8) | (rng.integers(0, 2, (M, K), dtype=np.uint8) << 7)
+    B = rng.integers(0x20, 0x48, (G, N, K), dtype=np.uint8) | (rng.integers(0, 2, (G, N, K), dtype=np.uint8) << 7)
+    SA = rng.uniform(0.5, 2.0, (M, KB)).astype(np.float32)
+    SB = rng.uniform(0.5, 2.0, (G, N // 128, KB)).astype(np.float32)
+    dev = tuple(torch.from_numpy(x).to(DEV) for x in (A, SA, B, SB, off))
+    refs = references(A, SA, B, SB, off, (0, 1))
+    first = None
+    for v in [-1] + [u for u in range(gg.num_variants()) if gg.variant_name(u) in ("160x256/2x4w/3s", "256x256/1x8w/3s-rb", "128x256/2x4w/3s-k2")]:
+        got = run_gpu(dev, M, N, v)
+        if family_of(v) == "plain":
+            first = got if first is None else first
+            assert np.array_equal(got, first), f"K = 2^22: variant {v} differs"
+        check_columns(refs, got, f"K = 2^22 variant {v}")
+    del dev, A, B, refs
+    # ---- N = 2^21: 8192 column tiles of 256, 16384 scale blocks
+    sizes, N, K = [5, 2], 1 << 21, 128
+    G, M = len(sizes), sum(sizes)
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    A = rng.integers(0, 0x7F, (M, K), dtype=np.uint8)
+    B = rng.integers(0x28, 0x40, (G, N, K), dtype=np.uint8) | (rng.integers(0, 2, (G, N, K), dtype=np.uint8) << 7)
+    SA = rng.uniform(0.5, 2.0, (M, 1)).astype(np.float32)
+    SB = rng.uniform(0.5, 2.0, (G, N // 128, 1)).astype(np.float32)
+    dev = tuple(torch.from_numpy(x).to(DEV) for x in (A, SA, B, SB, off))
+    refs = references(A, SA, B, SB, off, (0, 1, 8191, 16382, 16383))
+    for v in (-1, 2, 3):
+        C = canary_C(M + 2, N)
+        gg.grouped_gemm(*dev, C=C[1:M + 1], variant=v)
+        torch.cuda.synchronize()
+        bits = bits_of(C)
+        assert (bits[0] == CANARY).all() and (bits[M + 1] == CANARY).all()
+        check_columns(refs, bits[1:M + 1], f"N = 2^21 variant {v}")
+        assert (bits[1:M + 1] != CANARY).any(axis=0).all(), "a column was never written"
+
+
 @pytest.mark.parametrize("K", [512, 768, 1024, 1536])
 def test_several_tiles_per_workgroup_every_element(K):
     """More tiles than workgroups at a size the oracle can check in full: every workgroup walks through several
