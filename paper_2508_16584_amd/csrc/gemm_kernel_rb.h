@@ -64,6 +64,11 @@ struct RbCfg {
   // bounds check like any row past the group's end (zeros into LDS rows nobody reads, no traffic)
   static constexpr int A_BYTES = A_ITERS * 64 * 128;
   static constexpr int SA_WAVES = (BM + 63) / 64;
+  // Activation scales are read one band (four activation blocks, 64 rows) at a time into one of two registers of
+  // four: band b of a K step at block 4b - 3, band 0 of the next K step at block R_NEXT (three blocks before the
+  // end where the register's previous band has had its last use by then, else right after that use).
+  static constexpr int NBAND = SA_WAVES;
+  static constexpr int R_NEXT = BM / 16 - 3 > 4 * NBAND - 5 ? BM / 16 - 3 : 4 * NBAND - 5;
   static constexpr int SA_BYTES = SA_WAVES * 256;
   static constexpr int SB_BYTES = 256;
   static constexpr int DUMP_BYTES = 256;           // target of the scale DMA of waves that have no scales to fetch
@@ -157,13 +162,16 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
   // wave SB_WAVE the two weight scales, the others an out-of-range offset into a dump area.
   const bool sa_wave = w < Cfg::SA_WAVES, sb_wave = w == Cfg::SB_WAVE;
   const int s_kb_stride = sa_wave ? a.sa_kb_stride : 4;             // bytes from one K block's scale to the next
-  const int vS = sa_wave ? (w * 64 + l) * a.sa_row_stride : sb_wave ? (l < BN / 128 ? l : BN / 128 - 1) * (Cfg::FUSE ? inter >> 7 : 1) * KB * 4 : GG_OOB_OFFSET;
+  // activation scales: lane l fetches the scale of row 64w + 16*(l%4) + l/4 of the tile, so that LDS word 4r + i of
+  // the wave's 256 bytes holds row 16i + r and a lane reads the scales of its row r in four consecutive activation
+  // blocks with ONE 16-byte read (a 4-byte read per block costs the LDS pipe as much as a quarter of the operand reads)
+  const int vS = sa_wave ? (w * 64 + 16 * (l & 3) + (l >> 2)) * a.sa_row_stride : sb_wave ? (l < BN / 128 ? l : BN / 128 - 1) * (Cfg::FUSE ? inter >> 7 : 1) * KB * 4 : GG_OOB_OFFSET;
   const int ldsS = Cfg::A_BYTES + (sa_wave ? w * 256 : sb_wave ? Cfg::SA_BYTES : Cfg::SA_BYTES + Cfg::SB_BYTES);
   // operand reads: row r, chunks (2q, 2q+1), or (q, 4+q) with KP
   const int keyR = Cfg::KP ? swz_key_a1(r) : swz_key_a(r);
   const int rd0 = r * 128 + (((Cfg::KP ? q : 2 * q) ^ keyR) << 4);
   const int rd1 = r * 128 + (((Cfg::KP ? 4 + q : 2 * q + 1) ^ keyR) << 4);
-  const int saRd = Cfg::A_BYTES + r * 4;
+  const int saRd = Cfg::A_BYTES + r * 16;                               // + 256 * band: scales of blocks 4*band .. 4*band+3
   const int sbRd = Cfg::A_BYTES + Cfg::SA_BYTES + (Cfg::FUSE ? 0 : ((w * 32) >> 7) * 4);   // FUSE: gate block, up block at + 4
   uint8_t* const bslots = lds + Cfg::B_BASE + w * (Cfg::B_SLOTS * Cfg::B_SLOT_BYTES);   // this wave's weight slots
 
@@ -248,7 +256,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
   bool primed = false;
   v8i bfr[2][TN];                 // weight fragments of K block kb in set kb % 2
   v8i afr[AFR];
-  float sa[AFR];
+  v4f sa4[2];                     // activation scales of two bands of four activation blocks (see band_reg)
   float sb_next = 0.f, sb_next_up = 0.f;     // FUSE: the weight scales of the gate block and of the up block
   int stage = 0;                  // LDS buffer of block kb
   int bslot = 2;                  // slot of fragment 2*kb + 2
@@ -332,10 +340,8 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       bfr[0][0] = read_frag(bslots);
       bfr[0][1] = read_frag(bslots + Cfg::B_SLOT_BYTES);
 #pragma unroll
-      for (int i = 0; i < AFR - 1; ++i) {
-        afr[i] = read_frag(lds + i * 2048);
-        sa[i] = *(const float*)(lds + saRd + i * 64);
-      }
+      for (int i = 0; i < AFR - 1; ++i) afr[i] = read_frag(lds + i * 2048);
+      sa4[0] = *(const v4f*)(lds + saRd);
       // the slot reads must be done before their slots are refilled
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       dma_b(1, J1, 0);
@@ -375,27 +381,36 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
 
       v4f p[MF];
       float s[TM], s_up[Cfg::FUSE ? TM : 1];
+      // register of band b of this K step: bands are numbered through the K steps (an odd number of bands per step
+      // flips the assignment from step to step; a tile has an even number of steps and starts with register 0)
+      auto band_reg = [](int b) constexpr { return (BS * (Cfg::NBAND & 1) + b) & 1; };
+      // the scale reads of activation block mt (after the block's own scale product: in-order issue keeps the
+      // register's previous band intact for it)
+      auto read_scales = [&](auto mc) __attribute__((always_inline)) {
+        constexpr int mt = decltype(mc)::value;
+        if constexpr (mt % 4 == 1 && mt / 4 + 1 < Cfg::NBAND) sa4[band_reg(mt / 4 + 1)] = *(const v4f*)(st + saRd + (mt / 4 + 1) * 256);
+        if constexpr (mt == Cfg::R_NEXT) sa4[band_reg(Cfg::NBAND)] = *(const v4f*)(st1 + saRd);
+      };
       auto body = [&](auto tc) __attribute__((always_inline)) {
         constexpr int t = decltype(tc)::value;
         if constexpr (t < MF) {
           constexpr int mt = t / TN, j = t % TN;
           if constexpr (j == 0) {
-            s[mt] = sa[mt % AFR] * sb;
-            if constexpr (Cfg::FUSE) s_up[mt] = sa[mt % AFR] * sb_up;
+            s[mt] = sa4[band_reg(mt / 4)][mt % 4] * sb;
+            if constexpr (Cfg::FUSE) s_up[mt] = sa4[band_reg(mt / 4)][mt % 4] * sb_up;
             // fragment of activation block mt + AFR - 1 into the slot block mt - 1 has left; past the end of
             // this K block that is the next K block's, published by the barrier above
             constexpr int nb = mt + AFR - 1;
             if constexpr (nb < TM) {
               afr[nb % AFR] = read_frag(st + nb * 2048);
-              sa[nb % AFR] = *(const float*)(st + saRd + nb * 64);
             } else {
               afr[nb % AFR] = read_frag(st1 + (nb - TM) * 2048);
-              sa[nb % AFR] = *(const float*)(st1 + saRd + (nb - TM) * 64);
               if constexpr (nb == TM) {                                         // next block's weight scale(s)
                 sb_next = *(const float*)(st1 + sbRd);
                 if constexpr (Cfg::FUSE) sb_next_up = *(const float*)(st1 + sbRd + 4);
               }
             }
+            read_scales(std::integral_constant<int, mt>{});
           }
           p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[BS][j], afr[mt % AFR], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
           if constexpr (t >= Cfg::T_A0 && t < Cfg::T_A0 + Cfg::A_ITERS)
@@ -417,7 +432,9 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
           constexpr int j = t % TN;
           if constexpr (j == 0) {
             __builtin_amdgcn_sched_group_barrier(0x002, Cfg::FUSE ? 2 : 1, 0);                   // scale product(s)
-            __builtin_amdgcn_sched_group_barrier(0x100, t / TN + AFR - 1 == TM ? (Cfg::FUSE ? 5 : 4) : 3, 0);   // 3 (4, 5) DS reads
+            constexpr int mt = t / TN;                                                           // DS reads: 2 of a fragment,
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 + (mt + AFR - 1 == TM ? (Cfg::FUSE ? 2 : 1) : 0)   // weight scale(s),
+                                                            + (mt % 4 == 1 && mt / 4 + 1 < Cfg::NBAND ? 1 : 0) + (mt == Cfg::R_NEXT ? 1 : 0), 0);   // a band of scales
           }
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                     // 1 MFMA
           if constexpr (t >= Cfg::T_A0 && t < Cfg::T_A0 + Cfg::A_ITERS) {
@@ -447,25 +464,21 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
           static_for<mt * TN, mt * TN + TN>(order);
         } else {
           constexpr int nb = mt + AFR - 1;
+          s[mt] = sa4[band_reg(mt / 4)][mt % 4] * sb;     // before the band reads below, which may refill that register
           if constexpr (nb >= TM) {              // the next K block's first fragments and scales: always
             afr[nb % AFR] = read_frag(st1 + (nb - TM) * 2048);
-            sa[nb % AFR] = *(const float*)(st1 + saRd + (nb - TM) * 64);
             if constexpr (nb == TM) sb_next = *(const float*)(st1 + sbRd);
           }
+          read_scales(std::integral_constant<int, mt>{});
           if (mt < tm_run) {
-            s[mt] = sa[mt % AFR] * sb;
-            if constexpr (nb < TM) {
-              afr[nb % AFR] = read_frag(st + nb * 2048);
-              sa[nb % AFR] = *(const float*)(st + saRd + nb * 64);
-            }
+            if constexpr (nb < TM) afr[nb % AFR] = read_frag(st + nb * 2048);
             p[mt * TN] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[BS][0], afr[mt % AFR], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
             p[mt * TN + 1] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[BS][1], afr[mt % AFR], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
             if constexpr (mt >= 1) {             // the FMAs of the block before this one
               acc[mt - 1][0] += p[(mt - 1) * TN] * s[mt - 1];
               acc[mt - 1][1] += p[(mt - 1) * TN + 1] * s[mt - 1];
             }
-            __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
-            if constexpr (nb < TM) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+            if constexpr (nb < TM) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             if constexpr (mt >= 1) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
