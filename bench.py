@@ -332,6 +332,31 @@ def bench_ceilings():
                       "peaks": {"mfma_fp8_dense_TFLOPs": 5000.0, "hbm_GBps": 8000.0}}))
 
 
+def bench_kstep_parts():
+    """The second GEMM kernel with parts of its K step left out (gg_probe_gemm_kstep), on two balanced problems of
+    gate_up's N and K: 8 x 1152 rows in 192-row tiles and 8 x 1536 rows in 256-row tiles (768 tiles each: three full
+    passes over 256 workgroups).  One JSON line; times are microseconds per launch, the ideal is the matrix pipe's
+    time for the same tiles at the nominal clock.  Each build is launched once for every dispatch that is timed, so
+    the same command under `rocprofv3 --pmc GRBM_GUI_ACTIVE` gives the cycles of every build."""
+    import paper_2508_16584_amd as gg
+    parts = [(0, "nothing left out (the kernel as launched)"), (4, "no barrier"), (8, "no LDS reads of activations and scales"),
+             (16, "no waits for the fetches"), (20, "no waits for the fetches, no barrier"),
+             (32, "nothing left out, operands all zero bytes (same traffic, little power)"),
+             (2, "fetches issued to nowhere (no traffic, zero operands)"), (1, "no fetches"), (5, "no fetches, no barrier"),
+             (13, "no fetches, no barrier, no LDS reads (matrix instructions, FMAs, bookkeeping)")]
+    out = {}
+    for rows, per_group in ((192, 1152), (256, 1536)):
+        res = {}
+        for code, name in parts:
+            res[name] = round(gg.probe_gemm_kstep(rows, code, 8, per_group, 4096, 7168, 20), 1)
+        tiles_per_wg = 8 * (per_group // rows) * (4096 // 256) / 256.0
+        ideal_cycles = tiles_per_wg * (7168 // 128) * (rows // 16) * 2 * 2 * 32   # per SIMD: 2 waves x (rows/16 x 2) instructions x 32 cycles
+        out[f"{rows}x256 tiles, 8 groups x {per_group} rows, N=4096, K=7168"] = {
+            "us_per_launch": res, "matrix_pipe_minimum_cycles": int(ideal_cycles),
+            "matrix_pipe_minimum_us_at_2.4GHz": round(ideal_cycles / 2400.0, 1)}
+    print(json.dumps({"op": "kstep_parts", "second_gemm_kernel_with_parts_of_its_k_step_left_out": out}))
+
+
 def bench_pad_path(args, cfg, dev):
     """The comparison path of Sec. 3 step by step: pad (offsets + row copies), the GEMM on the padded problem, unpad.
     Each step is timed alone, `steps` launches back to back over rotating buffer sets (cold caches); the copies are
@@ -435,14 +460,15 @@ def main():
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="gate_up")
-    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows", "swiglu_quantize_rows", "expert_mlp", "ceilings", "pad_path"],
+    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows", "swiglu_quantize_rows", "expert_mlp", "ceilings", "pad_path", "kstep_parts"],
                     help="grouped_gemm: the hot path (default, the headline metric); quantize_rows: the producer of its "
                          "A operand on the same workload's activation shape; swiglu_quantize_rows: activation + quantiser "
                          "on the workload's output shape [M_total, N] (N = 2 x intermediate width); expert_mlp: the whole forward "
                          "chain quantise -> GEMM -> activation+quantise -> GEMM on the workload's routing, padding-free "
                          "against the same chain on 128-row padded groups; pad_path: the three steps of the pad-then-GEMM comparison path "
                          "(Sec. 3) each timed alone, the two copies against the HBM roofline; ceilings: no workload, the probes of "
-                         "include/gg_probe.h (register-only matrix loops, HBM streams, the L2 -> LDS fetch stream)")
+                         "include/gg_probe.h (register-only matrix loops, HBM streams, the L2 -> LDS fetch stream); kstep_parts: no workload, "
+                         "the second GEMM kernel timed with parts of its K step left out (fetches, barrier, LDS reads)")
     ap.add_argument("--clock-warmup-ms", type=float, default=150.0,
                     help="untimed launches for about this long before the W warm-up steps, so that the timed steps run at "
                          "the GPU's sustained clock (0: none)")
@@ -483,6 +509,9 @@ def main():
     torch.cuda.set_device(dev)
     if args.op == "ceilings":
         bench_ceilings()
+        return
+    if args.op == "kstep_parts":
+        bench_kstep_parts()
         return
     cfg = CONFIGS[args.workload]
     if args.op in ("quantize_rows", "swiglu_quantize_rows"):

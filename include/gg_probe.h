@@ -7,7 +7,8 @@
  *     (one product per 128-wide scale block, started from zero, then 4 fp32 FMAs per 16x16 block);
  *   - the same loop with further scalar, vector and LDS instructions per matrix instruction;
  *   - a plain HBM read and a plain HBM copy;
- *   - the L2 -> LDS fetch stream (16 bytes per lane, straight into LDS) with no compute behind it.
+ *   - the L2 -> LDS fetch stream (16 bytes per lane, straight into LDS) with no compute behind it;
+ *   - the second GEMM kernel itself with parts of its K step left out (fetches, barrier, LDS reads).
  *
  * Every call is synchronous: it allocates its own device buffers, launches on the null stream, waits, frees, and
  * returns 0 or the hipError_t that stopped it (nothing is left allocated).  Results are written through host
@@ -64,6 +65,25 @@ int gg_probe_hbm(int kind, size_t bytes, int reps, double* gbytes_per_s_out);
  * gbytes_per_s_out: 1e-9 * bytes landed in LDS / seconds over the chip; bytes_per_clk_cu_out: the same per
  * compute unit and cycle of the nominal shader clock (hipDeviceAttributeClockRate). */
 int gg_probe_lds_fetch(int pattern, int depth, int reps, double* gbytes_per_s_out, double* bytes_per_clk_cu_out);
+
+/* The second GEMM kernel of libgg_fp8 (weights through registers; paper Sec. 2.1 arithmetic) in measurement builds
+ * that LEAVE OUT parts of its K step, on a problem this call makes itself: `groups` equal groups of `rows_per_group`
+ * rows, N = n, K = k (n % 256 == 0, k % 256 == 0, k >= 512; every tensor under 2 GiB), operand bytes like
+ * e4m3-quantised normal samples, row-major activation scales.  What the step costs with and without each part says
+ * where the time between the matrix pipe's minimum and the kernel's duration goes.
+ *   tile_rows: 192 or 256 (the tiles 192x256 and 256x256 of the second kernel)
+ *   left_out:  0 nothing (the kernel as the library launches it); 1 the fetches of the K steps; 2 every fetch goes
+ *              to an out-of-range offset (issued, no traffic, the operands become zeros: compare cycles, not time);
+ *              4 the barrier of the K step; 8 the LDS reads of activation fragments and scales; 16 the waits for the
+ *              fetches (the data moves, nobody waits for it); 5 = 1 + 4; 20 = 16 + 4; 13 = 1 + 4 + 8 (matrix
+ *              instructions, FMAs and bookkeeping only); 32 nothing left out, but A and B are all zero bytes (the same
+ *              traffic as 0 at the power of 2).  Anything else: hipErrorInvalidValue.
+ *              Only accesses and waits are removed, so every remaining access stays in bounds; the OUTPUT IS
+ *              MEANINGLESS for every value but 0.
+ *   reps:      timed launches (launches of the same build for about 150 ms precede them: the sustained clock)
+ * us_out (host): microseconds per launch.  The shader clock differs between the builds (fewer operand bits moving,
+ * higher clock): for cycles run the same call under `rocprofv3 --pmc GRBM_GUI_ACTIVE`. */
+int gg_probe_gemm_kstep(int tile_rows, int left_out, int groups, int rows_per_group, int n, int k, int reps, double* us_out);
 
 #ifdef __cplusplus
 }

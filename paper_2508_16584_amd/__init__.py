@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     load_probe_library,
+    probe_gemm_kstep,
     probe_hbm,
     probe_issue_mix,
     probe_lds_fetch,

@@ -85,6 +85,8 @@ def load_probe_library() -> ctypes.CDLL:
     lib.gg_probe_hbm.argtypes = [i32, ctypes.c_size_t, i32, dp]
     lib.gg_probe_lds_fetch.restype = i32
     lib.gg_probe_lds_fetch.argtypes = [i32, i32, i32, dp, dp]
+    lib.gg_probe_gemm_kstep.restype = i32
+    lib.gg_probe_gemm_kstep.argtypes = [i32, i32, i32, i32, i32, i32, i32, dp]
     _probe = lib
     return lib
 
@@ -115,6 +117,12 @@ def probe_hbm(kind: int, nbytes: int = 2 << 30, reps: int = 3) -> float:
 def probe_lds_fetch(pattern: int, depth: int = 3, reps: int = 20):
     """(GB/s over the chip, bytes per clock and compute unit) of the L2 -> LDS fetch stream (gg_probe_lds_fetch)."""
     return _probe_call(load_probe_library().gg_probe_lds_fetch, pattern, depth, reps, n_out=2)
+
+
+def probe_gemm_kstep(tile_rows: int, left_out: int, groups: int = 8, rows_per_group: int = 1536, n: int = 4096,
+                     k: int = 7168, reps: int = 20) -> float:
+    """Microseconds per launch of the second GEMM kernel with parts of its K step left out (gg_probe_gemm_kstep)."""
+    return _probe_call(load_probe_library().gg_probe_gemm_kstep, tile_rows, left_out, groups, rows_per_group, n, k, reps)
 
 
 def load_library() -> ctypes.CDLL:

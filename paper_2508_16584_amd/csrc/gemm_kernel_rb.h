@@ -51,9 +51,19 @@ namespace gg {
 // ODDK: the number of K blocks may be odd (one more, empty K step per tile; see KBe in the kernel).  One more value
 // that lives in a scalar register through the whole kernel, which the largest tiles have no room for: the
 // instantiations for whole blocks keep to an even number.
-template <int BM_, int AFR_ = 4, bool KP_ = false, bool FUSE_ = false, bool SKIP_ = false, bool RAGGED_ = false, bool ODDK_ = RAGGED_>
+// TIMING (measurement builds of the probe library only; 0 in every kernel the GEMM library launches): a bit mask of
+// parts of a K step that are LEFT OUT, to time what each costs.  1: the fetches of the K steps (the prologue of a
+// workgroup's first tile still fetches); 2: every fetch goes to the out-of-range offset (issued, no traffic, zeros);
+// 4: the barrier of the K step; 8: the LDS reads of activation fragments and scales (the registers keep what the
+// prologue read); 16: the K step's waits for its fetches (operands are read whether they have arrived or not).
+// Accesses and waits are only ever removed, so everything that remains stays in bounds and every wait ends; the
+// results are meaningless.
+enum : int { kTimingNoFetch = 1, kTimingFetchNowhere = 2, kTimingNoBarrier = 4, kTimingNoLdsReads = 8, kTimingNoFetchWaits = 16 };
+template <int BM_, int AFR_ = 4, bool KP_ = false, bool FUSE_ = false, bool SKIP_ = false, bool RAGGED_ = false, bool ODDK_ = RAGGED_, int TIMING_ = 0>
 struct RbCfg {
   static constexpr bool KP = KP_, FUSE = FUSE_, SKIP = SKIP_, RAGGED = RAGGED_, ODDK = ODDK_;
+  static constexpr int TIMING = TIMING_;
+  static_assert(TIMING_ == 0 || !(FUSE_ || SKIP_ || RAGGED_ || ODDK_), "measurement builds exist for the plain tile only");
   static_assert(!(FUSE_ && SKIP_), "the activation epilogue runs full K steps only");
   static_assert(!(FUSE_ && RAGGED_), "the activation epilogue takes whole blocks only");
   static constexpr int BM = BM_, BN = 256, S = 3;
@@ -86,8 +96,15 @@ struct RbCfg {
   static constexpr int AFR = AFR_;                 // ring of activation fragments (prefetch distance AFR-1 blocks)
   // fetches per wave per K block, in issue order: 1 scale DMA, A_ITERS A slabs, 2 + 2 weight-slot refills
   static constexpr int N_A = 1 + A_ITERS;
-  static constexpr int T_A0 = 0;                   // A DMAs after MFMAs T_A0 .. T_A0 + A_ITERS - 1
-  static constexpr int T_R0 = A_ITERS + 2;         // refill of the slot read at the top of the block
+  // SPREAD: the fetches of a K step are dealt out over its matrix instructions one at a time (an A slab after every
+  // third, the two halves of a refill two apart) instead of in groups of three and two: the eight waves of a
+  // workgroup run in step, so a group in the source is a burst of 16 to 24 KB-sized requests at the fetch path.
+  // 2 - 3.5 % faster at 192 to 256 rows (gate_up, interleaved A/B); the shorter tiles have no room for it.
+  static constexpr bool SPREAD = BM_ >= 192 && !SKIP_;
+  static constexpr int A_STEP = SPREAD ? 3 : 1;    // MFMAs from one A DMA to the next
+  static constexpr int R_STEP = SPREAD ? 2 : 0;    // MFMAs between the two DMAs of a refill (0: back to back)
+  static constexpr int T_A0 = 0;                   // A DMAs after MFMAs T_A0, T_A0 + A_STEP, ...
+  static constexpr int T_R0 = SPREAD ? A_STEP * (A_ITERS - 1) + 2 : A_ITERS + 2;         // refill of the slot read at the top of the block
   static constexpr int T_MID = MFMAS / 2 + 2;      // wait for and read of the second fragment of the next block
   static constexpr int T_R1 = T_MID + 6 <= MFMAS ? T_MID + 4 : MFMAS - 2;   // refill of that slot
   // in flight across the top of a block: the 4 refill DMAs of the previous block
@@ -98,7 +115,7 @@ struct RbCfg {
   static_assert(BM % 16 == 0 && BM <= 256 && AFR_ >= 2 && TM % AFR_ == 0, "BM a multiple of 16, fragment ring a divisor of BM/16");
   static_assert(PIPE == TN, "the FMAs of an activation block are issued with the MFMAs of the next one");
   static_assert(SA_WAVES <= SB_WAVE, "scale fetchers must be distinct waves");
-  static_assert(T_R0 + 2 <= T_MID && T_R1 >= T_MID + 2 && T_R1 + 2 <= MFMAS && T_MID % TN == 0, "issue slots must fit the MFMA stream");
+  static_assert(T_R0 + R_STEP + 2 <= T_MID && T_R1 >= T_MID + 2 && T_R1 + R_STEP + 2 <= MFMAS && T_MID % TN == 0, "issue slots must fit the MFMA stream");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
@@ -276,28 +293,29 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       constexpr int i = decltype(ic)::value;
       const int kb = kb_t - kbase;
       const int kp = k_wrapped(kb + rot, KB);
-      const int vo = !Cfg::ODDK || kb < KB ? (Cfg::RAGGED && kp == KB - 1 ? vA_last : vA) : GG_OOB_OFFSET;
+      const int vo = (Cfg::TIMING & kTimingFetchNowhere) ? GG_OOB_OFFSET
+                     : !Cfg::ODDK || kb < KB ? (Cfg::RAGGED && kp == KB - 1 ? vA_last : vA) : GG_OOB_OFFSET;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(i == 0 ? dA0 : i == 1 ? dA1 : i == 2 ? dA2 : dA3, GG_LDS_PTR(lds + stage * Cfg::STAGE_BYTES + (w + i * NW) * 1024), 16, vo,
                                                __builtin_amdgcn_readfirstlane(kp * 128), 0, 0);
     };
     auto dma_scales = [&](int kb_t, int stage) __attribute__((always_inline)) {     // exactly one DMA in every wave
       const int kb = kb_t - kbase;
-      const int vo = !Cfg::ODDK || kb < KB ? vS : GG_OOB_OFFSET;
+      const int vo = (Cfg::TIMING & kTimingFetchNowhere) ? GG_OOB_OFFSET : !Cfg::ODDK || kb < KB ? vS : GG_OOB_OFFSET;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(dS, GG_LDS_PTR(lds + stage * Cfg::STAGE_BYTES + ldsS), 4, vo,
                                                __builtin_amdgcn_readfirstlane(k_wrapped(kb + rot, KB) * s_kb_stride), 0, 0);
     };
     // weight fragment j of block kb into slot `slot` of this wave: two slabs of 8 fragment rows
-    auto dma_b = [&](int kb_t, auto jc, int slot) __attribute__((always_inline)) {
+    auto dma_b = [&](int kb_t, auto jc, int slot, int halves = 3) __attribute__((always_inline)) {   // halves: bit 0 slab 0, bit 1 slab 1
       constexpr int j = decltype(jc)::value;
       const int kb = kb_t - (j == 0 ? kbase0 : kbase);
-      const bool in = !Cfg::ODDK || kb < KB;
+      const bool in = !(Cfg::TIMING & kTimingFetchNowhere) && (!Cfg::ODDK || kb < KB);
       uint8_t* dst = bslots + slot * Cfg::B_SLOT_BYTES;
       // all 256 weight rows of the tile exist: only the lane part of the offset needs the bounds check
       const int kp = k_wrapped(kb + (j == 0 ? rot0 : rot), KB);
       const bool last = Cfg::RAGGED && kp == KB - 1;
       const int so = __builtin_amdgcn_readfirstlane(kp * 128 + j * frag1_off);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(j == 0 ? dB0 : dB, GG_LDS_PTR(dst), 16, in ? (last ? vB0_last : vB0) : GG_OOB_OFFSET, so, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(j == 0 ? dB0 : dB, GG_LDS_PTR(dst + 1024), 16, in ? (last ? vB1_last : vB1) : GG_OOB_OFFSET, so, 0, 0);
+      if (halves & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(j == 0 ? dB0 : dB, GG_LDS_PTR(dst), 16, in ? (last ? vB0_last : vB0) : GG_OOB_OFFSET, so, 0, 0);
+      if (halves & 2) __builtin_amdgcn_raw_ptr_buffer_load_lds(j == 0 ? dB0 : dB, GG_LDS_PTR(dst + 1024), 16, in ? (last ? vB1_last : vB1) : GG_OOB_OFFSET, so, 0, 0);
     };
     constexpr std::integral_constant<int, 0> J0{};
     constexpr std::integral_constant<int, 1> J1{};
@@ -370,13 +388,13 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       const uint8_t* st1 = lds + stage1 * Cfg::STAGE_BYTES;
       // A(kb+1), its scales and weight fragment 2kb+2 are older than the 4 refill DMAs of block kb-1.  (Stores
       // of the previous tile are older still: they can only make this wait longer, never shorter.)
-      wait_vmcnt<Cfg::W_TOP>();
+      if constexpr (!(Cfg::TIMING & kTimingNoFetchWaits)) wait_vmcnt<Cfg::W_TOP>();
       // every wave has its part of block kb+1 in LDS and is done reading block kb-1
-      __builtin_amdgcn_s_barrier();
+      if constexpr (!(Cfg::TIMING & kTimingNoBarrier)) __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
       const float sb = sb_next, sb_up = sb_next_up;            // read a block ago: no LDS wait ahead of the first MFMA
       bfr[BS ^ 1][0] = read_frag(bslots + bslot * Cfg::B_SLOT_BYTES);
-      dma_scales(kb + 2, stageN);
+      if constexpr (!(Cfg::TIMING & kTimingNoFetch)) dma_scales(kb + 2, stageN);
       __builtin_amdgcn_sched_barrier(0);
 
       v4f p[MF];
@@ -388,8 +406,14 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       // register's previous band intact for it)
       auto read_scales = [&](auto mc) __attribute__((always_inline)) {
         constexpr int mt = decltype(mc)::value;
-        if constexpr (mt % 4 == 1 && mt / 4 + 1 < Cfg::NBAND) sa4[band_reg(mt / 4 + 1)] = *(const v4f*)(st + saRd + (mt / 4 + 1) * 256);
-        if constexpr (mt == Cfg::R_NEXT) sa4[band_reg(Cfg::NBAND)] = *(const v4f*)(st1 + saRd);
+        if constexpr (Cfg::TIMING & kTimingNoLdsReads) {
+          // the empty asm makes the register's old contents a new value for the compiler, as a read would
+          if constexpr (mt % 4 == 1 && mt / 4 + 1 < Cfg::NBAND) asm volatile("" : "+v"(sa4[band_reg(mt / 4 + 1)]));
+          if constexpr (mt == Cfg::R_NEXT) asm volatile("" : "+v"(sa4[band_reg(Cfg::NBAND)]));
+        } else {
+          if constexpr (mt % 4 == 1 && mt / 4 + 1 < Cfg::NBAND) sa4[band_reg(mt / 4 + 1)] = *(const v4f*)(st + saRd + (mt / 4 + 1) * 256);
+          if constexpr (mt == Cfg::R_NEXT) sa4[band_reg(Cfg::NBAND)] = *(const v4f*)(st1 + saRd);
+        }
       };
       auto body = [&](auto tc) __attribute__((always_inline)) {
         constexpr int t = decltype(tc)::value;
@@ -401,7 +425,9 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
             // fragment of activation block mt + AFR - 1 into the slot block mt - 1 has left; past the end of
             // this K block that is the next K block's, published by the barrier above
             constexpr int nb = mt + AFR - 1;
-            if constexpr (nb < TM) {
+            if constexpr (Cfg::TIMING & kTimingNoLdsReads) {
+              asm volatile("" : "+v"(afr[nb % AFR]));
+            } else if constexpr (nb < TM) {
               afr[nb % AFR] = read_frag(st + nb * 2048);
             } else {
               afr[nb % AFR] = read_frag(st1 + (nb - TM) * 2048);
@@ -413,12 +439,21 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
             read_scales(std::integral_constant<int, mt>{});
           }
           p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[BS][j], afr[mt % AFR], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
-          if constexpr (t >= Cfg::T_A0 && t < Cfg::T_A0 + Cfg::A_ITERS)
-            dma_a(std::integral_constant<int, t - Cfg::T_A0>{}, kb + 2, stageN);
-          // refills: fragment F+3 into the slot fragment F was copied from, some MFMAs (and the LDS reads they
-          // waited for, which return in order) after that copy
-          if constexpr (t == Cfg::T_R0) dma_b(kb + 2, J1, bslot);       // 2kb+2 -> 2kb+5
-          if constexpr (t == Cfg::T_R1) dma_b(kb + 3, J0, bslot1);      // 2kb+3 -> 2kb+6
+          if constexpr (!(Cfg::TIMING & kTimingNoFetch)) {
+            if constexpr (t >= Cfg::T_A0 && t < Cfg::T_A0 + Cfg::A_STEP * Cfg::A_ITERS && (t - Cfg::T_A0) % Cfg::A_STEP == 0)
+              dma_a(std::integral_constant<int, (t - Cfg::T_A0) / Cfg::A_STEP>{}, kb + 2, stageN);
+            // refills: fragment F+3 into the slot fragment F was copied from, some MFMAs (and the LDS reads they
+            // waited for, which return in order) after that copy
+            if constexpr (Cfg::R_STEP == 0) {
+              if constexpr (t == Cfg::T_R0) dma_b(kb + 2, J1, bslot);       // 2kb+2 -> 2kb+5
+              if constexpr (t == Cfg::T_R1) dma_b(kb + 3, J0, bslot1);      // 2kb+3 -> 2kb+6
+            } else {
+              if constexpr (t == Cfg::T_R0) dma_b(kb + 2, J1, bslot, 1);
+              if constexpr (t == Cfg::T_R0 + Cfg::R_STEP) dma_b(kb + 2, J1, bslot, 2);
+              if constexpr (t == Cfg::T_R1) dma_b(kb + 3, J0, bslot1, 1);
+              if constexpr (t == Cfg::T_R1 + Cfg::R_STEP) dma_b(kb + 3, J0, bslot1, 2);
+            }
+          }
         }
         if constexpr (t >= PIPE) {
           constexpr int u = t - PIPE;
@@ -433,17 +468,23 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
           if constexpr (j == 0) {
             __builtin_amdgcn_sched_group_barrier(0x002, Cfg::FUSE ? 2 : 1, 0);                   // scale product(s)
             constexpr int mt = t / TN;                                                           // DS reads: 2 of a fragment,
-            __builtin_amdgcn_sched_group_barrier(0x100, 2 + (mt + AFR - 1 == TM ? (Cfg::FUSE ? 2 : 1) : 0)   // weight scale(s),
-                                                            + (mt % 4 == 1 && mt / 4 + 1 < Cfg::NBAND ? 1 : 0) + (mt == Cfg::R_NEXT ? 1 : 0), 0);   // a band of scales
+            if constexpr (!(Cfg::TIMING & kTimingNoLdsReads))
+              __builtin_amdgcn_sched_group_barrier(0x100, 2 + (mt + AFR - 1 == TM ? (Cfg::FUSE ? 2 : 1) : 0)   // weight scale(s),
+                                                              + (mt % 4 == 1 && mt / 4 + 1 < Cfg::NBAND ? 1 : 0) + (mt == Cfg::R_NEXT ? 1 : 0), 0);   // a band of scales
           }
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                     // 1 MFMA
-          if constexpr (t >= Cfg::T_A0 && t < Cfg::T_A0 + Cfg::A_ITERS) {
+          if constexpr (t >= Cfg::T_A0 && t < Cfg::T_A0 + Cfg::A_STEP * Cfg::A_ITERS && (t - Cfg::T_A0) % Cfg::A_STEP == 0) {
             __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);                                   // offset select
             __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
           }
-          if constexpr (t == Cfg::T_R0 || t == Cfg::T_R1) {
-            __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+          if constexpr (Cfg::R_STEP == 0) {
+            if constexpr (t == Cfg::T_R0 || t == Cfg::T_R1) {
+              __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+              __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+            }
+          } else if constexpr (t == Cfg::T_R0 || t == Cfg::T_R1 || t == Cfg::T_R0 + Cfg::R_STEP || t == Cfg::T_R1 + Cfg::R_STEP) {
+            __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
           }
         }
         if constexpr (t >= PIPE) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);              // 4 FMAs
@@ -455,7 +496,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
         constexpr int mt = decltype(mc)::value;
         if constexpr (mt * TN == Cfg::T_MID) {
           // weight fragment 2kb+3, fetched a K block ago, is older than the W_MID newest fetches
-          wait_vmcnt<Cfg::W_MID>();
+          if constexpr (!(Cfg::TIMING & kTimingNoFetchWaits)) wait_vmcnt<Cfg::W_MID>();
           bfr[BS ^ 1][1] = read_frag(bslots + bslot1 * Cfg::B_SLOT_BYTES);
           __builtin_amdgcn_sched_barrier(0);
         }

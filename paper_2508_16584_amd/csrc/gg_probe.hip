@@ -8,6 +8,7 @@
 
 #include "gg_probe.h"
 #include "gemm_kernel.h"   // operand vector types, buffer descriptor flags, wait_vmcnt
+#include "gemm_kernel_rb.h"   // the second GEMM kernel, for its measurement builds (RbCfg<..., TIMING>)
 
 namespace {
 
@@ -268,6 +269,49 @@ hipError_t launch_fetch(const uint8_t* A, const uint8_t* B, int pattern, int ste
   return hipGetLastError();
 }
 
+
+// ---------------------------------------------------------------------------------------------- K step of the GEMM
+// Operand bytes like e4m3-quantised normal samples (sum of four uniforms, 3 sigma at the format's largest value),
+// made on the device with the hardware conversion; scales: positive values around 2^-7.
+__global__ void __launch_bounds__(256) fill_e4m3_kernel(uint8_t* p, size_t n, unsigned seed) {
+  const size_t stride = (size_t)gridDim.x * 256 * 4;
+  for (size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4; i < n; i += stride) {
+    float v[4];
+    for (int j = 0; j < 4; ++j) {
+      unsigned x = (unsigned)(i + j) * 2654435761u + seed;
+      float g = 0.f;
+      for (int u = 0; u < 4; ++u) {
+        x = x * 1664525u + 1013904223u;
+        g += (float)(x >> 8) * (1.0f / 16777216.0f) - 0.5f;
+      }
+      v[j] = g * 1.7320508f * (448.0f / 3.0f);
+    }
+    int w = __builtin_amdgcn_cvt_pk_fp8_f32(v[0], v[1], 0, false);
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(v[2], v[3], w, true);
+    *(int*)(p + i) = w;
+  }
+}
+__global__ void __launch_bounds__(256) fill_scale_kernel(float* p, size_t n, unsigned seed) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+    const unsigned x = ((unsigned)i * 2654435761u + seed) * 1664525u + 1013904223u;
+    p[i] = 0.0078125f * (1.0f + (float)(x >> 8) * (1.0f / 16777216.0f));
+  }
+}
+
+template <class Cfg>
+hipError_t launch_rb(const gg::GemmArgs& args, int grid) {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_gemm_rb_kernel<Cfg>), hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(gg::gg_gemm_rb_kernel<Cfg>, dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, 0, args);
+  return hipGetLastError();
+}
+template <int TIMING>
+hipError_t launch_rb_rows(int tile_rows, const gg::GemmArgs& args, int grid) {
+  if (tile_rows == 192) return launch_rb<gg::RbCfg<192, 4, false, false, false, false, false, TIMING>>(args, grid);
+  return launch_rb<gg::RbCfg<256, 2, false, false, false, false, false, TIMING>>(args, grid);
+}
+
 }  // namespace
 
 extern "C" {
@@ -468,6 +512,118 @@ int gg_probe_lds_fetch(int pattern, int depth, int reps, double* gbytes_per_s_ou
   const double bytes = 65536.0 * steps * grid, sec = (double)ms * 1e-3;
   *gbytes_per_s_out = bytes / sec * 1e-9;
   *bytes_per_clk_cu_out = khz > 0 ? bytes / sec / ((double)khz * 1e3) / grid : 0.0;
+  cleanup();
+  return 0;
+}
+
+int gg_probe_gemm_kstep(int tile_rows, int left_out, int groups, int rows_per_group, int n, int k, int reps, double* us_out) {
+  if ((tile_rows != 192 && tile_rows != 256) || groups < 1 || groups > 4096 || rows_per_group < 1 || n < 256 || n % 256 != 0 ||
+      k < 512 || k % 256 != 0 || reps < 1 || !us_out)
+    return (int)hipErrorInvalidValue;
+  const int64_t m_total = (int64_t)groups * rows_per_group;
+  if (m_total * k > 0x7FFFFFFFLL || (int64_t)n * k > 0x7FFFFFFFLL || m_total * n > 0x3FFFFFFFLL) return (int)hipErrorInvalidValue;
+  switch (left_out) {
+    case 0: case 1: case 2: case 4: case 8: case 5: case 13: case 16: case 20: case 32: break;
+    default: return (int)hipErrorInvalidValue;
+  }
+  const int kb = k / 128, nb = n / 128;
+  uint8_t *A = nullptr, *B = nullptr;
+  float *SA = nullptr, *SB = nullptr;
+  int32_t* off = nullptr;
+  uint16_t* C = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  auto cleanup = [&] {
+    if (A) (void)hipFree(A);
+    if (B) (void)hipFree(B);
+    if (SA) (void)hipFree(SA);
+    if (SB) (void)hipFree(SB);
+    if (off) (void)hipFree(off);
+    if (C) (void)hipFree(C);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+  };
+  const size_t a_bytes = (size_t)m_total * k, b_bytes = (size_t)groups * n * k;
+  PROBE_TRY(hipMalloc(&A, a_bytes));
+  PROBE_TRY(hipMalloc(&B, b_bytes));
+  PROBE_TRY(hipMalloc(&SA, (size_t)m_total * kb * 4));
+  PROBE_TRY(hipMalloc(&SB, (size_t)groups * nb * kb * 4));
+  PROBE_TRY(hipMalloc(&off, (size_t)(groups + 1) * 4));
+  PROBE_TRY(hipMalloc(&C, (size_t)m_total * n * 2));
+  std::vector<int32_t> h_off(groups + 1);
+  for (int g = 0; g <= groups; ++g) h_off[g] = g * rows_per_group;
+  PROBE_TRY(hipMemcpy(off, h_off.data(), h_off.size() * 4, hipMemcpyHostToDevice));
+  const int fgrid = cus() * 8;
+  if (left_out == 32) {   // the kernel as launched, on operands that are all zero bytes
+    PROBE_TRY(hipMemset(A, 0, a_bytes));
+    PROBE_TRY(hipMemset(B, 0, b_bytes));
+  } else {
+    hipLaunchKernelGGL(fill_e4m3_kernel, dim3(fgrid), dim3(256), 0, 0, A, a_bytes, 1u);
+    hipLaunchKernelGGL(fill_e4m3_kernel, dim3(fgrid), dim3(256), 0, 0, B, b_bytes, 2u);
+  }
+  hipLaunchKernelGGL(fill_scale_kernel, dim3(fgrid), dim3(256), 0, 0, SA, (size_t)m_total * kb, 3u);
+  hipLaunchKernelGGL(fill_scale_kernel, dim3(fgrid), dim3(256), 0, 0, SB, (size_t)groups * nb * kb, 4u);
+  PROBE_TRY(hipGetLastError());
+  PROBE_TRY(hipMemset(C, 0, (size_t)m_total * n * 2));
+
+  // the launch arguments as the GEMM library fills them for whole tiles and blocks, row-major activation scales
+  gg::GemmArgs args{};
+  args.A = A;
+  args.SA = SA;
+  args.B = B;
+  args.SB = SB;
+  args.off = off;
+  args.C = C;
+  args.G = groups;
+  args.M_total = (int)m_total;
+  args.N = n;
+  args.K = k;
+  args.KB = kb;
+  args.k_rem = 128;
+  args.n_tiles = n / 256;
+  args.n_chunk = args.n_tiles < 8 ? args.n_tiles : 8;
+  args.sa_row_stride = 4 * kb;
+  args.sa_kb_stride = 4;
+  args.rot_mul = (k % 8192 == 4096) ? 4 : 0;
+  const int64_t max_tiles = (int64_t)groups * ((rows_per_group + tile_rows - 1) / tile_rows) * args.n_tiles;
+  int64_t grid = cus();
+  if (grid > max_tiles) grid = max_tiles;
+  if (grid >= 8) {
+    grid -= grid % 8;
+    args.slots = (int)(grid / 8);
+  }
+  PROBE_TRY(hipEventCreate(&e0));
+  PROBE_TRY(hipEventCreate(&e1));
+  auto launch = [&]() -> hipError_t {
+    switch (left_out) {
+      case 0: case 32: return launch_rb_rows<0>(tile_rows, args, (int)grid);
+      case 1: return launch_rb_rows<1>(tile_rows, args, (int)grid);
+      case 2: return launch_rb_rows<2>(tile_rows, args, (int)grid);
+      case 4: return launch_rb_rows<4>(tile_rows, args, (int)grid);
+      case 8: return launch_rb_rows<8>(tile_rows, args, (int)grid);
+      case 5: return launch_rb_rows<5>(tile_rows, args, (int)grid);
+      case 16: return launch_rb_rows<16>(tile_rows, args, (int)grid);
+      case 20: return launch_rb_rows<20>(tile_rows, args, (int)grid);
+      default: return launch_rb_rows<13>(tile_rows, args, (int)grid);
+    }
+  };
+  // warm-up: launches of the same build for about 150 ms, so that the timed ones run at the sustained clock (after
+  // an idle period the clock takes about a hundred launches of this size to settle)
+  for (float warm_ms = 0.f; warm_ms < 150.f;) {
+    PROBE_TRY(hipEventRecord(e0, 0));
+    for (int i = 0; i < 10; ++i) PROBE_TRY(launch());
+    PROBE_TRY(hipEventRecord(e1, 0));
+    PROBE_TRY(hipEventSynchronize(e1));
+    float t = 0.f;
+    PROBE_TRY(hipEventElapsedTime(&t, e0, e1));
+    warm_ms += t > 0.01f ? t : 0.01f;
+  }
+  PROBE_TRY(hipEventRecord(e0, 0));
+  for (int i = 0; i < reps; ++i) PROBE_TRY(launch());
+  PROBE_TRY(hipEventRecord(e1, 0));
+  PROBE_TRY(hipEventSynchronize(e1));
+  float ms = 0.f;
+  PROBE_TRY(hipEventElapsedTime(&ms, e0, e1));
+  *us_out = (double)ms * 1e3 / reps;
   cleanup();
   return 0;
 }

@@ -41,7 +41,7 @@ def test_probe_library_exports_what_its_header_declares():
     header = os.path.join(os.path.dirname(HEADER), "gg_probe.h")
     text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
     names = sorted(set(re.findall(r"\b(gg_probe_\w+)\s*\(", text)))
-    assert names == ["gg_probe_hbm", "gg_probe_issue_mix", "gg_probe_lds_fetch", "gg_probe_mfma"]
+    assert names == ["gg_probe_gemm_kstep", "gg_probe_hbm", "gg_probe_issue_mix", "gg_probe_lds_fetch", "gg_probe_mfma"]
     if not os.path.exists(gg.probe_library_path()):
         gg.build_library()
     probe = gg.load_probe_library()
@@ -54,6 +54,12 @@ def test_probe_library_exports_what_its_header_declares():
     assert probe.gg_probe_hbm(2, 4096, 1, ctypes.byref(out)) != 0 and probe.gg_probe_hbm(0, 100, 1, ctypes.byref(out)) != 0
     assert probe.gg_probe_lds_fetch(3, 3, 1, ctypes.byref(out), ctypes.byref(out)) != 0
     assert probe.gg_probe_lds_fetch(0, 8, 1, ctypes.byref(out), ctypes.byref(out)) != 0
+    # tile height, build, shape (n % 256, k % 256, k >= 512) and the 2 GiB limit per tensor
+    assert probe.gg_probe_gemm_kstep(224, 0, 8, 1024, 4096, 7168, 1, ctypes.byref(out)) != 0
+    assert probe.gg_probe_gemm_kstep(192, 3, 8, 1024, 4096, 7168, 1, ctypes.byref(out)) != 0
+    assert probe.gg_probe_gemm_kstep(192, 0, 8, 1024, 4096 + 128, 7168, 1, ctypes.byref(out)) != 0
+    assert probe.gg_probe_gemm_kstep(192, 0, 8, 1024, 4096, 256, 1, ctypes.byref(out)) != 0
+    assert probe.gg_probe_gemm_kstep(192, 0, 64, 8192, 4096, 7168, 1, ctypes.byref(out)) != 0
 
 
 def test_version_status_strings_and_variants(lib):
