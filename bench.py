@@ -341,6 +341,8 @@ def bench_kstep_parts():
     import paper_2508_16584_amd as gg
     parts = [(0, "nothing left out (the kernel as launched)"), (4, "no barrier"), (8, "no LDS reads of activations and scales"),
              (16, "no waits for the fetches"), (20, "no waits for the fetches, no barrier"),
+             (28, "no waits for the fetches, no barrier, no LDS reads (the fetched data moves beside the arithmetic, nothing waits for it)"),
+             (92, "the same with the fetches landing in registers instead of LDS"),
              (32, "nothing left out, operands all zero bytes (same traffic, little power)"),
              (2, "fetches issued to nowhere (no traffic, zero operands)"), (1, "no fetches"), (5, "no fetches, no barrier"),
              (13, "no fetches, no barrier, no LDS reads (matrix instructions, FMAs, bookkeeping)")]

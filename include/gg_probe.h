@@ -75,11 +75,12 @@ int gg_probe_lds_fetch(int pattern, int depth, int reps, double* gbytes_per_s_ou
  *   left_out:  0 nothing (the kernel as the library launches it); 1 the fetches of the K steps; 2 every fetch goes
  *              to an out-of-range offset (issued, no traffic, the operands become zeros: compare cycles, not time);
  *              4 the barrier of the K step; 8 the LDS reads of activation fragments and scales; 16 the waits for the
- *              fetches (the data moves, nobody waits for it); 5 = 1 + 4; 20 = 16 + 4; 13 = 1 + 4 + 8 (matrix
- *              instructions, FMAs and bookkeeping only); 32 nothing left out, but A and B are all zero bytes (the same
- *              traffic as 0 at the power of 2).  Anything else: hipErrorInvalidValue.
- *              Only accesses and waits are removed, so every remaining access stays in bounds; the OUTPUT IS
- *              MEANINGLESS for every value but 0.
+ *              fetches (the data moves, nobody waits for it); 64 every fetch is an ordinary load into registers nobody
+ *              reads (the same requests to memory, no LDS write).  Built sums: 5 = 1 + 4; 20 = 16 + 4;
+ *              28 = 16 + 4 + 8; 92 = 28 + 64; 13 = 1 + 4 + 8 (matrix instructions, FMAs and bookkeeping only).
+ *              32: nothing left out, but A and B are all zero bytes (the traffic of 0 at the power of 2).
+ *              Anything else: hipErrorInvalidValue.  Only accesses and waits are removed, so every remaining access
+ *              stays in bounds; the OUTPUT IS MEANINGLESS for every value but 0 and 32.
  *   reps:      timed launches (launches of the same build for about 150 ms precede them: the sustained clock)
  * us_out (host): microseconds per launch.  The shader clock differs between the builds (fewer operand bits moving,
  * higher clock): for cycles run the same call under `rocprofv3 --pmc GRBM_GUI_ACTIVE`. */

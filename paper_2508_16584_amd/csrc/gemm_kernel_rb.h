@@ -58,7 +58,10 @@ namespace gg {
 // prologue read); 16: the K step's waits for its fetches (operands are read whether they have arrived or not).
 // Accesses and waits are only ever removed, so everything that remains stays in bounds and every wait ends; the
 // results are meaningless.
-enum : int { kTimingNoFetch = 1, kTimingFetchNowhere = 2, kTimingNoBarrier = 4, kTimingNoLdsReads = 8, kTimingNoFetchWaits = 16 };
+// 64: every fetch of the K steps goes to four registers that nobody reads instead of to LDS (the same requests to
+// memory; the operands in LDS stay what the prologue fetched).
+enum : int { kTimingNoFetch = 1, kTimingFetchNowhere = 2, kTimingNoBarrier = 4, kTimingNoLdsReads = 8, kTimingNoFetchWaits = 16,
+             kTimingFetchToRegs = 64 };
 template <int BM_, int AFR_ = 4, bool KP_ = false, bool FUSE_ = false, bool SKIP_ = false, bool RAGGED_ = false, bool ODDK_ = RAGGED_, int TIMING_ = 0>
 struct RbCfg {
   static constexpr bool KP = KP_, FUSE = FUSE_, SKIP = SKIP_, RAGGED = RAGGED_, ODDK = ODDK_;
@@ -135,7 +138,14 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t uniform_rsrc(const void* ptr, 
   return __builtin_amdgcn_make_buffer_rsrc((void*)(((uint64_t)hi << 32) | lo), 0, __builtin_amdgcn_readfirstlane(bytes), GG_RSRC_FLAGS);
 }
 
-// A buffer offset no descriptor of this kernel covers: loads return zero (a DMA writes zeros) and touch no memory.
+// kTimingFetchToRegs: the fetch as an ordinary load into registers that stay allocated to the end of the kernel
+// (the compiler does not know that the asm is a load; "+v" keeps it from giving the registers to anything else)
+__device__ __forceinline__ void timing_fetch16(v4i& sink, int voffset, __amdgpu_buffer_rsrc_t rsrc, int soffset) {
+  asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "+v"(sink) : "v"(voffset), "s"(rsrc), "s"(soffset));
+}
+__device__ __forceinline__ void timing_fetch4(v4i& sink, int voffset, __amdgpu_buffer_rsrc_t rsrc, int soffset) {
+  asm volatile("buffer_load_dword %0, %1, %2, %3 offen" : "+v"(sink.x) : "v"(voffset), "s"(rsrc), "s"(soffset));
+}
 
 template <class Cfg>
 __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
@@ -271,6 +281,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
   int rot = k_rotation(a, cur.n0), rot0 = rot;
   int kbase = 0, kbase0 = 0;      // K-block index at which the tile behind dA.., dB, dS (resp. dB0) starts
   bool primed = false;
+  v4i sink = {0, 0, 0, 0};        // kTimingFetchToRegs: where the fetches land (kept alive to the end of the kernel)
   v8i bfr[2][TN];                 // weight fragments of K block kb in set kb % 2
   v8i afr[AFR];
   v4f sa4[2];                     // activation scales of two bands of four activation blocks (see band_reg)
@@ -295,12 +306,18 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       const int kp = k_wrapped(kb + rot, KB);
       const int vo = (Cfg::TIMING & kTimingFetchNowhere) ? GG_OOB_OFFSET
                      : !Cfg::ODDK || kb < KB ? (Cfg::RAGGED && kp == KB - 1 ? vA_last : vA) : GG_OOB_OFFSET;
+      if constexpr (Cfg::TIMING & kTimingFetchToRegs)
+        timing_fetch16(sink, vo, i == 0 ? dA0 : i == 1 ? dA1 : i == 2 ? dA2 : dA3, __builtin_amdgcn_readfirstlane(kp * 128));
+      else
       __builtin_amdgcn_raw_ptr_buffer_load_lds(i == 0 ? dA0 : i == 1 ? dA1 : i == 2 ? dA2 : dA3, GG_LDS_PTR(lds + stage * Cfg::STAGE_BYTES + (w + i * NW) * 1024), 16, vo,
                                                __builtin_amdgcn_readfirstlane(kp * 128), 0, 0);
     };
     auto dma_scales = [&](int kb_t, int stage) __attribute__((always_inline)) {     // exactly one DMA in every wave
       const int kb = kb_t - kbase;
       const int vo = (Cfg::TIMING & kTimingFetchNowhere) ? GG_OOB_OFFSET : !Cfg::ODDK || kb < KB ? vS : GG_OOB_OFFSET;
+      if constexpr (Cfg::TIMING & kTimingFetchToRegs)
+        timing_fetch4(sink, vo, dS, __builtin_amdgcn_readfirstlane(k_wrapped(kb + rot, KB) * s_kb_stride));
+      else
       __builtin_amdgcn_raw_ptr_buffer_load_lds(dS, GG_LDS_PTR(lds + stage * Cfg::STAGE_BYTES + ldsS), 4, vo,
                                                __builtin_amdgcn_readfirstlane(k_wrapped(kb + rot, KB) * s_kb_stride), 0, 0);
     };
@@ -314,6 +331,11 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       const int kp = k_wrapped(kb + (j == 0 ? rot0 : rot), KB);
       const bool last = Cfg::RAGGED && kp == KB - 1;
       const int so = __builtin_amdgcn_readfirstlane(kp * 128 + j * frag1_off);
+      if constexpr (Cfg::TIMING & kTimingFetchToRegs) {
+        if (halves & 1) timing_fetch16(sink, vB0, j == 0 ? dB0 : dB, so);
+        if (halves & 2) timing_fetch16(sink, vB1, j == 0 ? dB0 : dB, so);
+        return;
+      }
       if (halves & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(j == 0 ? dB0 : dB, GG_LDS_PTR(dst), 16, in ? (last ? vB0_last : vB0) : GG_OOB_OFFSET, so, 0, 0);
       if (halves & 2) __builtin_amdgcn_raw_ptr_buffer_load_lds(j == 0 ? dB0 : dB, GG_LDS_PTR(dst + 1024), 16, in ? (last ? vB1_last : vB1) : GG_OOB_OFFSET, so, 0, 0);
     };
@@ -668,6 +690,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
     if (!has_next) {
       // the dropped fetches of the last K blocks still write zeros into this workgroup's LDS: let them land
       wait_vmcnt<0>();
+      if constexpr (Cfg::TIMING & kTimingFetchToRegs) asm volatile("" : : "v"(sink));
       return;
     }
     cur = nxt;

@@ -523,7 +523,7 @@ int gg_probe_gemm_kstep(int tile_rows, int left_out, int groups, int rows_per_gr
   const int64_t m_total = (int64_t)groups * rows_per_group;
   if (m_total * k > 0x7FFFFFFFLL || (int64_t)n * k > 0x7FFFFFFFLL || m_total * n > 0x3FFFFFFFLL) return (int)hipErrorInvalidValue;
   switch (left_out) {
-    case 0: case 1: case 2: case 4: case 8: case 5: case 13: case 16: case 20: case 32: break;
+    case 0: case 1: case 2: case 4: case 8: case 5: case 13: case 16: case 20: case 28: case 32: case 92: break;
     default: return (int)hipErrorInvalidValue;
   }
   const int kb = k / 128, nb = n / 128;
@@ -603,6 +603,8 @@ int gg_probe_gemm_kstep(int tile_rows, int left_out, int groups, int rows_per_gr
       case 5: return launch_rb_rows<5>(tile_rows, args, (int)grid);
       case 16: return launch_rb_rows<16>(tile_rows, args, (int)grid);
       case 20: return launch_rb_rows<20>(tile_rows, args, (int)grid);
+      case 28: return launch_rb_rows<28>(tile_rows, args, (int)grid);
+      case 92: return launch_rb_rows<92>(tile_rows, args, (int)grid);
       default: return launch_rb_rows<13>(tile_rows, args, (int)grid);
     }
   };
