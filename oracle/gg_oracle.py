@@ -30,7 +30,8 @@ Every function here is pinned by tests/test_oracle_pins.py (exact rational
 brute force, closed forms, the paper's worked example, the padded == unpadded
 invariant of Sec. 3.2; the encoder and the row quantiser at the end of the file
 against the library's float8 cast, round trips through the decode table and
-hand-made ties; the activation against the library's silu and closed forms).  No function is "parity unpinned".
+hand-made ties; the activation against the library's silu and closed forms).  One function is "parity unpinned" against the
+paper: grouped_gemm_wgrad, whose definition the paper does not give (see the comment above it).
 """
 from __future__ import annotations
 
@@ -248,6 +249,70 @@ def grouped_gemm(A, SA, B, SB, group_offsets, rows=None, with_abs_sum=False, out
 
     assert out in ("bf16", "f16")
     out = {"rows": rows, "group": grp, "D": D, "C": bf16_bits_from_f64(D) if out == "bf16" else f16_bits_from_f64(D)}
+    if with_abs_sum:
+        out["S"] = S
+    return out
+
+
+# ----------------------------------------------------------------------------
+# the variable-K grouped GEMM of training (the weight gradient of the same expert
+# layer).  The paper's title names training next to inference and its Sec. 4
+# points at the kernels around the grouped GEMM, but it defines neither layouts
+# nor scale granularity for this one: the definition below is this build's own
+# reading, and the function is PARITY UNPINNED AGAINST THE PAPER (its pins in
+# tests/test_oracle_pins.py are exact rationals, closed forms and the reduction
+# of its one-group case to grouped_gemm above).
+# ----------------------------------------------------------------------------
+def grouped_gemm_wgrad(XT, SX, DYT, SDY, group_offsets, with_abs_sum=False):
+    """dW^g = dY^g^T X^g for every group, the contraction running over the group's rows (tokens).
+
+    XT   uint8 [K, M_total]   e4m3 bytes of X transposed: XT[k, r] is feature k of token r
+    SX   float [K, ceil(M_total/128)]   one scale per (feature, block of 128 tokens); the token blocks are
+         [128 j, 128 j + 128) of the concatenated token axis, whatever the groups are (a block may hold tokens
+         of two or more groups)
+    DYT  uint8 [N, M_total]   e4m3 bytes of dY transposed
+    SDY  float [N, ceil(M_total/128)]
+    group_offsets int [G+1]   tokens of group g are [off[g], off[g+1])
+
+        dW[g, n, k] = sum_{j ascending} ( SDY[n, j] * SX[k, j] )
+                                        * ( sum_{r in block j and in group g} dec(DYT[n, r]) * dec(XT[k, r]) )
+
+    Tokens outside the group contribute nothing, whatever their bytes are (NaN codes included).  A group without
+    tokens gives zeros.  Returns {"D": float64 [G, N, K], "W": float32 [G, N, K] (D rounded once, to nearest even),
+    "S": float64 [G, N, K] (with_abs_sum): sum_j |sdy*sx| * sum_r |dy*x|}.
+    The inner sums are exact in float64 (at most 128 products, each a multiple of 2^-18 below 2^18) and so is
+    sdy*sx; only the accumulation over j rounds, in ascending order.
+    """
+    XT = np.asarray(XT)
+    DYT = np.asarray(DYT)
+    off = np.asarray(group_offsets, dtype=np.int64)
+    assert XT.dtype == np.uint8 and DYT.dtype == np.uint8 and XT.ndim == 2 and DYT.ndim == 2
+    K, M_total = XT.shape
+    N = DYT.shape[0]
+    assert DYT.shape[1] == M_total
+    MB = -(-M_total // SCALE_BLOCK)
+    SX = np.asarray(SX, dtype=np.float64)
+    SDY = np.asarray(SDY, dtype=np.float64)
+    assert SX.shape == (K, MB) and SDY.shape == (N, MB)
+    G = off.shape[0] - 1
+    assert np.all(np.diff(off) >= 0) and off[0] >= 0 and off[-1] <= M_total
+    D = np.zeros((G, N, K), dtype=np.float64)
+    S = np.zeros((G, N, K), dtype=np.float64) if with_abs_sum else None
+    for g in range(G):
+        lo, hi = int(off[g]), int(off[g + 1])
+        if hi <= lo:
+            continue
+        for j in range(lo // SCALE_BLOCK, -(-hi // SCALE_BLOCK)):
+            r0, r1 = max(j * SCALE_BLOCK, lo), min((j + 1) * SCALE_BLOCK, hi)
+            dy = e4m3_decode(DYT[:, r0:r1])             # [N, <=128]
+            x = e4m3_decode(XT[:, r0:r1])               # [K, <=128]
+            inner = dy @ x.T                            # exact
+            scale = SDY[:, j][:, None] * SX[:, j][None, :]
+            D[g] += scale * inner
+            if with_abs_sum:
+                S[g] += np.abs(scale) * (np.abs(dy) @ np.abs(x).T)
+    with np.errstate(over="ignore", invalid="ignore"):
+        out = {"D": D, "W": D.astype(np.float32)}       # float64 -> float32 is one RNE step
     if with_abs_sum:
         out["S"] = S
     return out
