@@ -158,6 +158,29 @@ int gg_fp8_grouped_gemm_swiglu(const void* A, const float* SA, const void* B, co
                                const int32_t* group_offsets, void* A2, float* SA2, void* act_out,
                                int G, int64_t M_total, int I, int K, void* stream, int variant, unsigned flags);
 
+/* The variable-K grouped GEMM of training: the weight gradient dW^g = dY^g^T X^g of the expert layer whose forward
+ * pass gg_fp8_grouped_gemm computes, the contraction running over the tokens of each group, with no group padded
+ * (the capability of Sec. 2.2 on the contraction dimension).  The paper's title names training and Sec. 4 the kernels
+ * around the grouped GEMM, but the paper defines neither layouts nor scale granularity for this operation: the
+ * definition is this library's own reading.
+ *   XT  e4m3 [K, M_total]   X transposed: feature k of token r at XT[k * M_total + r] (the token index contiguous)
+ *   SX  fp32 [K, ceil(M_total/128)]   one scale per feature and block of 128 tokens; the token blocks are
+ *       [128 j, 128 j + 128) of the concatenated token axis whatever the groups are (a block may hold tokens of
+ *       several groups), so every fetch is 16-byte aligned and a group may start and end at ANY token
+ *   DYT e4m3 [N, M_total], SDY fp32 [N, ceil(M_total/128)]   the output gradient, transposed likewise
+ *   group_offsets int32 [G+1] on the device: tokens of group g are [off[g], off[g+1]); clamped on the device like
+ *       those of gg_fp8_grouped_gemm (a bad array garbles results, it cannot make the kernel leave the tensors)
+ *   dW  fp32 [G, N, K], EVERY element written:
+ *       dW[g][n][k] = sum_j SDY[n][j] * SX[k][j] * sum_{r in block j and in group g} dec(DYT[n][r]) * dec(XT[k][r])
+ *       (blocks in ascending order; fp32 accumulation).  A group without tokens gets zeros.  Bytes of tokens outside
+ *       a group never reach a product of that group, whatever they are (NaN codes included).
+ * M_total a multiple of 16, N of 128, K of 256 (GG_ERR_UNSUPPORTED otherwise); K * M_total and N * M_total below
+ * 2^31, K at most 2^20 (GG_ERR_SHAPE).  G == 0: GG_OK, nothing enqueued; M_total == 0 with G > 0: zeros are written
+ * (XT, SX, DYT, SDY may then be NULL).  All pointers device memory, 16-byte aligned tensors.  No workspace, nothing
+ * allocated, asynchronous on `stream`. */
+int gg_fp8_grouped_gemm_wgrad(const void* XT, const float* SX, const void* DYT, const float* SDY,
+                              const int32_t* group_offsets, float* dW, int G, int64_t M_total, int N, int K, void* stream);
+
 /* ---- the pad-then-GEMM comparison path (the baseline of Sec. 3) ------------
  * Every group is copied to an offset that is a multiple of 128 rows, pad rows
  * are zero, the same GEMM kernels run on the aligned problem, and the valid

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     grouped_gemm_splitk_noalloc,
     noalloc_max_elements,
     grouped_gemm_swiglu,
+    grouped_gemm_wgrad,
     library_path,
     load_library,
     load_probe_library,

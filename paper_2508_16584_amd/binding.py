@@ -160,6 +160,8 @@ def load_library() -> ctypes.CDLL:
     lib.gg_fp8_noalloc_max_elements.restype = sz
     lib.gg_fp8_grouped_gemm_swiglu.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp, i32, ctypes.c_uint]
     lib.gg_fp8_grouped_gemm_swiglu.restype = i32
+    lib.gg_fp8_grouped_gemm_wgrad.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp]
+    lib.gg_fp8_grouped_gemm_wgrad.restype = i32
     lib.gg_fp8_pad_ex.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i64, i32, vp, ctypes.c_uint]
     lib.gg_fp8_pad_ex.restype = i32
     lib.gg_fp8_quantize_rows_ex.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, ctypes.c_uint]
@@ -196,6 +198,7 @@ EXPORTED_SYMBOLS = [
     "gg_fp8_grouped_gemm_variant", "gg_fp8_grouped_gemm_f16", "gg_fp8_grouped_gemm_ex", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_auto_variant", "gg_fp8_auto_variant_padded", "gg_fp8_padded_rows_cap",
     "gg_fp8_pad", "gg_fp8_grouped_gemm_padded", "gg_fp8_unpad", "gg_fp8_quantize_rows", "gg_fp8_swiglu_quantize_rows", "gg_fp8_check_offsets",
     "gg_fp8_grouped_gemm_splitk_noalloc", "gg_fp8_noalloc_max_elements", "gg_fp8_pad_ex", "gg_fp8_quantize_rows_ex", "gg_fp8_swiglu_quantize_rows_ex", "gg_fp8_grouped_gemm_swiglu",
+    "gg_fp8_grouped_gemm_wgrad",
 ]
 
 
@@ -394,6 +397,34 @@ def grouped_gemm_swiglu(A, SA, B, SB, group_offsets, A2=None, SA2=None, act_out=
                                           _ptr(act_out), G, M_total, inter, K, _stream(stream), int(variant),
                                           GG_SA_KMAJOR if sa_kmajor else 0))
     return A2, SA2, act_out
+
+
+def grouped_gemm_wgrad(XT, SX, DYT, SDY, group_offsets, dW=None, stream=None):
+    """gg_fp8_grouped_gemm_wgrad: dW [G, N, K] float32 from XT uint8 [K, M_total], SX float32 [K, ceil(M_total/128)],
+    DYT uint8 [N, M_total], SDY float32 [N, ceil(M_total/128)] and int32 group_offsets [G+1] (tokens of group g)."""
+    lib = load_library()
+    _want(XT, "XT", torch.uint8, 2)
+    _want(DYT, "DYT", torch.uint8, 2)
+    _want(SX, "SX", torch.float32, 2)
+    _want(SDY, "SDY", torch.float32, 2)
+    _want(group_offsets, "group_offsets", torch.int32, 1)
+    K, M_total = XT.shape
+    N = DYT.shape[0]
+    MB = (M_total + 127) // 128
+    G = group_offsets.shape[0] - 1
+    if DYT.shape[1] != M_total or tuple(SX.shape) != (K, MB) or tuple(SDY.shape) != (N, MB):
+        raise ValueError("XT [K, M_total], DYT [N, M_total], SX [K, ceil(M_total/128)], SDY [N, ceil(M_total/128)] expected")
+    for t, name in ((XT, "XT"), (SX, "SX"), (DYT, "DYT"), (SDY, "SDY"), (group_offsets, "group_offsets")):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous device tensor")
+    if dW is None:
+        dW = torch.empty((G, N, K), dtype=torch.float32, device=XT.device)
+    _want(dW, "dW", torch.float32, 3)
+    if tuple(dW.shape) != (G, N, K) or not dW.is_cuda or not dW.is_contiguous():
+        raise ValueError(f"dW must be a contiguous device tensor [{G}, {N}, {K}]")
+    _check(lib.gg_fp8_grouped_gemm_wgrad(_ptr(XT), _ptr(SX), _ptr(DYT), _ptr(SDY), _ptr(group_offsets), _ptr(dW),
+                                         G, M_total, N, K, _stream(stream)))
+    return dW
 
 
 def padded_rows_cap(G: int, M_total: int) -> int:

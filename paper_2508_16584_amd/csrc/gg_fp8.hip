@@ -13,6 +13,7 @@
 #include "gemm_kernel_rb.h"
 #include "pad_kernels.h"
 #include "quant_kernel.h"
+#include "wgrad_kernel.h"
 
 // Scratch of gg_fp8_grouped_gemm_splitk_noalloc: the partial sums of a split-K call, [2][M_total][N] fp32, for
 // problems of up to kScratchBytes / 8 output elements.  One copy per GPU the library runs on, held until the
@@ -423,6 +424,48 @@ int gg_fp8_grouped_gemm_splitk_noalloc(const void* A, const float* SA, const voi
 }
 
 size_t gg_fp8_noalloc_max_elements(void) { return kScratchBytes / (2 * sizeof(float)); }
+
+int gg_fp8_grouped_gemm_wgrad(const void* XT, const float* SX, const void* DYT, const float* SDY,
+                              const int32_t* group_offsets, float* dW, int G, int64_t M_total, int N, int K, void* stream) {
+  if (G < 0 || M_total < 0 || N <= 0 || K <= 0) return GG_ERR_SHAPE;
+  // whole output tiles of 256 features x 128 rows of dY^T; a row pitch that keeps every 128-token block 16-byte aligned
+  if (M_total % 16 != 0 || N % gg::WgradCfg::TN != 0 || K % gg::WgradCfg::TK != 0) return GG_ERR_UNSUPPORTED;
+  // the operands are addressed with 32-bit offsets from the start of each tensor, an output tile with 32-bit
+  // offsets from its first element
+  if (K > (1 << 20) || (int64_t)K * M_total > 0x7FFFFFFFLL || (int64_t)N * M_total > 0x7FFFFFFFLL) return GG_ERR_SHAPE;
+  if (G == 0) return GG_OK;
+  if (!group_offsets || !dW) return GG_ERR_NULL;
+  if (M_total > 0 && (!XT || !SX || !DYT || !SDY)) return GG_ERR_NULL;
+  const int64_t tiles = (int64_t)G * (N / gg::WgradCfg::TN) * (K / gg::WgradCfg::TK);
+  if (tiles > 0x7FFFFFFFLL) return GG_ERR_SHAPE;
+  gg::WgradArgs args;
+  args.XT = static_cast<const uint8_t*>(XT);
+  args.SX = SX;
+  args.DYT = static_cast<const uint8_t*>(DYT);
+  args.SDY = SDY;
+  args.off = group_offsets;
+  args.dW = dW;
+  args.G = G;
+  args.M_total = (int)M_total;
+  args.N = N;
+  args.K = K;
+  args.MB = (int)((M_total + 127) / 128);
+  args.n_tiles = N / gg::WgradCfg::TN;
+  args.k_tiles = K / gg::WgradCfg::TK;
+  args.per_xcd = tiles % kXcds == 0 ? (int)(tiles / kXcds) : 0;
+  static std::atomic<int> prepared[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return GG_ERR_HIP;
+  if (dev >= 0 && dev < 64 && !prepared[dev].load(std::memory_order_acquire)) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_wgrad_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            gg::WgradCfg::LDS_BYTES) != hipSuccess)
+      return GG_ERR_HIP;
+    prepared[dev].store(1, std::memory_order_release);
+  }
+  hipLaunchKernelGGL(gg::gg_wgrad_kernel, dim3((unsigned)tiles), dim3(gg::WgradCfg::NT), gg::WgradCfg::LDS_BYTES,
+                     static_cast<hipStream_t>(stream), args);
+  return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
+}
 
 int gg_fp8_grouped_gemm_swiglu(const void* A, const float* SA, const void* B, const float* SB,
                                const int32_t* group_offsets, void* A2, float* SA2, void* act_out,

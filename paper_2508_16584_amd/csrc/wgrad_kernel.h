@@ -1,0 +1,201 @@
+// Variable-K grouped GEMM of training for gfx950 (MI355X): the weight gradient of the expert layer whose forward
+// pass is the grouped GEMM of gemm_kernel.h (paper Sec. 2.1), computed without padding any group (the capability
+// of Sec. 2.2 carried over to the contraction dimension).  The paper's title names training and its Sec. 4 the
+// kernels around the grouped GEMM, but it defines no layouts or scale granularity for this operation; the
+// definition below is this library's own reading.
+//
+//   dW[g][n][k] = sum over token blocks j, ascending, of
+//                 SDY[n][j] * SX[k][j] * sum_{tokens r in block j and in group g} dec(DYT[n][r]) * dec(XT[k][r])
+//
+// XT [K, M_total] and DYT [N, M_total] are e4m3 bytes with the token index contiguous (both operands of the
+// contraction are then "row x 128 bytes" slabs, as in the forward kernel), SX [K, ceil(M_total/128)] and
+// SDY [N, ceil(M_total/128)] hold one fp32 scale per row and block of 128 tokens, the blocks being
+// [128 j, 128 j + 128) of the concatenated token axis whatever the groups are, and dW [G, N, K] is fp32.
+// Group boundaries may fall anywhere: the first and the last block of a group are fetched whole (16-byte aligned,
+// like every other block) and the bytes of tokens outside the group are cleared in registers, in BOTH operands, so
+// that a neighbouring group's bytes (NaN codes included) never reach a product.  A group without tokens gives zeros.
+//
+// Structure: one workgroup (8 waves, 4 along k x 2 along n) per output tile of 256 features x 128 rows of dY^T;
+// per token block the two operand tiles and their scales go global -> LDS by DMA into a ring of 3 buffers (two
+// blocks of look-ahead), swizzled like the forward kernels' tiles; a wave holds 4 + 4 operand fragments and 64 x 64
+// fp32 accumulators; one v_mfma_f32_16x16x128_f8f6f4 from zero per scale block, then acc += p * (sx * sdy) with
+// sx one of the lane's four feature rows and sdy the lane's dY^T row: 8 vector instructions per matrix instruction
+// (the factor differs per output element, not per lane as in the forward pass).
+#pragma once
+#include "gemm_kernel.h"
+
+namespace gg {
+
+struct WgradArgs {
+  const uint8_t* XT;    // [K, M_total]
+  const float* SX;      // [K, MB]
+  const uint8_t* DYT;   // [N, M_total]
+  const float* SDY;     // [N, MB]
+  const int32_t* off;   // [G + 1]
+  float* dW;            // [G, N, K]
+  int G, M_total, N, K, MB;
+  int n_tiles, k_tiles;   // N / 128, K / 256
+  int per_xcd;            // tiles per XCD when the grid is a multiple of 8, else 0
+};
+
+struct WgradCfg {
+  static constexpr int TK = 256, TN = 128, NW = 8, NT = 512, S = 3;
+  static constexpr int X_BYTES = TK * 128, Y_BYTES = TN * 128, SX_BYTES = TK * 4, SY_BYTES = TN * 4, DUMP_BYTES = 256;
+  static constexpr int STAGE_BYTES = X_BYTES + Y_BYTES + SX_BYTES + SY_BYTES + DUMP_BYTES;
+  static constexpr int LDS_BYTES = S * STAGE_BYTES;
+  static constexpr int X_ITERS = TK / 8 / NW, Y_ITERS = TN / 8 / NW;   // 8-row slabs per wave
+  static constexpr int NDMA = X_ITERS + Y_ITERS + 1;                   // per wave and token block, scale fetch included
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+};
+
+// The 32 operand bytes of a lane are bytes [32 q, 32 q + 32) of a 128-token block; token t of the block is valid
+// when lo <= t < hi.  Dword d of the fragment holds tokens 32 q + 4 d .. + 3.
+__device__ __forceinline__ int token_mask(int first, int lo, int hi) {
+  int a = lo - first, e = hi - first;
+  a = a < 0 ? 0 : (a > 4 ? 4 : a);
+  e = e < 0 ? 0 : (e > 4 ? 4 : e);
+  if (e <= a) return 0;
+  const unsigned upto_e = e == 4 ? 0xFFFFFFFFu : ((1u << (8 * e)) - 1u);
+  const unsigned from_a = a == 0 ? 0xFFFFFFFFu : ~((1u << (8 * a)) - 1u);
+  return (int)(upto_e & from_a);
+}
+
+__global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs a) {
+  using Cfg = WgradCfg;
+  extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+  const int tid = threadIdx.x;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l = tid & 63;
+  const int r = l & 15, q = l >> 4;
+  const int wk = w >> 1, wn = w & 1;
+  const int M = a.M_total;
+
+  // ---- which tile: workgroup b runs on XCD b % 8; every XCD takes a contiguous run of the tile list, in which the
+  // n tiles of one (group, k tile) follow each other and share that k tile's rows of XT in the XCD's L2
+  int T = blockIdx.x;
+  if (a.per_xcd > 0) T = (int)(blockIdx.x & 7) * a.per_xcd + (int)(blockIdx.x >> 3);
+  const int per_group = a.n_tiles * a.k_tiles;
+  const int g = T / per_group;
+  const int local = T - g * per_group;
+  const int kt = local / a.n_tiles, nt = local - kt * a.n_tiles;
+  const int k0 = kt * Cfg::TK, n0 = nt * Cfg::TN;
+
+  const GG_CONST_I32* offc = (const GG_CONST_I32*)a.off;
+  const int lo = clampi(offc[g], 0, M);
+  const int hi = clampi(offc[g + 1], lo, M);
+  const int j0 = lo >> 7, j1 = hi > lo ? (hi + 127) >> 7 : j0;     // token blocks [j0, j1)
+  const int steps = j1 - j0;
+
+  // ---- fetches: whole-tensor views (an offset past the end reads zeros), 16 bytes per lane, lane l of a slab lands
+  // at LDS byte 16 l (row l / 8, chunk l % 8); LDS chunk c of a row holds global chunk c ^ key(row)
+  const __amdgpu_buffer_rsrc_t dX = __builtin_amdgcn_make_buffer_rsrc((void*)a.XT, 0, a.K * M, GG_RSRC_FLAGS);
+  const __amdgpu_buffer_rsrc_t dY = __builtin_amdgcn_make_buffer_rsrc((void*)a.DYT, 0, a.N * M, GG_RSRC_FLAGS);
+  const __amdgpu_buffer_rsrc_t dSX = __builtin_amdgcn_make_buffer_rsrc((void*)a.SX, 0, a.K * a.MB * 4, GG_RSRC_FLAGS);
+  const __amdgpu_buffer_rsrc_t dSY = __builtin_amdgcn_make_buffer_rsrc((void*)a.SDY, 0, a.N * a.MB * 4, GG_RSRC_FLAGS);
+  const int lrow = l >> 3, pch = l & 7;
+  const int slab_row = w * 8 + lrow;                               // + 64 i
+  const int chunk = (pch ^ swz_key_a(slab_row)) << 4;              // key(row + 64 i) == key(row)
+  const int vX = (k0 + slab_row) * M + chunk;
+  const int vY = (n0 + slab_row) * M + chunk;
+  // scale fetch, one per wave: waves 0..3 the scales of 64 features each, waves 4, 5 those of 64 dY^T rows each,
+  // waves 6, 7 an out-of-range offset into a dump area (every wave issues the same number of fetches)
+  const bool sx_wave = w < 4, sy_wave = w == 4 || w == 5;
+  const int vS = sx_wave ? (k0 + w * 64 + l) * a.MB * 4 : sy_wave ? (n0 + (w - 4) * 64 + l) * a.MB * 4 : GG_OOB_OFFSET;
+  const int ldsS = Cfg::X_BYTES + Cfg::Y_BYTES + (sx_wave ? w * 256 : sy_wave ? Cfg::SX_BYTES + (w - 4) * 256 : Cfg::SX_BYTES + Cfg::SY_BYTES);
+
+  auto fetch = [&](int s, int stage) __attribute__((always_inline)) {   // token block j0 + s into LDS buffer `stage`
+    const bool in = s < steps;
+    const int col = __builtin_amdgcn_readfirstlane((j0 + s) * 128);
+    uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(sx_wave ? dSX : dSY, GG_LDS_PTR(st + ldsS), 4, in ? vS : GG_OOB_OFFSET,
+                                             __builtin_amdgcn_readfirstlane((j0 + s) * 4), 0, 0);
+#pragma unroll
+    for (int i = 0; i < Cfg::X_ITERS; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dX, GG_LDS_PTR(st + (w + i * 8) * 1024), 16, in ? vX + i * 64 * M : GG_OOB_OFFSET, col, 0, 0);
+#pragma unroll
+    for (int i = 0; i < Cfg::Y_ITERS; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dY, GG_LDS_PTR(st + Cfg::X_BYTES + (w + i * 8) * 1024), 16, in ? vY + i * 64 * M : GG_OOB_OFFSET, col, 0, 0);
+  };
+
+  // ---- operand reads: fragment row r, chunks 2q and 2q+1
+  const int keyR = swz_key_a(r);
+  const int rd0 = r * 128 + (((2 * q) ^ keyR) << 4), rd1 = r * 128 + (((2 * q + 1) ^ keyR) << 4);
+  const int xBase = (wk * 64) * 128, yBase = Cfg::X_BYTES + (wn * 64) * 128;
+  const int sxRd = Cfg::X_BYTES + Cfg::Y_BYTES + (wk * 64 + 4 * q) * 4;          // + 64 kf: four consecutive features
+  const int syRd = Cfg::X_BYTES + Cfg::Y_BYTES + Cfg::SX_BYTES + (wn * 64 + r) * 4;   // + 64 nf
+  auto read_frag = [&](const uint8_t* p) __attribute__((always_inline)) -> v8i {
+    const v4i x = *(const v4i*)(p + rd0);
+    const v4i y = *(const v4i*)(p + rd1);
+    return (v8i){x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
+  };
+
+  v4f acc[4][4];
+#pragma unroll
+  for (int kf = 0; kf < 4; ++kf)
+#pragma unroll
+    for (int nf = 0; nf < 4; ++nf) acc[kf][nf] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+  // One token block.  MASKED: the block holds tokens outside the group (its first or last block); their bytes are
+  // cleared in both operands.
+  auto block = [&](int s, int stage, auto masked_c) __attribute__((always_inline)) {
+    constexpr bool MASKED = decltype(masked_c)::value;
+    const uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
+    v8i xf[4], yf[4];
+    v4f sx[4];
+    float sy[4];
+#pragma unroll
+    for (int f = 0; f < 4; ++f) {
+      xf[f] = read_frag(st + xBase + f * 2048);
+      yf[f] = read_frag(st + yBase + f * 2048);
+      sx[f] = *(const v4f*)(st + sxRd + f * 64);
+      sy[f] = *(const float*)(st + syRd + f * 64);
+    }
+    if constexpr (MASKED) {
+      const int first = (j0 + s) * 128;
+      const int vlo = lo - first, vhi = hi - first;      // valid tokens of the block: [vlo, vhi), clipped by token_mask
+      v8i m;
+#pragma unroll
+      for (int d = 0; d < 8; ++d) m[d] = token_mask(32 * q + 4 * d, vlo, vhi);
+#pragma unroll
+      for (int f = 0; f < 4; ++f) {
+        xf[f] &= m;
+        yf[f] &= m;
+      }
+    }
+#pragma unroll
+    for (int kf = 0; kf < 4; ++kf)
+#pragma unroll
+      for (int nf = 0; nf < 4; ++nf) {
+        const v4f p = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xf[kf], yf[nf], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[kf][nf][i] += p[i] * (sx[kf][i] * sy[nf]);
+      }
+  };
+
+  // ---- ring of 3: blocks s + 1 and s + 2 are in flight while block s is multiplied ----------------------------
+  fetch(0, 0);
+  fetch(1, 1);
+  int stage = 0;
+  for (int s = 0; s < steps; ++s) {
+    wait_vmcnt<Cfg::NDMA>();            // this wave's part of block s has landed (block s + 1 may be in flight)
+    __builtin_amdgcn_s_barrier();       // ... and everybody's; everybody is done with the buffer refilled next
+    asm volatile("" ::: "memory");
+    const int nstage = stage == 0 ? 2 : stage - 1;       // buffer of block s + 2 = buffer of block s - 1
+    fetch(s + 2, nstage);
+    const int first = (j0 + s) * 128;
+    if (lo > first || hi < first + 128) block(s, stage, std::true_type{});
+    else block(s, stage, std::false_type{});
+    stage = stage == 2 ? 0 : stage + 1;
+  }
+
+  // ---- epilogue: fp32, 16 bytes per lane (four consecutive features of one dY^T row) ---------------------------
+  float* out = a.dW + ((int64_t)g * a.N + n0 + wn * 64) * a.K + k0 + wk * 64;
+#pragma unroll
+  for (int nf = 0; nf < 4; ++nf)
+#pragma unroll
+    for (int kf = 0; kf < 4; ++kf)
+      *(v4f*)(out + (int64_t)(16 * nf + r) * a.K + 16 * kf + 4 * q) = acc[kf][nf];
+  wait_vmcnt<0>();     // the fetches past the last block still write zeros into this workgroup's LDS: let them land
+}
+
+}  // namespace gg

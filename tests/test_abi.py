@@ -180,6 +180,19 @@ def test_fused_gemm_argument_validation(lib):
     assert f(M=0, A2=nul) == GG_OK
 
 
+def test_wgrad_argument_validation(lib):
+    p = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
+    nul = ctypes.c_void_p(0)
+    f = lambda G=2, M=1024, N=128, K=256, XT=p, dW=p, off=p: lib.gg_fp8_grouped_gemm_wgrad(XT, p, p, p, off, dW, G, M, N, K, nul)
+    assert f(M=1000 + 8) == GG_ERR_UNSUPPORTED      # the row pitch keeps every 128-token block 16-byte aligned
+    assert f(N=192) == GG_ERR_UNSUPPORTED and f(K=384) == GG_ERR_UNSUPPORTED     # whole output tiles
+    assert f(G=-1) == GG_ERR_SHAPE and f(M=-16) == GG_ERR_SHAPE and f(N=0) == GG_ERR_SHAPE
+    assert f(M=2 ** 24, K=256) == GG_ERR_SHAPE      # K * M_total beyond 32-bit offsets
+    assert f(K=2 ** 21, M=16) == GG_ERR_SHAPE
+    assert f(XT=nul) == GG_ERR_NULL and f(dW=nul) == GG_ERR_NULL and f(off=nul) == GG_ERR_NULL
+    assert f(G=0, XT=nul, dW=nul, off=nul) == GG_OK
+
+
 def test_binding_rejects_wrong_tensors_before_calling_the_library(lib):
     import torch
     A = torch.zeros((4, 256), dtype=torch.uint8)

@@ -1,0 +1,148 @@
+"""GPU parity of gg_fp8_grouped_gemm_wgrad (the variable-K grouped GEMM of training) against oracle.grouped_gemm_wgrad,
+element by element, through the C ABI.
+
+Tolerance, from the kernel's arithmetic (the same derivation as for the forward GEMM, see gg_testlib): one FP8 matrix
+instruction per 128-token block (products truncated inside groups of 8: at most 7 * 2^-13 of the block's absolute
+sum), the factor sx * sdy rounded to fp32, fp32 accumulation over J blocks, fp32 output:
+    |gpu - D| <= ulp_fp32(D) + 2^-10 * S          (HARD, every element)
+and on quantised normal data, where the truncation hardly ever triggers (EMPIRICAL, regression guard)
+    |gpu - D| <= ulp_fp32(D) + 2^-15 * S.
+Where every intermediate is exact (small integers, power-of-two scales) the GPU must equal the oracle bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2508_16584_amd as gg
+from oracle import gg_oracle as orc
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def random_bytes(rng, shape):
+    b = rng.integers(0, 256, size=shape, dtype=np.uint8)
+    b[(b & 0x7F) == 0x7F] = 0x3A
+    return b
+
+
+def quantised_normal(rng, rows, M_total, std=1.0):
+    """e4m3 bytes and per-(row, 128 tokens) scales of normal samples, by torch's float8 cast (test input only)."""
+    MB = -(-M_total // 128)
+    x = torch.from_numpy(rng.standard_normal((rows, MB * 128)).astype(np.float32) * std)
+    amax = x.view(rows, MB, 128).abs().amax(dim=2).clamp_min(1e-30)
+    scale = amax / 448.0
+    q = (x.view(rows, MB, 128) / scale[:, :, None]).clamp(-448, 448).to(torch.float8_e4m3fn)
+    return q.view(torch.uint8).view(rows, MB * 128)[:, :M_total].contiguous().numpy(), scale.numpy()
+
+
+def run_gpu(XT, SX, DYT, SDY, off):
+    t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a)).to(dt).to(DEV)
+    dW = gg.grouped_gemm_wgrad(t(XT, torch.uint8), t(SX, torch.float32), t(DYT, torch.uint8), t(SDY, torch.float32),
+                               t(np.asarray(off), torch.int32))
+    torch.cuda.synchronize()
+    return dW.cpu().numpy()
+
+
+def assert_wgrad_parity(got, ref, floor, what):
+    D, S = ref["D"], ref["S"]
+    assert got.shape == D.shape and got.dtype == np.float32
+    nan = np.isnan(D)
+    assert np.array_equal(np.isnan(got), nan), f"{what}: NaN pattern differs"
+    ok = ~nan
+    err = np.abs(np.where(ok, got.astype(np.float64) - D, 0.0))
+    ulp = np.spacing(np.abs(np.where(ok, D, 1.0)).astype(np.float32)).astype(np.float64)
+    bound = ulp + floor * np.where(ok, S, 0.0)
+    bad = np.argwhere(err > bound)
+    assert bad.size == 0, f"{what}: {bad.shape[0]} elements outside the bound, first {bad[:3].tolist()}: got {got[tuple(bad[0])]} want {D[tuple(bad[0])]}"
+    return float(np.mean(got[ok] == ref["W"][ok])), float(np.max(err / np.maximum(np.where(ok, S, 0.0), 1e-300)))
+
+
+def test_wgrad_groups_that_cut_through_token_blocks_full_range_bytes():
+    rng = np.random.default_rng(31)
+    M_total, N, K = 304, 128, 256
+    off = [0, 37, 37, 130, 291, 300, 304]
+    XT, DYT = random_bytes(rng, (K, M_total)), random_bytes(rng, (N, M_total))
+    SX = rng.uniform(0.25, 4.0, (K, 3)).astype(np.float32)
+    SDY = rng.uniform(0.25, 4.0, (N, 3)).astype(np.float32)
+    ref = orc.grouped_gemm_wgrad(XT, SX, DYT, SDY, off, with_abs_sum=True)
+    got = run_gpu(XT, SX, DYT, SDY, off)
+    assert_wgrad_parity(got, ref, 2.0 ** -10, "edge groups")
+    assert np.all(got[1] == 0)                                             # the empty group is written, as zeros
+
+
+def test_wgrad_several_tiles_quantised_data_and_unowned_tokens():
+    rng = np.random.default_rng(32)
+    M_total, N, K = 2000, 384, 768                                          # 3 x 3 output tiles per group
+    off = [16, 16, 555, 1403, 1404, 1990]                                   # tokens [0,16) and [1990,2000) belong to nobody
+    XT, SX = quantised_normal(rng, K, M_total)
+    DYT, SDY = quantised_normal(rng, N, M_total, std=0.02)
+    XT[:, :16] = 0x7F                                                       # NaN codes outside every group
+    DYT[:, 1990:] = 0xFF
+    ref = orc.grouped_gemm_wgrad(XT, SX, DYT, SDY, off, with_abs_sum=True)
+    assert not np.isnan(ref["D"]).any()
+    got = run_gpu(XT, SX, DYT, SDY, off)
+    equal, worst = assert_wgrad_parity(got, ref, 2.0 ** -15, "quantised")
+    assert equal >= 0.3, equal                                              # fp32 sums in another order: most still equal
+    assert np.all(got[0] == 0) and worst < 2.0 ** -15
+
+
+def test_wgrad_exact_where_every_intermediate_is_exact():
+    rng = np.random.default_rng(33)
+    M_total, N, K = 1024 + 48, 128, 256
+    off = [0, 5, 133, 700, 1072]
+    codes = np.array([0x00, 0x38, 0x40, 0x44, 0xB8, 0xC0], np.uint8)        # 0, 1, 2, 3, -1, -2
+    XT, DYT = codes[rng.integers(0, 6, (K, M_total))], codes[rng.integers(0, 6, (N, M_total))]
+    MB = -(-M_total // 128)
+    SX = (2.0 ** rng.integers(-3, 4, (K, MB))).astype(np.float32)
+    SDY = (2.0 ** rng.integers(-3, 4, (N, MB))).astype(np.float32)
+    ref = orc.grouped_gemm_wgrad(XT, SX, DYT, SDY, off)
+    got = run_gpu(XT, SX, DYT, SDY, off)
+    assert np.array_equal(got, ref["W"])
+
+
+def test_wgrad_nan_inside_a_group_reaches_its_feature_row_in_that_group_only():
+    rng = np.random.default_rng(34)
+    M_total, N, K = 512, 128, 256
+    off = [0, 200, 512]
+    XT, DYT = random_bytes(rng, (K, M_total)), random_bytes(rng, (N, M_total))
+    SX = np.ones((K, 4), np.float32)
+    SDY = np.ones((N, 4), np.float32)
+    XT[77, 300] = 0x7F
+    ref = orc.grouped_gemm_wgrad(XT, SX, DYT, SDY, off, with_abs_sum=True)
+    ref["S"] = np.nan_to_num(ref["S"], nan=0.0)
+    got = run_gpu(XT, SX, DYT, SDY, off)
+    assert_wgrad_parity(got, ref, 2.0 ** -10, "nan")
+    assert np.isnan(got).sum() == N and np.all(np.isnan(got[1, :, 77]))
+
+
+def test_wgrad_no_tokens_at_all_writes_zeros():
+    off = torch.zeros(4, dtype=torch.int32, device=DEV)
+    dW = torch.full((3, 128, 256), 7.0, dtype=torch.float32, device=DEV)
+    e8 = torch.empty((256, 0), dtype=torch.uint8, device=DEV)
+    gg.grouped_gemm_wgrad(e8, torch.empty((256, 0), dtype=torch.float32, device=DEV), e8[:128],
+                          torch.empty((128, 0), dtype=torch.float32, device=DEV), off, dW=dW)
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(dW).item() == 0
+
+
+def test_wgrad_full_size_sampled_rows_of_both_operands():
+    """gate_up's layer in training: 8 experts, 8192 tokens, hidden 7168, 4096 rows of dY^T.  The GPU computes all of
+    dW [8, 4096, 7168]; the oracle the 96 x 160 sampled (row of dY^T, feature) pairs of every group (rows of the two
+    operands are independent, so the oracle runs on the sampled rows alone)."""
+    from workloads import CONFIGS, group_sizes
+    cfg = CONFIGS["gate_up"]
+    sizes = group_sizes(cfg)
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    M_total, N, K = int(off[-1]), cfg.N, cfg.K
+    rng = np.random.default_rng(35)
+    XT, SX = quantised_normal(rng, K, M_total)
+    DYT, SDY = quantised_normal(rng, N, M_total, std=0.02)
+    got = run_gpu(XT, SX, DYT, SDY, off)
+    n_sel = np.sort(rng.choice(N, 96, replace=False))
+    k_sel = np.sort(rng.choice(K, 160, replace=False))
+    n_sel[0], n_sel[-1], k_sel[0], k_sel[-1] = 0, N - 1, 0, K - 1        # the corners of the output are among them
+    ref = orc.grouped_gemm_wgrad(XT[k_sel], SX[k_sel], DYT[n_sel], SDY[n_sel], off, with_abs_sum=True)
+    sub = got[:, n_sel][:, :, k_sel]
+    assert_wgrad_parity(sub, ref, 2.0 ** -15, "full size")
+    assert np.isfinite(got).all()
