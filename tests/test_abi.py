@@ -184,7 +184,7 @@ def test_wgrad_argument_validation(lib):
     p = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
     nul = ctypes.c_void_p(0)
     f = lambda G=2, M=1024, N=128, K=256, XT=p, dW=p, off=p: lib.gg_fp8_grouped_gemm_wgrad(XT, p, p, p, off, dW, G, M, N, K, nul)
-    assert f(M=1000 + 8) == GG_ERR_UNSUPPORTED      # the row pitch keeps every 128-token block 16-byte aligned
+    assert f(M=1000 + 4) == GG_ERR_UNSUPPORTED      # the row pitch keeps every 128-token block 16-byte aligned
     assert f(N=192) == GG_ERR_UNSUPPORTED and f(K=384) == GG_ERR_UNSUPPORTED     # whole output tiles
     assert f(G=-1) == GG_ERR_SHAPE and f(M=-16) == GG_ERR_SHAPE and f(N=0) == GG_ERR_SHAPE
     assert f(M=2 ** 24, K=256) == GG_ERR_SHAPE      # K * M_total beyond 32-bit offsets
