@@ -201,6 +201,87 @@ def bench_quantize_rows(args, cfg, dev):
     print(json.dumps(out))
 
 
+def bench_wgrad(args, cfg, dev):
+    """wgrad: the variable-K grouped GEMM of training on the workload's layer (gg_fp8_grouped_gemm_wgrad):
+    XT [K, M_total], DYT [N, M_total] e4m3 with one scale per row and block of 128 tokens -> dW [G, N, K] fp32, the
+    workload's group sizes as token counts.  The output is 4 G N K bytes (939.5 MB on gate_up against 92 MB of
+    operands and 96 us of matrix instructions at the datasheet peak): the roofline that bounds it is HBM."""
+    import numpy as np
+    import torch
+
+    import paper_2508_16584_amd as gg
+    from workloads import group_sizes
+
+    sizes = group_sizes(cfg, cfg.seed)
+    M = int(np.sum(sizes))
+    if M % 16:
+        raise SystemExit(f"bench.py --op wgrad: M_total = {M} is not a multiple of 16")
+    G, N, K = len(sizes), cfg.N, cfg.K
+    MB = (M + 127) // 128
+    off = torch.from_numpy(np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)).to(dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg.seed)
+
+    def operand(rows, std):
+        x = torch.randn((rows, MB * 128), generator=gen, device=dev, dtype=torch.float32) * std
+        amax = x.view(rows, MB, 128).abs().amax(dim=2).clamp_min(1e-30)
+        scale = amax / 448.0
+        q = (x.view(rows, MB, 128) / scale[:, :, None]).clamp(-448, 448).to(torch.float8_e4m3fn)
+        return q.view(torch.uint8).view(rows, MB * 128)[:, :M].contiguous(), scale.t().contiguous()
+
+    XT, SX = operand(K, 1.0)
+    DYT, SDY = operand(N, 0.02)
+    alg_bytes = (K + N) * M + 4 * (K + N) * MB + 4 * G * N * K
+    flops = 2.0 * M * N * K
+    copies = args.copies or (2 if 4 * G * N * K < (4 << 30) else 1)
+    outs = [torch.empty((G, N, K), dtype=torch.float32, device=dev) for _ in range(copies)]
+
+    def step(i):
+        gg.grouped_gemm_wgrad(XT, SX, DYT, SDY, off, dW=outs[i % copies])
+
+    n_ramp = clock_warmup(step, args.clock_warmup_ms)
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step, kern_avg_ms = timed_region(step, args.steps)
+    kern_ms = per_launch_ms(step, args.steps)
+    achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
+    out = {
+        "metric": "FP8 TFLOP/s on the tokens of the groups, variable-K grouped GEMM dW^g = dY^g^T X^g (e4m3 operands scaled per "
+                  "128 tokens, fp32 accumulate, fp32 out)",
+        "value": round(flops / (ms_per_step * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "fp8_e4m3 in, fp32 accumulate, fp32 out", "data": "synthetic",
+        "config": {"workload": args.workload + " layer, weight gradient", "op": "wgrad", "G": G, "M_total": M, "N": N, "K": K,
+                   "tokens_per_group_min_max": [int(sizes.min()), int(sizes.max())], "output_copies_rotated": copies,
+                   "clock_warmup_launches": n_ramp},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "gg_wgrad_kernel",
+                     "kernel_avg_ms": round(kern_avg_ms, 4), "kernel_median_ms": round(float(np.median(kern_ms)), 4),
+                     "kernel_min_ms": round(float(kern_ms.min()), 4), "algorithmic_bytes": int(alg_bytes),
+                     "mfma_frac_of_fp8_peak": round(flops / (kern_avg_ms * 1e-3) / 1e12 / FP8_MFMA_PEAK_TFLOPS, 4)},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import gg_oracle
+        rng = np.random.default_rng(cfg.seed)
+        n_sel, k_sel = np.sort(rng.choice(N, 256, replace=False)), np.sort(rng.choice(K, 512, replace=False))
+        h = lambda t, sel: t[torch.from_numpy(sel).to(dev)].cpu().numpy()
+        xt, dyt = h(XT, k_sel), h(DYT, n_sel)
+        sx, sdy = SX.cpu().numpy()[:, k_sel], SDY.cpu().numpy()[:, n_sel]
+        t0 = time.perf_counter()
+        ref = gg_oracle.grouped_gemm_wgrad(xt, sx, dyt, sdy, off.cpu().numpy(), with_abs_sum=True)
+        cpu_s = time.perf_counter() - t0
+        got = outs[(args.steps - 1) % copies][:, torch.from_numpy(n_sel).to(dev)][:, :, torch.from_numpy(k_sel).to(dev)].cpu().numpy()
+        err = np.abs(got.astype(np.float64) - ref["D"])
+        bound = np.spacing(np.abs(ref["D"]).astype(np.float32)).astype(np.float64) + 2.0 ** -10 * ref["S"]
+        assert np.all(err <= bound), "bench.py --op wgrad: GPU output outside the tolerance of tests/test_gpu_wgrad.py on the oracle's sample"
+        out["cpu_baseline"] = {"value": round(2.0 * M * len(n_sel) * len(k_sel) / cpu_s / 1e12, 5), "unit": "TFLOP/s", "cores": os.cpu_count(),
+                               "kind": "oracle", "sample": f"{len(n_sel)} rows of dY^T x {len(k_sel)} features of every group, NumPy oracle, {cpu_s:.1f} s",
+                               "gpu_bits_equal_oracle_on_sample": round(float(np.mean(got == ref["W"])), 5),
+                               "max_err_over_S": float(np.max(err / np.maximum(ref["S"], 1e-300)))}
+    print(json.dumps(out))
+
+
 def bench_expert_mlp(args, cfg, dev):
     """Forward pass of the experts' MLP on the workload's routing: bf16 tokens [M_total, K] gathered by expert and
     quantised, GEMM with [G, N, K] (gate | up), silu(gate) * up + quantise, GEMM with [G, K, N/2] (down).  Padding-
@@ -462,7 +543,7 @@ def main():
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="gate_up")
-    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows", "swiglu_quantize_rows", "expert_mlp", "ceilings", "pad_path", "kstep_parts"],
+    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows", "swiglu_quantize_rows", "expert_mlp", "ceilings", "pad_path", "kstep_parts", "wgrad"],
                     help="grouped_gemm: the hot path (default, the headline metric); quantize_rows: the producer of its "
                          "A operand on the same workload's activation shape; swiglu_quantize_rows: activation + quantiser "
                          "on the workload's output shape [M_total, N] (N = 2 x intermediate width); expert_mlp: the whole forward "
@@ -470,7 +551,8 @@ def main():
                          "against the same chain on 128-row padded groups; pad_path: the three steps of the pad-then-GEMM comparison path "
                          "(Sec. 3) each timed alone, the two copies against the HBM roofline; ceilings: no workload, the probes of "
                          "include/gg_probe.h (register-only matrix loops, HBM streams, the L2 -> LDS fetch stream); kstep_parts: no workload, "
-                         "the second GEMM kernel timed with parts of its K step left out (fetches, barrier, LDS reads)")
+                         "the second GEMM kernel timed with parts of its K step left out (fetches, barrier, LDS reads); wgrad: the variable-K "
+                         "grouped GEMM of training (weight gradient) on the workload's layer")
     ap.add_argument("--clock-warmup-ms", type=float, default=150.0,
                     help="untimed launches for about this long before the W warm-up steps, so that the timed steps run at "
                          "the GPU's sustained clock (0: none)")
@@ -516,6 +598,9 @@ def main():
         bench_kstep_parts()
         return
     cfg = CONFIGS[args.workload]
+    if args.op == "wgrad":
+        bench_wgrad(args, cfg, dev)
+        return
     if args.op in ("quantize_rows", "swiglu_quantize_rows"):
         bench_quantize_rows(args, cfg, dev)
         return

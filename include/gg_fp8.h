@@ -164,14 +164,15 @@ int gg_fp8_grouped_gemm_swiglu(const void* A, const float* SA, const void* B, co
  * around the grouped GEMM, but the paper defines neither layouts nor scale granularity for this operation: the
  * definition is this library's own reading.
  *   XT  e4m3 [K, M_total]   X transposed: feature k of token r at XT[k * M_total + r] (the token index contiguous)
- *   SX  fp32 [K, ceil(M_total/128)]   one scale per feature and block of 128 tokens; the token blocks are
+ *   SX  fp32 [ceil(M_total/128), K]   one scale per block of 128 tokens and feature, the scales of a block contiguous
+ *       (what a K step of a tile needs is then a few cache lines, not one per feature); the token blocks are
  *       [128 j, 128 j + 128) of the concatenated token axis whatever the groups are (a block may hold tokens of
  *       several groups), so every fetch is 16-byte aligned and a group may start and end at ANY token
- *   DYT e4m3 [N, M_total], SDY fp32 [N, ceil(M_total/128)]   the output gradient, transposed likewise
+ *   DYT e4m3 [N, M_total], SDY fp32 [ceil(M_total/128), N]   the output gradient, transposed likewise
  *   group_offsets int32 [G+1] on the device: tokens of group g are [off[g], off[g+1]); clamped on the device like
  *       those of gg_fp8_grouped_gemm (a bad array garbles results, it cannot make the kernel leave the tensors)
  *   dW  fp32 [G, N, K], EVERY element written:
- *       dW[g][n][k] = sum_j SDY[n][j] * SX[k][j] * sum_{r in block j and in group g} dec(DYT[n][r]) * dec(XT[k][r])
+ *       dW[g][n][k] = sum_j SDY[j][n] * SX[j][k] * sum_{r in block j and in group g} dec(DYT[n][r]) * dec(XT[k][r])
  *       (blocks in ascending order; fp32 accumulation).  A group without tokens gets zeros.  Bytes of tokens outside
  *       a group never reach a product of that group, whatever they are (NaN codes included).
  * M_total a multiple of 16, N of 128, K of 256 (GG_ERR_UNSUPPORTED otherwise); K * M_total and N * M_total below

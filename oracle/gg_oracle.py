@@ -267,14 +267,14 @@ def grouped_gemm_wgrad(XT, SX, DYT, SDY, group_offsets, with_abs_sum=False):
     """dW^g = dY^g^T X^g for every group, the contraction running over the group's rows (tokens).
 
     XT   uint8 [K, M_total]   e4m3 bytes of X transposed: XT[k, r] is feature k of token r
-    SX   float [K, ceil(M_total/128)]   one scale per (feature, block of 128 tokens); the token blocks are
-         [128 j, 128 j + 128) of the concatenated token axis, whatever the groups are (a block may hold tokens
-         of two or more groups)
+    SX   float [ceil(M_total/128), K]   one scale per (block of 128 tokens, feature), the scales of one block
+         contiguous; the token blocks are [128 j, 128 j + 128) of the concatenated token axis, whatever the groups
+         are (a block may hold tokens of two or more groups)
     DYT  uint8 [N, M_total]   e4m3 bytes of dY transposed
-    SDY  float [N, ceil(M_total/128)]
+    SDY  float [ceil(M_total/128), N]
     group_offsets int [G+1]   tokens of group g are [off[g], off[g+1])
 
-        dW[g, n, k] = sum_{j ascending} ( SDY[n, j] * SX[k, j] )
+        dW[g, n, k] = sum_{j ascending} ( SDY[j, n] * SX[j, k] )
                                         * ( sum_{r in block j and in group g} dec(DYT[n, r]) * dec(XT[k, r]) )
 
     Tokens outside the group contribute nothing, whatever their bytes are (NaN codes included).  A group without
@@ -293,7 +293,7 @@ def grouped_gemm_wgrad(XT, SX, DYT, SDY, group_offsets, with_abs_sum=False):
     MB = -(-M_total // SCALE_BLOCK)
     SX = np.asarray(SX, dtype=np.float64)
     SDY = np.asarray(SDY, dtype=np.float64)
-    assert SX.shape == (K, MB) and SDY.shape == (N, MB)
+    assert SX.shape == (MB, K) and SDY.shape == (MB, N)
     G = off.shape[0] - 1
     assert np.all(np.diff(off) >= 0) and off[0] >= 0 and off[-1] <= M_total
     D = np.zeros((G, N, K), dtype=np.float64)
@@ -307,7 +307,7 @@ def grouped_gemm_wgrad(XT, SX, DYT, SDY, group_offsets, with_abs_sum=False):
             dy = e4m3_decode(DYT[:, r0:r1])             # [N, <=128]
             x = e4m3_decode(XT[:, r0:r1])               # [K, <=128]
             inner = dy @ x.T                            # exact
-            scale = SDY[:, j][:, None] * SX[:, j][None, :]
+            scale = SDY[j][:, None] * SX[j][None, :]
             D[g] += scale * inner
             if with_abs_sum:
                 S[g] += np.abs(scale) * (np.abs(dy) @ np.abs(x).T)

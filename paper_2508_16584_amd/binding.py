@@ -400,8 +400,8 @@ def grouped_gemm_swiglu(A, SA, B, SB, group_offsets, A2=None, SA2=None, act_out=
 
 
 def grouped_gemm_wgrad(XT, SX, DYT, SDY, group_offsets, dW=None, stream=None):
-    """gg_fp8_grouped_gemm_wgrad: dW [G, N, K] float32 from XT uint8 [K, M_total], SX float32 [K, ceil(M_total/128)],
-    DYT uint8 [N, M_total], SDY float32 [N, ceil(M_total/128)] and int32 group_offsets [G+1] (tokens of group g)."""
+    """gg_fp8_grouped_gemm_wgrad: dW [G, N, K] float32 from XT uint8 [K, M_total], SX float32 [ceil(M_total/128), K],
+    DYT uint8 [N, M_total], SDY float32 [ceil(M_total/128), N] and int32 group_offsets [G+1] (tokens of group g)."""
     lib = load_library()
     _want(XT, "XT", torch.uint8, 2)
     _want(DYT, "DYT", torch.uint8, 2)
@@ -412,8 +412,8 @@ def grouped_gemm_wgrad(XT, SX, DYT, SDY, group_offsets, dW=None, stream=None):
     N = DYT.shape[0]
     MB = (M_total + 127) // 128
     G = group_offsets.shape[0] - 1
-    if DYT.shape[1] != M_total or tuple(SX.shape) != (K, MB) or tuple(SDY.shape) != (N, MB):
-        raise ValueError("XT [K, M_total], DYT [N, M_total], SX [K, ceil(M_total/128)], SDY [N, ceil(M_total/128)] expected")
+    if DYT.shape[1] != M_total or tuple(SX.shape) != (MB, K) or tuple(SDY.shape) != (MB, N):
+        raise ValueError("XT [K, M_total], DYT [N, M_total], SX [ceil(M_total/128), K], SDY [ceil(M_total/128), N] expected")
     for t, name in ((XT, "XT"), (SX, "SX"), (DYT, "DYT"), (SDY, "SDY"), (group_offsets, "group_offsets")):
         if not t.is_cuda or not t.is_contiguous():
             raise ValueError(f"{name} must be a contiguous device tensor")

@@ -5,12 +5,14 @@
 // definition below is this library's own reading.
 //
 //   dW[g][n][k] = sum over token blocks j, ascending, of
-//                 SDY[n][j] * SX[k][j] * sum_{tokens r in block j and in group g} dec(DYT[n][r]) * dec(XT[k][r])
+//                 SDY[j][n] * SX[j][k] * sum_{tokens r in block j and in group g} dec(DYT[n][r]) * dec(XT[k][r])
 //
 // XT [K, M_total] and DYT [N, M_total] are e4m3 bytes with the token index contiguous (both operands of the
-// contraction are then "row x 128 bytes" slabs, as in the forward kernel), SX [K, ceil(M_total/128)] and
-// SDY [N, ceil(M_total/128)] hold one fp32 scale per row and block of 128 tokens, the blocks being
-// [128 j, 128 j + 128) of the concatenated token axis whatever the groups are, and dW [G, N, K] is fp32.
+// contraction are then "row x 128 bytes" slabs, as in the forward kernel), SX [ceil(M_total/128), K] and
+// SDY [ceil(M_total/128), N] hold one fp32 scale per block of 128 tokens and row (block-major: the 256 + 128 scales
+// a tile needs for one block are 12 cache lines; row-major they would be 384, as many requests as the operand
+// tiles themselves), the blocks being [128 j, 128 j + 128) of the concatenated token axis whatever the groups
+// are, and dW [G, N, K] is fp32.
 // Group boundaries may fall anywhere: the first and the last block of a group are fetched whole (16-byte aligned,
 // like every other block) and the bytes of tokens outside the group are cleared in registers, in BOTH operands, so
 // that a neighbouring group's bytes (NaN codes included) never reach a product.  A group without tokens gives zeros.
@@ -28,9 +30,9 @@ namespace gg {
 
 struct WgradArgs {
   const uint8_t* XT;    // [K, M_total]
-  const float* SX;      // [K, MB]
+  const float* SX;      // [MB, K]
   const uint8_t* DYT;   // [N, M_total]
-  const float* SDY;     // [N, MB]
+  const float* SDY;     // [MB, N]
   const int32_t* off;   // [G + 1]
   float* dW;            // [G, N, K]
   int G, M_total, N, K, MB;
@@ -100,7 +102,8 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
   // scale fetch, one per wave: waves 0..3 the scales of 64 features each, waves 4, 5 those of 64 dY^T rows each,
   // waves 6, 7 an out-of-range offset into a dump area (every wave issues the same number of fetches)
   const bool sx_wave = w < 4, sy_wave = w == 4 || w == 5;
-  const int vS = sx_wave ? (k0 + w * 64 + l) * a.MB * 4 : sy_wave ? (n0 + (w - 4) * 64 + l) * a.MB * 4 : GG_OOB_OFFSET;
+  const int vS = sx_wave ? (k0 + w * 64 + l) * 4 : sy_wave ? (n0 + (w - 4) * 64 + l) * 4 : GG_OOB_OFFSET;
+  const int s_pitch = sx_wave ? a.K * 4 : a.N * 4;                 // bytes from one token block's scales to the next
   const int ldsS = Cfg::X_BYTES + Cfg::Y_BYTES + (sx_wave ? w * 256 : sy_wave ? Cfg::SX_BYTES + (w - 4) * 256 : Cfg::SX_BYTES + Cfg::SY_BYTES);
 
   auto fetch = [&](int s, int stage) __attribute__((always_inline)) {   // token block j0 + s into LDS buffer `stage`
@@ -108,7 +111,7 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
     const int col = __builtin_amdgcn_readfirstlane((j0 + s) * 128);
     uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(sx_wave ? dSX : dSY, GG_LDS_PTR(st + ldsS), 4, in ? vS : GG_OOB_OFFSET,
-                                             __builtin_amdgcn_readfirstlane((j0 + s) * 4), 0, 0);
+                                             __builtin_amdgcn_readfirstlane((j0 + s) * s_pitch), 0, 0);
 #pragma unroll
     for (int i = 0; i < Cfg::X_ITERS; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(dX, GG_LDS_PTR(st + (w + i * 8) * 1024), 16, in ? vX + i * 64 * M : GG_OOB_OFFSET, col, 0, 0);

@@ -28,8 +28,8 @@ def random_bytes(rng, shape):
 def problem(rng, M_total, N, K, lo=0.25, hi=4.0):
     MB = -(-M_total // 128)
     XT, DYT = random_bytes(rng, (K, M_total)), random_bytes(rng, (N, M_total))
-    SX = rng.uniform(lo, hi, size=(K, MB)).astype(np.float32)
-    SDY = rng.uniform(lo, hi, size=(N, MB)).astype(np.float32)
+    SX = rng.uniform(lo, hi, size=(MB, K)).astype(np.float32)
+    SDY = rng.uniform(lo, hi, size=(MB, N)).astype(np.float32)
     return XT, SX, DYT, SDY
 
 
@@ -44,7 +44,7 @@ def exact_wgrad(XT, SX, DYT, SDY, off):
             for k in range(K):
                 tot, tot_abs = Fraction(0), Fraction(0)
                 for r in range(off[g], off[g + 1]):
-                    s = Fraction(float(SDY[n, r // 128])) * Fraction(float(SX[k, r // 128]))
+                    s = Fraction(float(SDY[r // 128, n])) * Fraction(float(SX[r // 128, k]))
                     p = Fraction(Yi[n][r] * Xi[k][r], 1 << 18)
                     tot += s * p
                     tot_abs += abs(s * p)
@@ -69,15 +69,15 @@ def test_wgrad_against_exact_rationals_with_groups_that_cut_through_scale_blocks
 
 def test_wgrad_with_one_group_is_the_forward_definition_with_the_roles_renamed():
     """G = 1 over all tokens, SX constant over each 128 features: dW[0] = the D of Sec. 2.1's definition with
-    A := DYT (rows n, contraction index = token), B[0] := XT, SA := SDY, SB[0, k/128, j] := SX[k, j] -- the same
+    A := DYT (rows n, contraction index = token), B[0] := XT, SA[n, j] := SDY[j, n], SB[0, k/128, j] := SX[j, k] -- the same
     partial sums, the same factors, the same order, so the two oracles must agree bit for bit."""
     rng = np.random.default_rng(12)
     M_total, N, K = 384, 7, 256
     XT, SX, DYT, SDY = problem(rng, M_total, N, K)
     SXb = rng.uniform(0.25, 4.0, size=(K // 128, M_total // 128)).astype(np.float32)
-    SX = np.repeat(SXb, 128, axis=0)
+    SX = np.ascontiguousarray(np.repeat(SXb, 128, axis=0).T)
     w = orc.grouped_gemm_wgrad(XT, SX, DYT, SDY, [0, M_total])
-    f = orc.grouped_gemm(DYT, SDY, XT[None], SXb[None], [0, N])
+    f = orc.grouped_gemm(DYT, np.ascontiguousarray(SDY.T), XT[None], SXb[None], [0, N])
     assert np.array_equal(w["D"][0], f["D"])
 
 
@@ -85,8 +85,8 @@ def test_wgrad_closed_forms_linearity_and_sum_over_groups():
     M_total, N, K = 272, 4, 6
     off = [0, 5, 133, 133, 272]
     ones_x, ones_y = np.full((K, M_total), 0x38, np.uint8), np.full((N, M_total), 0x38, np.uint8)
-    SX = np.full((K, 3), 0.5, np.float32)
-    SDY = np.full((N, 3), 3.0, np.float32)
+    SX = np.full((3, K), 0.5, np.float32)
+    SDY = np.full((3, N), 3.0, np.float32)
     w = orc.grouped_gemm_wgrad(ones_x, SX, ones_y, SDY, off)
     for g, m in enumerate(np.diff(off)):
         assert np.all(w["D"][g] == 1.5 * m)                               # alpha * beta * M^g
@@ -94,14 +94,14 @@ def test_wgrad_closed_forms_linearity_and_sum_over_groups():
     rng = np.random.default_rng(13)
     codes = np.array([0x00, 0x38, 0x40, 0x44, 0xB8, 0xC0], np.uint8)      # 0, 1, 2, 3, -1, -2
     XT, DYT = codes[rng.integers(0, 6, (K, M_total))], codes[rng.integers(0, 6, (N, M_total))]
-    SX = (2.0 ** rng.integers(-3, 4, (K, 3))).astype(np.float32)
-    SDY = (2.0 ** rng.integers(-3, 4, (N, 3))).astype(np.float32)
+    SX = (2.0 ** rng.integers(-3, 4, (3, K))).astype(np.float32)
+    SDY = (2.0 ** rng.integers(-3, 4, (3, N))).astype(np.float32)
     parts = orc.grouped_gemm_wgrad(XT, SX, DYT, SDY, off)["D"]
     whole = orc.grouped_gemm_wgrad(XT, SX, DYT, SDY, [0, M_total])["D"]
     assert np.array_equal(parts.sum(axis=0), whole[0])
     # the same result from dequantised matrices and a plain product per group
-    xd = torch_decode(XT) * np.repeat(SX.astype(np.float64), 128, axis=1)[:, :M_total]
-    yd = torch_decode(DYT) * np.repeat(SDY.astype(np.float64), 128, axis=1)[:, :M_total]
+    xd = torch_decode(XT) * np.repeat(SX.T.astype(np.float64), 128, axis=1)[:, :M_total]
+    yd = torch_decode(DYT) * np.repeat(SDY.T.astype(np.float64), 128, axis=1)[:, :M_total]
     for g in range(4):
         assert np.array_equal(parts[g], yd[:, off[g]:off[g + 1]] @ xd[:, off[g]:off[g + 1]].T)
     # doubling SDY doubles the result; negating the bytes of one feature row negates its column
