@@ -452,7 +452,15 @@ int gg_fp8_grouped_gemm_wgrad(const void* XT, const float* SX, const void* DYT, 
   args.MB = (int)((M_total + 127) / 128);
   args.n_tiles = N / gg::WgradCfg::TN;
   args.k_tiles = K / gg::WgradCfg::TK;
-  args.per_xcd = tiles % kXcds == 0 ? (int)(tiles / kXcds) : 0;
+  args.tiles = (int)tiles;
+  int64_t grid = device_cus();
+  if (grid > tiles) grid = tiles;
+  if (grid >= kXcds) {
+    grid -= grid % kXcds;
+    args.slots = (int)(grid / kXcds);
+  } else {
+    args.slots = 0;
+  }
   static std::atomic<int> prepared[64];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return GG_ERR_HIP;
@@ -462,7 +470,7 @@ int gg_fp8_grouped_gemm_wgrad(const void* XT, const float* SX, const void* DYT, 
       return GG_ERR_HIP;
     prepared[dev].store(1, std::memory_order_release);
   }
-  hipLaunchKernelGGL(gg::gg_wgrad_kernel, dim3((unsigned)tiles), dim3(gg::WgradCfg::NT), gg::WgradCfg::LDS_BYTES,
+  hipLaunchKernelGGL(gg::gg_wgrad_kernel, dim3((unsigned)grid), dim3(gg::WgradCfg::NT), gg::WgradCfg::LDS_BYTES,
                      static_cast<hipStream_t>(stream), args);
   return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
 }

@@ -17,9 +17,11 @@
 // like every other block) and the bytes of tokens outside the group are cleared in registers, in BOTH operands, so
 // that a neighbouring group's bytes (NaN codes included) never reach a product.  A group without tokens gives zeros.
 //
-// Structure: one workgroup (8 waves, 4 along k x 2 along n) per output tile of 256 features x 128 rows of dY^T;
-// per token block the two operand tiles and their scales go global -> LDS by DMA into a ring of 3 buffers (two
-// blocks of look-ahead), swizzled like the forward kernels' tiles; a wave holds 4 + 4 operand fragments and 64 x 64
+// Structure: persistent workgroups (8 waves, 4 along k x 2 along n) walk the output tiles of 256 features x 128
+// rows of dY^T; per token block the two operand tiles and their scales go global -> LDS by DMA into a ring of 3
+// buffers, swizzled like the forward kernels' tiles, and the fetch stream runs two blocks ahead of the arithmetic
+// across tile boundaries (a group of 1000 tokens is 8 blocks: without that, every tile would start with an empty
+// pipeline and end with an idle one); a wave holds 4 + 4 operand fragments and 64 x 64
 // fp32 accumulators; one v_mfma_f32_16x16x128_f8f6f4 from zero per scale block, then acc += p * (sx * sdy) with
 // sx one of the lane's four feature rows and sdy the lane's dY^T row: 8 vector instructions per matrix instruction
 // (the factor differs per output element, not per lane as in the forward pass).
@@ -37,7 +39,8 @@ struct WgradArgs {
   float* dW;            // [G, N, K]
   int G, M_total, N, K, MB;
   int n_tiles, k_tiles;   // N / 128, K / 256
-  int per_xcd;            // tiles per XCD when the grid is a multiple of 8, else 0
+  int tiles;              // G * n_tiles * k_tiles
+  int slots;              // workgroups per XCD when the grid is a multiple of 8, else 0 (plain round-robin)
 };
 
 struct WgradCfg {
@@ -72,52 +75,75 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
   const int wk = w >> 1, wn = w & 1;
   const int M = a.M_total;
 
-  // ---- which tile: workgroup b runs on XCD b % 8; every XCD takes a contiguous run of the tile list, in which the
-  // n tiles of one (group, k tile) follow each other and share that k tile's rows of XT in the XCD's L2
-  int T = blockIdx.x;
-  if (a.per_xcd > 0) T = (int)(blockIdx.x & 7) * a.per_xcd + (int)(blockIdx.x >> 3);
-  const int per_group = a.n_tiles * a.k_tiles;
-  const int g = T / per_group;
-  const int local = T - g * per_group;
-  const int kt = local / a.n_tiles, nt = local - kt * a.n_tiles;
-  const int k0 = kt * Cfg::TK, n0 = nt * Cfg::TN;
-
+  // ---- persistent walk over the tile list (group, k tile, n tile; the n tiles of one (group, k tile) follow each
+  // other).  Workgroup b runs on XCD b % 8; every XCD takes contiguous runs of `slots` tiles, which share rows of
+  // XT in that XCD's L2.
+  struct Tile {
+    bool valid;
+    int g, k0, n0, lo, hi, j0, steps;
+  };
   const GG_CONST_I32* offc = (const GG_CONST_I32*)a.off;
-  const int lo = clampi(offc[g], 0, M);
-  const int hi = clampi(offc[g + 1], lo, M);
-  const int j0 = lo >> 7, j1 = hi > lo ? (hi + 127) >> 7 : j0;     // token blocks [j0, j1)
-  const int steps = j1 - j0;
+  const int per_group = a.n_tiles * a.k_tiles;
+  auto tile_at = [&](int it) __attribute__((always_inline)) -> Tile {
+    Tile t = {false, 0, 0, 0, 0, 0, 0, 0};
+    int T;
+    if (a.slots > 0) T = (it * 8 + (int)(blockIdx.x & 7)) * a.slots + (int)(blockIdx.x >> 3);
+    else T = it * (int)gridDim.x + (int)blockIdx.x;
+    if (T >= a.tiles) return t;
+    t.valid = true;
+    t.g = T / per_group;
+    const int local = T - t.g * per_group;
+    const int kt = local / a.n_tiles;
+    t.k0 = kt * Cfg::TK;
+    t.n0 = (local - kt * a.n_tiles) * Cfg::TN;
+    t.lo = clampi(offc[t.g], 0, M);
+    t.hi = clampi(offc[t.g + 1], t.lo, M);
+    t.j0 = t.lo >> 7;
+    t.steps = t.hi > t.lo ? ((t.hi + 127) >> 7) - t.j0 : 0;     // token blocks [j0, j0 + steps)
+    return t;
+  };
 
   // ---- fetches: whole-tensor views (an offset past the end reads zeros), 16 bytes per lane, lane l of a slab lands
-  // at LDS byte 16 l (row l / 8, chunk l % 8); LDS chunk c of a row holds global chunk c ^ key(row)
+  // at LDS byte 16 l (row l / 8, chunk l % 8); LDS chunk c of a row holds global chunk c ^ key(row).  The tile and
+  // the token block travel in the scalar offset, so the lane offsets are the same for every fetch.
   const __amdgpu_buffer_rsrc_t dX = __builtin_amdgcn_make_buffer_rsrc((void*)a.XT, 0, a.K * M, GG_RSRC_FLAGS);
   const __amdgpu_buffer_rsrc_t dY = __builtin_amdgcn_make_buffer_rsrc((void*)a.DYT, 0, a.N * M, GG_RSRC_FLAGS);
   const __amdgpu_buffer_rsrc_t dSX = __builtin_amdgcn_make_buffer_rsrc((void*)a.SX, 0, a.K * a.MB * 4, GG_RSRC_FLAGS);
   const __amdgpu_buffer_rsrc_t dSY = __builtin_amdgcn_make_buffer_rsrc((void*)a.SDY, 0, a.N * a.MB * 4, GG_RSRC_FLAGS);
   const int lrow = l >> 3, pch = l & 7;
   const int slab_row = w * 8 + lrow;                               // + 64 i
-  const int chunk = (pch ^ swz_key_a(slab_row)) << 4;              // key(row + 64 i) == key(row)
-  const int vX = (k0 + slab_row) * M + chunk;
-  const int vY = (n0 + slab_row) * M + chunk;
+  const int vRow = slab_row * M + ((pch ^ swz_key_a(slab_row)) << 4);   // key(row + 64 i) == key(row)
   // scale fetch, one per wave: waves 0..3 the scales of 64 features each, waves 4, 5 those of 64 dY^T rows each,
   // waves 6, 7 an out-of-range offset into a dump area (every wave issues the same number of fetches)
   const bool sx_wave = w < 4, sy_wave = w == 4 || w == 5;
-  const int vS = sx_wave ? (k0 + w * 64 + l) * 4 : sy_wave ? (n0 + (w - 4) * 64 + l) * 4 : GG_OOB_OFFSET;
+  const int vS = sx_wave ? (w * 64 + l) * 4 : sy_wave ? ((w - 4) * 64 + l) * 4 : GG_OOB_OFFSET;
   const int s_pitch = sx_wave ? a.K * 4 : a.N * 4;                 // bytes from one token block's scales to the next
   const int ldsS = Cfg::X_BYTES + Cfg::Y_BYTES + (sx_wave ? w * 256 : sy_wave ? Cfg::SX_BYTES + (w - 4) * 256 : Cfg::SX_BYTES + Cfg::SY_BYTES);
 
-  auto fetch = [&](int s, int stage) __attribute__((always_inline)) {   // token block j0 + s into LDS buffer `stage`
-    const bool in = s < steps;
-    const int col = __builtin_amdgcn_readfirstlane((j0 + s) * 128);
+  // The fetch stream runs two token blocks ahead of the arithmetic and on from tile to tile: F is the tile whose
+  // block sF comes next (tiles without tokens have nothing to fetch and are passed over), so the first blocks of a
+  // workgroup's next tile are in flight while the current one is finished and stored.
+  Tile F = tile_at(0);
+  int itF = 0, sF = 0;
+  auto fetch_next = [&](int stage) __attribute__((always_inline)) {
+    while (F.valid && sF >= F.steps) {
+      ++itF;
+      F = tile_at(itF);
+      sF = 0;
+    }
+    const bool in = F.valid;
+    const int j = F.j0 + sF;
+    const int sx_off = __builtin_amdgcn_readfirstlane(j * 128 + F.k0 * M), sy_off = __builtin_amdgcn_readfirstlane(j * 128 + F.n0 * M);
     uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(sx_wave ? dSX : dSY, GG_LDS_PTR(st + ldsS), 4, in ? vS : GG_OOB_OFFSET,
-                                             __builtin_amdgcn_readfirstlane((j0 + s) * s_pitch), 0, 0);
+                                             __builtin_amdgcn_readfirstlane(j * s_pitch + (sx_wave ? F.k0 : F.n0) * 4), 0, 0);
 #pragma unroll
     for (int i = 0; i < Cfg::X_ITERS; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(dX, GG_LDS_PTR(st + (w + i * 8) * 1024), 16, in ? vX + i * 64 * M : GG_OOB_OFFSET, col, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dX, GG_LDS_PTR(st + (w + i * 8) * 1024), 16, in ? vRow + i * 64 * M : GG_OOB_OFFSET, sx_off, 0, 0);
 #pragma unroll
     for (int i = 0; i < Cfg::Y_ITERS; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(dY, GG_LDS_PTR(st + Cfg::X_BYTES + (w + i * 8) * 1024), 16, in ? vY + i * 64 * M : GG_OOB_OFFSET, col, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dY, GG_LDS_PTR(st + Cfg::X_BYTES + (w + i * 8) * 1024), 16, in ? vRow + i * 64 * M : GG_OOB_OFFSET, sy_off, 0, 0);
+    ++sF;
   };
 
   // ---- operand reads: fragment row r, chunks 2q and 2q+1
@@ -132,15 +158,9 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
     return (v8i){x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
   };
 
-  v4f acc[4][4];
-#pragma unroll
-  for (int kf = 0; kf < 4; ++kf)
-#pragma unroll
-    for (int nf = 0; nf < 4; ++nf) acc[kf][nf] = (v4f){0.f, 0.f, 0.f, 0.f};
-
   // One token block.  MASKED: the block holds tokens outside the group (its first or last block); their bytes are
   // cleared in both operands.
-  auto block = [&](int s, int stage, auto masked_c) __attribute__((always_inline)) {
+  auto block = [&](int first, int lo, int hi, int stage, auto masked_c, v4f (&acc)[4][4]) __attribute__((always_inline)) {   // first: the block's first token
     constexpr bool MASKED = decltype(masked_c)::value;
     const uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
     v8i xf[4], yf[4];
@@ -154,7 +174,6 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
       sy[f] = *(const float*)(st + syRd + f * 64);
     }
     if constexpr (MASKED) {
-      const int first = (j0 + s) * 128;
       const int vlo = lo - first, vhi = hi - first;      // valid tokens of the block: [vlo, vhi), clipped by token_mask
       v8i m;
 #pragma unroll
@@ -165,39 +184,66 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
         yf[f] &= m;
       }
     }
+    __builtin_amdgcn_sched_barrier(0);
+    // software pipeline: matrix instruction t is issued two steps ahead of the 8 vector instructions that consume it
+    // (the factor product and the FMA of each of its four outputs), so the vector work runs under the matrix pipe
+    v4f p[16];
+    static_for<0, 16 + 2>([&](auto tc) __attribute__((always_inline)) {
+      constexpr int t = decltype(tc)::value;
+      if constexpr (t < 16)
+        p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xf[t / 4], yf[t % 4], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+      if constexpr (t >= 2) {
+        constexpr int u = t - 2, kf = u / 4, nf = u % 4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[kf][nf][i] += p[u][i] * (sx[kf][i] * sy[nf]);
+      }
+    });
+    static_for<0, 16 + 2>([&](auto tc) __attribute__((always_inline)) {
+      constexpr int t = decltype(tc)::value;
+      if constexpr (t < 16) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if constexpr (t >= 2) __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+    });
+    __builtin_amdgcn_sched_barrier(0);
+    // the accumulators are "used" here, so that every update above lands in the accumulator's own register
 #pragma unroll
     for (int kf = 0; kf < 4; ++kf)
 #pragma unroll
-      for (int nf = 0; nf < 4; ++nf) {
-        const v4f p = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xf[kf], yf[nf], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc[kf][nf][i] += p[i] * (sx[kf][i] * sy[nf]);
-      }
+      for (int nf = 0; nf < 4; ++nf) asm volatile("" : "+v"(acc[kf][nf]));
   };
 
-  // ---- ring of 3: blocks s + 1 and s + 2 are in flight while block s is multiplied ----------------------------
-  fetch(0, 0);
-  fetch(1, 1);
+  // ---- ring of 3: the blocks of the next two steps are in flight while a block is multiplied -------------------
+  fetch_next(0);
+  fetch_next(1);
   int stage = 0;
-  for (int s = 0; s < steps; ++s) {
-    wait_vmcnt<Cfg::NDMA>();            // this wave's part of block s has landed (block s + 1 may be in flight)
-    __builtin_amdgcn_s_barrier();       // ... and everybody's; everybody is done with the buffer refilled next
-    asm volatile("" ::: "memory");
-    const int nstage = stage == 0 ? 2 : stage - 1;       // buffer of block s + 2 = buffer of block s - 1
-    fetch(s + 2, nstage);
-    const int first = (j0 + s) * 128;
-    if (lo > first || hi < first + 128) block(s, stage, std::true_type{});
-    else block(s, stage, std::false_type{});
-    stage = stage == 2 ? 0 : stage + 1;
-  }
-
-  // ---- epilogue: fp32, 16 bytes per lane (four consecutive features of one dY^T row) ---------------------------
-  float* out = a.dW + ((int64_t)g * a.N + n0 + wn * 64) * a.K + k0 + wk * 64;
-#pragma unroll
-  for (int nf = 0; nf < 4; ++nf)
+  for (int it = 0;; ++it) {
+    const Tile cur = tile_at(it);
+    if (!cur.valid) break;
+    v4f acc[4][4];
 #pragma unroll
     for (int kf = 0; kf < 4; ++kf)
-      *(v4f*)(out + (int64_t)(16 * nf + r) * a.K + 16 * kf + 4 * q) = acc[kf][nf];
+#pragma unroll
+      for (int nf = 0; nf < 4; ++nf) acc[kf][nf] = (v4f){0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < cur.steps; ++s) {
+      // This wave's part of the block has landed: its fetches are older than those of the next block, the only
+      // ones allowed to stay in flight (the stores of the previous tile are younger still and count as well: they
+      // can make this wait longer, never shorter).
+      wait_vmcnt<Cfg::NDMA>();
+      __builtin_amdgcn_s_barrier();       // ... and everybody's; everybody is done with the buffer refilled next
+      asm volatile("" ::: "memory");
+      fetch_next(stage == 0 ? 2 : stage - 1);             // two steps ahead, into the buffer of the step before this one
+      const int first = (cur.j0 + s) * 128;
+      if (cur.lo > first || cur.hi < first + 128) block(first, cur.lo, cur.hi, stage, std::true_type{}, acc);
+      else block(first, cur.lo, cur.hi, stage, std::false_type{}, acc);
+      stage = stage == 2 ? 0 : stage + 1;
+    }
+    // ---- epilogue: fp32, 16 bytes per lane (four consecutive features of one dY^T row) -------------------------
+    float* out = a.dW + ((int64_t)cur.g * a.N + cur.n0 + wn * 64) * a.K + cur.k0 + wk * 64;
+#pragma unroll
+    for (int nf = 0; nf < 4; ++nf)
+#pragma unroll
+      for (int kf = 0; kf < 4; ++kf)
+        *(v4f*)(out + (int64_t)(16 * nf + r) * a.K + 16 * kf + 4 * q) = acc[kf][nf];
+  }
   wait_vmcnt<0>();     // the fetches past the last block still write zeros into this workgroup's LDS: let them land
 }
 
