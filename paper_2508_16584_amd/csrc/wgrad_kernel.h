@@ -215,6 +215,7 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
   fetch_next(0);
   fetch_next(1);
   int stage = 0;
+  int pend_stores = 0;      // stores issued since the last wait for a fetch
   for (int it = 0;; ++it) {
     const Tile cur = tile_at(it);
     if (!cur.valid) break;
@@ -224,10 +225,14 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
 #pragma unroll
       for (int nf = 0; nf < 4; ++nf) acc[kf][nf] = (v4f){0.f, 0.f, 0.f, 0.f};
     for (int s = 0; s < cur.steps; ++s) {
-      // This wave's part of the block has landed: its fetches are older than those of the next block, the only
-      // ones allowed to stay in flight (the stores of the previous tile are younger still and count as well: they
-      // can make this wait longer, never shorter).
-      wait_vmcnt<Cfg::NDMA>();
+      // This wave's part of the block has landed: its fetches are older than those of the next block and than the
+      // stores of the tiles finished since the last wait, which may all stay in flight (vector memory operations
+      // of a wave complete in the order they were issued; the counter holds 63 at most).
+      if (pend_stores == 0) wait_vmcnt<Cfg::NDMA>();
+      else if (pend_stores == 16) wait_vmcnt<Cfg::NDMA + 16>();
+      else if (pend_stores == 32) wait_vmcnt<Cfg::NDMA + 32>();
+      else wait_vmcnt<Cfg::NDMA>();
+      pend_stores = 0;
       __builtin_amdgcn_s_barrier();       // ... and everybody's; everybody is done with the buffer refilled next
       asm volatile("" ::: "memory");
       fetch_next(stage == 0 ? 2 : stage - 1);             // two steps ahead, into the buffer of the step before this one
@@ -243,6 +248,7 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
 #pragma unroll
       for (int kf = 0; kf < 4; ++kf)
         *(v4f*)(out + (int64_t)(16 * nf + r) * a.K + 16 * kf + 4 * q) = acc[kf][nf];
+    pend_stores += 16;
   }
   wait_vmcnt<0>();     // the fetches past the last block still write zeros into this workgroup's LDS: let them land
 }
