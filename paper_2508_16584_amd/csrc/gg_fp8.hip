@@ -148,8 +148,10 @@ const FusedVariant kFused[] = {
 // expected tile count: a group ends in a partial tile half of the time on average, which adds G/2 tiles per
 // column of tiles.  Candidates and their measured character on MI355X:
 //   160x256, ring 3 (variant 0): the safe default; best when groups are short;
-//   256x256, ring 2 (variant 1): fewest bytes per flop, one K block of look-ahead: best on the problems of 24576
-//       rows or more with K >= 4096 in the paper's grid;
+//   256x256, ring 2 (variant 1): fewest bytes per flop, one K block of look-ahead: was the best on the problems of
+//       24576 rows or more with K >= 4096 in the paper's grid and was forced there; since the second kernel deals its
+//       fetches out over the K step it is within -3 ... +1 % of that kernel's 256-row tile on such problems (five
+//       measured) and competes through the estimate like the others;
 //   second kernel at 192, 224 and 256 rows (variants 14, 15, 12): weights through registers, better overlap, K loop
 //       carried from tile to tile: best on the smaller problems and on every problem with a short K loop (K = 1024
 //       to 2560: the 256-row one is within 2 % of the per-point best everywhere on the paper's size generator, while
@@ -159,10 +161,12 @@ const FusedVariant kFused[] = {
 //   128x256 (variant 3): very short groups (weight streaming).
 // Between the candidates allowed for a shape, the estimated time is rounds x tile height / efficiency, where a
 // partly filled last round costs 0.3 + 0.7 x its fill (measured: the workgroups that do run get more of the L2
-// bandwidth) and the efficiency per row is 1 : 1.06 : 1.08 : 1.10 for 160 : 192 : 224 : 256 rows of the kernels
+// bandwidth) and the efficiency per row is 1 : 1.06 : 1.07 : 1.10 for 160 : 192 : 224 : 256 rows of the kernels
 // named above and, for the 256x256 ring-2 tile, 1.02 from K = 4096 on and 0.94 below.  The constants are a fit to the
 // five candidates on the paper's grid (Sec. 3.1) extended to K = 1024 ... 8192 (960 points) with caches flushed
-// before every launch: mean loss against the per-point best of the five 0.7 %.
+// before every launch: mean loss against the per-point best of the five 0.8 % (224 rows at 1.08 fitted the grid
+// equally well; 1.07 also takes the 192-row tile on the strongly skewed sizes of the down workload, where it is 0 - 4 %
+// the faster of the two).
 int pick_variant(int G, int64_t M_total, int N, int K) {
   const double avg = G > 0 ? (double)M_total / G : 0.0;
   const int n_tiles = (N + 255) / 256;
@@ -172,7 +176,6 @@ int pick_variant(int G, int64_t M_total, int N, int K) {
   if (N % 256 != 0 && (N % 128 != 0 || N < 256) && (double)n_tiles * 256 > 1.125 * N) return 2;
   if (avg < 64) return 3;
   if (avg < 192) return 0;
-  if (!ragged && K >= 4096 && M_total >= 24576) return 1;
   const double cus = (double)device_cus();   // the constants below are a fit on 256 CUs; the round count follows the chip
   auto cost = [&](int BM, double eff) {
     const double rounds = ((double)M_total / BM + 0.5 * G) * n_tiles / cus;
@@ -186,7 +189,7 @@ int pick_variant(int G, int64_t M_total, int N, int K) {
     if (c < c_best) { c_best = c; best = variant; }
   };
   if (second_kernel) consider(14, cost(192, 1.06));
-  if (second_kernel) consider(15, cost(224, 1.08));
+  if (second_kernel) consider(15, cost(224, 1.07));
   if (second_kernel) consider(12, cost(256, 1.10));
   if (!ragged) consider(1, cost(256, K >= 4096 ? 1.02 : 0.94));   // the 256 x 256 ring-2 tile takes whole blocks only
   return best;
