@@ -456,6 +456,7 @@ int gg_fp8_grouped_gemm_wgrad(const void* XT, const float* SX, const void* DYT, 
   args.n_tiles = N / gg::WgradCfg::TN;
   args.k_tiles = K / gg::WgradCfg::TK;
   args.tiles = (int)tiles;
+  args.blocked = args.k_tiles % 4 == 0 && args.n_tiles % 8 == 0;
   int64_t grid = device_cus();
   if (grid > tiles) grid = tiles;
   if (grid >= kXcds) {

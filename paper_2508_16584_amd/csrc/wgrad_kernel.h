@@ -41,7 +41,11 @@ struct WgradArgs {
   int n_tiles, k_tiles;   // N / 128, K / 256
   int tiles;              // G * n_tiles * k_tiles
   int slots;              // workgroups per XCD when the grid is a multiple of 8, else 0 (plain round-robin)
+  int blocked;            // 1: a group's tiles are listed in blocks of 4 k tiles x 8 n tiles (k_tiles % 4 == 0, n_tiles % 8 == 0)
 };
+
+// cache policy bits of a buffer store: sc0 | nt | sc1
+constexpr int kStoreStreaming = 1 | 2 | 16;
 
 struct WgradCfg {
   static constexpr int TK = 256, TN = 128, NW = 8, NT = 512, S = 3;
@@ -53,16 +57,15 @@ struct WgradCfg {
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
-// The 32 operand bytes of a lane are bytes [32 q, 32 q + 32) of a 128-token block; token t of the block is valid
-// when lo <= t < hi.  Dword d of the fragment holds tokens 32 q + 4 d .. + 3.
-__device__ __forceinline__ int token_mask(int first, int lo, int hi) {
-  int a = lo - first, e = hi - first;
-  a = a < 0 ? 0 : (a > 4 ? 4 : a);
-  e = e < 0 ? 0 : (e > 4 ? 4 : e);
-  if (e <= a) return 0;
-  const unsigned upto_e = e == 4 ? 0xFFFFFFFFu : ((1u << (8 * e)) - 1u);
-  const unsigned from_a = a == 0 ? 0xFFFFFFFFu : ~((1u << (8 * a)) - 1u);
-  return (int)(upto_e & from_a);
+// The 32 operand bytes of a lane are bytes [32 q, 32 q + 32) of a 128-token block; dword d of the fragment holds
+// tokens 32 q + 4 d .. + 3.  x4 = 4 * (bound - first token of the dword): the number of the dword's bytes below the
+// bound, times 4, is clamp(x4, 0, 16), and a shift by 32 bits is taken as two shifts by 16.
+__device__ __forceinline__ int bytes_from(int x4) {        // keeps the bytes at and above the bound
+  const int h = clampi(x4, 0, 16);
+  return (int)((0xFFFFFFFFu << h) << h);
+}
+__device__ __forceinline__ int bytes_below(int x4) {       // keeps the bytes below the bound
+  return ~bytes_from(x4);
 }
 
 __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs a) {
@@ -75,9 +78,9 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
   const int wk = w >> 1, wn = w & 1;
   const int M = a.M_total;
 
-  // ---- persistent walk over the tile list (group, k tile, n tile; the n tiles of one (group, k tile) follow each
-  // other).  Workgroup b runs on XCD b % 8; every XCD takes contiguous runs of `slots` tiles, which share rows of
-  // XT in that XCD's L2.
+  // ---- persistent walk over the tile list (group by group; inside a group blocks of 4 x 8 tiles, or k tile by k
+  // tile).  Workgroup b runs on XCD b % 8; every XCD takes contiguous runs of `slots` tiles, which share operand
+  // rows in that XCD's L2.
   struct Tile {
     bool valid;
     int g, k0, n0, lo, hi, j0, steps;
@@ -93,9 +96,21 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
     t.valid = true;
     t.g = T / per_group;
     const int local = T - t.g * per_group;
-    const int kt = local / a.n_tiles;
+    int kt, nt;
+    if (a.blocked) {
+      // 32 consecutive tiles (the tiles an XCD's workgroups work on at the same time, when it has 32) are 4 k tiles
+      // x 8 n tiles: they fetch 1024 + 1024 operand rows per token block between them, where a run of 32 n tiles
+      // fetches 256 + 4096, and what several workgroups fetch at about the same time comes out of the XCD's L2 once
+      const int sb = local >> 5, in = local & 31, per_row = a.n_tiles >> 3;
+      const int sbk = sb / per_row;
+      kt = sbk * 4 + (in >> 3);
+      nt = (sb - sbk * per_row) * 8 + (in & 7);
+    } else {
+      kt = local / a.n_tiles;
+      nt = local - kt * a.n_tiles;
+    }
     t.k0 = kt * Cfg::TK;
-    t.n0 = (local - kt * a.n_tiles) * Cfg::TN;
+    t.n0 = nt * Cfg::TN;
     t.lo = clampi(offc[t.g], 0, M);
     t.hi = clampi(offc[t.g + 1], t.lo, M);
     t.j0 = t.lo >> 7;
@@ -158,10 +173,9 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
     return (v8i){x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
   };
 
-  // One token block.  MASKED: the block holds tokens outside the group (its first or last block); their bytes are
-  // cleared in both operands.
-  auto block = [&](int first, int lo, int hi, int stage, auto masked_c, v4f (&acc)[4][4]) __attribute__((always_inline)) {   // first: the block's first token
-    constexpr bool MASKED = decltype(masked_c)::value;
+  // One token block.  Where the block holds tokens before the group's first or from the group's end on (it is the
+  // group's first or last block), their bytes are cleared in both operands.
+  auto block = [&](int first, int lo, int hi, int stage, v4f (&acc)[4][4]) __attribute__((always_inline)) {   // first: the block's first token
     const uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
     v8i xf[4], yf[4];
     v4f sx[4];
@@ -173,11 +187,21 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
       sx[f] = *(const v4f*)(st + sxRd + f * 64);
       sy[f] = *(const float*)(st + syRd + f * 64);
     }
-    if constexpr (MASKED) {
-      const int vlo = lo - first, vhi = hi - first;      // valid tokens of the block: [vlo, vhi), clipped by token_mask
+    const bool cut_lo = lo > first, cut_hi = hi < first + 128;
+    if (cut_lo || cut_hi) {
+      const int lo4 = 4 * (lo - first - 32 * q), hi4 = 4 * (hi - first - 32 * q);    // valid tokens of the block: [lo - first, hi - first)
       v8i m;
+      if (cut_lo) {
 #pragma unroll
-      for (int d = 0; d < 8; ++d) m[d] = token_mask(32 * q + 4 * d, vlo, vhi);
+        for (int d = 0; d < 8; ++d) m[d] = bytes_from(lo4 - 16 * d);
+        if (cut_hi) {
+#pragma unroll
+          for (int d = 0; d < 8; ++d) m[d] &= bytes_below(hi4 - 16 * d);
+        }
+      } else {
+#pragma unroll
+        for (int d = 0; d < 8; ++d) m[d] = bytes_below(hi4 - 16 * d);
+      }
 #pragma unroll
       for (int f = 0; f < 4; ++f) {
         xf[f] &= m;
@@ -237,17 +261,19 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
       asm volatile("" ::: "memory");
       fetch_next(stage == 0 ? 2 : stage - 1);             // two steps ahead, into the buffer of the step before this one
       const int first = (cur.j0 + s) * 128;
-      if (cur.lo > first || cur.hi < first + 128) block(first, cur.lo, cur.hi, stage, std::true_type{}, acc);
-      else block(first, cur.lo, cur.hi, stage, std::false_type{}, acc);
+      block(first, cur.lo, cur.hi, stage, acc);
       stage = stage == 2 ? 0 : stage + 1;
     }
-    // ---- epilogue: fp32, 16 bytes per lane (four consecutive features of one dY^T row) -------------------------
-    float* out = a.dW + ((int64_t)cur.g * a.N + cur.n0 + wn * 64) * a.K + cur.k0 + wk * 64;
+    // ---- epilogue: fp32, 16 bytes per lane (four consecutive features of one dY^T row), through a view of the
+    // tile; written once and never read here, so the stores carry the streaming cache policy (sc0 sc1 nt): the
+    // gradients do not push the operand tiles out of the L2 and the fetches beside them keep their latency
+    const __amdgpu_buffer_rsrc_t dOut = __builtin_amdgcn_make_buffer_rsrc((void*)(a.dW + ((int64_t)cur.g * a.N + cur.n0) * a.K + cur.k0), 0, ((Cfg::TN - 1) * a.K + Cfg::TK) * 4, GG_RSRC_FLAGS);
+    const int vOut = (r * a.K + 4 * q) * 4;
 #pragma unroll
     for (int nf = 0; nf < 4; ++nf)
 #pragma unroll
       for (int kf = 0; kf < 4; ++kf)
-        *(v4f*)(out + (int64_t)(16 * nf + r) * a.K + 16 * kf + 4 * q) = acc[kf][nf];
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, acc[kf][nf]), dOut, vOut, ((wn * 64 + 16 * nf) * a.K + wk * 64 + 16 * kf) * 4, kStoreStreaming);
     pend_stores += 16;
   }
   wait_vmcnt<0>();     // the fetches past the last block still write zeros into this workgroup's LDS: let them land
