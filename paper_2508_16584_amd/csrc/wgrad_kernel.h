@@ -173,20 +173,16 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
     return (v8i){x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
   };
 
-  // One token block.  Where the block holds tokens before the group's first or from the group's end on (it is the
-  // group's first or last block), their bytes are cleared in both operands.
-  auto block = [&](int first, int lo, int hi, int stage, v4f (&acc)[4][4]) __attribute__((always_inline)) {   // first: the block's first token
-    const uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
-    v8i xf[4], yf[4];
-    v4f sx[4];
-    float sy[4];
-#pragma unroll
-    for (int f = 0; f < 4; ++f) {
-      xf[f] = read_frag(st + xBase + f * 2048);
-      yf[f] = read_frag(st + yBase + f * 2048);
-      sx[f] = *(const v4f*)(st + sxRd + f * 64);
-      sy[f] = *(const float*)(st + syRd + f * 64);
-    }
+  // The operand fragments and scales of the block that is multiplied next live in registers: they are read out of
+  // LDS one block ahead, each into the registers of its predecessor as soon as that has been used for the last time.
+  v8i xf[4], yf[4];
+  v4f sx[4];
+  float sy[4];
+
+  // One token block out of the registers, while they are refilled from `nx` (the LDS buffer of the following block).
+  // Where the block holds tokens before the group's first or from the group's end on (it is the group's first or
+  // last block), their bytes are cleared in both operands first.
+  auto block = [&](int first, int lo, int hi, const uint8_t* nx, v4f (&acc)[4][4]) __attribute__((always_inline)) {   // first: the block's first token
     const bool cut_lo = lo > first, cut_hi = hi < first + 128;
     if (cut_lo || cut_hi) {
       const int lo4 = 4 * (lo - first - 32 * q), hi4 = 4 * (hi - first - 32 * q);    // valid tokens of the block: [lo - first, hi - first)
@@ -209,8 +205,9 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    // software pipeline: matrix instruction t is issued two steps ahead of the 8 vector instructions that consume it
-    // (the factor product and the FMA of each of its four outputs), so the vector work runs under the matrix pipe
+    // Software pipeline in 18 slots: slot t issues matrix instruction t (feature fragment t / 4 x dY^T fragment
+    // t % 4), the 8 vector instructions that consume matrix instruction t - 2 (the factor product and the FMA of each
+    // of its four outputs), and the LDS reads that refill what was used for the last time in the slot before.
     v4f p[16];
     static_for<0, 16 + 2>([&](auto tc) __attribute__((always_inline)) {
       constexpr int t = decltype(tc)::value;
@@ -221,11 +218,22 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
 #pragma unroll
         for (int i = 0; i < 4; ++i) acc[kf][nf][i] += p[u][i] * (sx[kf][i] * sy[nf]);
       }
+      if constexpr (t == 4 || t == 8 || t == 12 || t == 16) xf[t / 4 - 1] = read_frag(nx + xBase + (t / 4 - 1) * 2048);
+      if constexpr (t >= 13 && t <= 16) yf[t - 13] = read_frag(nx + yBase + (t - 13) * 2048);
+      if constexpr (t == 6 || t == 10 || t == 14) sx[(t - 6) / 4] = *(const v4f*)(nx + sxRd + ((t - 6) / 4) * 64);
+      if constexpr (t == 17) {
+        sx[3] = *(const v4f*)(nx + sxRd + 3 * 64);
+#pragma unroll
+        for (int f = 0; f < 4; ++f) sy[f] = *(const float*)(nx + syRd + f * 64);
+      }
     });
     static_for<0, 16 + 2>([&](auto tc) __attribute__((always_inline)) {
       constexpr int t = decltype(tc)::value;
       if constexpr (t < 16) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       if constexpr (t >= 2) __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+      constexpr int reads = (t == 4 || t == 8 || t == 12 ? 2 : 0) + (t >= 13 && t <= 15 ? 2 : 0) + (t == 16 ? 4 : 0) +
+                            (t == 6 || t == 10 || t == 14 ? 1 : 0) + (t == 17 ? 5 : 0);
+      if constexpr (reads > 0) __builtin_amdgcn_sched_group_barrier(0x100, reads, 0);
     });
     __builtin_amdgcn_sched_barrier(0);
     // the accumulators are "used" here, so that every update above lands in the accumulator's own register
@@ -235,10 +243,22 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
       for (int nf = 0; nf < 4; ++nf) asm volatile("" : "+v"(acc[kf][nf]));
   };
 
-  // ---- ring of 3: the blocks of the next two steps are in flight while a block is multiplied -------------------
+  // ---- ring of 3 LDS buffers + the registers: while block b is multiplied out of the registers, block b + 1 has
+  // landed and is being read into them, blocks b + 2 and b + 3 are in flight (b + 3 into the buffer block b came from)
   fetch_next(0);
   fetch_next(1);
-  int stage = 0;
+  fetch_next(2);
+  wait_vmcnt<2 * Cfg::NDMA>();
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+#pragma unroll
+  for (int f = 0; f < 4; ++f) {
+    xf[f] = read_frag(lds + xBase + f * 2048);
+    yf[f] = read_frag(lds + yBase + f * 2048);
+    sx[f] = *(const v4f*)(lds + sxRd + f * 64);
+    sy[f] = *(const float*)(lds + syRd + f * 64);
+  }
+  int stage = 0;            // the buffer the block in the registers came from
   int pend_stores = 0;      // stores issued since the last wait for a fetch
   for (int it = 0;; ++it) {
     const Tile cur = tile_at(it);
@@ -249,20 +269,22 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
 #pragma unroll
       for (int nf = 0; nf < 4; ++nf) acc[kf][nf] = (v4f){0.f, 0.f, 0.f, 0.f};
     for (int s = 0; s < cur.steps; ++s) {
-      // This wave's part of the block has landed: its fetches are older than those of the next block and than the
-      // stores of the tiles finished since the last wait, which may all stay in flight (vector memory operations
-      // of a wave complete in the order they were issued; the counter holds 63 at most).
+      // This wave has read all of the block it multiplies now, and its part of the following block has landed: those
+      // fetches are older than the ones of the block after it and than the stores of the tiles finished since the
+      // last wait, which may all stay in flight (vector memory operations of a wave complete in the order they were
+      // issued; the counter holds 63 at most).
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       if (pend_stores == 0) wait_vmcnt<Cfg::NDMA>();
       else if (pend_stores == 16) wait_vmcnt<Cfg::NDMA + 16>();
       else if (pend_stores == 32) wait_vmcnt<Cfg::NDMA + 32>();
       else wait_vmcnt<Cfg::NDMA>();
       pend_stores = 0;
-      __builtin_amdgcn_s_barrier();       // ... and everybody's; everybody is done with the buffer refilled next
+      __builtin_amdgcn_s_barrier();       // ... and everybody's; nobody reads the buffer of this step's block any more
       asm volatile("" ::: "memory");
-      fetch_next(stage == 0 ? 2 : stage - 1);             // two steps ahead, into the buffer of the step before this one
-      const int first = (cur.j0 + s) * 128;
-      block(first, cur.lo, cur.hi, stage, acc);
-      stage = stage == 2 ? 0 : stage + 1;
+      fetch_next(stage);                  // three steps ahead, into that buffer
+      const int next_stage = stage == 2 ? 0 : stage + 1;
+      block((cur.j0 + s) * 128, cur.lo, cur.hi, lds + next_stage * Cfg::STAGE_BYTES, acc);
+      stage = next_stage;
     }
     // ---- epilogue: fp32, 16 bytes per lane (four consecutive features of one dY^T row), through a view of the
     // tile; written once and never read here, so the stores carry the streaming cache policy (sc0 sc1 nt): the
