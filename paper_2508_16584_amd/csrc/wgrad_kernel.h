@@ -165,8 +165,10 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
   const int keyR = swz_key_a(r);
   const int rd0 = r * 128 + (((2 * q) ^ keyR) << 4), rd1 = r * 128 + (((2 * q + 1) ^ keyR) << 4);
   const int xBase = (wk * 64) * 128, yBase = Cfg::X_BYTES + (wn * 64) * 128;
-  const int sxRd = Cfg::X_BYTES + Cfg::Y_BYTES + (wk * 64 + 4 * q) * 4;          // + 64 kf: four consecutive features
-  const int syRd = Cfg::X_BYTES + Cfg::Y_BYTES + Cfg::SX_BYTES + (wn * 64 + r) * 4;   // + 64 nf
+  // a matrix instruction's output has dY^T rows 4 q .. 4 q + 3 of its fragment in the lane's four registers and
+  // feature r of its fragment in the lane, so that the 16 lanes of a row hold 64 consecutive bytes of dW
+  const int sxRd = Cfg::X_BYTES + Cfg::Y_BYTES + (wk * 64 + r) * 4;                     // + 64 kf
+  const int syRd = Cfg::X_BYTES + Cfg::Y_BYTES + Cfg::SX_BYTES + (wn * 64 + 4 * q) * 4;     // + 64 nf: four consecutive rows
   auto read_frag = [&](const uint8_t* p) __attribute__((always_inline)) -> v8i {
     const v4i x = *(const v4i*)(p + rd0);
     const v4i y = *(const v4i*)(p + rd1);
@@ -176,8 +178,8 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
   // The operand fragments and scales of the block that is multiplied next live in registers: they are read out of
   // LDS one block ahead, each into the registers of its predecessor as soon as that has been used for the last time.
   v8i xf[4], yf[4];
-  v4f sx[4];
-  float sy[4];
+  float sx[4];
+  v4f sy[4];
 
   // One token block out of the registers, while they are refilled from `nx` (the LDS buffer of the following block).
   // Where the block holds tokens before the group's first or from the group's end on (it is the group's first or
@@ -205,26 +207,26 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    // Software pipeline in 18 slots: slot t issues matrix instruction t (feature fragment t / 4 x dY^T fragment
+    // Software pipeline in 18 slots: slot t issues matrix instruction t (dY^T fragment t / 4 x feature fragment
     // t % 4), the 8 vector instructions that consume matrix instruction t - 2 (the factor product and the FMA of each
     // of its four outputs), and the LDS reads that refill what was used for the last time in the slot before.
     v4f p[16];
     static_for<0, 16 + 2>([&](auto tc) __attribute__((always_inline)) {
       constexpr int t = decltype(tc)::value;
       if constexpr (t < 16)
-        p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xf[t / 4], yf[t % 4], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+        p[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(yf[t / 4], xf[t % 4], (v4f){0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
       if constexpr (t >= 2) {
-        constexpr int u = t - 2, kf = u / 4, nf = u % 4;
+        constexpr int u = t - 2, nf = u / 4, kf = u % 4;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) acc[kf][nf][i] += p[u][i] * (sx[kf][i] * sy[nf]);
+        for (int i = 0; i < 4; ++i) acc[kf][nf][i] += p[u][i] * (sy[nf][i] * sx[kf]);
       }
-      if constexpr (t == 4 || t == 8 || t == 12 || t == 16) xf[t / 4 - 1] = read_frag(nx + xBase + (t / 4 - 1) * 2048);
-      if constexpr (t >= 13 && t <= 16) yf[t - 13] = read_frag(nx + yBase + (t - 13) * 2048);
-      if constexpr (t == 6 || t == 10 || t == 14) sx[(t - 6) / 4] = *(const v4f*)(nx + sxRd + ((t - 6) / 4) * 64);
+      if constexpr (t == 4 || t == 8 || t == 12 || t == 16) yf[t / 4 - 1] = read_frag(nx + yBase + (t / 4 - 1) * 2048);
+      if constexpr (t >= 13 && t <= 16) xf[t - 13] = read_frag(nx + xBase + (t - 13) * 2048);
+      if constexpr (t == 6 || t == 10 || t == 14) sy[(t - 6) / 4] = *(const v4f*)(nx + syRd + ((t - 6) / 4) * 64);
       if constexpr (t == 17) {
-        sx[3] = *(const v4f*)(nx + sxRd + 3 * 64);
+        sy[3] = *(const v4f*)(nx + syRd + 3 * 64);
 #pragma unroll
-        for (int f = 0; f < 4; ++f) sy[f] = *(const float*)(nx + syRd + f * 64);
+        for (int f = 0; f < 4; ++f) sx[f] = *(const float*)(nx + sxRd + f * 64);
       }
     });
     static_for<0, 16 + 2>([&](auto tc) __attribute__((always_inline)) {
@@ -255,11 +257,11 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
   for (int f = 0; f < 4; ++f) {
     xf[f] = read_frag(lds + xBase + f * 2048);
     yf[f] = read_frag(lds + yBase + f * 2048);
-    sx[f] = *(const v4f*)(lds + sxRd + f * 64);
-    sy[f] = *(const float*)(lds + syRd + f * 64);
+    sx[f] = *(const float*)(lds + sxRd + f * 64);
+    sy[f] = *(const v4f*)(lds + syRd + f * 64);
   }
   int stage = 0;            // the buffer the block in the registers came from
-  int pend_stores = 0;      // stores issued since the last wait for a fetch
+  bool next_landed = false; // this wave's part of the block after the one in the registers is known to have landed
   for (int it = 0;; ++it) {
     const Tile cur = tile_at(it);
     if (!cur.valid) break;
@@ -270,15 +272,11 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
       for (int nf = 0; nf < 4; ++nf) acc[kf][nf] = (v4f){0.f, 0.f, 0.f, 0.f};
     for (int s = 0; s < cur.steps; ++s) {
       // This wave has read all of the block it multiplies now, and its part of the following block has landed: those
-      // fetches are older than the ones of the block after it and than the stores of the tiles finished since the
-      // last wait, which may all stay in flight (vector memory operations of a wave complete in the order they were
-      // issued; the counter holds 63 at most).
+      // fetches are older than the ones of the block after it, which stay in flight (vector memory operations of a
+      // wave complete in the order they were issued); after a tile's epilogue that wait has been taken there.
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      if (pend_stores == 0) wait_vmcnt<Cfg::NDMA>();
-      else if (pend_stores == 16) wait_vmcnt<Cfg::NDMA + 16>();
-      else if (pend_stores == 32) wait_vmcnt<Cfg::NDMA + 32>();
-      else wait_vmcnt<Cfg::NDMA>();
-      pend_stores = 0;
+      if (!next_landed) wait_vmcnt<Cfg::NDMA>();
+      next_landed = false;
       __builtin_amdgcn_s_barrier();       // ... and everybody's; nobody reads the buffer of this step's block any more
       asm volatile("" ::: "memory");
       fetch_next(stage);                  // three steps ahead, into that buffer
@@ -286,17 +284,31 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
       block((cur.j0 + s) * 128, cur.lo, cur.hi, lds + next_stage * Cfg::STAGE_BYTES, acc);
       stage = next_stage;
     }
-    // ---- epilogue: fp32, 16 bytes per lane (four consecutive features of one dY^T row), through a view of the
-    // tile; written once and never read here, so the stores carry the streaming cache policy (sc0 sc1 nt): the
-    // gradients do not push the operand tiles out of the L2 and the fetches beside them keep their latency
+    // ---- epilogue: fp32 through a view of the tile, one register at a time: the 16 lanes of a dY^T row write 64
+    // consecutive bytes (with 16 bytes per lane, neighbouring lanes would write to different rows and every lane's
+    // piece would be a request of its own: a quarter of the store rate).  Written once and never read here, so the
+    // stores carry the streaming cache policy (sc0 sc1 nt): the gradients do not push the operand tiles out of the
+    // L2 and the fetches beside them keep their latency.  The counter of outstanding vector memory operations
+    // holds 63: no more than 24 are outstanding when a batch of 32 stores begins.
     const __amdgpu_buffer_rsrc_t dOut = __builtin_amdgcn_make_buffer_rsrc((void*)(a.dW + ((int64_t)cur.g * a.N + cur.n0) * a.K + cur.k0), 0, ((Cfg::TN - 1) * a.K + Cfg::TK) * 4, GG_RSRC_FLAGS);
-    const int vOut = (r * a.K + 4 * q) * 4;
+    const int vOut = (4 * q * a.K + r) * 4;
+    if (next_landed) {
+      wait_vmcnt<24>();
+    } else {
+      wait_vmcnt<Cfg::NDMA>();
+      next_landed = true;
+    }
 #pragma unroll
-    for (int nf = 0; nf < 4; ++nf)
+    for (int nf = 0; nf < 4; ++nf) {
+      if (nf == 2) wait_vmcnt<24>();
 #pragma unroll
-      for (int kf = 0; kf < 4; ++kf)
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, acc[kf][nf]), dOut, vOut, ((wn * 64 + 16 * nf) * a.K + wk * 64 + 16 * kf) * 4, kStoreStreaming);
-    pend_stores += 16;
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int kf = 0; kf < 4; ++kf) {
+          const float v = acc[kf][nf][i];      // (a bit cast of the vector element itself takes element 0)
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), dOut, vOut + 64 * kf, ((wn * 64 + 16 * nf + i) * a.K + wk * 64) * 4, kStoreStreaming);
+        }
+    }
   }
   wait_vmcnt<0>();     // the fetches past the last block still write zeros into this workgroup's LDS: let them land
 }
