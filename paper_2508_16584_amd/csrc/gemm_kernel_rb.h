@@ -668,6 +668,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       }
     } else {
     // ---- epilogue: bf16 (or binary16) RNE, one bounded 16-byte store per activation block ---------------------------------
+    const int cSrc = (16 * (l & 3) + (l >> 2)) * 4;      // byte address of the lane whose 16 bytes lane l stores
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt) {
       const v4f x = acc[mt][0], y = acc[mt][1];
@@ -682,9 +683,16 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_rb_kernel(const GemmArgs a) {
       int rows_mt = rows_valid - 16 * mt;
       rows_mt = rows_mt < 0 ? 0 : rows_mt;
       __amdgpu_buffer_rsrc_t dC = uniform_rsrc(a.C + (grow + 16 * mt) * N + n0, rows_mt > 0 ? rows_mt * N * 2 - n0 * 2 : 0);
+      // The lane (q, r) holds 16 bytes of row r; stored from there, neighbouring lanes would write to different
+      // rows and every lane's piece would be a request of its own.  Lane 4 r + q takes them instead (a transpose of
+      // the lane grid through the LDS crossbar), so that four neighbouring lanes write the wave's 64 bytes of a row.
+      out.x = __builtin_amdgcn_ds_bpermute(cSrc, out.x);
+      out.y = __builtin_amdgcn_ds_bpermute(cSrc, out.y);
+      out.z = __builtin_amdgcn_ds_bpermute(cSrc, out.z);
+      out.w = __builtin_amdgcn_ds_bpermute(cSrc, out.w);
       // RAGGED: N is a multiple of 8, so a lane's 8 columns exist together or not at all
-      const bool col_ok = !Cfg::RAGGED || n0 + w * 32 + 8 * q < N;
-      __builtin_amdgcn_raw_buffer_store_b128(out, dC, col_ok ? r * N * 2 + (w * 32 + 8 * q) * 2 : GG_OOB_OFFSET, 0, 0);
+      const bool col_ok = !Cfg::RAGGED || n0 + w * 32 + 8 * (l & 3) < N;
+      __builtin_amdgcn_raw_buffer_store_b128(out, dC, col_ok ? (l >> 2) * N * 2 + (w * 32 + 8 * (l & 3)) * 2 : GG_OOB_OFFSET, 0, 0);
     }
     }
     if (!has_next) {
