@@ -19,12 +19,14 @@
 //
 // Structure: persistent workgroups (8 waves, 4 along k x 2 along n) walk the output tiles of 256 features x 128
 // rows of dY^T; per token block the two operand tiles and their scales go global -> LDS by DMA into a ring of 3
-// buffers, swizzled like the forward kernels' tiles, and the fetch stream runs two blocks ahead of the arithmetic
+// buffers, swizzled like the forward kernels' tiles, and the fetch stream runs three blocks ahead of the arithmetic
 // across tile boundaries (a group of 1000 tokens is 8 blocks: without that, every tile would start with an empty
-// pipeline and end with an idle one); a wave holds 4 + 4 operand fragments and 64 x 64
-// fp32 accumulators; one v_mfma_f32_16x16x128_f8f6f4 from zero per scale block, then acc += p * (sx * sdy) with
-// sx one of the lane's four feature rows and sdy the lane's dY^T row: 8 vector instructions per matrix instruction
-// (the factor differs per output element, not per lane as in the forward pass).
+// pipeline and end with an idle one).  A wave holds the 4 + 4 operand fragments and the scales of the block it
+// multiplies in registers and refills them from the next block's buffer while it multiplies, and 64 x 64 fp32
+// accumulators; one v_mfma_f32_16x16x128_f8f6f4 from zero per scale block (dY^T fragment first: an output row's 16
+// lanes then hold consecutive features), then acc += p * (sdy * sx) with sdy one of the lane's four dY^T rows and
+// sx the lane's feature: 8 vector instructions per matrix instruction (the factor differs per output element, not
+// per lane as in the forward pass).
 #pragma once
 #include "gemm_kernel.h"
 
