@@ -660,9 +660,13 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
       }
     } else {
     // ---- epilogue: bf16 (or binary16) RNE, 16-byte bounded stores ---------------------------------------------
+    // Lane (q, r) holds 16 bytes of row r; stored from there, neighbouring lanes would write to different rows and
+    // every lane's piece would be a request of its own.  Lane 4 r + q takes them instead (a transpose of the lane
+    // grid through the LDS crossbar), so that four neighbouring lanes write 64 consecutive bytes of a row.
+    const int cSrc = (16 * (l & 3) + (l >> 2)) * 4;
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt) {
-      const int row = wm * WTM + 16 * mt + r;
+      const int row = wm * WTM + 16 * mt + (l >> 2);
 #pragma unroll
       for (int pr = 0; pr < TN / 2; ++pr) {
         const v4f x = acc[mt][2 * pr], y = acc[mt][2 * pr + 1];
@@ -672,7 +676,11 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
         out.y = pack2_rne(x[2], x[3], f16);
         out.z = pack2_rne(y[0], y[1], f16);
         out.w = pack2_rne(y[2], y[3], f16);
-        const int col = wn * WTN + 32 * pr + 8 * q;     // 8 columns; N is a multiple of 8, so they exist together or not at all
+        out.x = __builtin_amdgcn_ds_bpermute(cSrc, out.x);
+        out.y = __builtin_amdgcn_ds_bpermute(cSrc, out.y);
+        out.z = __builtin_amdgcn_ds_bpermute(cSrc, out.z);
+        out.w = __builtin_amdgcn_ds_bpermute(cSrc, out.w);
+        const int col = wn * WTN + 32 * pr + 8 * (l & 3);     // 8 columns; N is a multiple of 8, so they exist together or not at all
         __builtin_amdgcn_raw_buffer_store_b128(out, dC, (!RAGGED || col < n_rem) ? row * N * 2 + col * 2 : GG_OOB_OFFSET, 0, 0);
       }
     }
