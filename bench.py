@@ -440,6 +440,28 @@ def bench_kstep_parts():
     print(json.dumps({"op": "kstep_parts", "second_gemm_kernel_with_parts_of_its_k_step_left_out": out}))
 
 
+def bench_wgrad_parts():
+    """The weight-gradient kernel with parts of a token block's work left out (gg_probe_wgrad_parts), on gate_up's
+    layer with 8 equal groups of 1000 tokens (8 blocks each, the first and the last of them cut by a group boundary)
+    and on a store-bound layer (32 groups of 48 tokens, same N and K).  One JSON line; microseconds per launch; the
+    ideal is the matrix pipe's time for the same blocks at the nominal clock."""
+    import paper_2508_16584_amd as gg
+    parts = [(0, "nothing left out (the kernel as launched)"), (2, "no stores"), (1, "no fetches"),
+             (3, "neither (arithmetic, LDS reads, barrier, masks)"), (7, "the same without the barrier"),
+             (11, "neither fetches nor stores, no byte masks"), (19, "neither fetches nor stores, no LDS reads"),
+             (31, "matrix instructions and FMAs alone")]
+    out = {}
+    for groups, tokens in ((8, 1000), (32, 48)):
+        res = {name: round(gg.probe_wgrad_parts(code, groups, tokens, 4096, 7168, 20), 1) for code, name in parts}
+        first, last = [g * tokens // 128 for g in range(groups)], [(g * tokens + tokens - 1) // 128 for g in range(groups)]
+        blocks = sum(b - a + 1 for a, b in zip(first, last))
+        ideal_cycles = blocks * (4096 // 128) * (7168 // 256) * 128 * 32 / 1024.0     # 128 instructions per tile and block, 1024 SIMDs
+        out[f"{groups} groups x {tokens} tokens, N=4096, K=7168"] = {
+            "us_per_launch": res, "token_blocks_of_all_groups": blocks, "matrix_pipe_minimum_us_at_2.4GHz": round(ideal_cycles / 2400.0, 1),
+            "dW_bytes": groups * 4096 * 7168 * 4}
+    print(json.dumps({"op": "wgrad_parts", "weight_gradient_kernel_with_parts_left_out": out}))
+
+
 def bench_pad_path(args, cfg, dev):
     """The comparison path of Sec. 3 step by step: pad (offsets + row copies), the GEMM on the padded problem, unpad.
     Each step is timed alone, `steps` launches back to back over rotating buffer sets (cold caches); the copies are
@@ -543,7 +565,7 @@ def main():
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="gate_up")
-    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows", "swiglu_quantize_rows", "expert_mlp", "ceilings", "pad_path", "kstep_parts", "wgrad"],
+    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows", "swiglu_quantize_rows", "expert_mlp", "ceilings", "pad_path", "kstep_parts", "wgrad", "wgrad_parts"],
                     help="grouped_gemm: the hot path (default, the headline metric); quantize_rows: the producer of its "
                          "A operand on the same workload's activation shape; swiglu_quantize_rows: activation + quantiser "
                          "on the workload's output shape [M_total, N] (N = 2 x intermediate width); expert_mlp: the whole forward "
@@ -593,6 +615,9 @@ def main():
     torch.cuda.set_device(dev)
     if args.op == "ceilings":
         bench_ceilings()
+        return
+    if args.op == "wgrad_parts":
+        bench_wgrad_parts()
         return
     if args.op == "kstep_parts":
         bench_kstep_parts()

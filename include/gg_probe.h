@@ -86,6 +86,21 @@ int gg_probe_lds_fetch(int pattern, int depth, int reps, double* gbytes_per_s_ou
  * higher clock): for cycles run the same call under `rocprofv3 --pmc GRBM_GUI_ACTIVE`. */
 int gg_probe_gemm_kstep(int tile_rows, int left_out, int groups, int rows_per_group, int n, int k, int reps, double* us_out);
 
+/* The weight-gradient kernel of libgg_fp8 (gg_fp8_grouped_gemm_wgrad: the variable-K grouped GEMM of training, which
+ * the paper's title names and its text does not define) in measurement builds that LEAVE OUT parts of a token block's
+ * work, on a problem this call makes itself: `groups` equal groups of `tokens_per_group` tokens (any count: a group
+ * whose ends fall inside a 128-token block has masked first and last blocks), dW [groups, n, k] fp32 (n % 128 == 0,
+ * k % 256 == 0; operands under 2 GiB, dW under 4 GiB), operand bytes like e4m3-quantised normal samples, block-major
+ * scales.
+ *   left_out:  sum of 1 the fetches of the token blocks, 2 the stores of dW, 4 the barrier of a block, 8 the byte
+ *              masks of a group's first and last block, 16 the LDS reads that refill the operand registers.
+ *              Built: 0 (the kernel as the library launches it), 1, 2, 3, 7, 11, 19, 31 (matrix instructions and
+ *              FMAs only).  Anything else: hipErrorInvalidValue.  Only accesses, waits and masks are removed, so every
+ *              remaining access stays in bounds; the OUTPUT IS MEANINGLESS for every value but 0.
+ *   reps:      timed launches (launches of the same build for about 150 ms precede them: the sustained clock)
+ * us_out (host): microseconds per launch. */
+int gg_probe_wgrad_parts(int left_out, int groups, int tokens_per_group, int n, int k, int reps, double* us_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     load_library,
     load_probe_library,
     probe_gemm_kstep,
+    probe_wgrad_parts,
     probe_hbm,
     probe_issue_mix,
     probe_lds_fetch,

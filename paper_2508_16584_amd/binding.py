@@ -87,6 +87,8 @@ def load_probe_library() -> ctypes.CDLL:
     lib.gg_probe_lds_fetch.argtypes = [i32, i32, i32, dp, dp]
     lib.gg_probe_gemm_kstep.restype = i32
     lib.gg_probe_gemm_kstep.argtypes = [i32, i32, i32, i32, i32, i32, i32, dp]
+    lib.gg_probe_wgrad_parts.restype = i32
+    lib.gg_probe_wgrad_parts.argtypes = [i32, i32, i32, i32, i32, i32, dp]
     _probe = lib
     return lib
 
@@ -123,6 +125,12 @@ def probe_gemm_kstep(tile_rows: int, left_out: int, groups: int = 8, rows_per_gr
                      k: int = 7168, reps: int = 20) -> float:
     """Microseconds per launch of the second GEMM kernel with parts of its K step left out (gg_probe_gemm_kstep)."""
     return _probe_call(load_probe_library().gg_probe_gemm_kstep, tile_rows, left_out, groups, rows_per_group, n, k, reps)
+
+
+def probe_wgrad_parts(left_out: int, groups: int = 8, tokens_per_group: int = 1000, n: int = 4096, k: int = 7168,
+                      reps: int = 20) -> float:
+    """Microseconds per launch of the weight-gradient kernel with parts of a block's work left out (gg_probe_wgrad_parts)."""
+    return _probe_call(load_probe_library().gg_probe_wgrad_parts, left_out, groups, tokens_per_group, n, k, reps)
 
 
 def load_library() -> ctypes.CDLL:

@@ -469,12 +469,12 @@ int gg_fp8_grouped_gemm_wgrad(const void* XT, const float* SX, const void* DYT, 
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return GG_ERR_HIP;
   if (dev >= 0 && dev < 64 && !prepared[dev].load(std::memory_order_acquire)) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_wgrad_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_wgrad_kernel<0>), hipFuncAttributeMaxDynamicSharedMemorySize,
                             gg::WgradCfg::LDS_BYTES) != hipSuccess)
       return GG_ERR_HIP;
     prepared[dev].store(1, std::memory_order_release);
   }
-  hipLaunchKernelGGL(gg::gg_wgrad_kernel, dim3((unsigned)grid), dim3(gg::WgradCfg::NT), gg::WgradCfg::LDS_BYTES,
+  hipLaunchKernelGGL(gg::gg_wgrad_kernel<0>, dim3((unsigned)grid), dim3(gg::WgradCfg::NT), gg::WgradCfg::LDS_BYTES,
                      static_cast<hipStream_t>(stream), args);
   return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
 }

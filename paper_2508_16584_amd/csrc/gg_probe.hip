@@ -9,6 +9,7 @@
 #include "gg_probe.h"
 #include "gemm_kernel.h"   // operand vector types, buffer descriptor flags, wait_vmcnt
 #include "gemm_kernel_rb.h"   // the second GEMM kernel, for its measurement builds (RbCfg<..., TIMING>)
+#include "wgrad_kernel.h"     // the weight-gradient kernel, for its measurement builds (gg_wgrad_kernel<TIMING>)
 
 namespace {
 
@@ -312,6 +313,19 @@ hipError_t launch_rb_rows(int tile_rows, const gg::GemmArgs& args, int grid) {
   return launch_rb<gg::RbCfg<256, 2, false, false, false, false, false, TIMING>>(args, grid);
 }
 
+template <int TIMING>
+hipError_t launch_wgrad(const gg::WgradArgs& args, int grid) {
+  static bool prepared = false;
+  if (!prepared) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_wgrad_kernel<TIMING>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, gg::WgradCfg::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    prepared = true;
+  }
+  hipLaunchKernelGGL(gg::gg_wgrad_kernel<TIMING>, dim3((unsigned)grid), dim3(gg::WgradCfg::NT), gg::WgradCfg::LDS_BYTES, 0, args);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 extern "C" {
@@ -611,6 +625,107 @@ int gg_probe_gemm_kstep(int tile_rows, int left_out, int groups, int rows_per_gr
   // warm-up: launches of the same build for about 150 ms, so that the timed ones run at the sustained clock (after
   // an idle period the clock takes about a hundred launches of this size to settle)
   for (float warm_ms = 0.f; warm_ms < 150.f;) {
+    PROBE_TRY(hipEventRecord(e0, 0));
+    for (int i = 0; i < 10; ++i) PROBE_TRY(launch());
+    PROBE_TRY(hipEventRecord(e1, 0));
+    PROBE_TRY(hipEventSynchronize(e1));
+    float t = 0.f;
+    PROBE_TRY(hipEventElapsedTime(&t, e0, e1));
+    warm_ms += t > 0.01f ? t : 0.01f;
+  }
+  PROBE_TRY(hipEventRecord(e0, 0));
+  for (int i = 0; i < reps; ++i) PROBE_TRY(launch());
+  PROBE_TRY(hipEventRecord(e1, 0));
+  PROBE_TRY(hipEventSynchronize(e1));
+  float ms = 0.f;
+  PROBE_TRY(hipEventElapsedTime(&ms, e0, e1));
+  *us_out = (double)ms * 1e3 / reps;
+  cleanup();
+  return 0;
+}
+
+int gg_probe_wgrad_parts(int left_out, int groups, int tokens_per_group, int n, int k, int reps, double* us_out) {
+  if (groups < 1 || groups > 4096 || tokens_per_group < 1 || n < 128 || n % 128 != 0 || k < 256 || k % 256 != 0 || reps < 1 || !us_out)
+    return (int)hipErrorInvalidValue;
+  switch (left_out) {
+    case 0: case 1: case 2: case 3: case 7: case 11: case 19: case 31: break;
+    default: return (int)hipErrorInvalidValue;
+  }
+  // the token axis is padded to a multiple of 16 behind the last group, as the library asks
+  const int64_t m_total = ((int64_t)groups * tokens_per_group + 15) / 16 * 16;
+  const int64_t mb = (m_total + 127) / 128;
+  if ((int64_t)k * m_total > 0x7FFFFFFFLL || (int64_t)n * m_total > 0x7FFFFFFFLL || (int64_t)groups * n * k > 0x3FFFFFFFLL)
+    return (int)hipErrorInvalidValue;
+  uint8_t *XT = nullptr, *DYT = nullptr;
+  float *SX = nullptr, *SDY = nullptr, *dW = nullptr;
+  int32_t* off = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  auto cleanup = [&] {
+    if (XT) (void)hipFree(XT);
+    if (DYT) (void)hipFree(DYT);
+    if (SX) (void)hipFree(SX);
+    if (SDY) (void)hipFree(SDY);
+    if (dW) (void)hipFree(dW);
+    if (off) (void)hipFree(off);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+  };
+  const size_t x_bytes = (size_t)k * m_total, y_bytes = (size_t)n * m_total, w_bytes = (size_t)groups * n * k * 4;
+  PROBE_TRY(hipMalloc(&XT, x_bytes));
+  PROBE_TRY(hipMalloc(&DYT, y_bytes));
+  PROBE_TRY(hipMalloc(&SX, (size_t)mb * k * 4));
+  PROBE_TRY(hipMalloc(&SDY, (size_t)mb * n * 4));
+  PROBE_TRY(hipMalloc(&dW, w_bytes));
+  PROBE_TRY(hipMalloc(&off, (size_t)(groups + 1) * 4));
+  std::vector<int32_t> h_off(groups + 1);
+  for (int g = 0; g <= groups; ++g) h_off[g] = g * tokens_per_group;
+  PROBE_TRY(hipMemcpy(off, h_off.data(), h_off.size() * 4, hipMemcpyHostToDevice));
+  const int fgrid = cus() * 8;
+  hipLaunchKernelGGL(fill_e4m3_kernel, dim3(fgrid), dim3(256), 0, 0, XT, x_bytes, 5u);
+  hipLaunchKernelGGL(fill_e4m3_kernel, dim3(fgrid), dim3(256), 0, 0, DYT, y_bytes, 6u);
+  hipLaunchKernelGGL(fill_scale_kernel, dim3(fgrid), dim3(256), 0, 0, SX, (size_t)mb * k, 7u);
+  hipLaunchKernelGGL(fill_scale_kernel, dim3(fgrid), dim3(256), 0, 0, SDY, (size_t)mb * n, 8u);
+  PROBE_TRY(hipGetLastError());
+  PROBE_TRY(hipMemset(dW, 0, w_bytes));
+
+  // the launch arguments as the GEMM library fills them
+  gg::WgradArgs args{};
+  args.XT = XT;
+  args.SX = SX;
+  args.DYT = DYT;
+  args.SDY = SDY;
+  args.off = off;
+  args.dW = dW;
+  args.G = groups;
+  args.M_total = (int)m_total;
+  args.N = n;
+  args.K = k;
+  args.MB = (int)mb;
+  args.n_tiles = n / gg::WgradCfg::TN;
+  args.k_tiles = k / gg::WgradCfg::TK;
+  args.tiles = groups * args.n_tiles * args.k_tiles;
+  args.blocked = args.k_tiles % 4 == 0 && args.n_tiles % 8 == 0;
+  int64_t grid = cus();
+  if (grid > args.tiles) grid = args.tiles;
+  if (grid >= 8) {
+    grid -= grid % 8;
+    args.slots = (int)(grid / 8);
+  }
+  PROBE_TRY(hipEventCreate(&e0));
+  PROBE_TRY(hipEventCreate(&e1));
+  auto launch = [&]() -> hipError_t {
+    switch (left_out) {
+      case 0: return launch_wgrad<0>(args, (int)grid);
+      case 1: return launch_wgrad<1>(args, (int)grid);
+      case 2: return launch_wgrad<2>(args, (int)grid);
+      case 3: return launch_wgrad<3>(args, (int)grid);
+      case 7: return launch_wgrad<7>(args, (int)grid);
+      case 11: return launch_wgrad<11>(args, (int)grid);
+      case 19: return launch_wgrad<19>(args, (int)grid);
+      default: return launch_wgrad<31>(args, (int)grid);
+    }
+  };
+  for (float warm_ms = 0.f; warm_ms < 150.f;) {     // the sustained clock, as in gg_probe_gemm_kstep
     PROBE_TRY(hipEventRecord(e0, 0));
     for (int i = 0; i < 10; ++i) PROBE_TRY(launch());
     PROBE_TRY(hipEventRecord(e1, 0));

@@ -70,6 +70,12 @@ __device__ __forceinline__ int bytes_below(int x4) {       // keeps the bytes be
   return ~bytes_from(x4);
 }
 
+// TIMING (measurement builds of the probe library only; the GEMM library instantiates 0): parts of a block's work
+// left out to time the rest.  Only accesses, waits and the masks are removed: every access that remains is one the
+// full kernel makes.  The outputs of such builds are meaningless.
+enum : int { kWgNoFetch = 1, kWgNoStore = 2, kWgNoBarrier = 4, kWgNoMask = 8, kWgNoLdsReads = 16 };
+
+template <int TIMING>
 __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs a) {
   using Cfg = WgradCfg;
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
@@ -187,7 +193,7 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
   // Where the block holds tokens before the group's first or from the group's end on (it is the group's first or
   // last block), their bytes are cleared in both operands first.
   auto block = [&](int first, int lo, int hi, const uint8_t* nx, v4f (&acc)[4][4]) __attribute__((always_inline)) {   // first: the block's first token
-    const bool cut_lo = lo > first, cut_hi = hi < first + 128;
+    const bool cut_lo = !(TIMING & kWgNoMask) && lo > first, cut_hi = !(TIMING & kWgNoMask) && hi < first + 128;
     if (cut_lo || cut_hi) {
       const int lo4 = 4 * (lo - first - 32 * q), hi4 = 4 * (hi - first - 32 * q);    // valid tokens of the block: [lo - first, hi - first)
       v8i m;
@@ -222,13 +228,19 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
 #pragma unroll
         for (int i = 0; i < 4; ++i) acc[kf][nf][i] += p[u][i] * (sy[nf][i] * sx[kf]);
       }
-      if constexpr (t == 4 || t == 8 || t == 12 || t == 16) yf[t / 4 - 1] = read_frag(nx + yBase + (t / 4 - 1) * 2048);
-      if constexpr (t >= 13 && t <= 16) xf[t - 13] = read_frag(nx + xBase + (t - 13) * 2048);
-      if constexpr (t == 6 || t == 10 || t == 14) sy[(t - 6) / 4] = *(const v4f*)(nx + syRd + ((t - 6) / 4) * 64);
-      if constexpr (t == 17) {
-        sy[3] = *(const v4f*)(nx + syRd + 3 * 64);
+      if constexpr (!(TIMING & kWgNoLdsReads)) {
+        if constexpr (t == 4 || t == 8 || t == 12 || t == 16) yf[t / 4 - 1] = read_frag(nx + yBase + (t / 4 - 1) * 2048);
+        if constexpr (t >= 13 && t <= 16) xf[t - 13] = read_frag(nx + xBase + (t - 13) * 2048);
+        if constexpr (t == 6 || t == 10 || t == 14) sy[(t - 6) / 4] = *(const v4f*)(nx + syRd + ((t - 6) / 4) * 64);
+        if constexpr (t == 17) {
+          sy[3] = *(const v4f*)(nx + syRd + 3 * 64);
 #pragma unroll
-        for (int f = 0; f < 4; ++f) sx[f] = *(const float*)(nx + sxRd + f * 64);
+          for (int f = 0; f < 4; ++f) sx[f] = *(const float*)(nx + sxRd + f * 64);
+        }
+      } else if constexpr (t == 17) {
+        // the registers keep what the prologue read; they are made opaque, so that the block is not hoisted out of the loop
+#pragma unroll
+        for (int f = 0; f < 4; ++f) asm volatile("" : "+v"(xf[f]), "+v"(yf[f]), "+v"(sx[f]), "+v"(sy[f]));
       }
     });
     static_for<0, 16 + 2>([&](auto tc) __attribute__((always_inline)) {
@@ -279,9 +291,9 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       if (!next_landed) wait_vmcnt<Cfg::NDMA>();
       next_landed = false;
-      __builtin_amdgcn_s_barrier();       // ... and everybody's; nobody reads the buffer of this step's block any more
+      if constexpr (!(TIMING & kWgNoBarrier)) __builtin_amdgcn_s_barrier();       // ... and everybody's; nobody reads the buffer of this step's block any more
       asm volatile("" ::: "memory");
-      fetch_next(stage);                  // three steps ahead, into that buffer
+      if constexpr (!(TIMING & kWgNoFetch)) fetch_next(stage);                  // three steps ahead, into that buffer
       const int next_stage = stage == 2 ? 0 : stage + 1;
       block((cur.j0 + s) * 128, cur.lo, cur.hi, lds + next_stage * Cfg::STAGE_BYTES, acc);
       stage = next_stage;
@@ -308,7 +320,9 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
 #pragma unroll
         for (int kf = 0; kf < 4; ++kf) {
           const float v = acc[kf][nf][i];      // (a bit cast of the vector element itself takes element 0)
-          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), dOut, vOut + 64 * kf, ((wn * 64 + 16 * nf + i) * a.K + wk * 64) * 4, kStoreStreaming);
+          if constexpr (TIMING & kWgNoStore) asm volatile("" : : "v"(v));
+          else
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), dOut, vOut + 64 * kf, ((wn * 64 + 16 * nf + i) * a.K + wk * 64) * 4, kStoreStreaming);
         }
     }
   }

@@ -41,7 +41,8 @@ def test_probe_library_exports_what_its_header_declares():
     header = os.path.join(os.path.dirname(HEADER), "gg_probe.h")
     text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
     names = sorted(set(re.findall(r"\b(gg_probe_\w+)\s*\(", text)))
-    assert names == ["gg_probe_gemm_kstep", "gg_probe_hbm", "gg_probe_issue_mix", "gg_probe_lds_fetch", "gg_probe_mfma"]
+    assert names == ["gg_probe_gemm_kstep", "gg_probe_hbm", "gg_probe_issue_mix", "gg_probe_lds_fetch", "gg_probe_mfma",
+                     "gg_probe_wgrad_parts"]
     if not os.path.exists(gg.probe_library_path()):
         gg.build_library()
     probe = gg.load_probe_library()
@@ -60,6 +61,10 @@ def test_probe_library_exports_what_its_header_declares():
     assert probe.gg_probe_gemm_kstep(192, 0, 8, 1024, 4096 + 128, 7168, 1, ctypes.byref(out)) != 0
     assert probe.gg_probe_gemm_kstep(192, 0, 8, 1024, 4096, 256, 1, ctypes.byref(out)) != 0
     assert probe.gg_probe_gemm_kstep(192, 0, 64, 8192, 4096, 7168, 1, ctypes.byref(out)) != 0
+    assert probe.gg_probe_wgrad_parts(5, 8, 1000, 4096, 7168, 1, ctypes.byref(out)) != 0          # a sum that is not built
+    assert probe.gg_probe_wgrad_parts(0, 8, 1000, 4096 + 64, 7168, 1, ctypes.byref(out)) != 0
+    assert probe.gg_probe_wgrad_parts(0, 8, 1000, 4096, 7168 + 128, 1, ctypes.byref(out)) != 0
+    assert probe.gg_probe_wgrad_parts(0, 64, 32, 4096, 7168, 1, ctypes.byref(out)) != 0           # dW beyond 4 GiB
 
 
 def test_version_status_strings_and_variants(lib):
