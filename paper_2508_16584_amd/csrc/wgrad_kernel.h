@@ -23,10 +23,10 @@
 // across tile boundaries (a group of 1000 tokens is 8 blocks: without that, every tile would start with an empty
 // pipeline and end with an idle one).  A wave holds the 4 + 4 operand fragments and the scales of the block it
 // multiplies in registers and refills them from the next block's buffer while it multiplies, and 64 x 64 fp32
-// accumulators; one v_mfma_f32_16x16x128_f8f6f4 from zero per scale block (dY^T fragment first: an output row's 16
-// lanes then hold consecutive features), then acc += p * (sdy * sx) with sdy one of the lane's four dY^T rows and
-// sx the lane's feature: 8 vector instructions per matrix instruction (the factor differs per output element, not
-// per lane as in the forward pass).
+// accumulators; one v_mfma_f32_16x16x128_f8f6f4 from zero per scale block (dY^T fragment first, and the features
+// permuted on their way into LDS: an output row's 16 lanes then hold 32 consecutive features, two each), then
+// acc += p * (sdy * sx) with sdy one of the lane's four dY^T rows and sx the lane's feature: 8 vector instructions
+// per matrix instruction (the factor differs per output element, not per lane as in the forward pass).
 #pragma once
 #include "gemm_kernel.h"
 
@@ -136,10 +136,15 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
   const int lrow = l >> 3, pch = l & 7;
   const int slab_row = w * 8 + lrow;                               // + 64 i
   const int vRow = slab_row * M + ((pch ^ swz_key_a(slab_row)) << 4);   // key(row + 64 i) == key(row)
+  // Features change places on the way into LDS: slot 16 f + r of a wave's 64 features (fragment f, row r) holds
+  // feature 32 (f / 2) + 2 r + f % 2, so that the lane of row r has two neighbouring features in the accumulators of
+  // a fragment pair and the 16 lanes of an output row write 128 consecutive bytes.
+  auto feature_of_slot = [](int s) { return 32 * (s >> 5) + 2 * (s & 15) + ((s >> 4) & 1); };
+  const int vRowX = feature_of_slot(slab_row) * M + ((pch ^ swz_key_a(slab_row)) << 4);
   // scale fetch, one per wave: waves 0..3 the scales of 64 features each, waves 4, 5 those of 64 dY^T rows each,
   // waves 6, 7 an out-of-range offset into a dump area (every wave issues the same number of fetches)
   const bool sx_wave = w < 4, sy_wave = w == 4 || w == 5;
-  const int vS = sx_wave ? (w * 64 + l) * 4 : sy_wave ? ((w - 4) * 64 + l) * 4 : GG_OOB_OFFSET;
+  const int vS = sx_wave ? (w * 64 + feature_of_slot(l)) * 4 : sy_wave ? ((w - 4) * 64 + l) * 4 : GG_OOB_OFFSET;
   const int s_pitch = sx_wave ? a.K * 4 : a.N * 4;                 // bytes from one token block's scales to the next
   const int ldsS = Cfg::X_BYTES + Cfg::Y_BYTES + (sx_wave ? w * 256 : sy_wave ? Cfg::SX_BYTES + (w - 4) * 256 : Cfg::SX_BYTES + Cfg::SY_BYTES);
 
@@ -162,7 +167,7 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
                                              __builtin_amdgcn_readfirstlane(j * s_pitch + (sx_wave ? F.k0 : F.n0) * 4), 0, 0);
 #pragma unroll
     for (int i = 0; i < Cfg::X_ITERS; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(dX, GG_LDS_PTR(st + (w + i * 8) * 1024), 16, in ? vRow + i * 64 * M : GG_OOB_OFFSET, sx_off, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dX, GG_LDS_PTR(st + (w + i * 8) * 1024), 16, in ? vRowX + i * 64 * M : GG_OOB_OFFSET, sx_off, 0, 0);
 #pragma unroll
     for (int i = 0; i < Cfg::Y_ITERS; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(dY, GG_LDS_PTR(st + Cfg::X_BYTES + (w + i * 8) * 1024), 16, in ? vRow + i * 64 * M : GG_OOB_OFFSET, sy_off, 0, 0);
@@ -192,7 +197,7 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
   // One token block out of the registers, while they are refilled from `nx` (the LDS buffer of the following block).
   // Where the block holds tokens before the group's first or from the group's end on (it is the group's first or
   // last block), their bytes are cleared in both operands first.
-  auto block = [&](int first, int lo, int hi, const uint8_t* nx, v4f (&acc)[4][4]) __attribute__((always_inline)) {   // first: the block's first token
+  auto block = [&](int first, int lo, int hi, const uint8_t* nx, v2f (&acc)[2][4][4]) __attribute__((always_inline)) {   // first: the block's first token
     const bool cut_lo = !(TIMING & kWgNoMask) && lo > first, cut_hi = !(TIMING & kWgNoMask) && hi < first + 128;
     if (cut_lo || cut_hi) {
       const int lo4 = 4 * (lo - first - 32 * q), hi4 = 4 * (hi - first - 32 * q);    // valid tokens of the block: [lo - first, hi - first)
@@ -226,7 +231,7 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
       if constexpr (t >= 2) {
         constexpr int u = t - 2, nf = u / 4, kf = u % 4;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) acc[kf][nf][i] += p[u][i] * (sy[nf][i] * sx[kf]);
+        for (int i = 0; i < 4; ++i) acc[kf >> 1][nf][i][kf & 1] += p[u][i] * (sy[nf][i] * sx[kf]);
       }
       if constexpr (!(TIMING & kWgNoLdsReads)) {
         if constexpr (t == 4 || t == 8 || t == 12 || t == 16) yf[t / 4 - 1] = read_frag(nx + yBase + (t / 4 - 1) * 2048);
@@ -254,9 +259,11 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
     __builtin_amdgcn_sched_barrier(0);
     // the accumulators are "used" here, so that every update above lands in the accumulator's own register
 #pragma unroll
-    for (int kf = 0; kf < 4; ++kf)
+    for (int pr = 0; pr < 2; ++pr)
 #pragma unroll
-      for (int nf = 0; nf < 4; ++nf) asm volatile("" : "+v"(acc[kf][nf]));
+      for (int nf = 0; nf < 4; ++nf)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) asm volatile("" : "+v"(acc[pr][nf][i]));
   };
 
   // ---- ring of 3 LDS buffers + the registers: while block b is multiplied out of the registers, block b + 1 has
@@ -275,56 +282,69 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
     sy[f] = *(const v4f*)(lds + syRd + f * 64);
   }
   int stage = 0;            // the buffer the block in the registers came from
-  bool next_landed = false; // this wave's part of the block after the one in the registers is known to have landed
+  int st_prev = 0, st_prev2 = 0;   // batches of 32 stores issued since the last top of a step / between the two before
+  bool top_done = false;           // the top of the coming step has been taken already (at the end of a tile)
+  // The top of a step.  This wave has read all of the block it multiplies next, and its part of the following block
+  // has landed: those fetches were issued two tops ago; newer are the fetches of the last top and the stores of the
+  // tiles finished since, which may all stay in flight (vector memory operations of a wave complete in the order
+  // they were issued; the counter holds 63 and never gets there: no batch of stores begins with more than 31
+  // outstanding and no top's fetches with more than 56, and with two batches and a fetch behind it the awaited fetch
+  // cannot be among 56 outstanding operations).
+  auto top = [&]() __attribute__((always_inline)) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    const int batches = st_prev + st_prev2;
+    if (batches == 0) wait_vmcnt<Cfg::NDMA>();
+    else if (batches == 1) wait_vmcnt<Cfg::NDMA + 32>();
+    else wait_vmcnt<63 - Cfg::NDMA>();          // room for this top's fetches
+    st_prev2 = st_prev;
+    st_prev = 0;
+    if constexpr (!(TIMING & kWgNoBarrier)) __builtin_amdgcn_s_barrier();       // ... and everybody's; nobody reads the buffer of the coming block any more
+    asm volatile("" ::: "memory");
+    if constexpr (!(TIMING & kWgNoFetch)) fetch_next(stage);                  // three steps ahead, into that buffer
+  };
   for (int it = 0;; ++it) {
     const Tile cur = tile_at(it);
     if (!cur.valid) break;
-    v4f acc[4][4];
+    v2f acc[2][4][4];             // [pair of feature fragments][dY^T fragment][row 4 q + i]: two neighbouring features
 #pragma unroll
-    for (int kf = 0; kf < 4; ++kf)
+    for (int pr = 0; pr < 2; ++pr)
 #pragma unroll
-      for (int nf = 0; nf < 4; ++nf) acc[kf][nf] = (v4f){0.f, 0.f, 0.f, 0.f};
+      for (int nf = 0; nf < 4; ++nf)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[pr][nf][i] = (v2f){0.f, 0.f};
     for (int s = 0; s < cur.steps; ++s) {
-      // This wave has read all of the block it multiplies now, and its part of the following block has landed: those
-      // fetches are older than the ones of the block after it, which stay in flight (vector memory operations of a
-      // wave complete in the order they were issued); after a tile's epilogue that wait has been taken there.
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      if (!next_landed) wait_vmcnt<Cfg::NDMA>();
-      next_landed = false;
-      if constexpr (!(TIMING & kWgNoBarrier)) __builtin_amdgcn_s_barrier();       // ... and everybody's; nobody reads the buffer of this step's block any more
-      asm volatile("" ::: "memory");
-      if constexpr (!(TIMING & kWgNoFetch)) fetch_next(stage);                  // three steps ahead, into that buffer
+      if (!top_done) top();
+      top_done = false;
       const int next_stage = stage == 2 ? 0 : stage + 1;
       block((cur.j0 + s) * 128, cur.lo, cur.hi, lds + next_stage * Cfg::STAGE_BYTES, acc);
       stage = next_stage;
     }
-    // ---- epilogue: fp32 through a view of the tile, one register at a time: the 16 lanes of a dY^T row write 64
-    // consecutive bytes (with 16 bytes per lane, neighbouring lanes would write to different rows and every lane's
-    // piece would be a request of its own: a quarter of the store rate).  Written once and never read here, so the
-    // stores carry the streaming cache policy (sc0 sc1 nt): the gradients do not push the operand tiles out of the
-    // L2 and the fetches beside them keep their latency.  The counter of outstanding vector memory operations
-    // holds 63: no more than 24 are outstanding when a batch of 32 stores begins.
-    const __amdgpu_buffer_rsrc_t dOut = __builtin_amdgcn_make_buffer_rsrc((void*)(a.dW + ((int64_t)cur.g * a.N + cur.n0) * a.K + cur.k0), 0, ((Cfg::TN - 1) * a.K + Cfg::TK) * 4, GG_RSRC_FLAGS);
-    const int vOut = (4 * q * a.K + r) * 4;
-    if (next_landed) {
-      wait_vmcnt<24>();
-    } else {
-      wait_vmcnt<Cfg::NDMA>();
-      next_landed = true;
+    // ---- epilogue: fp32 through a view of the tile, 8 bytes per lane: the 16 lanes of a dY^T row write 128
+    // consecutive bytes (with the features in a lane's registers and 16 bytes per lane, neighbouring lanes would write
+    // to different rows and every lane's piece would be a request of its own: a quarter of the store rate).  Written
+    // once and never read here, so the stores carry the streaming cache policy (sc0 sc1 nt): the gradients do not
+    // push the operand tiles out of the L2 and the fetches beside them keep their latency.  The top of the step that
+    // follows is taken first: its fetch and the one before are then older than the stores, and no wait covers the
+    // stores before the fourth step from here.
+    if (!top_done) {
+      top();
+      top_done = true;
     }
+    const __amdgpu_buffer_rsrc_t dOut = __builtin_amdgcn_make_buffer_rsrc((void*)(a.dW + ((int64_t)cur.g * a.N + cur.n0) * a.K + cur.k0), 0, ((Cfg::TN - 1) * a.K + Cfg::TK) * 4, GG_RSRC_FLAGS);
+    const int vOut = (4 * q * a.K + 2 * r) * 4;
+    wait_vmcnt<31>();
 #pragma unroll
-    for (int nf = 0; nf < 4; ++nf) {
-      if (nf == 2) wait_vmcnt<24>();
+    for (int nf = 0; nf < 4; ++nf)
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int kf = 0; kf < 4; ++kf) {
-          const float v = acc[kf][nf][i];      // (a bit cast of the vector element itself takes element 0)
+        for (int pr = 0; pr < 2; ++pr) {
+          const v2f v = acc[pr][nf][i];
           if constexpr (TIMING & kWgNoStore) asm volatile("" : : "v"(v));
           else
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), dOut, vOut + 64 * kf, ((wn * 64 + 16 * nf + i) * a.K + wk * 64) * 4, kStoreStreaming);
+            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(v2i, v), dOut, vOut + 128 * pr, ((wn * 64 + 16 * nf + i) * a.K + wk * 64) * 4, kStoreStreaming);
         }
-    }
+    ++st_prev;
   }
   wait_vmcnt<0>();     // the fetches past the last block still write zeros into this workgroup's LDS: let them land
 }
