@@ -153,7 +153,12 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
   // workgroup's next tile are in flight while the current one is finished and stored.
   Tile F = tile_at(0);
   int itF = 0, sF = 0;
-  auto fetch_next = [&](int stage) __attribute__((always_inline)) {
+  // A block's fetches are prepared at the top of a step (the cursor moves on, the scalar offsets are formed) and
+  // issued one at a time between the matrix instructions of the step: issued together, the eight waves' 56 fetches
+  // wait for the address unit one behind the other, and a wave that waits there issues no matrix instruction.
+  int f_x_off = 0, f_y_off = 0, f_s_off = 0;     // scalar offsets of the prepared block: XT, DYT, scales
+  int vXsel = GG_OOB_OFFSET, vYsel = GG_OOB_OFFSET, vSsel = GG_OOB_OFFSET;   // lane offsets, out of range when no tile is left
+  auto fetch_prepare = [&]() __attribute__((always_inline)) {
     while (F.valid && sF >= F.steps) {
       ++itF;
       F = tile_at(itF);
@@ -161,17 +166,31 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
     }
     const bool in = F.valid;
     const int j = F.j0 + sF;
-    const int sx_off = __builtin_amdgcn_readfirstlane(j * 128 + F.k0 * M), sy_off = __builtin_amdgcn_readfirstlane(j * 128 + F.n0 * M);
-    uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(sx_wave ? dSX : dSY, GG_LDS_PTR(st + ldsS), 4, in ? vS : GG_OOB_OFFSET,
-                                             __builtin_amdgcn_readfirstlane(j * s_pitch + (sx_wave ? F.k0 : F.n0) * 4), 0, 0);
-#pragma unroll
-    for (int i = 0; i < Cfg::X_ITERS; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(dX, GG_LDS_PTR(st + (w + i * 8) * 1024), 16, in ? vRowX + i * 64 * M : GG_OOB_OFFSET, sx_off, 0, 0);
-#pragma unroll
-    for (int i = 0; i < Cfg::Y_ITERS; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(dY, GG_LDS_PTR(st + Cfg::X_BYTES + (w + i * 8) * 1024), 16, in ? vRow + i * 64 * M : GG_OOB_OFFSET, sy_off, 0, 0);
+    f_x_off = __builtin_amdgcn_readfirstlane(j * 128 + F.k0 * M);
+    f_y_off = __builtin_amdgcn_readfirstlane(j * 128 + F.n0 * M);
+    f_s_off = __builtin_amdgcn_readfirstlane(j * s_pitch + (sx_wave ? F.k0 : F.n0) * 4);
+    vXsel = in ? vRowX : GG_OOB_OFFSET;
+    vYsel = in ? vRow : GG_OOB_OFFSET;
+    vSsel = in ? vS : GG_OOB_OFFSET;
     ++sF;
+  };
+  // piece 0: the wave's scales; 1 .. X_ITERS: its slabs of the X tile; the rest: its slabs of the dY^T tile
+  auto fetch_piece = [&](auto ic, uint8_t* st) __attribute__((always_inline)) {
+    constexpr int I = decltype(ic)::value;
+    if constexpr (I == 0) {
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(sx_wave ? dSX : dSY, GG_LDS_PTR(st + ldsS), 4, vSsel, f_s_off, 0, 0);
+    } else if constexpr (I <= Cfg::X_ITERS) {
+      constexpr int i = I - 1;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dX, GG_LDS_PTR(st + (w + i * 8) * 1024), 16, vXsel, f_x_off + i * 64 * M, 0, 0);
+    } else {
+      constexpr int i = I - 1 - Cfg::X_ITERS;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dY, GG_LDS_PTR(st + Cfg::X_BYTES + (w + i * 8) * 1024), 16, vYsel, f_y_off + i * 64 * M, 0, 0);
+    }
+  };
+  auto fetch_next = [&](int stage) __attribute__((always_inline)) {     // all of a block at once (the prologue)
+    fetch_prepare();
+    uint8_t* st = lds + stage * Cfg::STAGE_BYTES;
+    static_for<0, Cfg::NDMA>([&](auto ic) __attribute__((always_inline)) { fetch_piece(ic, st); });
   };
 
   // ---- operand reads: fragment row r, chunks 2q and 2q+1
@@ -197,7 +216,7 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
   // One token block out of the registers, while they are refilled from `nx` (the LDS buffer of the following block).
   // Where the block holds tokens before the group's first or from the group's end on (it is the group's first or
   // last block), their bytes are cleared in both operands first.
-  auto block = [&](int first, int lo, int hi, const uint8_t* nx, v2f (&acc)[2][4][4]) __attribute__((always_inline)) {   // first: the block's first token
+  auto block = [&](int first, int lo, int hi, const uint8_t* nx, uint8_t* fst, v2f (&acc)[2][4][4]) __attribute__((always_inline)) {   // first: the block's first token; fst: the buffer the prepared fetches go to
     const bool cut_lo = !(TIMING & kWgNoMask) && lo > first, cut_hi = !(TIMING & kWgNoMask) && hi < first + 128;
     if (cut_lo || cut_hi) {
       const int lo4 = 4 * (lo - first - 32 * q), hi4 = 4 * (hi - first - 32 * q);    // valid tokens of the block: [lo - first, hi - first)
@@ -233,6 +252,7 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
 #pragma unroll
         for (int i = 0; i < 4; ++i) acc[kf >> 1][nf][i][kf & 1] += p[u][i] * (sy[nf][i] * sx[kf]);
       }
+      if constexpr (!(TIMING & kWgNoFetch) && t % 2 == 1 && t / 2 < Cfg::NDMA) fetch_piece(std::integral_constant<int, t / 2>{}, fst);
       if constexpr (!(TIMING & kWgNoLdsReads)) {
         if constexpr (t == 4 || t == 8 || t == 12 || t == 16) yf[t / 4 - 1] = read_frag(nx + yBase + (t / 4 - 1) * 2048);
         if constexpr (t >= 13 && t <= 16) xf[t - 13] = read_frag(nx + xBase + (t - 13) * 2048);
@@ -252,6 +272,7 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
       constexpr int t = decltype(tc)::value;
       if constexpr (t < 16) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       if constexpr (t >= 2) __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+      if constexpr (!(TIMING & kWgNoFetch) && t % 2 == 1 && t / 2 < Cfg::NDMA) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
       constexpr int reads = (t == 4 || t == 8 || t == 12 ? 2 : 0) + (t >= 13 && t <= 15 ? 2 : 0) + (t == 16 ? 4 : 0) +
                             (t == 6 || t == 10 || t == 14 ? 1 : 0) + (t == 17 ? 5 : 0);
       if constexpr (reads > 0) __builtin_amdgcn_sched_group_barrier(0x100, reads, 0);
@@ -283,24 +304,23 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
   }
   int stage = 0;            // the buffer the block in the registers came from
   int st_prev = 0, st_prev2 = 0;   // batches of 32 stores issued since the last top of a step / between the two before
-  bool top_done = false;           // the top of the coming step has been taken already (at the end of a tile)
   // The top of a step.  This wave has read all of the block it multiplies next, and its part of the following block
-  // has landed: those fetches were issued two tops ago; newer are the fetches of the last top and the stores of the
-  // tiles finished since, which may all stay in flight (vector memory operations of a wave complete in the order
+  // has landed: those fetches were issued two steps ago; newer are the fetches of the last step and the stores of
+  // the tiles finished since, which may all stay in flight (vector memory operations of a wave complete in the order
   // they were issued; the counter holds 63 and never gets there: no batch of stores begins with more than 31
-  // outstanding and no top's fetches with more than 56, and with two batches and a fetch behind it the awaited fetch
+  // outstanding and no step's fetches with more than 56, and with two batches and a fetch behind it the awaited fetch
   // cannot be among 56 outstanding operations).
   auto top = [&]() __attribute__((always_inline)) {
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     const int batches = st_prev + st_prev2;
     if (batches == 0) wait_vmcnt<Cfg::NDMA>();
     else if (batches == 1) wait_vmcnt<Cfg::NDMA + 32>();
-    else wait_vmcnt<63 - Cfg::NDMA>();          // room for this top's fetches
+    else wait_vmcnt<63 - Cfg::NDMA>();          // room for this step's fetches
     st_prev2 = st_prev;
     st_prev = 0;
     if constexpr (!(TIMING & kWgNoBarrier)) __builtin_amdgcn_s_barrier();       // ... and everybody's; nobody reads the buffer of the coming block any more
     asm volatile("" ::: "memory");
-    if constexpr (!(TIMING & kWgNoFetch)) fetch_next(stage);                  // three steps ahead, into that buffer
+    if constexpr (!(TIMING & kWgNoFetch)) fetch_prepare();                    // three steps ahead, into that buffer
   };
   for (int it = 0;; ++it) {
     const Tile cur = tile_at(it);
@@ -313,23 +333,16 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
 #pragma unroll
         for (int i = 0; i < 4; ++i) acc[pr][nf][i] = (v2f){0.f, 0.f};
     for (int s = 0; s < cur.steps; ++s) {
-      if (!top_done) top();
-      top_done = false;
+      top();
       const int next_stage = stage == 2 ? 0 : stage + 1;
-      block((cur.j0 + s) * 128, cur.lo, cur.hi, lds + next_stage * Cfg::STAGE_BYTES, acc);
+      block((cur.j0 + s) * 128, cur.lo, cur.hi, lds + next_stage * Cfg::STAGE_BYTES, lds + stage * Cfg::STAGE_BYTES, acc);
       stage = next_stage;
     }
     // ---- epilogue: fp32 through a view of the tile, 8 bytes per lane: the 16 lanes of a dY^T row write 128
     // consecutive bytes (with the features in a lane's registers and 16 bytes per lane, neighbouring lanes would write
     // to different rows and every lane's piece would be a request of its own: a quarter of the store rate).  Written
     // once and never read here, so the stores carry the streaming cache policy (sc0 sc1 nt): the gradients do not
-    // push the operand tiles out of the L2 and the fetches beside them keep their latency.  The top of the step that
-    // follows is taken first: its fetch and the one before are then older than the stores, and no wait covers the
-    // stores before the fourth step from here.
-    if (!top_done) {
-      top();
-      top_done = true;
-    }
+    // push the operand tiles out of the L2 and the fetches beside them keep their latency.
     const __amdgpu_buffer_rsrc_t dOut = __builtin_amdgcn_make_buffer_rsrc((void*)(a.dW + ((int64_t)cur.g * a.N + cur.n0) * a.K + cur.k0), 0, ((Cfg::TN - 1) * a.K + Cfg::TK) * 4, GG_RSRC_FLAGS);
     const int vOut = (4 * q * a.K + 2 * r) * 4;
     wait_vmcnt<31>();
