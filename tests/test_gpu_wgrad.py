@@ -88,6 +88,27 @@ def test_wgrad_several_tiles_quantised_data_and_unowned_tokens():
     assert np.all(got[0] == 0)
 
 
+def test_wgrad_blocked_tile_list_every_element():
+    """4 k tiles x 8 n tiles: the tile list runs in blocks of 4 x 8 (the order the full-size layers take); every
+    element of every group against the oracle, with a group that ends on a block boundary, one inside a single block
+    and an empty one."""
+    rng = np.random.default_rng(36)
+    M_total, N, K = 912, 1024, 1024
+    off = [5, 5, 256, 300, 901]                                             # [5,5) empty, [5,256) ends on a boundary, [256,300) inside one block
+    XT, SX = quantised_normal(rng, K, M_total)
+    DYT, SDY = quantised_normal(rng, N, M_total, std=0.02)
+    ref = orc.grouped_gemm_wgrad(XT, SX, DYT, SDY, off, with_abs_sum=True)
+    got = run_gpu(XT, SX, DYT, SDY, off)
+    assert_wgrad_parity(got, ref, 2.0 ** -13, "blocked tile list")
+    assert np.all(got[0] == 0)
+    # the same problem with exact inputs: bit-equal, so a tile written to the wrong place cannot hide in the tolerance
+    codes = np.array([0x00, 0x38, 0x40, 0x44, 0xB8, 0xC0], np.uint8)
+    XTe, DYTe = codes[rng.integers(0, 6, (K, M_total))], codes[rng.integers(0, 6, (N, M_total))]
+    SXe = (2.0 ** rng.integers(-3, 4, SX.shape)).astype(np.float32)
+    SDYe = (2.0 ** rng.integers(-3, 4, SDY.shape)).astype(np.float32)
+    assert np.array_equal(run_gpu(XTe, SXe, DYTe, SDYe, off), orc.grouped_gemm_wgrad(XTe, SXe, DYTe, SDYe, off)["W"])
+
+
 def test_wgrad_exact_where_every_intermediate_is_exact():
     rng = np.random.default_rng(33)
     M_total, N, K = 1024 + 48, 128, 256
