@@ -30,8 +30,10 @@ Every function here is pinned by tests/test_oracle_pins.py (exact rational
 brute force, closed forms, the paper's worked example, the padded == unpadded
 invariant of Sec. 3.2; the encoder and the row quantiser at the end of the file
 against the library's float8 cast, round trips through the decode table and
-hand-made ties; the activation against the library's silu and closed forms).  One function is "parity unpinned" against the
-paper: grouped_gemm_wgrad, whose definition the paper does not give (see the comment above it).
+hand-made ties; the activation against the library's silu and closed forms).  Two functions are "parity unpinned"
+against the paper, which does not define them: grouped_gemm_wgrad (see the comment above it; pinned by
+tests/test_oracle_wgrad_pins.py to the mathematics of its definition) and quantize_cols, the producer of its
+operands (pinned there to quantize_rows, the same recipe on the transposed matrix).
 """
 from __future__ import annotations
 
@@ -469,6 +471,46 @@ def quantize_rows(X_bf16_bits: np.ndarray, row_src=None, M_total=None):
     A[ok] = e4m3_encode_rne(y).reshape(-1, K)
     SA[ok] = scale
     return A, SA
+
+
+def quantize_cols(X_bf16_bits: np.ndarray, row_src=None, M_total=None):
+    """Producer of the operands of grouped_gemm_wgrad: the quantiser of quantize_rows applied ALONG THE TOKENS.
+    Token r of the output is input row row_src[r] (identity if None); feature k of it goes to XT[k][r], and the
+    1x128 blocks of Sec. 2.1 run along r: block j of feature k holds tokens [128 j, 128 j + 128) of the output order
+    (whatever the groups are), the last block those that exist.  Per block the recipe of quantize_rows, in float32:
+
+        amax  = max( max |x| over the block's tokens with NaNs skipped, 2^-100 )
+        scale = amax / 448,  inv = 448 / amax,  byte = e4m3_encode_rne( clamp(x * inv, -448, 448) ), NaN -> 0x7F
+
+    A source index outside [0, T) stands for a row of zeros.  The paper defines neither this operation nor its
+    layouts (PARITY UNPINNED AGAINST THE PAPER, like grouped_gemm_wgrad); it is pinned to quantize_rows, which is
+    the same recipe on the transposed matrix.
+    Returns (uint8 [K, M_total], float32 [ceil(M_total / 128), K]).
+    """
+    Xb = np.asarray(X_bf16_bits)
+    assert Xb.dtype == np.uint16 and Xb.ndim == 2
+    T, K = Xb.shape
+    if row_src is None:
+        row_src = np.arange(T if M_total is None else M_total, dtype=np.int64)
+    row_src = np.asarray(row_src, dtype=np.int64)
+    M = row_src.shape[0]
+    MB = -(-M // SCALE_BLOCK)
+    ok = (row_src >= 0) & (row_src < T)
+    x = np.zeros((M, K), dtype=np.float32)
+    x[ok] = (Xb[row_src[ok]].astype(np.uint32) << 16).view(np.float32)
+    XT = np.zeros((K, M), dtype=np.uint8)
+    SX = np.empty((MB, K), dtype=np.float32)
+    for j in range(MB):
+        blk = x[j * SCALE_BLOCK:(j + 1) * SCALE_BLOCK]               # [tokens of the block, K]
+        with np.errstate(invalid="ignore", divide="ignore", over="ignore"):
+            amax = np.nan_to_num(np.abs(blk), nan=0.0, posinf=np.inf).max(axis=0).astype(np.float32)
+            amax = np.maximum(amax, np.float32(AMAX_FLOOR))
+            SX[j] = (amax / np.float32(E4M3_MAX)).astype(np.float32)
+            inv = (np.float32(E4M3_MAX) / amax).astype(np.float32)
+            y = (blk * inv[None, :]).astype(np.float32)
+            y = np.where(np.isnan(y), y, np.clip(y, -E4M3_MAX, E4M3_MAX)).astype(np.float32)
+        XT[:, j * SCALE_BLOCK:j * SCALE_BLOCK + blk.shape[0]] = e4m3_encode_rne(y).T
+    return XT, SX
 
 
 def swiglu_rows(H_bf16_bits: np.ndarray) -> np.ndarray:

@@ -128,3 +128,44 @@ def test_wgrad_tokens_outside_a_group_do_not_matter_not_even_nan_codes():
     mask = np.ones_like(d, bool)
     mask[2, :, 1] = False
     assert np.array_equal(d[mask], base[mask])
+
+
+def bf16_bits(x):
+    return (torch.from_numpy(np.asarray(x, np.float32)).to(torch.bfloat16).view(torch.int16).numpy().astype(np.int32) & 0xFFFF).astype(np.uint16)
+
+
+def test_quantize_cols_is_quantize_rows_on_the_transposed_matrix():
+    """Whole token blocks: feature k's blocks along the tokens are the blocks of row k of X^T, so the (pinned) row
+    quantiser on the transposed, gathered matrix must give the same bytes and the same scales, bit for bit."""
+    rng = np.random.default_rng(21)
+    T, K, M = 300, 24, 256
+    X = bf16_bits(rng.standard_normal((T, K)) * np.exp(rng.uniform(-6, 6, (T, 1))))
+    X[7, 3], X[9, 5], X[200, 0] = 0x7FC0, 0x7F80, 0xFF80                 # a NaN and two infinities
+    row_src = rng.integers(-2, T + 2, M)                                  # some indices outside [0, T): rows of zeros
+    XT, SX = orc.quantize_cols(X, row_src)
+    gathered = np.zeros((M, K), np.uint16)
+    ok = (row_src >= 0) & (row_src < T)
+    gathered[ok] = X[row_src[ok]]
+    A, SA = orc.quantize_rows(np.ascontiguousarray(gathered.T))           # [K, M], [K, M / 128]
+    assert XT.shape == (K, M) and SX.shape == (2, K)
+    assert np.array_equal(XT, A) and np.array_equal(SX, SA.T)
+
+
+def test_quantize_cols_partial_last_block_and_closed_form():
+    rng = np.random.default_rng(22)
+    T, K = 200, 8                                                          # 128 + 72 tokens
+    X = bf16_bits(rng.standard_normal((T, K)))
+    XT, SX = orc.quantize_cols(X)
+    # the last block sees its 72 tokens only: the same as a whole block whose other 56 tokens are zeros
+    Xz = np.zeros((256, K), np.uint16)
+    Xz[:T] = X
+    XTz, SXz = orc.quantize_cols(Xz)
+    assert XT.shape == (K, T) and np.array_equal(XT, XTz[:, :T]) and np.array_equal(SX, SXz)
+    assert np.all(XTz[:, T:] == 0)
+    # e4m3 values times a power of two per feature come back as their codes, with scale 2^e * max|value| / 448
+    codes = rng.integers(1, 0x7F, (128, K)).astype(np.uint8)
+    codes[0] = 0x7E                                                        # every feature holds 448
+    e = rng.integers(-5, 6, K)
+    vals = orc.e4m3_decode(codes) * 2.0 ** e[None, :]
+    XTc, SXc = orc.quantize_cols(bf16_bits(vals))
+    assert np.array_equal(XTc, codes.T) and np.array_equal(SXc[0], (2.0 ** e).astype(np.float32))
