@@ -122,7 +122,9 @@ def bench_quantize_rows(args, cfg, dev):
     """quantize_rows: bf16 activations [M_total, K] of the workload -> e4m3 + 1x128 scales, gathered by a routing
     permutation (2K bytes read, K + 4K/128 written per row, plus 4 bytes of index).
     swiglu_quantize_rows: the workload's GEMM output [M_total, N] bf16 (gate | up) -> e4m3 [M_total, N/2] + scales
-    (2N bytes read, N/2 + 4(N/2)/128 written per row).  Both are HBM-bound."""
+    (2N bytes read, N/2 + 4(N/2)/128 written per row).
+    quantize_cols: the same activations -> XT [K, M_total] e4m3 + [M_total/128, K] scales, quantised along the tokens
+    and transposed (the producer of the weight-gradient GEMM's operands; the same bytes per row).  All HBM-bound."""
     import numpy as np
     import torch
 
@@ -130,7 +132,8 @@ def bench_quantize_rows(args, cfg, dev):
     from workloads import group_sizes
 
     fused = args.op == "swiglu_quantize_rows"
-    km = args.sa_layout == "kmajor"
+    cols = args.op == "quantize_cols"
+    km = args.sa_layout == "kmajor" and not cols
     sizes = group_sizes(cfg, cfg.seed)
     M = int(np.sum(sizes))
     width_in = cfg.N if fused else cfg.K                      # columns of the bf16 input
@@ -144,6 +147,10 @@ def bench_quantize_rows(args, cfg, dev):
     for _ in range(copies):
         X = (torch.randn((M, width_in), generator=gen, device=dev, dtype=torch.float32) * (1.7 if fused else 1.0)).to(torch.bfloat16)
         src = None if fused else torch.from_numpy(rng.permutation(M).astype(np.int32)).to(dev)
+        if cols:
+            sets.append((X, src, torch.empty((width_out, M), dtype=torch.uint8, device=dev),
+                         torch.empty(((M + 127) // 128, width_out), dtype=torch.float32, device=dev)))
+            continue
         sets.append((X, src, torch.empty((M, width_out), dtype=torch.uint8, device=dev),
                      torch.empty((width_out // 128, M) if km else (M, width_out // 128), dtype=torch.float32, device=dev)))
 
@@ -151,6 +158,8 @@ def bench_quantize_rows(args, cfg, dev):
         X, src, A, SA = sets[i % copies]
         if fused:
             gg.swiglu_quantize_rows(X, A=A, SA=SA, sa_kmajor=km)
+        elif cols:
+            gg.quantize_cols(X, src, XT=A, SX=SA)
         else:
             gg.quantize_rows(X, src, A=A, SA=SA, sa_kmajor=km)
 
@@ -163,10 +172,11 @@ def bench_quantize_rows(args, cfg, dev):
     if args.copy_calibration:
         copy_calibration(dev)
     achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
-    kname = "gg_swiglu_quantize_rows_kernel" if fused else "gg_quantize_rows_kernel"
+    kname = "gg_swiglu_quantize_rows_kernel" if fused else "gg_quantize_cols_kernel" if cols else "gg_quantize_rows_kernel"
     traffic = profiled_traffic(args.op, args.workload, args.sa_layout, kname)
     out = {
         "metric": "algorithmic GB/s, " + ("bf16 gate|up rows -> silu(gate)*up -> e4m3 + 1x128 scales" if fused else
+                                          "bf16 rows -> e4m3 [K, M_total] + scales per 128 tokens, gathered into group order and transposed" if cols else
                                           "bf16 rows -> e4m3 + 1x128 scales gathered into group order"),
         "value": round(alg_bytes / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
@@ -174,7 +184,7 @@ def bench_quantize_rows(args, cfg, dev):
         "config": {"workload": args.workload + (" output" if fused else " activations"), "op": args.op, "M_total": M,
                    "columns_in": width_in, "columns_out": width_out, "input_copies_rotated": copies,
                    "clock_warmup_launches": n_ramp,
-                   "sa_layout": "K-block-major [K/128, M_total]" if km else "row-major [M_total, K/128]"},
+                   "sa_layout": "block-major [M_total/128, K]" if cols else "K-block-major [K/128, M_total]" if km else "row-major [M_total, K/128]"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "traffic_source": TRAFFIC_SOURCE if traffic is not None else None, "kernel": kname,
@@ -188,15 +198,24 @@ def bench_quantize_rows(args, cfg, dev):
         rows = np.arange(0, M, max(1, M // 4096))[:4096]
         xb = X.view(torch.int16).cpu().numpy().view(np.uint16)
         t0 = time.perf_counter()
-        if fused:
+        if cols:
+            feats = np.arange(0, width_out, max(1, width_out // 1024))[:1024]        # features are independent of each other
+            rows = np.arange(M)
+            A_ref, SA_ref = gg_oracle.quantize_cols(np.ascontiguousarray(xb[:, feats]), src.cpu().numpy())
+        elif fused:
             _, A_ref, SA_ref = gg_oracle.swiglu_quantize_rows(xb[rows])
         else:
             A_ref, SA_ref = gg_oracle.quantize_rows(xb, src.cpu().numpy()[rows])
         cpu_s = time.perf_counter() - t0
-        same = float(np.mean(A.cpu().numpy()[rows] == A_ref))
-        out["cpu_baseline"] = {"value": round(len(rows) * alg_bytes / M / cpu_s / 1e9, 4), "unit": "GB/s",
+        if cols:
+            same = float(np.mean(A.cpu().numpy()[feats] == A_ref))
+            assert same == 1.0 and np.array_equal(SA.cpu().numpy()[:, feats], SA_ref), "bench.py --op quantize_cols: GPU output differs from the oracle on the sample"
+            rows = feats             # for the sample's description below
+        else:
+            same = float(np.mean(A.cpu().numpy()[rows] == A_ref))
+        out["cpu_baseline"] = {"value": round(len(rows) / (width_out if cols else M) * alg_bytes / cpu_s / 1e9, 4), "unit": "GB/s",
                                "cores": 1, "kind": "oracle",
-                               "sample": f"{len(rows)} of the {M} output rows, NumPy oracle, {cpu_s:.1f} s",
+                               "sample": (f"{len(rows)} of the {width_out} features, all tokens" if cols else f"{len(rows)} of the {M} output rows") + f", NumPy oracle, {cpu_s:.1f} s",
                                "gpu_bytes_equal_oracle_on_sample": round(same, 6)}
     print(json.dumps(out))
 
@@ -565,7 +584,7 @@ def main():
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="gate_up")
-    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows", "swiglu_quantize_rows", "expert_mlp", "ceilings", "pad_path", "kstep_parts", "wgrad", "wgrad_parts"],
+    ap.add_argument("--op", default="grouped_gemm", choices=["grouped_gemm", "quantize_rows", "swiglu_quantize_rows", "quantize_cols", "expert_mlp", "ceilings", "pad_path", "kstep_parts", "wgrad", "wgrad_parts"],
                     help="grouped_gemm: the hot path (default, the headline metric); quantize_rows: the producer of its "
                          "A operand on the same workload's activation shape; swiglu_quantize_rows: activation + quantiser "
                          "on the workload's output shape [M_total, N] (N = 2 x intermediate width); expert_mlp: the whole forward "
@@ -626,7 +645,7 @@ def main():
     if args.op == "wgrad":
         bench_wgrad(args, cfg, dev)
         return
-    if args.op in ("quantize_rows", "swiglu_quantize_rows"):
+    if args.op in ("quantize_rows", "swiglu_quantize_rows", "quantize_cols"):
         bench_quantize_rows(args, cfg, dev)
         return
     if args.op == "expert_mlp":

@@ -182,6 +182,20 @@ int gg_fp8_grouped_gemm_swiglu(const void* A, const float* SA, const void* B, co
 int gg_fp8_grouped_gemm_wgrad(const void* XT, const float* SX, const void* DYT, const float* SDY,
                               const int32_t* group_offsets, float* dW, int G, int64_t M_total, int N, int K, void* stream);
 
+/* The producer of gg_fp8_grouped_gemm_wgrad's operands: the block quantiser of gg_fp8_quantize_rows (the 1x128
+ * scaling stated below Table 1 of the paper) applied ALONG THE TOKENS, with the transpose that call wants.  The paper
+ * defines neither the operation nor its layouts (Sec. 4 only names the kernels around the grouped GEMM).
+ *   X        device, bf16 [T, K], token-major (an activation or an output-gradient tensor as the forward pass holds it)
+ *   row_src  device, int32 [M_total]: output token r is row row_src[r] of X (the routing permutation); an index
+ *            outside [0, T) stands for a row of zeros; NULL = identity
+ *   XT       device, out, e4m3 bytes [K, M_total]: XT[k][r] = quantised X[row_src[r]][k]
+ *   SX       device, out, fp32 [ceil(M_total / 128), K], block-major: SX[j][k] scales tokens [128 j, 128 j + 128) of
+ *            feature k (the last block: the tokens that exist); amax, scale and rounding as in gg_fp8_quantize_rows
+ * K a multiple of 64 and M_total a multiple of 16 (GG_ERR_UNSUPPORTED otherwise).  Bytes and scales are reproducible
+ * bit for bit on the host.  XT 16-byte aligned.  Nothing is allocated; asynchronous on `stream`. */
+int gg_fp8_quantize_cols(const void* X, const int32_t* row_src, void* XT, float* SX, int64_t T, int64_t M_total, int K,
+                         void* stream);
+
 /* ---- the pad-then-GEMM comparison path (the baseline of Sec. 3) ------------
  * Every group is copied to an offset that is a multiple of 128 rows, pad rows
  * are zero, the same GEMM kernels run on the aligned problem, and the valid

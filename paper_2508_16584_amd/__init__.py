@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     noalloc_max_elements,
     grouped_gemm_swiglu,
     grouped_gemm_wgrad,
+    quantize_cols,
     library_path,
     load_library,
     load_probe_library,

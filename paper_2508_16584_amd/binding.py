@@ -170,6 +170,8 @@ def load_library() -> ctypes.CDLL:
     lib.gg_fp8_grouped_gemm_swiglu.restype = i32
     lib.gg_fp8_grouped_gemm_wgrad.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp]
     lib.gg_fp8_grouped_gemm_wgrad.restype = i32
+    lib.gg_fp8_quantize_cols.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp]
+    lib.gg_fp8_quantize_cols.restype = i32
     lib.gg_fp8_pad_ex.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i64, i32, vp, ctypes.c_uint]
     lib.gg_fp8_pad_ex.restype = i32
     lib.gg_fp8_quantize_rows_ex.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, ctypes.c_uint]
@@ -206,7 +208,7 @@ EXPORTED_SYMBOLS = [
     "gg_fp8_grouped_gemm_variant", "gg_fp8_grouped_gemm_f16", "gg_fp8_grouped_gemm_ex", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_auto_variant", "gg_fp8_auto_variant_padded", "gg_fp8_padded_rows_cap",
     "gg_fp8_pad", "gg_fp8_grouped_gemm_padded", "gg_fp8_unpad", "gg_fp8_quantize_rows", "gg_fp8_swiglu_quantize_rows", "gg_fp8_check_offsets",
     "gg_fp8_grouped_gemm_splitk_noalloc", "gg_fp8_noalloc_max_elements", "gg_fp8_pad_ex", "gg_fp8_quantize_rows_ex", "gg_fp8_swiglu_quantize_rows_ex", "gg_fp8_grouped_gemm_swiglu",
-    "gg_fp8_grouped_gemm_wgrad",
+    "gg_fp8_grouped_gemm_wgrad", "gg_fp8_quantize_cols",
 ]
 
 
@@ -433,6 +435,31 @@ def grouped_gemm_wgrad(XT, SX, DYT, SDY, group_offsets, dW=None, stream=None):
     _check(lib.gg_fp8_grouped_gemm_wgrad(_ptr(XT), _ptr(SX), _ptr(DYT), _ptr(SDY), _ptr(group_offsets), _ptr(dW),
                                          G, M_total, N, K, _stream(stream)))
     return dW
+
+
+def quantize_cols(X, row_src=None, M_total=None, XT=None, SX=None, stream=None):
+    """gg_fp8_quantize_cols: X [T, K] bf16 -> (XT uint8 [K, M_total], SX float32 [ceil(M_total/128), K]): the block
+    quantiser along the tokens, transposed; output token r is input row row_src[r] (int32 [M_total] on the device;
+    None = identity)."""
+    lib = load_library()
+    _want(X, "X", torch.bfloat16, 2)
+    T, K = X.shape
+    if row_src is not None:
+        _want(row_src, "row_src", torch.int32, 1)
+        M_total = row_src.shape[0]
+    elif M_total is None:
+        M_total = T
+    MB = (M_total + 127) // 128
+    if XT is None:
+        XT = torch.empty((K, M_total), dtype=torch.uint8, device=X.device)
+    if SX is None:
+        SX = torch.empty((MB, K), dtype=torch.float32, device=X.device)
+    _want(XT, "XT", torch.uint8, 2)
+    _want(SX, "SX", torch.float32, 2)
+    if tuple(XT.shape) != (K, M_total) or tuple(SX.shape) != (MB, K):
+        raise ValueError("XT or SX does not have the shape of the output")
+    _check(lib.gg_fp8_quantize_cols(_ptr(X), _ptr(row_src), _ptr(XT), _ptr(SX), T, M_total, K, _stream(stream)))
+    return XT, SX
 
 
 def padded_rows_cap(G: int, M_total: int) -> int:

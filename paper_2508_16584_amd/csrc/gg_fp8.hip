@@ -654,6 +654,24 @@ int gg_fp8_swiglu_quantize_rows(const void* H, void* A, float* SA, void* act_out
   return gg_fp8_swiglu_quantize_rows_ex(H, A, SA, act_out, M_total, I, stream, 0);
 }
 
+int gg_fp8_quantize_cols(const void* X, const int32_t* row_src, void* XT, float* SX, int64_t T, int64_t M_total, int K,
+                         void* stream) {
+  if (T < 0 || M_total < 0 || K <= 0) return GG_ERR_SHAPE;
+  if (M_total > 0x7FFFFFFFLL || T > 0x7FFFFFFFLL || K > (1 << 22)) return GG_ERR_SHAPE;
+  // tiles of 64 features; a row pitch of XT that keeps every 16-byte piece aligned (what the weight-gradient GEMM asks too)
+  if (K % gg::QC_FEATS != 0 || M_total % 16 != 0) return GG_ERR_UNSUPPORTED;
+  if (M_total == 0) return GG_OK;
+  if (!XT || !SX || (!X && T > 0)) return GG_ERR_NULL;
+  const int64_t mb = (M_total + 127) / 128;
+  const int64_t tiles = mb * (K / gg::QC_FEATS);
+  int64_t grid = (int64_t)device_cus() * 8;
+  if (grid > tiles) grid = tiles;
+  hipLaunchKernelGGL(gg::gg_quantize_cols_kernel, dim3((unsigned)grid), dim3(gg::Q_THREADS), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(X), row_src,
+                     static_cast<uint8_t*>(XT), SX, T, (int)M_total, K, (int)mb);
+  return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
+}
+
 int gg_fp8_check_offsets(const int32_t* group_offsets, int G, int64_t M_total, void* stream) {
   if (G < 0 || M_total < 0) return GG_ERR_SHAPE;
   if (!group_offsets) return GG_ERR_NULL;

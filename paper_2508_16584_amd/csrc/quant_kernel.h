@@ -226,6 +226,78 @@ __device__ __forceinline__ int e4m3x4_of(const float* v, float inv) {
   return w | (int)nan;
 }
 
+// The producer of the weight-gradient GEMM's operands: the same block quantiser ALONG THE TOKENS, with the transpose
+// that GEMM wants.  X [T, K] bf16 (token-major) -> XT [K, M_total] e4m3 (token index contiguous) and SX [MB, K]:
+// output token r is input row row_src[r]; feature k's block j holds tokens [128 j, 128 j + 128) of the output order,
+// the last block those that exist.  (The paper defines neither this operation nor its layouts.)
+// A workgroup takes tiles of one token block x 64 features: 128 rows of 128 bytes go through LDS (every group of 32
+// rows shifted by 32 bytes, so that the four lanes of a feature read from different banks); lane 4 k + p then owns
+// tokens 32 p .. 32 p + 31 of feature k: amax over its 32 values and over the quad, 32 bytes out — the four lanes of
+// a feature write one 128-byte line of XT.
+constexpr int QC_FEATS = 64;
+constexpr int QC_LDS_BYTES = 128 * 128 + 3 * 32;
+
+__global__ void __launch_bounds__(Q_THREADS) gg_quantize_cols_kernel(const uint16_t* __restrict__ X,
+                                                                     const int32_t* __restrict__ row_src,
+                                                                     uint8_t* __restrict__ XT, float* __restrict__ SX,
+                                                                     int64_t T, int M_total, int K, int MB) {
+  __shared__ __attribute__((aligned(16))) uint8_t tile[QC_LDS_BYTES];
+  const int t = threadIdx.x;
+  const int kt = K / QC_FEATS;
+  const int64_t tiles = (int64_t)MB * kt;
+  const int k = t >> 2, part = t & 3;
+  for (int64_t id = blockIdx.x; id < tiles; id += gridDim.x) {
+    const int j = (int)(id / kt), k0 = (int)(id - (int64_t)j * kt) * QC_FEATS;
+    // piece t + 256 i: token (t + 256 i) / 8 of the block, features 8 (t % 8) .. + 7; all four loads before any use
+    q_v4i raw[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = 128 * j + ((t + 256 * i) >> 3);
+      raw[i] = (q_v4i){0, 0, 0, 0};                        // a token past the end or a source outside [0, T): zeros
+      if (r < M_total) {
+        const int64_t src = row_src ? (int64_t)row_src[r] : (int64_t)r;
+        if (src >= 0 && src < T) raw[i] = *(const q_v4i*)(X + src * K + k0 + 8 * (t & 7));
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int tok = (t + 256 * i) >> 3;
+      *(q_v4i*)(tile + tok * 128 + (tok >> 5) * 32 + 16 * (t & 7)) = raw[i];
+    }
+    __syncthreads();
+    float v[32];
+    unsigned top = 0;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      const unsigned bits = *(const uint16_t*)(tile + (32 * part + i) * 128 + part * 32 + 2 * k);
+      v[i] = __builtin_bit_cast(float, bits << 16);
+      const unsigned a = amax_bits_of(v[i]);
+      top = top > a ? top : a;
+    }
+    unsigned o;
+    o = (unsigned)__builtin_amdgcn_update_dpp(0, (int)top, 0xB1, 0xF, 0xF, false);      // quad_perm [1, 0, 3, 2]
+    top = top > o ? top : o;
+    o = (unsigned)__builtin_amdgcn_update_dpp(0, (int)top, 0x4E, 0xF, 0xF, false);      // quad_perm [2, 3, 0, 1]
+    top = top > o ? top : o;
+    const float amax = block_amax(top);
+    const float scale = amax / 448.0f;
+    const float inv = 448.0f / amax;
+    q_v4i out0, out1;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      out0[d] = e4m3x4_of(v + 4 * d, inv);
+      out1[d] = e4m3x4_of(v + 16 + 4 * d, inv);
+    }
+    // M_total is a multiple of 16: a 16-byte piece of a row of XT exists whole or not at all
+    const int tok0 = 128 * j + 32 * part;
+    uint8_t* dst = XT + (int64_t)(k0 + k) * M_total + tok0;
+    if (tok0 < M_total) *(q_v4i*)dst = out0;
+    if (tok0 + 16 < M_total) *(q_v4i*)(dst + 16) = out1;
+    if (part == 0) SX[(int64_t)j * K + k0 + k] = scale;
+    __syncthreads();                                        // before the next tile's rows overwrite these
+  }
+}
+
 __global__ void __launch_bounds__(Q_THREADS) gg_swiglu_quantize_rows_kernel(const uint16_t* __restrict__ H,
                                                                             uint8_t* __restrict__ A, float* __restrict__ SA,
                                                                             uint16_t* __restrict__ act_out,

@@ -185,6 +185,16 @@ def test_fused_gemm_argument_validation(lib):
     assert f(M=0, A2=nul) == GG_OK
 
 
+def test_quantize_cols_argument_validation(lib):
+    p = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
+    nul = ctypes.c_void_p(0)
+    f = lambda T=256, M=256, K=128, X=p, XT=p, SX=p: lib.gg_fp8_quantize_cols(X, nul, XT, SX, T, M, K, nul)
+    assert f(K=96) == GG_ERR_UNSUPPORTED and f(M=250) == GG_ERR_UNSUPPORTED
+    assert f(T=-1) == GG_ERR_SHAPE and f(M=-16) == GG_ERR_SHAPE and f(K=0) == GG_ERR_SHAPE and f(K=2 ** 23) == GG_ERR_SHAPE
+    assert f(X=nul) == GG_ERR_NULL and f(XT=nul) == GG_ERR_NULL and f(SX=nul) == GG_ERR_NULL
+    assert f(M=0, X=nul, XT=nul, SX=nul) == GG_OK
+
+
 def test_wgrad_argument_validation(lib):
     p = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
     nul = ctypes.c_void_p(0)
