@@ -246,10 +246,10 @@ __global__ void __launch_bounds__(Q_THREADS) gg_quantize_cols_kernel(const uint1
   const int kt = K / QC_FEATS;
   const int64_t tiles = (int64_t)MB * kt;
   const int k = t >> 2, part = t & 3;
-  for (int64_t id = blockIdx.x; id < tiles; id += gridDim.x) {
+  // piece t + 256 i of a tile: token (t + 256 i) / 8 of the block, features 8 (t % 8) .. + 7
+  q_v4i raw[4];
+  auto load_tile = [&](int64_t id) __attribute__((always_inline)) {
     const int j = (int)(id / kt), k0 = (int)(id - (int64_t)j * kt) * QC_FEATS;
-    // piece t + 256 i: token (t + 256 i) / 8 of the block, features 8 (t % 8) .. + 7; all four loads before any use
-    q_v4i raw[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int r = 128 * j + ((t + 256 * i) >> 3);
@@ -259,34 +259,62 @@ __global__ void __launch_bounds__(Q_THREADS) gg_quantize_cols_kernel(const uint1
         if (src >= 0 && src < T) raw[i] = *(const q_v4i*)(X + src * K + k0 + 8 * (t & 7));
       }
     }
+  };
+  if ((int64_t)blockIdx.x < tiles) load_tile(blockIdx.x);
+  for (int64_t id = blockIdx.x; id < tiles; id += gridDim.x) {
+    const int j = (int)(id / kt), k0 = (int)(id - (int64_t)j * kt) * QC_FEATS;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int tok = (t + 256 * i) >> 3;
       *(q_v4i*)(tile + tok * 128 + (tok >> 5) * 32 + 16 * (t & 7)) = raw[i];
     }
     __syncthreads();
+    if (id + gridDim.x < tiles) load_tile(id + gridDim.x);      // the next tile's rows are on their way during this one's arithmetic
     float v[32];
     unsigned top = 0;
 #pragma unroll
     for (int i = 0; i < 32; ++i) {
       const unsigned bits = *(const uint16_t*)(tile + (32 * part + i) * 128 + part * 32 + 2 * k);
       v[i] = __builtin_bit_cast(float, bits << 16);
-      const unsigned a = amax_bits_of(v[i]);
-      top = top > a ? top : a;
+      top = top > (bits & 0x7FFFu) ? top : (bits & 0x7FFFu);          // |x| of non-NaN values orders like its bit pattern
+    }
+    // NaNs and infinities are rare: one wave-uniform branch keeps their handling out of the common path
+    const bool special = __builtin_amdgcn_ballot_w64(top >= 0x7F80u) != 0;
+    if (special) {
+      top = 0;
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        const unsigned a = amax_bits_of(v[i]) >> 16;                  // a NaN counts as zero
+        top = top > a ? top : a;
+      }
     }
     unsigned o;
     o = (unsigned)__builtin_amdgcn_update_dpp(0, (int)top, 0xB1, 0xF, 0xF, false);      // quad_perm [1, 0, 3, 2]
     top = top > o ? top : o;
     o = (unsigned)__builtin_amdgcn_update_dpp(0, (int)top, 0x4E, 0xF, 0xF, false);      // quad_perm [2, 3, 0, 1]
     top = top > o ? top : o;
-    const float amax = block_amax(top);
+    const float amax = block_amax(top << 16);
     const float scale = amax / 448.0f;
     const float inv = 448.0f / amax;
     q_v4i out0, out1;
+    if (!special) {
 #pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      out0[d] = e4m3x4_of(v + 4 * d, inv);
-      out1[d] = e4m3x4_of(v + 16 + 4 * d, inv);
+      for (int d = 0; d < 8; ++d) {
+        float y[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = __builtin_amdgcn_fmed3f(v[4 * d + e] * inv, -448.0f, 448.0f);
+        int wd = 0;
+        wd = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], wd, false);
+        wd = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], wd, true);
+        if (d < 4) out0[d] = wd;
+        else out1[d - 4] = wd;
+      }
+    } else {
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        out0[d] = e4m3x4_of(v + 4 * d, inv);
+        out1[d] = e4m3x4_of(v + 16 + 4 * d, inv);
+      }
     }
     // M_total is a multiple of 16: a 16-byte piece of a row of XT exists whole or not at all
     const int tok0 = 128 * j + 32 * part;
