@@ -204,8 +204,13 @@ __device__ __forceinline__ int swz_key_b(int row) {   // rows read: base + 8*(r/
 // and a unit stores its fp32 partial sums instead of C; gg_splitk_combine_kernel adds the two halves in that order
 // and rounds (paper Sec. 3.2: where few rows meet many weights, a launch has too few tiles to fill the chip; the K
 // loop is the one dimension left to split).  KB must be even; whole tiles and whole K blocks only.
-template <class Cfg, bool RAGGED = false, bool SPLITK = false>
+// BSTREAM: the weight fetches carry the streaming cache policy (nt sc1).  For groups of at most one row tile every
+// weight byte is fetched once; left to the default policy the 7.5 GB of a 256-expert layer push the activation tiles
+// (which the 16 column tiles of a group share) out of the L2.  Where several row tiles share a group's weights the
+// policy costs 17 - 35 %, so the host asks for it only when M_total <= G * BM.
+template <class Cfg, bool RAGGED = false, bool SPLITK = false, bool BSTREAM = false>
 __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
+  constexpr int kBAux = BSTREAM ? (2 | 16) : 0;
   static_assert(!(SPLITK && (RAGGED || Cfg::XPF)), "split-K: whole tiles, the ring-of-buffers path");
   constexpr int BM = Cfg::BM, BN = Cfg::BN, WN = Cfg::WN, NW = Cfg::NW;
   constexpr int TM = Cfg::TM, TN = Cfg::TN, WTM = Cfg::WTM, WTN = Cfg::WTN, STAGES = Cfg::STAGES;
@@ -365,9 +370,9 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
       } else {
         constexpr int i = idx - A_FULL;
         if constexpr (RAGGED)
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(st + Cfg::A_BYTES + (w + i * NW) * 1024), 16, (last && b_tail) ? GG_OOB_OFFSET : vB + i * (NW * 8) * K, kb * 128, 0, 0);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(st + Cfg::A_BYTES + (w + i * NW) * 1024), 16, (last && b_tail) ? GG_OOB_OFFSET : vB + i * (NW * 8) * K, kb * 128, 0, kBAux);
         else
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(st + Cfg::A_BYTES + (w + i * NW) * 1024), 16, vB, i * (NW * 8) * K + kb * 128, 0, 0);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(st + Cfg::A_BYTES + (w + i * NW) * 1024), 16, vB, i * (NW * 8) * K + kb * 128, 0, kBAux);
       }
     };
     auto dma_head = [&](int kb_l, int stg) {   // everything that is not issued inside the stream
@@ -386,7 +391,7 @@ __global__ void __launch_bounds__(Cfg::NT) gg_gemm_kernel(const GemmArgs a) {
         if (w < Cfg::B_SLABS % NW)
           __builtin_amdgcn_raw_ptr_buffer_load_lds(dB, GG_LDS_PTR(st + Cfg::A_BYTES + (w + B_FULL * NW) * 1024), 16,
                                                    RAGGED ? ((last && b_tail) ? GG_OOB_OFFSET : vB + B_FULL * (NW * 8) * K) : vB,
-                                                   (RAGGED ? 0 : B_FULL * (NW * 8) * K) + kb * 128, 0, 0);
+                                                   (RAGGED ? 0 : B_FULL * (NW * 8) * K) + kb * 128, 0, kBAux);
       }
     };
     auto dma_all = [&](int kb, int stg) {

@@ -50,9 +50,11 @@ struct Variant {
   hipError_t (*launch_ragged)(const gg::GemmArgs&, int grid, hipStream_t) = nullptr;
   bool min_kb3 = false;        // the second kernel: its prologue fetches three K blocks (K > 256)
   bool splitk = false;         // two work units per tile (halves of the K loop) and a combine pass; needs a workspace
+  // the same tile with the streaming cache policy on the weight fetches, for groups of at most one row tile; null: none
+  hipError_t (*launch_bstream)(const gg::GemmArgs&, int grid, hipStream_t) = nullptr;
 };
 
-template <class Cfg, bool RAGGED = false, bool SPLITK = false>
+template <class Cfg, bool RAGGED = false, bool SPLITK = false, bool BSTREAM = false>
 hipError_t launch_gemm(const gg::GemmArgs& args, int grid, hipStream_t stream) {
   static std::atomic<int> prepared[64];
   int dev = 0;
@@ -60,12 +62,12 @@ hipError_t launch_gemm(const gg::GemmArgs& args, int grid, hipStream_t stream) {
   if (e != hipSuccess) return e;
   if (dev >= 0 && dev < 64 && !prepared[dev].load(std::memory_order_acquire)) {
     // more than 64 KB of LDS per workgroup has to be requested explicitly
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_gemm_kernel<Cfg, RAGGED, SPLITK>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_gemm_kernel<Cfg, RAGGED, SPLITK, BSTREAM>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
     if (e != hipSuccess) return e;
     prepared[dev].store(1, std::memory_order_release);
   }
-  hipLaunchKernelGGL((gg::gg_gemm_kernel<Cfg, RAGGED, SPLITK>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, args);
+  hipLaunchKernelGGL((gg::gg_gemm_kernel<Cfg, RAGGED, SPLITK, BSTREAM>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, args);
   return hipGetLastError();
 }
 
@@ -93,14 +95,18 @@ hipError_t launch_gemm_rb(const gg::GemmArgs& args, int grid, hipStream_t stream
 #define GG_VARIANT_R(BM, BN, WM, WN, ST, XPF, GAP, WGPC)   /* with the instantiation for ragged N and K */         \
   {#BM "x" #BN "/" #WM "x" #WN "w/" #ST "s" XPF_SUFFIX_##XPF, BM, BN, gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>::LDS_BYTES, \
    WGPC, &launch_gemm<gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>>, &launch_gemm<gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>, true>}
+#define GG_VARIANT_RS(BM, BN, WM, WN, ST, XPF, GAP, WGPC)   /* ... and the one with streamed weight fetches */     \
+  {#BM "x" #BN "/" #WM "x" #WN "w/" #ST "s" XPF_SUFFIX_##XPF, BM, BN, gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>::LDS_BYTES, \
+   WGPC, &launch_gemm<gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>>, &launch_gemm<gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>, true>, \
+   false, false, &launch_gemm<gg::GemmCfg<BM, BN, WM, WN, ST, XPF, GAP>, false, false, true>}
 #define XPF_SUFFIX_false ""
 #define XPF_SUFFIX_true "x"
 
 const Variant kVariants[] = {
-    GG_VARIANT_R(160, 256, 2, 4, 3, false, 2, 1),   // 0: the largest tile that leaves room for a ring of 3 in 160 KB of LDS
+    GG_VARIANT_RS(160, 256, 2, 4, 3, false, 2, 1),   // 0: the largest tile that leaves room for a ring of 3 in 160 KB of LDS
     GG_VARIANT(256, 256, 2, 4, 2, false, 2, 1),   // 1: the largest tile the accumulators allow; ring of 2 only
     GG_VARIANT_R(128, 128, 2, 4, 4, false, 0, 1),   // 2: for N % 256 != 0
-    GG_VARIANT_R(128, 256, 2, 4, 3, false, 0, 1),   // 3
+    GG_VARIANT_RS(128, 256, 2, 4, 3, false, 0, 1),   // 3
     GG_VARIANT(64, 256, 1, 8, 3, false, 0, 1),    // 4
     GG_VARIANT_R(32, 256, 1, 8, 4, false, 0, 1),    // 5
     GG_VARIANT(16, 256, 1, 8, 2, false, 0, 2),    // 6
@@ -324,7 +330,9 @@ int run_gemm(const void* A, const float* SA, const void* B, const float* SB, con
   } else {
     args.slots = 0;
   }
-  hipError_t e = (ragged ? v.launch_ragged : v.launch)(args, (int)grid, static_cast<hipStream_t>(stream));
+  // groups of at most one row tile on average: every weight byte is fetched once, and streamed past the L2
+  const bool bstream = !ragged && v.launch_bstream && M_total <= (int64_t)G * v.BM;
+  hipError_t e = (ragged ? v.launch_ragged : bstream ? v.launch_bstream : v.launch)(args, (int)grid, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return GG_ERR_HIP;
   if (v.splitk) {
     const int64_t groups8 = M_total * (int64_t)(N / 8);
