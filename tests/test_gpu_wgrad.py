@@ -109,6 +109,33 @@ def test_wgrad_blocked_tile_list_every_element():
     assert np.array_equal(run_gpu(XTe, SXe, DYTe, SDYe, off), orc.grouped_gemm_wgrad(XTe, SXe, DYTe, SDYe, off)["W"])
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_wgrad_seeded_random_shapes(seed):
+    """Random group counts, sizes (many groups empty or shorter than a block, so that tiles which only store zeros
+    and tiles of one masked block follow each other), unowned tokens at both ends, N and K from one tile to a blocked
+    tile list; every element against the oracle, and bit-equal on exact inputs."""
+    rng = np.random.default_rng(4000 + seed)
+    N = int(rng.choice([128, 256, 384, 1024]))
+    K = int(rng.choice([256, 512, 1024]))
+    G = int(rng.integers(1, 9))
+    sizes = rng.integers(0, 400, G) * (rng.random(G) < 0.7)
+    sizes[rng.integers(0, G)] = int(rng.integers(1, 40))
+    lead = int(rng.integers(0, 3)) * 7
+    total = lead + int(sizes.sum()) + int(rng.integers(0, 30))
+    M_total = max(16, -(-total // 16) * 16)
+    off = (lead + np.concatenate([[0], np.cumsum(sizes)])).astype(np.int64)
+    XT, SX = quantised_normal(rng, K, M_total)
+    DYT, SDY = quantised_normal(rng, N, M_total, std=0.02)
+    ref = orc.grouped_gemm_wgrad(XT, SX, DYT, SDY, off, with_abs_sum=True)
+    got = run_gpu(XT, SX, DYT, SDY, off)
+    assert_wgrad_parity(got, ref, 2.0 ** -13, f"seed {seed}: G={G} N={N} K={K} M={M_total} sizes={sizes.tolist()}")
+    codes = np.array([0x00, 0x38, 0x40, 0x44, 0xB8, 0xC0], np.uint8)
+    XTe, DYTe = codes[rng.integers(0, 6, (K, M_total))], codes[rng.integers(0, 6, (N, M_total))]
+    SXe = (2.0 ** rng.integers(-3, 4, SX.shape)).astype(np.float32)
+    SDYe = (2.0 ** rng.integers(-3, 4, SDY.shape)).astype(np.float32)
+    assert np.array_equal(run_gpu(XTe, SXe, DYTe, SDYe, off), orc.grouped_gemm_wgrad(XTe, SXe, DYTe, SDYe, off)["W"])
+
+
 def test_wgrad_exact_where_every_intermediate_is_exact():
     rng = np.random.default_rng(33)
     M_total, N, K = 1024 + 48, 128, 256
