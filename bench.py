@@ -250,13 +250,15 @@ def bench_wgrad(args, cfg, dev):
 
     XT, SX = operand(K, 1.0)
     DYT, SDY = operand(N, 0.02)
-    alg_bytes = (K + N) * M + 4 * (K + N) * MB + 4 * G * N * K
+    bf16 = args.wgrad_out == "bf16"
+    es = 2 if bf16 else 4
+    alg_bytes = (K + N) * M + 4 * (K + N) * MB + es * G * N * K
     flops = 2.0 * M * N * K
-    copies = args.copies or (2 if 4 * G * N * K < (4 << 30) else 1)
-    outs = [torch.empty((G, N, K), dtype=torch.float32, device=dev) for _ in range(copies)]
+    copies = args.copies or (2 if es * G * N * K < (4 << 30) else 1)
+    outs = [torch.empty((G, N, K), dtype=torch.bfloat16 if bf16 else torch.float32, device=dev) for _ in range(copies)]
 
     def step(i):
-        gg.grouped_gemm_wgrad(XT, SX, DYT, SDY, off, dW=outs[i % copies])
+        gg.grouped_gemm_wgrad(XT, SX, DYT, SDY, off, dW=outs[i % copies], out_bf16=bf16)
 
     n_ramp = clock_warmup(step, args.clock_warmup_ms)
     for i in range(args.warmup):
@@ -267,11 +269,11 @@ def bench_wgrad(args, cfg, dev):
     achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
     out = {
         "metric": "FP8 TFLOP/s on the tokens of the groups, variable-K grouped GEMM dW^g = dY^g^T X^g (e4m3 operands scaled per "
-                  "128 tokens, fp32 accumulate, fp32 out)",
+                  "128 tokens, fp32 accumulate, " + ("bf16" if bf16 else "fp32") + " out)",
         "value": round(flops / (ms_per_step * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "fp8_e4m3 in, fp32 accumulate, fp32 out", "data": "synthetic",
-        "config": {"workload": args.workload + " layer, weight gradient", "op": "wgrad", "G": G, "M_total": M, "N": N, "K": K,
+        "vs_baseline": None, "dtype": "fp8_e4m3 in, fp32 accumulate, " + ("bf16" if bf16 else "fp32") + " out", "data": "synthetic",
+        "config": {"workload": args.workload + " layer, weight gradient", "op": "wgrad", "output": args.wgrad_out, "G": G, "M_total": M, "N": N, "K": K,
                    "tokens_per_group_min_max": [int(sizes.min()), int(sizes.max())], "output_copies_rotated": copies,
                    "clock_warmup_launches": n_ramp},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -290,13 +292,14 @@ def bench_wgrad(args, cfg, dev):
         t0 = time.perf_counter()
         ref = gg_oracle.grouped_gemm_wgrad(xt, sx, dyt, sdy, off.cpu().numpy(), with_abs_sum=True)
         cpu_s = time.perf_counter() - t0
-        got = outs[(args.steps - 1) % copies][:, torch.from_numpy(n_sel).to(dev)][:, :, torch.from_numpy(k_sel).to(dev)].cpu().numpy()
+        got = outs[(args.steps - 1) % copies][:, torch.from_numpy(n_sel).to(dev)][:, :, torch.from_numpy(k_sel).to(dev)].float().cpu().numpy()
         err = np.abs(got.astype(np.float64) - ref["D"])
-        bound = np.spacing(np.abs(ref["D"]).astype(np.float32)).astype(np.float64) + 2.0 ** -10 * ref["S"]
+        ulp = gg_oracle.bf16_ulp(ref["D"]) if bf16 else np.spacing(np.abs(ref["D"]).astype(np.float32)).astype(np.float64)
+        bound = ulp + 2.0 ** -10 * ref["S"]
         assert np.all(err <= bound), "bench.py --op wgrad: GPU output outside the tolerance of tests/test_gpu_wgrad.py on the oracle's sample"
         out["cpu_baseline"] = {"value": round(2.0 * M * len(n_sel) * len(k_sel) / cpu_s / 1e12, 5), "unit": "TFLOP/s", "cores": os.cpu_count(),
                                "kind": "oracle", "sample": f"{len(n_sel)} rows of dY^T x {len(k_sel)} features of every group, NumPy oracle, {cpu_s:.1f} s",
-                               "gpu_bits_equal_oracle_on_sample": round(float(np.mean(got == ref["W"])), 5),
+                               "gpu_bits_equal_oracle_on_sample": round(float(np.mean(got == (gg_oracle.f64_from_bf16_bits(gg_oracle.bf16_bits_from_f64(ref["D"])) if bf16 else ref["W"]))), 5),
                                "max_err_over_S": float(np.max(err / np.maximum(ref["S"], 1e-300)))}
     print(json.dumps(out))
 
@@ -581,6 +584,7 @@ def pmc_summary(folder):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--wgrad-out", default="fp32", choices=["fp32", "bf16"], help="--op wgrad: the type of dW")
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="gate_up")

@@ -120,8 +120,9 @@ int gg_fp8_grouped_gemm_f16(const void* A, const float* SA, const void* B, const
  *  GG_PADDED_GROUPS  a promise that every group holds a multiple of 128 rows (the pad path of Sec. 3, what
  *                gg_fp8_grouped_gemm_padded passes): the automatic choice (variant = -1) then only considers tile
  *                heights that divide such groups, and reads M_total as a capacity (M_pad_cap).  Results do not
- *                depend on it. */
-enum { GG_OUT_F16 = 1, GG_SA_KMAJOR = 2, GG_PADDED_GROUPS = 4 };
+ *                depend on it.
+ *  GG_OUT_BF16   gg_fp8_grouped_gemm_wgrad_ex only: its output is bfloat16 instead of fp32. */
+enum { GG_OUT_F16 = 1, GG_SA_KMAJOR = 2, GG_PADDED_GROUPS = 4, GG_OUT_BF16 = 8 };
 
 /* gg_fp8_grouped_gemm_variant with options (Sec. 2.1, 2.2 as above).  variant = -1 chooses automatically. */
 int gg_fp8_grouped_gemm_ex(const void* A, const float* SA, const void* B, const float* SB,
@@ -181,6 +182,13 @@ int gg_fp8_grouped_gemm_swiglu(const void* A, const float* SA, const void* B, co
  * allocated, asynchronous on `stream`. */
 int gg_fp8_grouped_gemm_wgrad(const void* XT, const float* SX, const void* DYT, const float* SDY,
                               const int32_t* group_offsets, float* dW, int G, int64_t M_total, int N, int K, void* stream);
+
+/* The same with options.  flags: GG_OUT_BF16 (only this call takes it): dW is bfloat16 [G, N, K], the fp32 sum of
+ * the definition above rounded once, to nearest even (half the output bytes, which are nine tenths of the operation's
+ * traffic); 0: fp32, as gg_fp8_grouped_gemm_wgrad.  Any other bit: GG_ERR_UNSUPPORTED. */
+int gg_fp8_grouped_gemm_wgrad_ex(const void* XT, const float* SX, const void* DYT, const float* SDY,
+                                 const int32_t* group_offsets, void* dW, int G, int64_t M_total, int N, int K, void* stream,
+                                 unsigned flags);
 
 /* The producer of gg_fp8_grouped_gemm_wgrad's operands: the block quantiser of gg_fp8_quantize_rows (the 1x128
  * scaling stated below Table 1 of the paper) applied ALONG THE TOKENS, with the transpose that call wants.  The paper

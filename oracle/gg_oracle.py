@@ -265,7 +265,7 @@ def grouped_gemm(A, SA, B, SB, group_offsets, rows=None, with_abs_sum=False, out
 # tests/test_oracle_pins.py are exact rationals, closed forms and the reduction
 # of its one-group case to grouped_gemm above).
 # ----------------------------------------------------------------------------
-def grouped_gemm_wgrad(XT, SX, DYT, SDY, group_offsets, with_abs_sum=False):
+def grouped_gemm_wgrad(XT, SX, DYT, SDY, group_offsets, with_abs_sum=False, out="fp32"):
     """dW^g = dY^g^T X^g for every group, the contraction running over the group's rows (tokens).
 
     XT   uint8 [K, M_total]   e4m3 bytes of X transposed: XT[k, r] is feature k of token r
@@ -281,7 +281,8 @@ def grouped_gemm_wgrad(XT, SX, DYT, SDY, group_offsets, with_abs_sum=False):
 
     Tokens outside the group contribute nothing, whatever their bytes are (NaN codes included).  A group without
     tokens gives zeros.  Returns {"D": float64 [G, N, K], "W": float32 [G, N, K] (D rounded once, to nearest even),
-    "S": float64 [G, N, K] (with_abs_sum): sum_j |sdy*sx| * sum_r |dy*x|}.
+    "S": float64 [G, N, K] (with_abs_sum): sum_j |sdy*sx| * sum_r |dy*x|}; with out="bf16" also "C": the bfloat16
+    bits of D rounded once, to nearest even (the two-byte output of the library's option).
     The inner sums are exact in float64 (at most 128 products, each a multiple of 2^-18 below 2^18) and so is
     sdy*sx; only the accumulation over j rounds, in ascending order.
     """
@@ -314,10 +315,13 @@ def grouped_gemm_wgrad(XT, SX, DYT, SDY, group_offsets, with_abs_sum=False):
             if with_abs_sum:
                 S[g] += np.abs(scale) * (np.abs(dy) @ np.abs(x).T)
     with np.errstate(over="ignore", invalid="ignore"):
-        out = {"D": D, "W": D.astype(np.float32)}       # float64 -> float32 is one RNE step
+        res = {"D": D, "W": D.astype(np.float32)}       # float64 -> float32 is one RNE step
     if with_abs_sum:
-        out["S"] = S
-    return out
+        res["S"] = S
+    assert out in ("fp32", "bf16")
+    if out == "bf16":
+        res["C"] = bf16_bits_from_f64(D)
+    return res
 
 
 # ----------------------------------------------------------------------------

@@ -170,6 +170,8 @@ def load_library() -> ctypes.CDLL:
     lib.gg_fp8_grouped_gemm_swiglu.restype = i32
     lib.gg_fp8_grouped_gemm_wgrad.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp]
     lib.gg_fp8_grouped_gemm_wgrad.restype = i32
+    lib.gg_fp8_grouped_gemm_wgrad_ex.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, vp, ctypes.c_uint]
+    lib.gg_fp8_grouped_gemm_wgrad_ex.restype = i32
     lib.gg_fp8_quantize_cols.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp]
     lib.gg_fp8_quantize_cols.restype = i32
     lib.gg_fp8_pad_ex.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i64, i32, vp, ctypes.c_uint]
@@ -208,7 +210,7 @@ EXPORTED_SYMBOLS = [
     "gg_fp8_grouped_gemm_variant", "gg_fp8_grouped_gemm_f16", "gg_fp8_grouped_gemm_ex", "gg_fp8_num_variants", "gg_fp8_variant_name", "gg_fp8_auto_variant", "gg_fp8_auto_variant_padded", "gg_fp8_padded_rows_cap",
     "gg_fp8_pad", "gg_fp8_grouped_gemm_padded", "gg_fp8_unpad", "gg_fp8_quantize_rows", "gg_fp8_swiglu_quantize_rows", "gg_fp8_check_offsets",
     "gg_fp8_grouped_gemm_splitk_noalloc", "gg_fp8_noalloc_max_elements", "gg_fp8_pad_ex", "gg_fp8_quantize_rows_ex", "gg_fp8_swiglu_quantize_rows_ex", "gg_fp8_grouped_gemm_swiglu",
-    "gg_fp8_grouped_gemm_wgrad", "gg_fp8_quantize_cols",
+    "gg_fp8_grouped_gemm_wgrad", "gg_fp8_grouped_gemm_wgrad_ex", "gg_fp8_quantize_cols",
 ]
 
 
@@ -241,7 +243,7 @@ def _want(t, name, dtype, ndim):
         raise ValueError(f"{name} must live on the GPU")
 
 
-GG_OUT_F16, GG_SA_KMAJOR, GG_PADDED_GROUPS = 1, 2, 4        # flags of the _ex entry points
+GG_OUT_F16, GG_SA_KMAJOR, GG_PADDED_GROUPS, GG_OUT_BF16 = 1, 2, 4, 8        # flags of the _ex entry points
 
 
 def _gemm_shapes(A, SA, B, SB, group_offsets, sa_kmajor=False):
@@ -409,9 +411,10 @@ def grouped_gemm_swiglu(A, SA, B, SB, group_offsets, A2=None, SA2=None, act_out=
     return A2, SA2, act_out
 
 
-def grouped_gemm_wgrad(XT, SX, DYT, SDY, group_offsets, dW=None, stream=None):
-    """gg_fp8_grouped_gemm_wgrad: dW [G, N, K] float32 from XT uint8 [K, M_total], SX float32 [ceil(M_total/128), K],
-    DYT uint8 [N, M_total], SDY float32 [ceil(M_total/128), N] and int32 group_offsets [G+1] (tokens of group g)."""
+def grouped_gemm_wgrad(XT, SX, DYT, SDY, group_offsets, dW=None, stream=None, out_bf16=False):
+    """gg_fp8_grouped_gemm_wgrad(_ex): dW [G, N, K] float32 (bfloat16 with out_bf16) from XT uint8 [K, M_total], SX
+    float32 [ceil(M_total/128), K], DYT uint8 [N, M_total], SDY float32 [ceil(M_total/128), N] and int32 group_offsets
+    [G+1] (tokens of group g)."""
     lib = load_library()
     _want(XT, "XT", torch.uint8, 2)
     _want(DYT, "DYT", torch.uint8, 2)
@@ -427,13 +430,14 @@ def grouped_gemm_wgrad(XT, SX, DYT, SDY, group_offsets, dW=None, stream=None):
     for t, name in ((XT, "XT"), (SX, "SX"), (DYT, "DYT"), (SDY, "SDY"), (group_offsets, "group_offsets")):
         if not t.is_cuda or not t.is_contiguous():
             raise ValueError(f"{name} must be a contiguous device tensor")
+    out_dtype = torch.bfloat16 if out_bf16 else torch.float32
     if dW is None:
-        dW = torch.empty((G, N, K), dtype=torch.float32, device=XT.device)
-    _want(dW, "dW", torch.float32, 3)
+        dW = torch.empty((G, N, K), dtype=out_dtype, device=XT.device)
+    _want(dW, "dW", out_dtype, 3)
     if tuple(dW.shape) != (G, N, K) or not dW.is_cuda or not dW.is_contiguous():
         raise ValueError(f"dW must be a contiguous device tensor [{G}, {N}, {K}]")
-    _check(lib.gg_fp8_grouped_gemm_wgrad(_ptr(XT), _ptr(SX), _ptr(DYT), _ptr(SDY), _ptr(group_offsets), _ptr(dW),
-                                         G, M_total, N, K, _stream(stream)))
+    args = (_ptr(XT), _ptr(SX), _ptr(DYT), _ptr(SDY), _ptr(group_offsets), _ptr(dW), G, M_total, N, K, _stream(stream))
+    _check(lib.gg_fp8_grouped_gemm_wgrad_ex(*args, GG_OUT_BF16) if out_bf16 else lib.gg_fp8_grouped_gemm_wgrad(*args))
     return dW
 
 

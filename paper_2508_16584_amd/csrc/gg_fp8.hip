@@ -436,8 +436,11 @@ int gg_fp8_grouped_gemm_splitk_noalloc(const void* A, const float* SA, const voi
 
 size_t gg_fp8_noalloc_max_elements(void) { return kScratchBytes / (2 * sizeof(float)); }
 
-int gg_fp8_grouped_gemm_wgrad(const void* XT, const float* SX, const void* DYT, const float* SDY,
-                              const int32_t* group_offsets, float* dW, int G, int64_t M_total, int N, int K, void* stream) {
+int gg_fp8_grouped_gemm_wgrad_ex(const void* XT, const float* SX, const void* DYT, const float* SDY,
+                                 const int32_t* group_offsets, void* dW, int G, int64_t M_total, int N, int K, void* stream,
+                                 unsigned flags) {
+  if (flags & ~(unsigned)GG_OUT_BF16) return GG_ERR_UNSUPPORTED;
+  const bool out16 = (flags & GG_OUT_BF16) != 0;
   if (G < 0 || M_total < 0 || N <= 0 || K <= 0) return GG_ERR_SHAPE;
   // whole output tiles of 256 features x 128 rows of dY^T; a row pitch that keeps every 128-token block 16-byte aligned
   if (M_total % 16 != 0 || N % gg::WgradCfg::TN != 0 || K % gg::WgradCfg::TK != 0) return GG_ERR_UNSUPPORTED;
@@ -455,7 +458,7 @@ int gg_fp8_grouped_gemm_wgrad(const void* XT, const float* SX, const void* DYT, 
   args.DYT = static_cast<const uint8_t*>(DYT);
   args.SDY = SDY;
   args.off = group_offsets;
-  args.dW = dW;
+  args.dW = static_cast<float*>(dW);
   args.G = G;
   args.M_total = (int)M_total;
   args.N = N;
@@ -477,14 +480,25 @@ int gg_fp8_grouped_gemm_wgrad(const void* XT, const float* SX, const void* DYT, 
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return GG_ERR_HIP;
   if (dev >= 0 && dev < 64 && !prepared[dev].load(std::memory_order_acquire)) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_wgrad_kernel<0>), hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_wgrad_kernel<0, false>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            gg::WgradCfg::LDS_BYTES) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&gg::gg_wgrad_kernel<0, true>), hipFuncAttributeMaxDynamicSharedMemorySize,
                             gg::WgradCfg::LDS_BYTES) != hipSuccess)
       return GG_ERR_HIP;
     prepared[dev].store(1, std::memory_order_release);
   }
-  hipLaunchKernelGGL(gg::gg_wgrad_kernel<0>, dim3((unsigned)grid), dim3(gg::WgradCfg::NT), gg::WgradCfg::LDS_BYTES,
-                     static_cast<hipStream_t>(stream), args);
+  if (out16)
+    hipLaunchKernelGGL((gg::gg_wgrad_kernel<0, true>), dim3((unsigned)grid), dim3(gg::WgradCfg::NT), gg::WgradCfg::LDS_BYTES,
+                       static_cast<hipStream_t>(stream), args);
+  else
+    hipLaunchKernelGGL((gg::gg_wgrad_kernel<0, false>), dim3((unsigned)grid), dim3(gg::WgradCfg::NT), gg::WgradCfg::LDS_BYTES,
+                       static_cast<hipStream_t>(stream), args);
   return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP;
+}
+
+int gg_fp8_grouped_gemm_wgrad(const void* XT, const float* SX, const void* DYT, const float* SDY,
+                              const int32_t* group_offsets, float* dW, int G, int64_t M_total, int N, int K, void* stream) {
+  return gg_fp8_grouped_gemm_wgrad_ex(XT, SX, DYT, SDY, group_offsets, dW, G, M_total, N, K, stream, 0);
 }
 
 int gg_fp8_grouped_gemm_swiglu(const void* A, const float* SA, const void* B, const float* SB,

@@ -75,7 +75,8 @@ __device__ __forceinline__ int bytes_below(int x4) {       // keeps the bytes be
 // full kernel makes.  The outputs of such builds are meaningless.
 enum : int { kWgNoFetch = 1, kWgNoStore = 2, kWgNoBarrier = 4, kWgNoMask = 8, kWgNoLdsReads = 16 };
 
-template <int TIMING>
+// OUT16: dW is bfloat16 (round to nearest even), half the output bytes.
+template <int TIMING, bool OUT16 = false>
 __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs a) {
   using Cfg = WgradCfg;
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
@@ -343,8 +344,9 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
     // to different rows and every lane's piece would be a request of its own: a quarter of the store rate).  Written
     // once and never read here, so the stores carry the streaming cache policy (sc0 sc1 nt): the gradients do not
     // push the operand tiles out of the L2 and the fetches beside them keep their latency.
-    const __amdgpu_buffer_rsrc_t dOut = __builtin_amdgcn_make_buffer_rsrc((void*)(a.dW + ((int64_t)cur.g * a.N + cur.n0) * a.K + cur.k0), 0, ((Cfg::TN - 1) * a.K + Cfg::TK) * 4, GG_RSRC_FLAGS);
-    const int vOut = (4 * q * a.K + 2 * r) * 4;
+    constexpr int ES = OUT16 ? 2 : 4;      // bytes per element of dW
+    const __amdgpu_buffer_rsrc_t dOut = __builtin_amdgcn_make_buffer_rsrc((void*)((uint8_t*)a.dW + (((int64_t)cur.g * a.N + cur.n0) * a.K + cur.k0) * ES), 0, ((Cfg::TN - 1) * a.K + Cfg::TK) * ES, GG_RSRC_FLAGS);
+    const int vOut = (4 * q * a.K + 2 * r) * ES;
     wait_vmcnt<31>();
 #pragma unroll
     for (int nf = 0; nf < 4; ++nf)
@@ -354,6 +356,8 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
         for (int pr = 0; pr < 2; ++pr) {
           const v2f v = acc[pr][nf][i];
           if constexpr (TIMING & kWgNoStore) asm volatile("" : : "v"(v));
+          else if constexpr (OUT16)      // the lane's two neighbouring features in one dword: a row's 16 lanes write 64 bytes
+            __builtin_amdgcn_raw_buffer_store_b32(pack2_rne(v.x, v.y, false), dOut, vOut + 64 * pr, ((wn * 64 + 16 * nf + i) * a.K + wk * 64) * 2, kStoreStreaming);
           else
             __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(v2i, v), dOut, vOut + 128 * pr, ((wn * 64 + 16 * nf + i) * a.K + wk * 64) * 4, kStoreStreaming);
         }

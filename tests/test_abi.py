@@ -206,6 +206,8 @@ def test_wgrad_argument_validation(lib):
     assert f(K=2 ** 21, M=16) == GG_ERR_SHAPE
     assert f(XT=nul) == GG_ERR_NULL and f(dW=nul) == GG_ERR_NULL and f(off=nul) == GG_ERR_NULL
     assert f(G=0, XT=nul, dW=nul, off=nul) == GG_OK
+    g = lambda flags: lib.gg_fp8_grouped_gemm_wgrad_ex(p, p, p, p, p, p, 0, 1024, 128, 256, nul, flags)
+    assert g(8) == GG_OK and g(0) == GG_OK and g(1) == GG_ERR_UNSUPPORTED and g(8 | 2) == GG_ERR_UNSUPPORTED
 
 
 def test_binding_rejects_wrong_tensors_before_calling_the_library(lib):

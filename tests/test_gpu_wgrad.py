@@ -136,6 +136,43 @@ def test_wgrad_seeded_random_shapes(seed):
     assert np.array_equal(run_gpu(XTe, SXe, DYTe, SDYe, off), orc.grouped_gemm_wgrad(XTe, SXe, DYTe, SDYe, off)["W"])
 
 
+def run_gpu_bf16(XT, SX, DYT, SDY, off):
+    t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a)).to(dt).to(DEV)
+    dW = gg.grouped_gemm_wgrad(t(XT, torch.uint8), t(SX, torch.float32), t(DYT, torch.uint8), t(SDY, torch.float32),
+                               t(np.asarray(off), torch.int32), out_bf16=True)
+    torch.cuda.synchronize()
+    return dW.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def test_wgrad_bfloat16_output():
+    """gg_fp8_grouped_gemm_wgrad_ex with GG_OUT_BF16: the same sums rounded once to bfloat16; the bounds of the
+    forward GEMM's bfloat16 output (gg_testlib.assert_parity: hard max(ulp, ulp/2 + 2^-10 S) on every element,
+    empirical ulp/2 + 2^-15 S and the shares within one ulp and bit-equal on quantised data), bit-equal on exact
+    inputs, zeros for a group without tokens."""
+    from gg_testlib import assert_parity
+    rng = np.random.default_rng(37)
+    M_total, N, K = 1200, 384, 1024
+    off = [16, 16, 555, 1100, 1190]
+    XT, SX = quantised_normal(rng, K, M_total)
+    DYT, SDY = quantised_normal(rng, N, M_total, std=0.02)
+    ref = orc.grouped_gemm_wgrad(XT, SX, DYT, SDY, off, with_abs_sum=True, out="bf16")
+    got = run_gpu_bf16(XT, SX, DYT, SDY, off)
+    assert_parity(got, ref, empirical=True, what="bf16 weight gradient")
+    assert np.all(got[0] == 0)
+    codes = np.array([0x00, 0x38, 0x40, 0x44, 0xB8, 0xC0], np.uint8)
+    XTe, DYTe = codes[rng.integers(0, 6, (K, M_total))], codes[rng.integers(0, 6, (N, M_total))]
+    SXe = (2.0 ** rng.integers(-3, 4, SX.shape)).astype(np.float32)
+    SDYe = (2.0 ** rng.integers(-3, 4, SDY.shape)).astype(np.float32)
+    ref_e = orc.grouped_gemm_wgrad(XTe, SXe, DYTe, SDYe, off, out="bf16")
+    assert np.array_equal(run_gpu_bf16(XTe, SXe, DYTe, SDYe, off), ref_e["C"])
+    # full-range bytes (hard bound only) and a NaN inside a group
+    XTr, DYTr = random_bytes(rng, (K, M_total)), random_bytes(rng, (N, M_total))
+    XTr[5, 700] = 0x7F
+    ref_r = orc.grouped_gemm_wgrad(XTr, SX, DYTr, SDY, off, with_abs_sum=True, out="bf16")
+    ref_r["S"] = np.nan_to_num(ref_r["S"], nan=0.0)
+    assert_parity(run_gpu_bf16(XTr, SX, DYTr, SDY, off), ref_r, empirical=False, what="bf16 weight gradient, raw bytes")
+
+
 def test_wgrad_exact_where_every_intermediate_is_exact():
     rng = np.random.default_rng(33)
     M_total, N, K = 1024 + 48, 128, 256
