@@ -12,7 +12,7 @@
 // SDY [ceil(M_total/128), N] hold one fp32 scale per block of 128 tokens and row (block-major: the 256 + 128 scales
 // a tile needs for one block are 12 cache lines; row-major they would be 384, as many requests as the operand
 // tiles themselves), the blocks being [128 j, 128 j + 128) of the concatenated token axis whatever the groups
-// are, and dW [G, N, K] is fp32.
+// are, and dW [G, N, K] is fp32 (or bfloat16).
 // Group boundaries may fall anywhere: the first and the last block of a group are fetched whole (16-byte aligned,
 // like every other block) and the bytes of tokens outside the group are cleared in registers, in BOTH operands, so
 // that a neighbouring group's bytes (NaN codes included) never reach a product.  A group without tokens gives zeros.
@@ -38,7 +38,7 @@ struct WgradArgs {
   const uint8_t* DYT;   // [N, M_total]
   const float* SDY;     // [MB, N]
   const int32_t* off;   // [G + 1]
-  float* dW;            // [G, N, K]
+  float* dW;            // [G, N, K] fp32, or bfloat16 in the OUT16 instantiation
   int G, M_total, N, K, MB;
   int n_tiles, k_tiles;   // N / 128, K / 256
   int tiles;              // G * n_tiles * k_tiles
@@ -149,7 +149,7 @@ __global__ void __launch_bounds__(WgradCfg::NT) gg_wgrad_kernel(const WgradArgs 
   const int s_pitch = sx_wave ? a.K * 4 : a.N * 4;                 // bytes from one token block's scales to the next
   const int ldsS = Cfg::X_BYTES + Cfg::Y_BYTES + (sx_wave ? w * 256 : sy_wave ? Cfg::SX_BYTES + (w - 4) * 256 : Cfg::SX_BYTES + Cfg::SY_BYTES);
 
-  // The fetch stream runs two token blocks ahead of the arithmetic and on from tile to tile: F is the tile whose
+  // The fetch stream runs three token blocks ahead of the arithmetic and on from tile to tile: F is the tile whose
   // block sF comes next (tiles without tokens have nothing to fetch and are passed over), so the first blocks of a
   // workgroup's next tile are in flight while the current one is finished and stored.
   Tile F = tile_at(0);
