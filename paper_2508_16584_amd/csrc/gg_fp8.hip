@@ -24,7 +24,7 @@ static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 namespace {
 
-constexpr int kVersion = 101;  // 0.1.1
+constexpr int kVersion = 200;  // 0.2.0: the weight-gradient GEMM and the column quantiser
 constexpr int kXcds = 8;       // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
 
 // Number of compute units of the current device (queried once per device, cached).
