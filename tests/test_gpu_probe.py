@@ -28,3 +28,15 @@ def test_hbm_and_fetch_streams_report_plausible_rates():
     for pattern in range(3):
         gbps, per_clk_cu = gg.probe_lds_fetch(pattern, 3, 2)
         assert 1000.0 < gbps < 60000.0 and 1.0 < per_clk_cu < 128.0, (pattern, gbps, per_clk_cu)
+
+
+def test_kernels_with_parts_left_out_run_and_leaving_out_is_not_slower():
+    """The measurement builds of the second GEMM kernel and of the weight-gradient kernel on small problems: they
+    run, and a build with its fetches and stores left out is not slower than the kernel as launched."""
+    full = gg.probe_gemm_kstep(192, 0, 4, 768, 1024, 2048, 3)
+    bare = gg.probe_gemm_kstep(192, 13, 4, 768, 1024, 2048, 3)
+    assert 1.0 < bare < 1.05 * full < 5000.0, (full, bare)
+    full = gg.probe_wgrad_parts(0, 4, 500, 1024, 1024, 3)
+    bare = gg.probe_wgrad_parts(3, 4, 500, 1024, 1024, 3)
+    alone = gg.probe_wgrad_parts(31, 4, 500, 1024, 1024, 3)
+    assert 1.0 < alone < 1.05 * bare < 1.1 * full < 5000.0, (full, bare, alone)
