@@ -267,6 +267,7 @@ def bench_wgrad(args, cfg, dev):
     ms_per_step, kern_avg_ms = timed_region(step, args.steps)
     kern_ms = per_launch_ms(step, args.steps)
     achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
+    wg_traffic = profiled_traffic("wgrad", args.workload, args.wgrad_out, "gg_wgrad_kernel")
     out = {
         "metric": "FP8 TFLOP/s on the tokens of the groups, variable-K grouped GEMM dW^g = dY^g^T X^g (e4m3 operands scaled per "
                   "128 tokens, fp32 accumulate, " + ("bf16" if bf16 else "fp32") + " out)",
@@ -277,7 +278,8 @@ def bench_wgrad(args, cfg, dev):
                    "tokens_per_group_min_max": [int(sizes.min()), int(sizes.max())], "output_copies_rotated": copies,
                    "clock_warmup_launches": n_ramp},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "gg_wgrad_kernel",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": wg_traffic,
+                     "traffic_source": TRAFFIC_SOURCE if wg_traffic is not None else None, "kernel": "gg_wgrad_kernel",
                      "kernel_avg_ms": round(kern_avg_ms, 4), "kernel_median_ms": round(float(np.median(kern_ms)), 4),
                      "kernel_min_ms": round(float(kern_ms.min()), 4), "algorithmic_bytes": int(alg_bytes),
                      "mfma_frac_of_fp8_peak": round(flops / (kern_avg_ms * 1e-3) / 1e12 / FP8_MFMA_PEAK_TFLOPS, 4)},
