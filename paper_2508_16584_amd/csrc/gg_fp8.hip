@@ -686,7 +686,7 @@ int gg_fp8_quantize_cols(const void* X, const int32_t* row_src, void* XT, float*
   if (!XT || !SX || (!X && T > 0)) return GG_ERR_NULL;
   const int64_t mb = (M_total + 127) / 128;
   const int64_t tiles = mb * (K / gg::QC_FEATS);
-  int64_t grid = (int64_t)device_cus() * 4;      // four workgroups fit a compute unit (registers); each walks its tiles with the next one's rows in flight
+  int64_t grid = (int64_t)device_cus() * 5;      // five workgroups fit a compute unit (registers); each walks its tiles with the next one's rows in flight
   if (grid > tiles) grid = tiles;
   hipLaunchKernelGGL(gg::gg_quantize_cols_kernel, dim3((unsigned)grid), dim3(gg::Q_THREADS), 0,
                      static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(X), row_src,

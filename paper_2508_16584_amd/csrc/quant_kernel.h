@@ -230,12 +230,13 @@ __device__ __forceinline__ int e4m3x4_of(const float* v, float inv) {
 // that GEMM wants.  X [T, K] bf16 (token-major) -> XT [K, M_total] e4m3 (token index contiguous) and SX [MB, K]:
 // output token r is input row row_src[r]; feature k's block j holds tokens [128 j, 128 j + 128) of the output order,
 // the last block those that exist.  (The paper defines neither this operation nor its layouts.)
-// A workgroup takes tiles of one token block x 64 features: 128 rows of 128 bytes go through LDS (every group of 32
-// rows shifted by 32 bytes, so that the four lanes of a feature read from different banks); lane 4 k + p then owns
-// tokens 32 p .. 32 p + 31 of feature k: amax over its 32 values and over the quad, 32 bytes out — the four lanes of
-// a feature write one 128-byte line of XT.
+// A workgroup takes tiles of one token block x 64 features: 128 rows of 128 bytes go through LDS (every group of 16
+// rows shifted by 32 bytes, so that the eight lanes of a feature pair read from different banks); lane 8 f + p then
+// owns tokens 16 p .. 16 p + 15 of features 2 f and 2 f + 1 (one 4-byte LDS read per token): amax over its 16 values
+// per feature and over the eight lanes, 16 bytes out per feature - the eight lanes of a feature write one 128-byte
+// line of XT.
 constexpr int QC_FEATS = 64;
-constexpr int QC_LDS_BYTES = 128 * 128 + 3 * 32;
+constexpr int QC_LDS_BYTES = 128 * 128 + 7 * 32;
 
 __global__ void __launch_bounds__(Q_THREADS) gg_quantize_cols_kernel(const uint16_t* __restrict__ X,
                                                                      const int32_t* __restrict__ row_src,
@@ -245,7 +246,7 @@ __global__ void __launch_bounds__(Q_THREADS) gg_quantize_cols_kernel(const uint1
   const int t = threadIdx.x;
   const int kt = K / QC_FEATS;
   const int64_t tiles = (int64_t)MB * kt;
-  const int k = t >> 2, part = t & 3;
+  const int fp = t >> 3, part = t & 7;
   // piece t + 256 i of a tile: token (t + 256 i) / 8 of the block, features 8 (t % 8) .. + 7
   q_v4i raw[4];
   auto load_tile = [&](int64_t id) __attribute__((always_inline)) {
@@ -266,62 +267,69 @@ __global__ void __launch_bounds__(Q_THREADS) gg_quantize_cols_kernel(const uint1
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int tok = (t + 256 * i) >> 3;
-      *(q_v4i*)(tile + tok * 128 + (tok >> 5) * 32 + 16 * (t & 7)) = raw[i];
+      *(q_v4i*)(tile + tok * 128 + (tok >> 4) * 32 + 16 * (t & 7)) = raw[i];
     }
     __syncthreads();
     if (id + gridDim.x < tiles) load_tile(id + gridDim.x);      // the next tile's rows are on their way during this one's arithmetic
-    float v[32];
-    unsigned top = 0;
+    float v[2][16];
+    unsigned top[2] = {0, 0};
 #pragma unroll
-    for (int i = 0; i < 32; ++i) {
-      const unsigned bits = *(const uint16_t*)(tile + (32 * part + i) * 128 + part * 32 + 2 * k);
-      v[i] = __builtin_bit_cast(float, bits << 16);
-      top = top > (bits & 0x7FFFu) ? top : (bits & 0x7FFFu);          // |x| of non-NaN values orders like its bit pattern
+    for (int i = 0; i < 16; ++i) {
+      const unsigned two = *(const unsigned*)(tile + (16 * part + i) * 128 + part * 32 + 4 * fp);
+      v[0][i] = __builtin_bit_cast(float, two << 16);
+      v[1][i] = __builtin_bit_cast(float, two & 0xFFFF0000u);
+      const unsigned a0 = two & 0x7FFFu, a1 = (two >> 16) & 0x7FFFu;      // |x| of non-NaN values orders like its bit pattern
+      top[0] = top[0] > a0 ? top[0] : a0;
+      top[1] = top[1] > a1 ? top[1] : a1;
     }
     // NaNs and infinities are rare: one wave-uniform branch keeps their handling out of the common path
-    const bool special = __builtin_amdgcn_ballot_w64(top >= 0x7F80u) != 0;
-    if (special) {
-      top = 0;
+    const bool special = __builtin_amdgcn_ballot_w64((top[0] > top[1] ? top[0] : top[1]) >= 0x7F80u) != 0;
+    q_v4i out[2];
+    float scale[2];
 #pragma unroll
-      for (int i = 0; i < 32; ++i) {
-        const unsigned a = amax_bits_of(v[i]) >> 16;                  // a NaN counts as zero
-        top = top > a ? top : a;
+    for (int f = 0; f < 2; ++f) {
+      unsigned m = top[f];
+      if (special) {
+        m = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const unsigned a = amax_bits_of(v[f][i]) >> 16;               // a NaN counts as zero
+          m = m > a ? m : a;
+        }
       }
-    }
-    unsigned o;
-    o = (unsigned)__builtin_amdgcn_update_dpp(0, (int)top, 0xB1, 0xF, 0xF, false);      // quad_perm [1, 0, 3, 2]
-    top = top > o ? top : o;
-    o = (unsigned)__builtin_amdgcn_update_dpp(0, (int)top, 0x4E, 0xF, 0xF, false);      // quad_perm [2, 3, 0, 1]
-    top = top > o ? top : o;
-    const float amax = block_amax(top << 16);
-    const float scale = amax / 448.0f;
-    const float inv = 448.0f / amax;
-    q_v4i out0, out1;
-    if (!special) {
-#pragma unroll
-      for (int d = 0; d < 8; ++d) {
-        float y[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) y[e] = __builtin_amdgcn_fmed3f(v[4 * d + e] * inv, -448.0f, 448.0f);
-        int wd = 0;
-        wd = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], wd, false);
-        wd = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], wd, true);
-        if (d < 4) out0[d] = wd;
-        else out1[d - 4] = wd;
-      }
-    } else {
+      unsigned o;
+      o = (unsigned)__builtin_amdgcn_update_dpp(0, (int)m, 0xB1, 0xF, 0xF, false);       // quad_perm [1, 0, 3, 2]
+      m = m > o ? m : o;
+      o = (unsigned)__builtin_amdgcn_update_dpp(0, (int)m, 0x4E, 0xF, 0xF, false);       // quad_perm [2, 3, 0, 1]
+      m = m > o ? m : o;
+      o = (unsigned)__builtin_amdgcn_update_dpp(0, (int)m, 0x141, 0xF, 0xF, false);      // row_half_mirror: the other quad of the eight
+      m = m > o ? m : o;
+      const float amax = block_amax(m << 16);
+      scale[f] = amax / 448.0f;
+      const float inv = 448.0f / amax;
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
-        out0[d] = e4m3x4_of(v + 4 * d, inv);
-        out1[d] = e4m3x4_of(v + 16 + 4 * d, inv);
+        if (!special) {
+          float y[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) y[e] = __builtin_amdgcn_fmed3f(v[f][4 * d + e] * inv, -448.0f, 448.0f);
+          int wd = 0;
+          wd = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], wd, false);
+          wd = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], wd, true);
+          out[f][d] = wd;
+        } else {
+          out[f][d] = e4m3x4_of(v[f] + 4 * d, inv);
+        }
       }
     }
     // M_total is a multiple of 16: a 16-byte piece of a row of XT exists whole or not at all
-    const int tok0 = 128 * j + 32 * part;
-    uint8_t* dst = XT + (int64_t)(k0 + k) * M_total + tok0;
-    if (tok0 < M_total) *(q_v4i*)dst = out0;
-    if (tok0 + 16 < M_total) *(q_v4i*)(dst + 16) = out1;
-    if (part == 0) SX[(int64_t)j * K + k0 + k] = scale;
+    const int tok0 = 128 * j + 16 * part;
+    if (tok0 < M_total) {
+      uint8_t* dst = XT + (int64_t)(k0 + 2 * fp) * M_total + tok0;
+      *(q_v4i*)dst = out[0];
+      *(q_v4i*)(dst + M_total) = out[1];
+    }
+    if (part == 0) *(q_v2i*)(SX + (int64_t)j * K + k0 + 2 * fp) = (q_v2i){__builtin_bit_cast(int, scale[0]), __builtin_bit_cast(int, scale[1])};
     __syncthreads();                                        // before the next tile's rows overwrite these
   }
 }
