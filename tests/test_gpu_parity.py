@@ -126,6 +126,32 @@ def test_many_empty_groups_and_a_wide_output():
         assert_parity(run_gpu(dev, p["M_total"], 16384, v), ref, what=f"N=16384 variant {v}")
 
 
+def test_operands_written_by_a_kernel_just_before_the_launch():
+    """Short groups take the instantiation whose weight fetches carry the streaming cache policy, and C is stored with
+    it: operands that a device kernel on the same stream wrote immediately before the launch (still in the caches, over
+    memory that held other bytes) must be what the GEMM reads, and a device kernel right behind it must read the C it
+    wrote.  Several rounds with new contents in the same buffers."""
+    rng = np.random.default_rng(62)
+    cfg = WorkloadConfig("fresh", 55, 24, 1024, 512, 0, "custom", "latency")
+    sizes = rng.integers(0, 120, 24)
+    bufs = None
+    for rnd in range(3):
+        p = make_problem(cfg, sizes=sizes, seed=550 + rnd)
+        ref = orc.grouped_gemm(*np_problem(p), with_abs_sum=True)
+        src = {k: p[k].to(DEV) for k in ("A", "SA", "B", "SB", "group_offsets")}
+        if bufs is None:
+            bufs = {k: torch.empty_like(v) for k, v in src.items()}
+            C = torch.empty((p["M_total"], 512), dtype=torch.bfloat16, device=DEV)
+        torch.cuda.synchronize()
+        for k in bufs:
+            bufs[k].copy_(src[k])                       # device kernels; no synchronisation before the GEMM
+        for v in (-1, 0, 3):
+            gg.grouped_gemm(bufs["A"], bufs["SA"], bufs["B"], bufs["SB"], bufs["group_offsets"], C=C, variant=v)
+            C2 = C.clone()                              # a device kernel reading C right behind the GEMM
+            torch.cuda.synchronize()
+            assert_parity(bits_of(C2), ref, empirical=False, what=f"round {rnd} variant {v}")
+
+
 @pytest.mark.timeout(600)
 def test_largest_k_and_largest_n_the_library_takes():
     """K = 2^22 and N = 2^21, the limits of the argument check (32-bit offsets inside a tile).  The oracle evaluates
