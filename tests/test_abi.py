@@ -89,6 +89,16 @@ def test_version_status_strings_and_variants(lib):
         gg.auto_variant(1, 1, 100, 128)
 
 
+def test_automatic_choice_on_the_four_full_size_workloads(lib):
+    """The tiles the measurements of the four workloads were taken with (the choice is host arithmetic on G, M_total,
+    N, K alone): a change of the estimate that moves one of them should be a decision, not an accident."""
+    name = lambda G, M, N, K: gg.variant_name(gg.auto_variant(G, M, N, K))
+    assert name(8, 8192, 4096, 7168) == "192x256/1x8w/3s-rb"          # gate_up
+    assert name(32, 16384, 7168, 2048) == "256x256/1x8w/3s-rb"        # down
+    assert name(256, 32768, 4096, 7168) == "160x256/2x4w/3s"          # many_small
+    assert name(64, 2048, 4096, 7168) == "128x256/2x4w/3s"            # decode
+
+
 def test_padded_rows_cap_and_workspace(lib):
     assert gg.padded_rows_cap(0, 0) == 0
     assert gg.padded_rows_cap(8, 8192) == 128 * (64 + 8)
